@@ -1,0 +1,49 @@
+"""Model shapes of the benchmark configurations (random-init Llama-style decoders).
+
+The paper evaluates Vicuna-7B/13B/33B (Sec. 6 "Setup"); the shapes below are
+those architectures' public dimensions.  Trained weights are not used: every
+tensor is random-init from a seed (see weights.py).
+"""
+from dataclasses import dataclass
+
+
+@dataclass(frozen=True)
+class ModelShape:
+    name: str
+    n_layers: int
+    hidden: int
+    n_heads: int
+    head_dim: int
+    ffn: int
+    vocab: int
+    rope_base: float = 10000.0
+    rms_eps: float = 1e-5
+    dtype: str = "bf16"  # storage type of weights and KV cache: "bf16" or "f32"
+
+    @property
+    def qkv_dim(self) -> int:
+        return self.n_heads * self.head_dim
+
+    def layer_param_count(self) -> int:
+        h, q, f = self.hidden, self.qkv_dim, self.ffn
+        return 3 * q * h + h * q + 3 * f * h
+
+    def weight_bytes_per_layer(self) -> int:
+        return self.layer_param_count() * (2 if self.dtype == "bf16" else 4)
+
+
+SHAPES = {
+    # 2-layer oracle-scale model, fp32
+    "tiny": ModelShape("tiny", 2, 256, 4, 64, 688, 1024, dtype="f32"),
+    # same tiny dimensions stored in bf16 (exercises the MFMA path at oracle scale)
+    "tiny_bf16": ModelShape("tiny_bf16", 2, 256, 4, 64, 688, 1024, dtype="bf16"),
+    # a mid-size bf16 model with head_dim 128 that the oracle still finishes in seconds
+    "small_bf16": ModelShape("small_bf16", 3, 1024, 8, 128, 2752, 4096, dtype="bf16"),
+    "7b": ModelShape("7b", 32, 4096, 32, 128, 11008, 32000),
+    "13b": ModelShape("13b", 40, 5120, 40, 128, 13824, 32000),
+    "33b": ModelShape("33b", 60, 6656, 52, 128, 17920, 32000),
+}
+
+
+def shape_by_name(name: str) -> ModelShape:
+    return SHAPES[name]
