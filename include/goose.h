@@ -1,0 +1,193 @@
+/*
+ * goose.h -- C ABI of the tree-verification library for MI355X (gfx950).
+ *
+ * One call sequence verifies one draft tree in one pass of the target model
+ * (Goose, Sec. 4, stage 2 "one forward pass scores every candidate" and stage 3
+ * "greedy walk"; Alg. 2):
+ *
+ *   goose_build_mask  ->  goose_embed  ->  goose_verify_layer x n_layers
+ *   ->  goose_lm_head_argmax  ->  goose_accept  ->  goose_compact_kv
+ *
+ * goose_verify_step runs that whole sequence from device-resident inputs.
+ *
+ * Conventions for every call
+ *   - returns GOOSE_OK (0) or a negative goose_status; never throws, never aborts;
+ *   - `d_*` arguments are DEVICE pointers owned by the caller (the library never
+ *     frees or reallocates them); `h_*` arguments are HOST pointers;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); work is
+ *     queued on it and results are valid once the caller has synchronised it;
+ *     no call synchronises the device or the stream;
+ *   - a goose_ctx owns device workspace only.  One ctx serves one stream at a time:
+ *     calls on the same ctx from different streams race on that workspace.
+ *
+ * Tree: B nodes in topological order, node 0 = root (the anchor token, which is part of
+ * the pass and not yet in the cache), parent[0] = -1, 0 <= parent[i] < i, 1 <= B <= 128.
+ * P = number of committed cache slots (the prefix).  A node sees slots [0,P) plus the
+ * slots P+j of the nodes j on its own root path, itself included, and sits at
+ * position P + depth (Sec. 4 "tree attention mask": each node attends only to its
+ * root-to-node ancestors).
+ *
+ * Model: pre-norm Llama-style decoder (the architecture the paper evaluates, Sec. 6):
+ * RMSNorm x*rsqrt(mean(x^2)+eps)*g, rotary embedding on q,k with half-split pairing
+ * (j, j+d/2) and angle pos*base^(-2j/d), scores/sqrt(d), softmax, SwiGLU MLP, untied LM
+ * head, no biases, n_kv_heads == n_heads.  Raw weight matrices are row-major [out][in].
+ *
+ * Storage types.  desc.dtype selects the storage type T of weights, KV cache and gains:
+ * GOOSE_DTYPE_BF16 (MFMA kernels, fp32 accumulation) or GOOSE_DTYPE_F32 (plain fp32
+ * kernels for small models).  The residual stream x is always fp32 [B][hidden].
+ *
+ * KV cache: two allocations, K and V, each T[n_layers][n_heads][cap][head_dim];
+ * K is stored after the rotary embedding.  verify_layer writes slots [P, P+B) of its
+ * layer, compact_kv rewrites slots [P, P+L] of every layer; slots above P+L hold
+ * leftovers afterwards.
+ */
+#ifndef GOOSE_H
+#define GOOSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GOOSE_OK = 0,
+  GOOSE_ERR_ARG = -1,             /* NULL pointer or a value out of its documented range */
+  GOOSE_ERR_SHAPE = -2,           /* model dimensions the kernels do not support */
+  GOOSE_ERR_CAPACITY = -3,        /* B > max_B, or P + B > cap */
+  GOOSE_ERR_NOT_TOPOLOGICAL = -4, /* parent array is not a rooted tree in topological order */
+  GOOSE_ERR_HIP = -5,             /* a HIP runtime call failed */
+  GOOSE_ERR_UNSUPPORTED = -6
+} goose_status;
+
+enum { GOOSE_DTYPE_BF16 = 0, GOOSE_DTYPE_F32 = 1 };
+enum { GOOSE_MAX_B = 128 };
+
+typedef struct {
+  int32_t n_layers, hidden, n_heads, head_dim, ffn, vocab;
+  float rope_base, rms_eps;
+  int32_t dtype; /* GOOSE_DTYPE_* */
+} goose_model_desc;
+
+/* Raw weights of one decoder layer as a checkpoint stores them: device pointers,
+ * row-major [out][in] of the model's storage type. */
+typedef struct {
+  const void *wq, *wk, *wv; /* [n_heads*head_dim][hidden] */
+  const void *wo;           /* [hidden][n_heads*head_dim] */
+  const void *wg, *wu;      /* [ffn][hidden] */
+  const void *wd;           /* [hidden][ffn] */
+  const void *g1, *g2;      /* [hidden] RMSNorm gains before attention / before the MLP */
+} goose_layer_weights;
+
+typedef struct goose_ctx goose_ctx;
+
+const char* goose_strerror(int status);
+
+/* Creates a context with workspace for trees of up to max_B nodes and caches of `cap`
+ * slots per head.  Allocates device memory on the current device. */
+int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** out);
+void goose_destroy(goose_ctx* ctx);
+
+/* Host-side check of a parent array (h_parent is a HOST pointer): GOOSE_OK,
+ * GOOSE_ERR_ARG (NULL, B outside [1,128]) or GOOSE_ERR_NOT_TOPOLOGICAL.
+ * The device kernels never fault on a bad array (an offending node is treated as a child
+ * of the root) but their result is then meaningless; callers validate trees here. */
+int goose_check_parent(const int32_t* h_parent, int B);
+
+/* ---- weight packing (once, at load time) -------------------------------------------
+ * The kernels stream weights from a packed copy: for bf16 each matrix is re-tiled so
+ * that one wavefront load instruction reads 1 KiB of consecutive bytes that is exactly
+ * one MFMA operand (32 output rows x 16 inputs); q,k,v rows are concatenated and
+ * gate/up rows interleaved in blocks of 32.  For fp32 the blob holds plain row-major
+ * matrices.  The caller allocates goose_packed_layer_bytes() per layer; all layers of a
+ * model live in one allocation, layer l at byte offset l * goose_packed_layer_bytes(). */
+size_t goose_packed_layer_bytes(const goose_ctx* ctx);
+int goose_pack_layer(goose_ctx* ctx, const goose_layer_weights* raw, void* d_packed_layer, void* stream);
+size_t goose_packed_lm_head_bytes(const goose_ctx* ctx);
+/* d_gf: final RMSNorm gain T[hidden]; d_wlm: LM head T[vocab][hidden]. */
+int goose_pack_lm_head(goose_ctx* ctx, const void* d_gf, const void* d_wlm, void* d_packed_head, void* stream);
+
+/* ---- 1. ancestor bitmask -------------------------------------------------------------
+ * mask[i] = mask[parent[i]] | bit(i), depth[i] = depth[parent[i]] + 1, pos[i] = P + depth[i]
+ * (Sec. 4, tree attention mask).  d_mask: uint64 [B][ceil(B/64)], bit (j%64) of word j/64 of
+ * row i set iff node j is i or an ancestor of i.  d_depth, d_pos: int32 [B].
+ * P is taken from *d_P when d_P is not NULL, else from the argument P. */
+int goose_build_mask(goose_ctx* ctx, const int32_t* d_parent, int B, int P, const int32_t* d_P,
+                     uint64_t* d_mask, int32_t* d_depth, int32_t* d_pos, void* stream);
+
+/* ---- 2. embedding gather: x[i][:] = fp32(E[tokens[i]][:]).  d_embed: T[vocab][hidden]. */
+int goose_embed(goose_ctx* ctx, const void* d_embed, const int32_t* d_tokens, int B, float* d_x, void* stream);
+
+/* ---- 3. one decoder layer over the B packed nodes (Alg. 2 line 1, per layer) ------------
+ * d_x fp32 [B][hidden], updated in place.  d_kcache/d_vcache: THIS layer's T[n_heads][cap][head_dim].
+ * d_mask/d_pos as written by goose_build_mask.  P from *d_P when d_P != NULL (then the
+ * argument P must be an upper bound of *d_P; it sizes the launch), else the argument. */
+int goose_verify_layer(goose_ctx* ctx, const void* d_packed_layer, float* d_x, void* d_kcache, void* d_vcache,
+                       int P, const int32_t* d_P, int B, const uint64_t* d_mask, const int32_t* d_pos,
+                       void* stream);
+
+/* ---- 4. final norm + LM head + per-node argmax (Alg. 2 line 2) ------------------------
+ * d_argmax int32 [B]: greedy prediction at every node, lowest index on ties.
+ * d_logits_or_null fp32 [B][vocab]; d_margin_or_null fp32 [B] = top-1 minus top-2 logit. */
+int goose_lm_head_argmax(goose_ctx* ctx, const void* d_packed_head, const float* d_x, int B, int32_t* d_argmax,
+                         float* d_logits_or_null, float* d_margin_or_null, void* stream);
+
+/* ---- 5. greedy walk (Alg. 2 lines 3-13; Sec. 4.2) -------------------------------------
+ * From the root, step to the child whose draft token equals the prediction at the current
+ * node; spine-tagged children are examined before branch children, lower node index first
+ * within a tag; stop when no child matches.  d_is_spine_or_null: uint8 [B] (NULL = all spine).
+ * Outputs: d_accept_len[0] = L (accepted drafts, root and bonus not counted);
+ * d_path int32 [B]: path[0] = 0, path[1..L] = accepted nodes, rest = -1;
+ * d_bonus[0] = prediction at the last node of the path. */
+int goose_accept(goose_ctx* ctx, const int32_t* d_parent, const int32_t* d_tokens, const uint8_t* d_is_spine_or_null,
+                 const int32_t* d_argmax, int B, int32_t* d_accept_len, int32_t* d_path, int32_t* d_bonus,
+                 void* stream);
+
+/* ---- 6. commit the accepted path to the cache -----------------------------------------
+ * For every layer, K and V: slot P + path[j] -> slot P + j, j = 0..L (the root and the
+ * accepted nodes become cache slots P..P+L; valid because a node's K was rotated at
+ * P + depth and depth(path[j]) = j).  Exact byte copies.  The paper does not describe
+ * cache handling; this is the standard commit of tree speculation.
+ * d_kcache_all/d_vcache_all: the whole T[n_layers][n_heads][cap][head_dim] allocations.
+ * If d_new_P_or_null != NULL it receives P + L + 1 (it may alias d_P). */
+int goose_compact_kv(goose_ctx* ctx, void* d_kcache_all, void* d_vcache_all, int P, const int32_t* d_P,
+                     const int32_t* d_path, const int32_t* d_accept_len, int32_t* d_new_P_or_null, void* stream);
+
+/* ---- whole step from device-resident inputs (no host round trip inside) --------------
+ * Runs 1..6 above.  *d_P is read at the start and replaced by P + L + 1 at the end;
+ * P_max is a host upper bound of *d_P used to size launches (P_max + B <= cap).
+ * d_next_root_or_null receives the bonus token (e.g. tokens[0] of the next step's tree). */
+typedef struct {
+  const void* d_embed;         /* T[vocab][hidden] */
+  const void* d_packed_layers; /* n_layers * goose_packed_layer_bytes() */
+  const void* d_packed_head;
+  void* d_kcache_all;
+  void* d_vcache_all;
+} goose_model_ptrs;
+
+typedef struct {
+  const int32_t* d_tokens;   /* [B] */
+  const int32_t* d_parent;   /* [B] */
+  const uint8_t* d_is_spine; /* [B] or NULL */
+  int32_t* d_P;              /* [1] in/out */
+  int32_t* d_argmax;         /* [B] out */
+  int32_t* d_accept_len;     /* [1] out */
+  int32_t* d_path;           /* [B] out */
+  int32_t* d_bonus;          /* [1] out */
+  int32_t* d_next_root_or_null;
+  float* d_logits_or_null;   /* [B][vocab] */
+  float* d_margin_or_null;   /* [B] */
+} goose_step_io;
+
+int goose_verify_step(goose_ctx* ctx, const goose_model_ptrs* model, const goose_step_io* io, int B, int P_max,
+                      void* stream);
+
+/* Device-side diagnostics: bit 0 set if any kernel since the last call saw a parent
+ * array that is not topological.  Synchronises `stream`. */
+int goose_device_flags(goose_ctx* ctx, void* stream, int32_t* h_flags_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GOOSE_H */

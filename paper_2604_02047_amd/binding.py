@@ -1,0 +1,220 @@
+"""ctypes binding of libgoose.so: argument marshalling only, every step runs in the HIP kernels.
+
+Method names mirror the C ABI (include/goose.h).  Tensors are torch tensors living on the GPU;
+the binding passes their data pointers and the current torch stream.  There is no fallback: if the
+library is missing, loading raises.
+"""
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+
+EXPORTS = [
+    "goose_strerror", "goose_create", "goose_destroy", "goose_check_parent",
+    "goose_packed_layer_bytes", "goose_pack_layer", "goose_packed_lm_head_bytes", "goose_pack_lm_head",
+    "goose_build_mask", "goose_embed", "goose_verify_layer", "goose_lm_head_argmax",
+    "goose_accept", "goose_compact_kv", "goose_verify_step", "goose_device_flags",
+]
+
+GOOSE_DTYPE_BF16, GOOSE_DTYPE_F32 = 0, 1
+
+
+class GooseError(RuntimeError):
+    def __init__(self, status, what):
+        super().__init__(f"{what}: status {status} ({_strerror(status)})")
+        self.status = status
+
+
+class _Desc(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("ffn", C.c_int32), ("vocab", C.c_int32), ("rope_base", C.c_float), ("rms_eps", C.c_float),
+                ("dtype", C.c_int32)]
+
+
+class _LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2")]
+
+
+class _ModelPtrs(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("d_embed", "d_packed_layers", "d_packed_head", "d_kcache_all",
+                                          "d_vcache_all")]
+
+
+class _StepIO(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("d_tokens", "d_parent", "d_is_spine", "d_P", "d_argmax", "d_accept_len",
+                                          "d_path", "d_bonus", "d_next_root_or_null", "d_logits_or_null",
+                                          "d_margin_or_null")]
+
+
+@dataclass
+class ModelDesc:
+    n_layers: int
+    hidden: int
+    n_heads: int
+    head_dim: int
+    ffn: int
+    vocab: int
+    rope_base: float = 10000.0
+    rms_eps: float = 1e-5
+    dtype: str = "bf16"
+
+    @classmethod
+    def from_shape(cls, s):
+        return cls(s.n_layers, s.hidden, s.n_heads, s.head_dim, s.ffn, s.vocab, s.rope_base, s.rms_eps, s.dtype)
+
+    def _c(self):
+        return _Desc(self.n_layers, self.hidden, self.n_heads, self.head_dim, self.ffn, self.vocab,
+                     self.rope_base, self.rms_eps, GOOSE_DTYPE_BF16 if self.dtype == "bf16" else GOOSE_DTYPE_F32)
+
+
+_lib = None
+
+
+def lib_path():
+    return os.path.join(_PKG, "libgoose.so")
+
+
+def load_library():
+    """Loads libgoose.so built in-tree (python -m paper_2604_02047_amd.build).  Raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} is not built; run `python -m paper_2604_02047_amd.build`")
+    lib = C.CDLL(path)
+    lib.goose_strerror.restype = C.c_char_p
+    lib.goose_strerror.argtypes = [C.c_int]
+    lib.goose_create.argtypes = [C.POINTER(_Desc), C.c_int, C.c_int, C.POINTER(C.c_void_p)]
+    lib.goose_destroy.argtypes = [C.c_void_p]
+    lib.goose_destroy.restype = None
+    lib.goose_check_parent.argtypes = [C.c_void_p, C.c_int]
+    lib.goose_packed_layer_bytes.argtypes = [C.c_void_p]
+    lib.goose_packed_layer_bytes.restype = C.c_size_t
+    lib.goose_packed_lm_head_bytes.argtypes = [C.c_void_p]
+    lib.goose_packed_lm_head_bytes.restype = C.c_size_t
+    lib.goose_pack_layer.argtypes = [C.c_void_p, C.POINTER(_LayerWeights), C.c_void_p, C.c_void_p]
+    lib.goose_pack_lm_head.argtypes = [C.c_void_p] * 5
+    lib.goose_build_mask.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 5
+    lib.goose_embed.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+    lib.goose_verify_layer.argtypes = [C.c_void_p] * 5 + [C.c_int, C.c_void_p, C.c_int] + [C.c_void_p] * 3
+    lib.goose_lm_head_argmax.argtypes = [C.c_void_p] * 3 + [C.c_int] + [C.c_void_p] * 4
+    lib.goose_accept.argtypes = [C.c_void_p] * 5 + [C.c_int] + [C.c_void_p] * 4
+    lib.goose_compact_kv.argtypes = [C.c_void_p] * 3 + [C.c_int] + [C.c_void_p] * 5
+    lib.goose_verify_step.argtypes = [C.c_void_p, C.POINTER(_ModelPtrs), C.POINTER(_StepIO), C.c_int, C.c_int,
+                                      C.c_void_p]
+    lib.goose_device_flags.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
+    for name in EXPORTS:
+        fn = getattr(lib, name)
+        if name not in ("goose_strerror", "goose_destroy", "goose_packed_layer_bytes", "goose_packed_lm_head_bytes"):
+            fn.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _strerror(status):
+    try:
+        return load_library().goose_strerror(int(status)).decode()
+    except Exception:  # pragma: no cover
+        return "?"
+
+
+def _check(status, what):
+    if status != 0:
+        raise GooseError(status, what)
+
+
+def goose_check_parent(parent) -> int:
+    """Host-side validation of a parent array; returns the C status code (0 = ok)."""
+    if parent is None:
+        return load_library().goose_check_parent(None, 0)
+    a = np.ascontiguousarray(np.asarray(parent, dtype=np.int32))
+    return load_library().goose_check_parent(a.ctypes.data_as(C.c_void_p), int(a.shape[0]))
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class GooseContext:
+    """Owns a goose_ctx.  Methods are the C entry points with torch tensors as arguments."""
+
+    def __init__(self, desc: ModelDesc, max_B: int, cap: int):
+        self.lib = load_library()
+        self.desc = desc
+        self.max_B, self.cap = max_B, cap
+        h = C.c_void_p()
+        cd = desc._c()
+        _check(self.lib.goose_create(C.byref(cd), max_B, cap, C.byref(h)), "goose_create")
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self.lib.goose_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- sizes
+    def goose_packed_layer_bytes(self) -> int:
+        return int(self.lib.goose_packed_layer_bytes(self._h))
+
+    def goose_packed_lm_head_bytes(self) -> int:
+        return int(self.lib.goose_packed_lm_head_bytes(self._h))
+
+    # ---- packing
+    def goose_pack_layer(self, raw: dict, packed_layer):
+        w = _LayerWeights(*[raw[n].data_ptr() for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2")])
+        _check(self.lib.goose_pack_layer(self._h, C.byref(w), _ptr(packed_layer), _stream()), "goose_pack_layer")
+
+    def goose_pack_lm_head(self, gf, wlm, packed_head):
+        _check(self.lib.goose_pack_lm_head(self._h, _ptr(gf), _ptr(wlm), _ptr(packed_head), _stream()),
+               "goose_pack_lm_head")
+
+    # ---- the verification path
+    def goose_build_mask(self, parent, B, P, mask, depth, pos, d_P=None):
+        _check(self.lib.goose_build_mask(self._h, _ptr(parent), B, P, _ptr(d_P), _ptr(mask), _ptr(depth), _ptr(pos),
+                                         _stream()), "goose_build_mask")
+
+    def goose_embed(self, embed, tokens, B, x):
+        _check(self.lib.goose_embed(self._h, _ptr(embed), _ptr(tokens), B, _ptr(x), _stream()), "goose_embed")
+
+    def goose_verify_layer(self, packed_layer, x, kcache, vcache, P, B, mask, pos, d_P=None):
+        _check(self.lib.goose_verify_layer(self._h, _ptr(packed_layer), _ptr(x), _ptr(kcache), _ptr(vcache), P,
+                                           _ptr(d_P), B, _ptr(mask), _ptr(pos), _stream()), "goose_verify_layer")
+
+    def goose_lm_head_argmax(self, packed_head, x, B, argmax, logits=None, margin=None):
+        _check(self.lib.goose_lm_head_argmax(self._h, _ptr(packed_head), _ptr(x), B, _ptr(argmax), _ptr(logits),
+                                             _ptr(margin), _stream()), "goose_lm_head_argmax")
+
+    def goose_accept(self, parent, tokens, is_spine, argmax, B, accept_len, path, bonus):
+        _check(self.lib.goose_accept(self._h, _ptr(parent), _ptr(tokens), _ptr(is_spine), _ptr(argmax), B,
+                                     _ptr(accept_len), _ptr(path), _ptr(bonus), _stream()), "goose_accept")
+
+    def goose_compact_kv(self, kcache_all, vcache_all, P, path, accept_len, new_P=None, d_P=None):
+        _check(self.lib.goose_compact_kv(self._h, _ptr(kcache_all), _ptr(vcache_all), P, _ptr(d_P), _ptr(path),
+                                         _ptr(accept_len), _ptr(new_P), _stream()), "goose_compact_kv")
+
+    def goose_verify_step(self, model: dict, io: dict, B, P_max):
+        m = _ModelPtrs(*[model[n].data_ptr() for n in ("embed", "packed_layers", "packed_head", "kcache", "vcache")])
+        names = ("tokens", "parent", "is_spine", "P", "argmax", "accept_len", "path", "bonus", "next_root", "logits",
+                 "margin")
+        s = _StepIO(*[(io[n].data_ptr() if io.get(n) is not None else None) for n in names])
+        _check(self.lib.goose_verify_step(self._h, C.byref(m), C.byref(s), B, P_max, _stream()), "goose_verify_step")
+
+    def goose_device_flags(self) -> int:
+        out = C.c_int32(0)
+        _check(self.lib.goose_device_flags(self._h, _stream(), C.byref(out)), "goose_device_flags")
+        return out.value

@@ -1,0 +1,416 @@
+// C ABI of the tree-verification library: argument checks, workspace, kernel sequencing.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "goose_internal.h"
+
+namespace {
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+inline size_t elem_size(int dtype) { return dtype == GOOSE_DTYPE_BF16 ? 2 : 4; }
+
+int env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  return (v && *v) ? atoi(v) : dflt;
+}
+
+void compute_layouts(goose_ctx* c) {
+  const goose_model_desc& d = c->d;
+  const size_t es = elem_size(d.dtype);
+  const size_t A = 256;
+  size_t off = 0;
+  PackedLayout& p = c->pl;
+  p.g1 = off; off = round_up_sz(off + (size_t)d.hidden * es, A);
+  p.g2 = off; off = round_up_sz(off + (size_t)d.hidden * es, A);
+  if (d.dtype == GOOSE_DTYPE_BF16) {
+    const size_t f32r = (size_t)round_up(d.ffn, 32);
+    p.wqkv = off; off = round_up_sz(off + (size_t)round_up(3 * c->Hq, 32) * c->Kh * 2, A);
+    p.wo = off;   off = round_up_sz(off + (size_t)round_up(d.hidden, 32) * c->Kq * 2, A);
+    p.wgu = off;  off = round_up_sz(off + 2 * f32r * c->Kh * 2, A);
+    p.wd = off;   off = round_up_sz(off + (size_t)round_up(d.hidden, 32) * c->Fpad * 2, A);
+  } else {
+    p.wqkv = off; off = round_up_sz(off + (size_t)3 * c->Hq * d.hidden * 4, A);
+    p.wo = off;   off = round_up_sz(off + (size_t)d.hidden * c->Hq * 4, A);
+    p.wgu = off;  off = round_up_sz(off + (size_t)2 * d.ffn * d.hidden * 4, A);
+    p.wd = off;   off = round_up_sz(off + (size_t)d.hidden * d.ffn * 4, A);
+  }
+  p.total = off;
+  PackedHeadLayout& hl = c->ph;
+  hl.gf = 0;
+  hl.wlm = round_up_sz((size_t)d.hidden * es, A);
+  hl.total = round_up_sz(hl.wlm + (d.dtype == GOOSE_DTYPE_BF16 ? (size_t)c->Vpad * c->Kh * 2
+                                                               : (size_t)d.vocab * d.hidden * 4), A);
+}
+
+int dev_alloc(void** p, size_t bytes) {
+  if (hipMalloc(p, bytes) != hipSuccess) return GOOSE_ERR_HIP;
+  if (hipMemset(*p, 0, bytes) != hipSuccess) return GOOSE_ERR_HIP;
+  return GOOSE_OK;
+}
+
+int check_tree_args(const goose_ctx* ctx, int B, int P) {
+  if (!ctx) return GOOSE_ERR_ARG;
+  if (B < 1 || P < 0) return GOOSE_ERR_ARG;
+  if (B > ctx->max_B || B > GOOSE_MAX_B) return GOOSE_ERR_CAPACITY;
+  if ((long)P + B > ctx->cap) return GOOSE_ERR_CAPACITY;
+  return GOOSE_OK;
+}
+
+// Resolves "P from memory if given, else the host value" to a device pointer.
+int resolve_P(goose_ctx* ctx, int P, const int32_t* d_P, hipStream_t st, const int32_t** out) {
+  if (d_P) { *out = d_P; return GOOSE_OK; }
+  int rc = launch_set_int(ctx->s_P, P, st);
+  *out = ctx->s_P;
+  return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* goose_strerror(int status) {
+  switch (status) {
+    case GOOSE_OK: return "ok";
+    case GOOSE_ERR_ARG: return "invalid argument";
+    case GOOSE_ERR_SHAPE: return "unsupported model shape";
+    case GOOSE_ERR_CAPACITY: return "tree or cache capacity exceeded";
+    case GOOSE_ERR_NOT_TOPOLOGICAL: return "parent array is not a tree in topological order";
+    case GOOSE_ERR_HIP: return "HIP runtime error";
+    case GOOSE_ERR_UNSUPPORTED: return "unsupported";
+  }
+  return "unknown status";
+}
+
+int goose_check_parent(const int32_t* h_parent, int B) {
+  if (!h_parent || B < 1 || B > GOOSE_MAX_B) return GOOSE_ERR_ARG;
+  if (h_parent[0] != -1) return GOOSE_ERR_NOT_TOPOLOGICAL;
+  for (int i = 1; i < B; ++i)
+    if (h_parent[i] < 0 || h_parent[i] >= i) return GOOSE_ERR_NOT_TOPOLOGICAL;
+  return GOOSE_OK;
+}
+
+int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** out) {
+  if (!desc || !out) return GOOSE_ERR_ARG;
+  *out = nullptr;
+  if (max_B < 1 || max_B > GOOSE_MAX_B || cap < max_B) return GOOSE_ERR_ARG;
+  const goose_model_desc& d = *desc;
+  if (d.n_layers < 1 || d.hidden < 1 || d.n_heads < 1 || d.head_dim < 2 || d.ffn < 1 || d.vocab < 1)
+    return GOOSE_ERR_ARG;
+  if (d.dtype != GOOSE_DTYPE_BF16 && d.dtype != GOOSE_DTYPE_F32) return GOOSE_ERR_ARG;
+  if (!(d.rope_base > 1.0f) || !(d.rms_eps >= 0.0f)) return GOOSE_ERR_ARG;
+  if (d.head_dim % 8 != 0 || d.head_dim > 256) return GOOSE_ERR_SHAPE;
+  if (d.dtype == GOOSE_DTYPE_BF16) {
+    // MFMA kernels: 16-byte vector access to rows, two head sizes
+    if (d.head_dim != 64 && d.head_dim != 128) return GOOSE_ERR_SHAPE;
+    if (d.hidden % 8 != 0 || d.ffn % 8 != 0) return GOOSE_ERR_SHAPE;
+  }
+  goose_ctx* c = new (std::nothrow) goose_ctx();
+  if (!c) return GOOSE_ERR_ARG;
+  memset(c, 0, sizeof(*c));
+  c->d = d;
+  c->max_B = max_B;
+  c->Bpad = round_up(max_B, 32);
+  c->cap = cap;
+  c->Hq = d.n_heads * d.head_dim;
+  c->Kh = round_up(d.hidden, 64);
+  c->Kq = round_up(c->Hq, 64);
+  c->Fpad = round_up(d.ffn, 64);
+  c->Vpad = round_up(d.vocab, 32);
+  c->max_splits = 32;
+  c->max_ksplit = 16;
+  compute_layouts(c);
+
+  const size_t es = elem_size(d.dtype);
+  size_t widest = (size_t)round_up(3 * c->Hq, 32);
+  if ((size_t)2 * c->Fpad > widest) widest = (size_t)2 * c->Fpad;
+  if ((size_t)c->Kh > widest) widest = c->Kh;
+  c->part_ld = widest;
+  int rc = GOOSE_OK;
+  auto A = [&](void** p, size_t bytes) { if (rc == GOOSE_OK) rc = dev_alloc(p, bytes); };
+  A(&c->xn, (size_t)c->Bpad * c->Kh * es);
+  A((void**)&c->part, (size_t)c->max_ksplit * c->Bpad * c->part_ld * sizeof(float));
+  A(&c->q, (size_t)c->Bpad * c->Kq * es);
+  A(&c->o, (size_t)c->Bpad * c->Kq * es);
+  A(&c->h, (size_t)c->Bpad * c->Fpad * es);
+  A((void**)&c->att_o, (size_t)d.n_heads * c->max_splits * c->Bpad * d.head_dim * sizeof(float));
+  A((void**)&c->att_ml, (size_t)d.n_heads * c->max_splits * c->Bpad * 2 * sizeof(float));
+  A((void**)&c->logits, (size_t)c->Bpad * c->Vpad * sizeof(float));
+  A((void**)&c->inv_freq, (size_t)(d.head_dim / 2) * sizeof(double));
+  A((void**)&c->s_mask, 128 * 2 * sizeof(uint64_t));
+  A((void**)&c->s_depth, 128 * sizeof(int32_t));
+  A((void**)&c->s_pos, 128 * sizeof(int32_t));
+  A((void**)&c->s_x, (size_t)c->Bpad * d.hidden * sizeof(float));
+  A((void**)&c->flags, sizeof(int32_t));
+  A((void**)&c->s_P, sizeof(int32_t));
+  if (rc == GOOSE_OK) {
+    std::vector<double> f(d.head_dim / 2);
+    for (int j = 0; j < d.head_dim / 2; ++j) f[j] = pow((double)d.rope_base, -2.0 * j / d.head_dim);
+    if (hipMemcpy(c->inv_freq, f.data(), f.size() * sizeof(double), hipMemcpyHostToDevice) != hipSuccess)
+      rc = GOOSE_ERR_HIP;
+  }
+  // the zero fills above ran on the null stream; callers use their own streams
+  if (rc == GOOSE_OK && hipDeviceSynchronize() != hipSuccess) rc = GOOSE_ERR_HIP;
+  if (rc != GOOSE_OK) { goose_destroy(c); return rc; }
+  *out = c;
+  return GOOSE_OK;
+}
+
+void goose_destroy(goose_ctx* c) {
+  if (!c) return;
+  void* ptrs[] = {c->xn, c->part, c->q, c->o, c->h, c->att_o, c->att_ml, c->logits, c->inv_freq,
+                  c->s_mask, c->s_depth, c->s_pos, c->s_x, c->flags, c->s_P};
+  for (void* p : ptrs)
+    if (p) (void)hipFree(p);
+  delete c;
+}
+
+size_t goose_packed_layer_bytes(const goose_ctx* ctx) { return ctx ? ctx->pl.total : 0; }
+size_t goose_packed_lm_head_bytes(const goose_ctx* ctx) { return ctx ? ctx->ph.total : 0; }
+
+int goose_pack_layer(goose_ctx* c, const goose_layer_weights* w, void* d_packed, void* stream) {
+  if (!c || !w || !d_packed) return GOOSE_ERR_ARG;
+  if (!w->wq || !w->wk || !w->wv || !w->wo || !w->wg || !w->wu || !w->wd || !w->g1 || !w->g2) return GOOSE_ERR_ARG;
+  hipStream_t st = as_stream(stream);
+  const goose_model_desc& d = c->d;
+  char* base = (char*)d_packed;
+  const size_t es = elem_size(d.dtype);
+  const hipMemcpyKind D2D = hipMemcpyDeviceToDevice;
+  GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.g1, w->g1, d.hidden * es, D2D, st));
+  GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.g2, w->g2, d.hidden * es, D2D, st));
+  if (d.dtype == GOOSE_DTYPE_BF16) {
+    int rc = launch_pack_bf16(PACK_QKV, w->wq, w->wk, w->wv, c->Hq, d.hidden, round_up(3 * c->Hq, 32), c->Kh,
+                              base + c->pl.wqkv, st);
+    if (rc) return rc;
+    rc = launch_pack_bf16(PACK_PLAIN, w->wo, nullptr, nullptr, d.hidden, c->Hq, round_up(d.hidden, 32), c->Kq,
+                          base + c->pl.wo, st);
+    if (rc) return rc;
+    rc = launch_pack_bf16(PACK_GATE_UP, w->wg, w->wu, nullptr, d.ffn, d.hidden, 2 * round_up(d.ffn, 32), c->Kh,
+                          base + c->pl.wgu, st);
+    if (rc) return rc;
+    return launch_pack_bf16(PACK_PLAIN, w->wd, nullptr, nullptr, d.hidden, d.ffn, round_up(d.hidden, 32), c->Fpad,
+                            base + c->pl.wd, st);
+  }
+  const size_t qb = (size_t)c->Hq * d.hidden * 4, fb = (size_t)d.ffn * d.hidden * 4;
+  GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.wqkv, w->wq, qb, D2D, st));
+  GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.wqkv + qb, w->wk, qb, D2D, st));
+  GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.wqkv + 2 * qb, w->wv, qb, D2D, st));
+  GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.wo, w->wo, qb, D2D, st));
+  GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.wgu, w->wg, fb, D2D, st));
+  GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.wgu + fb, w->wu, fb, D2D, st));
+  GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.wd, w->wd, fb, D2D, st));
+  return GOOSE_OK;
+}
+
+int goose_pack_lm_head(goose_ctx* c, const void* d_gf, const void* d_wlm, void* d_packed, void* stream) {
+  if (!c || !d_gf || !d_wlm || !d_packed) return GOOSE_ERR_ARG;
+  hipStream_t st = as_stream(stream);
+  const goose_model_desc& d = c->d;
+  char* base = (char*)d_packed;
+  GOOSE_HIP_TRY(hipMemcpyAsync(base + c->ph.gf, d_gf, d.hidden * elem_size(d.dtype), hipMemcpyDeviceToDevice, st));
+  if (d.dtype == GOOSE_DTYPE_BF16)
+    return launch_pack_bf16(PACK_PLAIN, d_wlm, nullptr, nullptr, d.vocab, d.hidden, c->Vpad, c->Kh,
+                            base + c->ph.wlm, st);
+  GOOSE_HIP_TRY(hipMemcpyAsync(base + c->ph.wlm, d_wlm, (size_t)d.vocab * d.hidden * 4, hipMemcpyDeviceToDevice, st));
+  return GOOSE_OK;
+}
+
+int goose_build_mask(goose_ctx* c, const int32_t* d_parent, int B, int P, const int32_t* d_P, uint64_t* d_mask,
+                     int32_t* d_depth, int32_t* d_pos, void* stream) {
+  int rc = check_tree_args(c, B, P);
+  if (rc) return rc;
+  if (!d_parent || !d_mask || !d_depth || !d_pos) return GOOSE_ERR_ARG;
+  hipStream_t st = as_stream(stream);
+  const int32_t* dP;
+  rc = resolve_P(c, P, d_P, st, &dP);
+  if (rc) return rc;
+  return launch_build_mask(d_parent, B, dP, d_mask, d_depth, d_pos, c->flags, st);
+}
+
+int goose_embed(goose_ctx* c, const void* d_embed, const int32_t* d_tokens, int B, float* d_x, void* stream) {
+  if (!c || !d_embed || !d_tokens || !d_x) return GOOSE_ERR_ARG;
+  if (B < 1) return GOOSE_ERR_ARG;
+  if (B > c->max_B) return GOOSE_ERR_CAPACITY;
+  return launch_embed(c->d.dtype, d_embed, d_tokens, B, c->d.hidden, c->d.vocab, d_x, as_stream(stream));
+}
+
+int goose_verify_layer(goose_ctx* c, const void* d_packed_layer, float* d_x, void* d_kcache, void* d_vcache, int P,
+                       const int32_t* d_P, int B, const uint64_t* d_mask, const int32_t* d_pos, void* stream) {
+  int rc = check_tree_args(c, B, P);
+  if (rc) return rc;
+  if (!d_packed_layer || !d_x || !d_kcache || !d_vcache || !d_mask || !d_pos) return GOOSE_ERR_ARG;
+  hipStream_t st = as_stream(stream);
+  const int32_t* dP;
+  rc = resolve_P(c, P, d_P, st, &dP);
+  if (rc) return rc;
+  const goose_model_desc& d = c->d;
+  const char* w = (const char*)d_packed_layer;
+  const size_t pstride = (size_t)c->Bpad * c->part_ld;
+  const int H = d.hidden, Hq = c->Hq;
+
+  // x_hat = RMSNorm(x) * g1
+  rc = launch_resid_norm(d.dtype, d_x, H, nullptr, 0, 0, 0, w + c->pl.g1, d.rms_eps, c->xn, c->Kh, B, st);
+  if (rc) return rc;
+
+  if (d.dtype == GOOSE_DTYPE_BF16) {
+    const int Nqkv = round_up(3 * Hq, 32), Nh = round_up(H, 32), Ngu = 2 * round_up(d.ffn, 32);
+    static const int ks_qkv_env = env_int("GOOSE_KSPLIT_QKV", 0), ks_o_env = env_int("GOOSE_KSPLIT_O", 0),
+                     ks_d_env = env_int("GOOSE_KSPLIT_DOWN", 0), splits_env = env_int("GOOSE_ATTN_SPLITS", 0);
+    int ks = ks_qkv_env > 0 ? ks_qkv_env : pick_ksplit(Nqkv, c->Kh, c->max_ksplit);
+    if (ks > c->max_ksplit) ks = c->max_ksplit;
+    rc = launch_gemm_bf16(EPI_PARTIAL, c->xn, c->Kh, w + c->pl.wqkv, Nqkv, c->Kh, B, ks, c->part, c->part_ld, pstride,
+                          st);
+    if (rc) return rc;
+    rc = launch_rope_kv(d.dtype, c->part, ks, pstride, c->part_ld, B, d.n_heads, d.head_dim, d_pos, c->inv_freq, dP,
+                        c->cap, c->q, c->Kq, d_kcache, d_vcache, st);
+    if (rc) return rc;
+    int splits = splits_env > 0 ? splits_env : pick_attn_splits(d.n_heads, P + B, c->max_splits);
+    if (splits > c->max_splits) splits = c->max_splits;
+    rc = launch_attn_bf16(c->q, c->Kq, d_kcache, d_vcache, d.n_heads, d.head_dim, c->cap, dP, B, d_mask, splits,
+                          c->att_o, c->att_ml, c->Bpad, c->o, c->Kq, st);
+    if (rc) return rc;
+    ks = ks_o_env > 0 ? ks_o_env : pick_ksplit(Nh, c->Kq, c->max_ksplit);
+    if (ks > c->max_ksplit) ks = c->max_ksplit;
+    rc = launch_gemm_bf16(EPI_PARTIAL, c->o, c->Kq, w + c->pl.wo, Nh, c->Kq, B, ks, c->part, c->part_ld, pstride, st);
+    if (rc) return rc;
+    // x += attention projection; x_hat = RMSNorm(x) * g2
+    rc = launch_resid_norm(d.dtype, d_x, H, c->part, ks, pstride, c->part_ld, w + c->pl.g2, d.rms_eps, c->xn, c->Kh,
+                           B, st);
+    if (rc) return rc;
+    rc = launch_gemm_bf16(EPI_SWIGLU, c->xn, c->Kh, w + c->pl.wgu, Ngu, c->Kh, B, 1, c->h, c->Fpad, 0, st);
+    if (rc) return rc;
+    ks = ks_d_env > 0 ? ks_d_env : pick_ksplit(Nh, c->Fpad, c->max_ksplit);
+    if (ks > c->max_ksplit) ks = c->max_ksplit;
+    rc = launch_gemm_bf16(EPI_PARTIAL, c->h, c->Fpad, w + c->pl.wd, Nh, c->Fpad, B, ks, c->part, c->part_ld, pstride,
+                          st);
+    if (rc) return rc;
+    // x += MLP output
+    return launch_resid_norm(d.dtype, d_x, H, c->part, ks, pstride, c->part_ld, nullptr, d.rms_eps, nullptr, 0, B, st);
+  }
+
+  // fp32 storage: plain kernels
+  const float* xn = (const float*)c->xn;
+  rc = launch_gemm_f32(xn, c->Kh, (const float*)(w + c->pl.wqkv), 3 * Hq, H, B, c->part, c->part_ld, st);
+  if (rc) return rc;
+  rc = launch_rope_kv(d.dtype, c->part, 1, pstride, c->part_ld, B, d.n_heads, d.head_dim, d_pos, c->inv_freq, dP,
+                      c->cap, c->q, c->Kq, d_kcache, d_vcache, st);
+  if (rc) return rc;
+  rc = launch_attn_f32((const float*)c->q, c->Kq, (const float*)d_kcache, (const float*)d_vcache, d.n_heads,
+                       d.head_dim, c->cap, dP, B, d_mask, (float*)c->o, c->Kq, P, st);
+  if (rc) return rc;
+  rc = launch_gemm_f32((const float*)c->o, c->Kq, (const float*)(w + c->pl.wo), H, Hq, B, c->part, c->part_ld, st);
+  if (rc) return rc;
+  rc = launch_resid_norm(d.dtype, d_x, H, c->part, 1, pstride, c->part_ld, w + c->pl.g2, d.rms_eps, c->xn, c->Kh, B,
+                         st);
+  if (rc) return rc;
+  rc = launch_gemm_f32(xn, c->Kh, (const float*)(w + c->pl.wgu), 2 * d.ffn, H, B, c->part, c->part_ld, st);
+  if (rc) return rc;
+  rc = launch_swiglu_f32(c->part, c->part_ld, d.ffn, (float*)c->h, c->Fpad, B, st);
+  if (rc) return rc;
+  rc = launch_gemm_f32((const float*)c->h, c->Fpad, (const float*)(w + c->pl.wd), H, d.ffn, B, c->part, c->part_ld,
+                       st);
+  if (rc) return rc;
+  return launch_resid_norm(d.dtype, d_x, H, c->part, 1, pstride, c->part_ld, nullptr, d.rms_eps, nullptr, 0, B, st);
+}
+
+int goose_lm_head_argmax(goose_ctx* c, const void* d_packed_head, const float* d_x, int B, int32_t* d_argmax,
+                         float* d_logits_or_null, float* d_margin_or_null, void* stream) {
+  if (!c || !d_packed_head || !d_x || !d_argmax) return GOOSE_ERR_ARG;
+  if (B < 1) return GOOSE_ERR_ARG;
+  if (B > c->max_B) return GOOSE_ERR_CAPACITY;
+  hipStream_t st = as_stream(stream);
+  const goose_model_desc& d = c->d;
+  const char* w = (const char*)d_packed_head;
+  // the residual stream is left untouched: normalise into the operand buffer only
+  int rc = launch_resid_norm(d.dtype, const_cast<float*>(d_x), d.hidden, nullptr, 0, 0, 0, w + c->ph.gf, d.rms_eps,
+                             c->xn, c->Kh, B, st);
+  if (rc) return rc;
+  float* logits = d_logits_or_null ? d_logits_or_null : c->logits;
+  const size_t ld = d_logits_or_null ? (size_t)d.vocab : (size_t)c->Vpad;
+  if (d.dtype == GOOSE_DTYPE_BF16) {
+    if (d_logits_or_null && (d.vocab % 32) != 0) {
+      // tiles are 32 columns wide: write into the padded workspace, then copy rows out
+      rc = launch_gemm_bf16(EPI_PARTIAL, c->xn, c->Kh, w + c->ph.wlm, c->Vpad, c->Kh, B, 1, c->logits, c->Vpad, 0, st);
+      if (rc) return rc;
+      GOOSE_HIP_TRY(hipMemcpy2DAsync(d_logits_or_null, (size_t)d.vocab * 4, c->logits, (size_t)c->Vpad * 4,
+                                     (size_t)d.vocab * 4, B, hipMemcpyDeviceToDevice, st));
+      logits = c->logits;
+      return launch_argmax(logits, c->Vpad, d.vocab, B, d_argmax, d_margin_or_null, st);
+    }
+    rc = launch_gemm_bf16(EPI_PARTIAL, c->xn, c->Kh, w + c->ph.wlm, c->Vpad, c->Kh, B, 1, logits, ld, 0, st);
+  } else {
+    rc = launch_gemm_f32((const float*)c->xn, c->Kh, (const float*)(w + c->ph.wlm), d.vocab, d.hidden, B, logits, ld,
+                         st);
+  }
+  if (rc) return rc;
+  return launch_argmax(logits, ld, d.vocab, B, d_argmax, d_margin_or_null, st);
+}
+
+int goose_accept(goose_ctx* c, const int32_t* d_parent, const int32_t* d_tokens, const uint8_t* d_is_spine_or_null,
+                 const int32_t* d_argmax, int B, int32_t* d_accept_len, int32_t* d_path, int32_t* d_bonus,
+                 void* stream) {
+  if (!c || !d_parent || !d_tokens || !d_argmax || !d_accept_len || !d_path || !d_bonus) return GOOSE_ERR_ARG;
+  if (B < 1) return GOOSE_ERR_ARG;
+  if (B > GOOSE_MAX_B) return GOOSE_ERR_CAPACITY;
+  return launch_accept(d_parent, d_tokens, d_is_spine_or_null, d_argmax, B, d_accept_len, d_path, d_bonus, nullptr,
+                       as_stream(stream));
+}
+
+int goose_compact_kv(goose_ctx* c, void* d_kcache_all, void* d_vcache_all, int P, const int32_t* d_P,
+                     const int32_t* d_path, const int32_t* d_accept_len, int32_t* d_new_P_or_null, void* stream) {
+  if (!c || !d_kcache_all || !d_vcache_all || !d_path || !d_accept_len) return GOOSE_ERR_ARG;
+  if (P < 0 || P >= c->cap) return GOOSE_ERR_CAPACITY;
+  hipStream_t st = as_stream(stream);
+  const int32_t* dP;
+  int rc = resolve_P(c, P, d_P, st, &dP);
+  if (rc) return rc;
+  const goose_model_desc& d = c->d;
+  return launch_compact((int)elem_size(d.dtype), d_kcache_all, d_vcache_all, d.n_layers, d.n_heads, c->cap,
+                        d.head_dim, dP, d_path, d_accept_len, d_new_P_or_null, st);
+}
+
+int goose_verify_step(goose_ctx* c, const goose_model_ptrs* m, const goose_step_io* io, int B, int P_max,
+                      void* stream) {
+  if (!c || !m || !io) return GOOSE_ERR_ARG;
+  int rc = check_tree_args(c, B, P_max);
+  if (rc) return rc;
+  if (!m->d_embed || !m->d_packed_layers || !m->d_packed_head || !m->d_kcache_all || !m->d_vcache_all)
+    return GOOSE_ERR_ARG;
+  if (!io->d_tokens || !io->d_parent || !io->d_P || !io->d_argmax || !io->d_accept_len || !io->d_path || !io->d_bonus)
+    return GOOSE_ERR_ARG;
+  hipStream_t st = as_stream(stream);
+  const goose_model_desc& d = c->d;
+  rc = launch_build_mask(io->d_parent, B, io->d_P, c->s_mask, c->s_depth, c->s_pos, c->flags, st);
+  if (rc) return rc;
+  rc = launch_embed(d.dtype, m->d_embed, io->d_tokens, B, d.hidden, d.vocab, c->s_x, st);
+  if (rc) return rc;
+  const size_t layer_cache = (size_t)d.n_heads * c->cap * d.head_dim * elem_size(d.dtype);
+  for (int l = 0; l < d.n_layers; ++l) {
+    rc = goose_verify_layer(c, (const char*)m->d_packed_layers + (size_t)l * c->pl.total, c->s_x,
+                            (char*)m->d_kcache_all + l * layer_cache, (char*)m->d_vcache_all + l * layer_cache, P_max,
+                            io->d_P, B, c->s_mask, c->s_pos, stream);
+    if (rc) return rc;
+  }
+  rc = goose_lm_head_argmax(c, m->d_packed_head, c->s_x, B, io->d_argmax, io->d_logits_or_null, io->d_margin_or_null,
+                            stream);
+  if (rc) return rc;
+  rc = launch_accept(io->d_parent, io->d_tokens, io->d_is_spine, io->d_argmax, B, io->d_accept_len, io->d_path,
+                     io->d_bonus, io->d_next_root_or_null, st);
+  if (rc) return rc;
+  return launch_compact((int)elem_size(d.dtype), m->d_kcache_all, m->d_vcache_all, d.n_layers, d.n_heads, c->cap,
+                        d.head_dim, io->d_P, io->d_path, io->d_accept_len, io->d_P, st);
+}
+
+int goose_device_flags(goose_ctx* c, void* stream, int32_t* h_flags_out) {
+  if (!c || !h_flags_out) return GOOSE_ERR_ARG;
+  hipStream_t st = as_stream(stream);
+  GOOSE_HIP_TRY(hipMemcpyAsync(h_flags_out, c->flags, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+  GOOSE_HIP_TRY(hipStreamSynchronize(st));
+  GOOSE_HIP_TRY(hipMemsetAsync(c->flags, 0, sizeof(int32_t), st));
+  return GOOSE_OK;
+}
+
+}  // extern "C"

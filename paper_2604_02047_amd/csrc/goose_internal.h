@@ -1,0 +1,103 @@
+// Internal declarations shared by the library's translation units (host side).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "goose.h"
+
+typedef __bf16 bf16_t;
+
+#define GOOSE_HIP_TRY(expr)                    \
+  do {                                         \
+    hipError_t e_ = (expr);                    \
+    if (e_ != hipSuccess) return GOOSE_ERR_HIP; \
+  } while (0)
+
+static inline int goose_launch_status() { return hipGetLastError() == hipSuccess ? GOOSE_OK : GOOSE_ERR_HIP; }
+
+static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+static inline size_t round_up_sz(size_t x, size_t m) { return (x + m - 1) / m * m; }
+
+// Byte offsets of the pieces of a packed layer / packed head blob.
+struct PackedLayout {
+  size_t g1, g2, wqkv, wo, wgu, wd, total;
+};
+struct PackedHeadLayout {
+  size_t gf, wlm, total;
+};
+
+struct goose_ctx {
+  goose_model_desc d;
+  int max_B;   // as requested
+  int Bpad;    // rounded up to 32: row count of every activation buffer
+  int cap;     // cache slots per head
+  int Hq;      // n_heads * head_dim
+  int Fpad;    // ffn rounded up to 64 (bf16) -- the K extent of the down projection
+  int Kh;      // hidden rounded up to 64
+  int Kq;      // Hq rounded up to 64
+  int Vpad;    // vocab rounded up to 32
+  int max_splits;  // attention key splits the workspace is sized for
+  int max_ksplit;  // split-K factor the partial buffer is sized for
+  PackedLayout pl;
+  PackedHeadLayout ph;
+
+  // device workspace
+  void* xn;        // T [Bpad][Kh]   normalised activations (GEMM operand)
+  float* part;     // f32 [max_ksplit][Bpad][part_ld]   GEMM outputs / split-K partials
+  size_t part_ld;  // row length of `part`
+  void* q;         // T [Bpad][Kq]   rotated queries
+  void* o;         // T [Bpad][Kq]   attention output (GEMM operand)
+  void* h;         // T [Bpad][Fpad] SwiGLU output (GEMM operand)
+  float* att_o;    // f32 [n_heads][max_splits][Bpad][head_dim]
+  float* att_ml;   // f32 [n_heads][max_splits][Bpad][2]
+  float* logits;   // f32 [Bpad][Vpad]  (when the caller does not ask for logits)
+  double* inv_freq;  // f64 [head_dim/2]
+  // scratch for goose_verify_step
+  uint64_t* s_mask;  // [128][2]
+  int32_t* s_depth;  // [128]
+  int32_t* s_pos;    // [128]
+  float* s_x;        // [Bpad][hidden]
+  int32_t* flags;    // [1]
+  int32_t* s_P;      // [1] holds a host-supplied P for kernels that read it from memory
+};
+
+// ---- small kernels (kernels_small.hip)
+int launch_set_int(int32_t* dst, int v, hipStream_t st);
+int launch_build_mask(const int32_t* parent, int B, const int32_t* dP, uint64_t* mask, int32_t* depth, int32_t* pos,
+                      int32_t* flags, hipStream_t st);
+int launch_embed(int dtype, const void* E, const int32_t* tokens, int B, int H, int V, float* x, hipStream_t st);
+// x[m][:] += sum_s part[s][m][:H] (S may be 0); xn[m][:] = T(rmsnorm(x[m]) * g) if xn != NULL
+int launch_resid_norm(int dtype, float* x, int H, const float* part, int S, size_t part_stride, size_t part_ld,
+                      const void* g, float eps, void* xn, int ldxn, int B, hipStream_t st);
+// qkv = sum_s part[s][m][0:3Hq]; rotary on q,k; q -> qout, k/v -> cache slots P+m
+int launch_rope_kv(int dtype, const float* part, int S, size_t part_stride, size_t part_ld, int B, int n_heads,
+                   int head_dim, const int32_t* pos, const double* inv_freq, const int32_t* dP, int cap, void* qout,
+                   int ldq, void* kcache, void* vcache, hipStream_t st);
+int launch_swiglu_f32(const float* gu, size_t ld, int F, float* h, int ldh, int B, hipStream_t st);
+int launch_argmax(const float* logits, size_t ld, int V, int B, int32_t* argmax, float* margin, hipStream_t st);
+int launch_accept(const int32_t* parent, const int32_t* tokens, const uint8_t* is_spine, const int32_t* argmax, int B,
+                  int32_t* accept_len, int32_t* path, int32_t* bonus, int32_t* next_root, hipStream_t st);
+int launch_compact(int elem_bytes, void* kall, void* vall, int n_layers, int n_heads, int cap, int head_dim,
+                   const int32_t* dP, const int32_t* path, const int32_t* accept_len, int32_t* new_P, hipStream_t st);
+
+// ---- fp32 path (f32_path.hip)
+// out[m][n] = sum_k A[m][k] * W[n][k]
+int launch_gemm_f32(const float* A, int lda, const float* W, int N, int K, int M, float* out, size_t ldo,
+                    hipStream_t st);
+int launch_attn_f32(const float* q, int ldq, const float* kc, const float* vc, int n_heads, int head_dim, int cap,
+                    const int32_t* dP, int B, const uint64_t* mask, float* o, int ldo, int P_max, hipStream_t st);
+
+// ---- bf16 path (gemm_bf16.hip, attn_bf16.hip)
+enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
+// Re-tiles raw [rows][K] bf16 matrices into MFMA-operand order; Npad x Kpad zero padded.
+int launch_pack_bf16(int mode, const void* s0, const void* s1, const void* s2, int rows_each, int K, int Npad,
+                     int Kpad, void* dst, hipStream_t st);
+enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
+// out partials f32 [ksplit][Bpad][ldo] (EPI_PARTIAL) or bf16 h [Bpad][ldo] (EPI_SWIGLU, ksplit must be 1)
+int launch_gemm_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit,
+                     void* out, size_t ldo, size_t out_split_stride, hipStream_t st);
+int pick_ksplit(int Npad, int Kpad, int max_ksplit);
+int launch_attn_bf16(const void* q, int ldq, const void* kc, const void* vc, int n_heads, int head_dim, int cap,
+                     const int32_t* dP, int B, const uint64_t* mask, int splits, float* att_o, float* att_ml,
+                     int Bpad, void* o, int ldo, hipStream_t st);
+int pick_attn_splits(int n_heads, int keys_max, int max_splits);

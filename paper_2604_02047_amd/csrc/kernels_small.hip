@@ -1,0 +1,328 @@
+// Small kernels of the verification step: ancestor mask, embedding gather, residual +
+// RMSNorm, rotary embedding + KV-tail write, argmax, greedy walk, KV compaction.
+#include <limits.h>
+
+#include "goose_internal.h"
+
+namespace {
+
+template <typename T>
+__device__ inline float to_f32(T v) { return (float)v; }
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ void k_set_int(int32_t* dst, int v) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *dst = v;
+}
+
+// Ancestor-or-self bit rows, depth and position of every node (Sec. 4, tree attention mask).
+// One thread per node climbs its own root path; parent[v] < v makes every climb finite.
+__global__ __launch_bounds__(128) void k_build_mask(const int32_t* __restrict__ parent, int B,
+                                                    const int32_t* __restrict__ dP, uint64_t* __restrict__ mask,
+                                                    int32_t* __restrict__ depth, int32_t* __restrict__ pos,
+                                                    int32_t* __restrict__ flags) {
+  const int i = threadIdx.x;
+  if (i >= B) return;
+  const int W = (B + 63) >> 6;
+  uint64_t w0 = 0, w1 = 0;
+  int dep = 0;
+  bool bad = (i == 0 && parent[0] != -1);
+  int v = i;
+  for (int it = 0; it < B; ++it) {
+    if (v < 64) w0 |= 1ull << v; else w1 |= 1ull << (v - 64);
+    if (v == 0) break;
+    int p = parent[v];
+    if (p < 0 || p >= v) { bad = true; p = 0; }  // never index outside the tree
+    v = p;
+    ++dep;
+  }
+  mask[(size_t)i * W] = w0;
+  if (W > 1) mask[(size_t)i * W + 1] = w1;
+  depth[i] = dep;
+  pos[i] = *dP + dep;
+  if (bad) atomicOr(flags, 1);
+}
+
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_embed(const T* __restrict__ E, const int32_t* __restrict__ tokens, int H,
+                                               int V, float* __restrict__ x) {
+  const int m = blockIdx.x;
+  int t = tokens[m];
+  t = t < 0 ? 0 : (t >= V ? V - 1 : t);
+  const T* row = E + (size_t)t * H;
+  for (int c = threadIdx.x; c < H; c += 256) x[(size_t)m * H + c] = to_f32(row[c]);
+}
+
+// ------------------------------------------------------------------------------------------
+// x[m] += sum of S partial GEMM outputs; xn[m] = T(x[m] * rsqrt(mean(x[m]^2) + eps) * g).
+template <typename T>
+__global__ __launch_bounds__(256) void k_resid_norm(float* __restrict__ x, int H, const float* __restrict__ part,
+                                                    int S, size_t part_stride, size_t part_ld,
+                                                    const T* __restrict__ g, float eps, T* __restrict__ xn, int ldxn) {
+  const int m = blockIdx.x;
+  float* xr = x + (size_t)m * H;
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < H; c += 256) {
+    float v = xr[c];
+    for (int s = 0; s < S; ++s) v += part[s * part_stride + (size_t)m * part_ld + c];
+    if (S > 0) xr[c] = v;
+    ss += v * v;
+  }
+  __shared__ float red[4];
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  if (xn == nullptr) return;
+  const float tot = red[0] + red[1] + red[2] + red[3];
+  const float rstd = 1.0f / sqrtf(tot / (float)H + eps);
+  for (int c = threadIdx.x; c < H; c += 256) xn[(size_t)m * ldxn + c] = (T)((xr[c] * rstd) * to_f32(g[c]));
+}
+
+// ------------------------------------------------------------------------------------------
+// Sum the split-K partials of the fused q|k|v projection, rotate q and k by the node's
+// position (half-split pairing (j, j+d/2), angle pos * base^(-2j/d)) and store q for the
+// attention kernel and k, v into cache slot P + m.
+template <typename T>
+__global__ void k_rope_kv(const float* __restrict__ part, int S, size_t part_stride, size_t part_ld, int n_heads,
+                          int head_dim, const int32_t* __restrict__ pos, const double* __restrict__ inv_freq,
+                          const int32_t* __restrict__ dP, int cap, T* __restrict__ qout, int ldq,
+                          T* __restrict__ kcache, T* __restrict__ vcache) {
+  const int m = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
+  const int half = head_dim >> 1;
+  const int Hq = n_heads * head_dim;
+  const int slot = *dP + m;
+  if (slot >= cap) return;
+  float v6[6] = {0, 0, 0, 0, 0, 0};
+  for (int s = 0; s < S; ++s) {
+    const float* r = part + s * part_stride + (size_t)m * part_ld + h * head_dim + j;
+    v6[0] += r[0];
+    v6[1] += r[half];
+    v6[2] += r[Hq];
+    v6[3] += r[Hq + half];
+    v6[4] += r[2 * Hq];
+    v6[5] += r[2 * Hq + half];
+  }
+  // reduce the angle in double, then evaluate in float: |error| ~ 1e-7 rad at any position
+  double ang = (double)pos[m] * inv_freq[j];
+  const double two_pi = 6.283185307179586476925286766559;
+  ang -= two_pi * rint(ang / two_pi);
+  float sn, cs;
+  sincosf((float)ang, &sn, &cs);
+  const float q1 = v6[0] * cs - v6[1] * sn, q2 = v6[1] * cs + v6[0] * sn;
+  const float k1 = v6[2] * cs - v6[3] * sn, k2 = v6[3] * cs + v6[2] * sn;
+  T* qo = qout + (size_t)m * ldq + h * head_dim + j;
+  qo[0] = (T)q1;
+  qo[half] = (T)q2;
+  const size_t row = ((size_t)h * cap + slot) * head_dim + j;
+  kcache[row] = (T)k1;
+  kcache[row + half] = (T)k2;
+  vcache[row] = (T)v6[4];
+  vcache[row + half] = (T)v6[5];
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_swiglu_f32(const float* __restrict__ gu, size_t ld, int F,
+                                                    float* __restrict__ h, int ldh) {
+  const int m = blockIdx.y;
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= F) return;
+  const float g = gu[(size_t)m * ld + c], u = gu[(size_t)m * ld + F + c];
+  h[(size_t)m * ldh + c] = g / (1.0f + expf(-g)) * u;
+}
+
+// ------------------------------------------------------------------------------------------
+struct Top2 {
+  float v1, v2;
+  int i1;
+};
+__device__ inline Top2 top2_merge(Top2 a, Top2 b) {
+  const bool a_first = (a.v1 > b.v1) || (a.v1 == b.v1 && a.i1 < b.i1);
+  Top2 r;
+  if (a_first) { r.v1 = a.v1; r.i1 = a.i1; r.v2 = fmaxf(a.v2, b.v1); }
+  else         { r.v1 = b.v1; r.i1 = b.i1; r.v2 = fmaxf(b.v2, a.v1); }
+  return r;
+}
+
+// Per-row argmax (lowest index on ties) and top-1 minus top-2 margin.
+__global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits, size_t ld, int V,
+                                                int32_t* __restrict__ argmax, float* __restrict__ margin) {
+  const int m = blockIdx.x;
+  const float* row = logits + (size_t)m * ld;
+  Top2 t = {-INFINITY, -INFINITY, INT_MAX};
+  for (int c = threadIdx.x; c < V; c += 256) {
+    Top2 e = {row[c], -INFINITY, c};
+    t = top2_merge(t, e);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    Top2 o;
+    o.v1 = __shfl_xor(t.v1, off, 64);
+    o.v2 = __shfl_xor(t.v2, off, 64);
+    o.i1 = __shfl_xor(t.i1, off, 64);
+    t = top2_merge(t, o);
+  }
+  __shared__ Top2 red[4];
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = t;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    Top2 r = top2_merge(top2_merge(red[0], red[1]), top2_merge(red[2], red[3]));
+    argmax[m] = r.i1;
+    if (margin) margin[m] = r.v1 - r.v2;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Greedy walk (Alg. 2).  Every node whose own edge matches (its token equals the prediction
+// at its parent) bids for its parent with the key (branch?1:0, node index); the lowest key
+// wins, i.e. spine children before branch children, lower index first.  Thread 0 then follows
+// the winners from the root; node indices grow along any path, so the walk is finite.
+__global__ __launch_bounds__(128) void k_accept(const int32_t* __restrict__ parent, const int32_t* __restrict__ tokens,
+                                                const uint8_t* __restrict__ is_spine,
+                                                const int32_t* __restrict__ argmax, int B,
+                                                int32_t* __restrict__ accept_len, int32_t* __restrict__ path,
+                                                int32_t* __restrict__ bonus, int32_t* __restrict__ next_root) {
+  __shared__ int nxt[GOOSE_MAX_B];
+  __shared__ int xh[GOOSE_MAX_B];
+  __shared__ int L_sh;
+  const int i = threadIdx.x;
+  if (i < B) {
+    nxt[i] = INT_MAX;
+    xh[i] = argmax[i];
+  }
+  __syncthreads();
+  if (i >= 1 && i < B) {
+    const int p = parent[i];
+    if (p >= 0 && p < i && tokens[i] == xh[p]) {
+      const int branch = (is_spine != nullptr && is_spine[i] == 0) ? 1 : 0;
+      atomicMin(&nxt[p], (branch << 16) | i);
+    }
+  }
+  __syncthreads();
+  if (i == 0) {
+    int v = 0, L = 0;
+    path[0] = 0;
+    while (nxt[v] != INT_MAX && L < B - 1) {
+      v = nxt[v] & 0xFFFF;
+      path[++L] = v;
+    }
+    *accept_len = L;
+    *bonus = xh[v];
+    if (next_root) *next_root = xh[v];
+    L_sh = L;
+  }
+  __syncthreads();
+  if (i > L_sh && i < B) path[i] = -1;
+}
+
+// ------------------------------------------------------------------------------------------
+// Move cache rows P + path[j] -> P + j, j = 1..L, in every (layer, K|V, head).  One thread
+// owns one 16-byte column chunk of all rows and walks j upward: path[j] >= j, so a row is
+// always read before the same thread can overwrite it.
+__global__ __launch_bounds__(64) void k_compact(uint4* __restrict__ kall, uint4* __restrict__ vall, int n_heads,
+                                                int cap, int row_chunks, const int32_t* __restrict__ dP,
+                                                const int32_t* __restrict__ path,
+                                                const int32_t* __restrict__ accept_len) {
+  const int c = threadIdx.x;
+  if (c >= row_chunks) return;
+  const int lh = blockIdx.x;  // layer * n_heads + head
+  uint4* base = (blockIdx.y == 0 ? kall : vall) + (size_t)lh * cap * row_chunks;
+  const int P = *dP;
+  int L = *accept_len;
+  if (L > GOOSE_MAX_B - 1) L = GOOSE_MAX_B - 1;
+  for (int j = 1; j <= L; ++j) {
+    const int src = path[j];
+    if (src < j || src >= GOOSE_MAX_B || P + src >= cap) break;  // malformed path: stop, stay in bounds
+    if (src != j) base[(size_t)(P + j) * row_chunks + c] = base[(size_t)(P + src) * row_chunks + c];
+  }
+}
+
+__global__ void k_new_P(const int32_t* dP, const int32_t* accept_len, int32_t* new_P) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    const int p = *dP, l = *accept_len;
+    *new_P = p + l + 1;
+  }
+}
+
+}  // namespace
+
+// ============================================================================================
+int launch_set_int(int32_t* dst, int v, hipStream_t st) {
+  hipLaunchKernelGGL(k_set_int, dim3(1), dim3(1), 0, st, dst, v);
+  return goose_launch_status();
+}
+
+int launch_build_mask(const int32_t* parent, int B, const int32_t* dP, uint64_t* mask, int32_t* depth, int32_t* pos,
+                      int32_t* flags, hipStream_t st) {
+  hipLaunchKernelGGL(k_build_mask, dim3(1), dim3(128), 0, st, parent, B, dP, mask, depth, pos, flags);
+  return goose_launch_status();
+}
+
+int launch_embed(int dtype, const void* E, const int32_t* tokens, int B, int H, int V, float* x, hipStream_t st) {
+  if (dtype == GOOSE_DTYPE_BF16)
+    hipLaunchKernelGGL(k_embed<bf16_t>, dim3(B), dim3(256), 0, st, (const bf16_t*)E, tokens, H, V, x);
+  else
+    hipLaunchKernelGGL(k_embed<float>, dim3(B), dim3(256), 0, st, (const float*)E, tokens, H, V, x);
+  return goose_launch_status();
+}
+
+int launch_resid_norm(int dtype, float* x, int H, const float* part, int S, size_t part_stride, size_t part_ld,
+                      const void* g, float eps, void* xn, int ldxn, int B, hipStream_t st) {
+  if (dtype == GOOSE_DTYPE_BF16)
+    hipLaunchKernelGGL(k_resid_norm<bf16_t>, dim3(B), dim3(256), 0, st, x, H, part, S, part_stride, part_ld,
+                       (const bf16_t*)g, eps, (bf16_t*)xn, ldxn);
+  else
+    hipLaunchKernelGGL(k_resid_norm<float>, dim3(B), dim3(256), 0, st, x, H, part, S, part_stride, part_ld,
+                       (const float*)g, eps, (float*)xn, ldxn);
+  return goose_launch_status();
+}
+
+int launch_rope_kv(int dtype, const float* part, int S, size_t part_stride, size_t part_ld, int B, int n_heads,
+                   int head_dim, const int32_t* pos, const double* inv_freq, const int32_t* dP, int cap, void* qout,
+                   int ldq, void* kcache, void* vcache, hipStream_t st) {
+  dim3 grid(B, n_heads), block(head_dim / 2);
+  if (dtype == GOOSE_DTYPE_BF16)
+    hipLaunchKernelGGL(k_rope_kv<bf16_t>, grid, block, 0, st, part, S, part_stride, part_ld, n_heads, head_dim, pos,
+                       inv_freq, dP, cap, (bf16_t*)qout, ldq, (bf16_t*)kcache, (bf16_t*)vcache);
+  else
+    hipLaunchKernelGGL(k_rope_kv<float>, grid, block, 0, st, part, S, part_stride, part_ld, n_heads, head_dim, pos,
+                       inv_freq, dP, cap, (float*)qout, ldq, (float*)kcache, (float*)vcache);
+  return goose_launch_status();
+}
+
+int launch_swiglu_f32(const float* gu, size_t ld, int F, float* h, int ldh, int B, hipStream_t st) {
+  hipLaunchKernelGGL(k_swiglu_f32, dim3((F + 255) / 256, B), dim3(256), 0, st, gu, ld, F, h, ldh);
+  return goose_launch_status();
+}
+
+int launch_argmax(const float* logits, size_t ld, int V, int B, int32_t* argmax, float* margin, hipStream_t st) {
+  hipLaunchKernelGGL(k_argmax, dim3(B), dim3(256), 0, st, logits, ld, V, argmax, margin);
+  return goose_launch_status();
+}
+
+int launch_accept(const int32_t* parent, const int32_t* tokens, const uint8_t* is_spine, const int32_t* argmax, int B,
+                  int32_t* accept_len, int32_t* path, int32_t* bonus, int32_t* next_root, hipStream_t st) {
+  hipLaunchKernelGGL(k_accept, dim3(1), dim3(128), 0, st, parent, tokens, is_spine, argmax, B, accept_len, path,
+                     bonus, next_root);
+  return goose_launch_status();
+}
+
+int launch_compact(int elem_bytes, void* kall, void* vall, int n_layers, int n_heads, int cap, int head_dim,
+                   const int32_t* dP, const int32_t* path, const int32_t* accept_len, int32_t* new_P,
+                   hipStream_t st) {
+  const int row_chunks = head_dim * elem_bytes / 16;  // <= 64 for head_dim <= 256 (fp32)
+  hipLaunchKernelGGL(k_compact, dim3(n_layers * n_heads, 2), dim3(64), 0, st, (uint4*)kall, (uint4*)vall, n_heads,
+                     cap, row_chunks, dP, path, accept_len);
+  int rc = goose_launch_status();
+  if (rc != GOOSE_OK) return rc;
+  if (new_P) {
+    hipLaunchKernelGGL(k_new_P, dim3(1), dim3(1), 0, st, dP, accept_len, new_P);
+    rc = goose_launch_status();
+  }
+  return rc;
+}

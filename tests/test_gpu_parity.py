@@ -1,0 +1,164 @@
+"""Parity of the HIP verification path with the CPU oracle, element by element.
+
+Tolerances (max abs error relative to the logit scale max|logit_oracle| of the step):
+fp32 storage 1e-4, bf16 storage 2e-2.  Integer results are bit-exact; an accept decision is only
+compared where the oracle's top-2 logit margin at the deciding node exceeds the tolerance.
+"""
+import numpy as np
+import pytest
+import torch
+
+import goose_inputs as gi
+from oracle import goose_oracle as orc
+from util import device_cache_as_oracle, gpu_model, load_prefix_cache, oracle_model, torch_model
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def _gpu_prefill(gm, prefix, chunk):
+    """Prefill through the verification path itself: chain trees, every row kept."""
+    done = 0
+    while done < len(prefix):
+        n = min(chunk, len(prefix) - done)
+        tree = gi.tree_chain(n)
+        out = gm.verify_step_calls(prefix[done:done + n], tree.parent, tree.is_spine, commit=False)
+        done += n
+        gm.set_P(done)
+    return out
+
+
+def _compare_step(shape, gm, om, cache, tokens, tree, tol, check_hidden=True):
+    """Runs one step on both sides from the same state and compares everything.  Returns both results."""
+    P = cache[0][0].shape[1]
+    assert gm.P == P
+    hidden = []
+    g = gm.verify_step_calls(tokens, tree.parent, tree.is_spine, want_logits=True, commit=True,
+                             layer_hook=(lambda l, x: hidden.append(x.double().cpu().numpy())) if check_hidden else None)
+    o = orc.verify_step(om, cache, tokens, tree.parent, tree.is_spine, return_hidden=True)
+    B = tree.B
+    # integer structure: bit-exact
+    assert np.array_equal(g["mask"].cpu().numpy().view(np.uint64), orc.mask_words(o["anc"]))
+    assert np.array_equal(g["depth"].cpu().numpy(), o["depth"])
+    assert np.array_equal(g["pos"].cpu().numpy(), P + o["depth"])
+    # hidden states per layer and logits: within tolerance of the scale
+    if check_hidden:
+        for l, (gh, oh) in enumerate(zip(hidden, o["hidden"])):
+            assert np.abs(gh - oh).max() <= tol * np.abs(oh).max(), f"layer {l}"
+    scale = np.abs(o["logits"]).max()
+    gl = g["logits"].double().cpu().numpy()
+    err = np.abs(gl - o["logits"]).max()
+    assert err <= tol * scale, (err, scale)
+    # KV rows written for the tree nodes
+    for l, (k_new, v_new) in enumerate(o["new_kv"]):
+        gk = g["tail_k"][l].double().cpu().numpy()
+        gv = g["tail_v"][l].double().cpu().numpy()
+        assert np.abs(gk - k_new).max() <= tol * max(1e-9, np.abs(k_new).max())
+        assert np.abs(gv - v_new).max() <= tol * max(1e-9, np.abs(v_new).max())
+    # the fused argmax is the argmax of the logits the kernel itself produced (lowest index on ties)
+    assert np.array_equal(g["argmax"].cpu().numpy(), np.argmax(gl, axis=-1))
+    part = np.partition(gl, -2, axis=-1)
+    np.testing.assert_allclose(g["margin"].cpu().numpy(), part[:, -1] - part[:, -2], rtol=0, atol=1e-6)
+    # predictions agree wherever the oracle's decision is not a near-tie
+    safe = o["margin"] > 2 * tol * scale
+    assert np.array_equal(g["argmax"].cpu().numpy()[safe], o["x_hat"][safe])
+    # the walk on the kernel's own predictions is exactly Alg. 2 ...
+    acc, bonus = orc.greedy_walk(tree.parent, tokens, tree.is_spine, g["argmax"].cpu().numpy())
+    assert g["accept_len"] == len(acc) and g["bonus"] == bonus
+    assert g["path"].tolist() == [0] + acc + [-1] * (B - 1 - len(acc))
+    # ... and equals the oracle's walk when every decision on the way was safe
+    decisive = all(safe[v] for v in o["path"])
+    if decisive:
+        assert acc == o["accepted"] and bonus == o["bonus"]
+    # compaction: the new cache tail is byte-identical to the rows the layers wrote
+    L = len(acc)
+    idx = torch.as_tensor([0] + acc, device=gm.device)
+    assert gm.P == P + L + 1
+    assert torch.equal(gm.kcache[:, :, P:P + L + 1], g["tail_k"][:, :, idx])
+    assert torch.equal(gm.vcache[:, :, P:P + L + 1], g["tail_v"][:, :, idx])
+    return g, o, decisive
+
+
+def _run_cycles(shape_name, n_cycles, P0, trees, seed, oracle_prefill, chunk=16, planted=True):
+    shape = gi.SHAPES[shape_name]
+    tol = TOL[shape.dtype]
+    tm = torch_model(shape, seed=seed, gain_jitter=0.1)
+    om = oracle_model(shape, tm)
+    gm = gpu_model(shape, tm, max_B=128, cap=P0 + 128 * (n_cycles + 1))
+    prefix = gi.prefix_tokens(seed, P0, shape.vocab)
+    last = _gpu_prefill(gm, prefix, chunk)
+    if oracle_prefill:
+        cache = orc.prefill(om, prefix)           # fully independent state
+        for l, (k, v) in enumerate(cache):        # chain prefill on the GPU == causal prefill of the oracle
+            gk = gm.kcache[l, :, :P0].double().cpu().numpy()
+            assert np.abs(gk - k).max() <= tol * np.abs(k).max()
+    else:
+        cache = device_cache_as_oracle(gm, P0)    # the device's stored bytes are the oracle's input
+    # the anchor: prediction after the prefix
+    ref_logits, _ = orc.causal_logits(om, prefix)
+    root = int(np.argmax(ref_logits[-1]))
+    greedy = orc.greedy_decode(om, list(prefix) + [root], 10 * n_cycles) if planted else None
+    emitted_g, emitted_o = [root], [root]
+    in_sync = True
+    accepted_total = 0
+    for cyc in range(n_cycles):
+        tree = trees[cyc % len(trees)]
+        tokens = gi.draft_tokens_uniform(1000 + cyc, tree.parent, shape.vocab, root)
+        if planted and in_sync:
+            cont = np.array(greedy[len(emitted_o) - 1:len(emitted_o) + 9])
+            tokens = gi.plant_drafts(2000 + cyc, tree.parent, tree.is_spine, tokens, cont, shape.vocab,
+                                     p_spine=0.8, p_branch=0.8, p_grand=0.8)
+        g, o, decisive = _compare_step(shape, gm, om, cache, tokens, tree, tol)
+        emitted_g += [int(tokens[v]) for v in g["path"][1:g["accept_len"] + 1]] + [g["bonus"]]
+        emitted_o += [int(tokens[v]) for v in o["accepted"]] + [o["bonus"]]
+        accepted_total += g["accept_len"]
+        if not decisive:
+            in_sync = False
+            break   # a near-tie was decided differently: later states legitimately differ
+        cache = o["cache"] if oracle_prefill else device_cache_as_oracle(gm, gm.P)
+        root = o["bonus"]
+    if in_sync:
+        assert emitted_g == emitted_o
+        if planted and oracle_prefill:
+            assert emitted_o == ([emitted_o[0]] + greedy)[:len(emitted_o)]   # lossless: plain greedy decoding
+        if planted:
+            assert accepted_total >= n_cycles // 2  # compaction of multi-node paths really happened
+    gm.ctx.close()
+    return in_sync
+
+
+def test_tiny_fp32_cycles_match_the_oracle():
+    trees = [gi.tree_tiny_spine(), gi.tree_random(16, 3, spine_len=6), gi.tree_star(9), gi.tree_chain(12),
+             gi.tree_single(), gi.tree_random(33, 4, spine_len=8)]
+    assert _run_cycles("tiny", 8, 128, trees, seed=0, oracle_prefill=True)
+
+
+def test_tiny_fp32_empty_prefix_and_big_trees():
+    trees = [gi.tree_spine_7b(1), gi.tree_spine_stress(), gi.tree_balanced(), gi.tree_random(65, 2)]
+    shape = gi.SHAPES["tiny"]
+    tm = torch_model(shape, seed=1, gain_jitter=0.1)
+    om = oracle_model(shape, tm)
+    gm = gpu_model(shape, tm, max_B=128, cap=1024)
+    gm.set_P(0)
+    cache = orc.empty_cache(om)
+    root = 17
+    for n, tree in enumerate(trees):
+        tokens = gi.draft_tokens_uniform(n, tree.parent, shape.vocab, root)
+        g, o, decisive = _compare_step(shape, gm, om, cache, tokens, tree, TOL["f32"])
+        assert decisive
+        cache, root = o["cache"], o["bonus"]
+    gm.ctx.close()
+
+
+@pytest.mark.parametrize("shape_name,P0,chunk", [("tiny_bf16", 128, 16), ("small_bf16", 200, 50)])
+def test_bf16_cycles_match_the_oracle(shape_name, P0, chunk):
+    """bf16 MFMA path; the oracle starts every cycle from the device's own stored cache bytes."""
+    trees = [gi.tree_tiny_spine(), gi.tree_spine_7b(0), gi.tree_random(33, 4, spine_len=8), gi.tree_spine_13b(),
+             gi.tree_spine_stress(), gi.tree_single(), gi.tree_balanced()]
+    _run_cycles(shape_name, 7, P0, trees, seed=2, oracle_prefill=False, chunk=chunk)
+
+
+def test_bf16_independent_prefill_stays_within_tolerance():
+    trees = [gi.tree_spine_7b(3), gi.tree_tiny_spine()]
+    _run_cycles("small_bf16", 2, 96, trees, seed=5, oracle_prefill=True, chunk=32)

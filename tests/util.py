@@ -41,3 +41,26 @@ def oracle_model(shape, tm) -> orc.OracleModel:
     layers = [{k: to_f64(v) for k, v in lw.items()} for lw in tm["layers"]]
     return orc.OracleModel(shape.n_heads, shape.head_dim, shape.rope_base, shape.rms_eps,
                            layers, to_f64(tm["embed"]), to_f64(tm["lm_head"]), to_f64(tm["final_norm"]))
+
+
+def gpu_model(shape, tm, max_B, cap):
+    """The HIP-side model built from the same stored weight bytes as `oracle_model`."""
+    from paper_2604_02047_amd import ModelDesc
+    from paper_2604_02047_amd.runner import GooseModel
+    return GooseModel(ModelDesc.from_shape(shape), max_B, cap, lambda l: tm["layers"][l], tm["embed"],
+                      tm["lm_head"], tm["final_norm"])
+
+
+def load_prefix_cache(gm, cache):
+    """Copies an oracle cache (list of (K,V) float64 [n_h,P,d]) into the device cache (rounded to its type)."""
+    P = cache[0][0].shape[1]
+    for l, (k, v) in enumerate(cache):
+        gm.kcache[l, :, :P] = torch.from_numpy(k).to(gm.dt).to(gm.device)
+        gm.vcache[l, :, :P] = torch.from_numpy(v).to(gm.dt).to(gm.device)
+    gm.set_P(P)
+
+
+def device_cache_as_oracle(gm, P):
+    """The device cache's first P slots as an oracle cache (exact upcast of the stored values)."""
+    return [(gm.kcache[l, :, :P].to(torch.float64).cpu().numpy(), gm.vcache[l, :, :P].to(torch.float64).cpu().numpy())
+            for l in range(gm.desc.n_layers)]
