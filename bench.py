@@ -1,0 +1,308 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verification step on one MI355X.
+
+A step = one whole verification cycle on device-resident inputs: ancestor mask, embedding,
+all decoder layers (tree attention + projections), LM head + argmax, greedy walk, KV
+compaction (goose_verify_step).  Default workload: the 7B shape, B=64 spine tree, KV prefix
+1024, consecutive steps with the accepted path committed between steps.
+
+Prints ONE JSON line.  `value` = steps/s; `roofline` prices the dominant kernel (gate/up
+projection GEMM) against the 8 TB/s HBM peak from live HIP-event timings; `cpu_baseline` is the
+fp64 NumPy oracle timed on this machine's host cores on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+WORKLOADS = {
+    # name: (shape, B, P0, tree generator(seed), default steps)
+    "7b_B64_P1024": ("7b", 64, 1024, "spine_7b", 100),
+    "13b_B80_P2048": ("13b", 80, 2048, "spine_13b", 100),
+    "33b_B80_P4096": ("33b", 80, 4096, "spine_33b", 50),
+    "7b_stress_B128_P16384": ("7b", 128, 16384, "spine_stress", 50),
+    "7b_balanced_B128_P16384": ("7b", 128, 16384, "balanced", 50),
+    "small_B64_P200": ("small_bf16", 64, 200, "spine_7b", 20),
+}
+
+
+def make_tree(kind, seed):
+    import goose_inputs as gi
+    return {"spine_7b": lambda: gi.tree_spine_7b(seed), "spine_13b": gi.tree_spine_13b,
+            "spine_33b": gi.tree_spine_33b, "spine_stress": gi.tree_spine_stress,
+            "balanced": gi.tree_balanced}[kind]()
+
+
+def step_bytes(shape, B, P):
+    """Algorithmic HBM bytes of one step: every weight once, the KV prefix once, the tail rows written and read."""
+    es = 2 if shape.dtype == "bf16" else 4
+    w = shape.n_layers * shape.layer_param_count() * es
+    head = shape.vocab * shape.hidden * es
+    kv_prefix = 2 * P * shape.qkv_dim * es * shape.n_layers
+    kv_tail = 2 * 2 * B * shape.qkv_dim * es * shape.n_layers
+    return w + head + kv_prefix + kv_tail
+
+
+def greedy_lookahead(gm, root, n):
+    """The model's next n greedy tokens after `root`, by n single-node steps; the cache length is restored."""
+    import goose_inputs as gi
+    P_keep = gm.P
+    tree = gi.tree_single()
+    out, tok = [], root
+    for _ in range(n):
+        r = gm.verify_step_calls([tok], tree.parent, tree.is_spine, commit=True)
+        tok = r["bonus"]
+        out.append(tok)
+    gm.set_P(P_keep)
+    return np.asarray(out, dtype=np.int32)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="7b_B64_P1024", choices=sorted(WORKLOADS))
+    ap.add_argument("--drafts", default="planted", choices=["planted", "random"])
+    ap.add_argument("--graph", type=int, default=1, help="replay each step as a captured HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the verification pass of one request does not shard); "
+              f"--gpus {args.gpus} is not supported.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import goose_inputs as gi
+    from paper_2604_02047_amd import ModelDesc
+    from paper_2604_02047_amd.runner import GooseModel
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    shape_name, B, P0, tree_kind, dflt_steps = WORKLOADS[args.workload]
+    shape = gi.SHAPES[shape_name]
+    K = args.steps if args.steps is not None else dflt_steps
+    W = args.warmup
+    total = K + W
+    cap = P0 + total * 20 + 2 * B
+    P_max = cap - B
+
+    def log(msg):
+        print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+    t0 = time.time()
+    gm = GooseModel(ModelDesc.from_shape(shape), B, cap,
+                    lambda l: gi.layer_weights(shape, args.seed, l, dev),
+                    gi.embedding(shape, args.seed, dev), gi.lm_head(shape, args.seed, dev),
+                    gi.final_norm(shape, args.seed, dev))
+    torch.cuda.synchronize()
+    log(f"model {shape.name} resident ({gm.packed_layers.numel() / 1e9:.2f} GB packed) in {time.time() - t0:.1f}s")
+
+    # ---- prefill P0 random tokens through the verification path itself (chain trees, all rows kept)
+    prefix = gi.prefix_tokens(args.seed, P0, shape.vocab)
+    done = 0
+    while done < P0:
+        n = min(B, P0 - done)
+        ch = gi.tree_chain(n)
+        r = gm.verify_step_calls(prefix[done:done + n], ch.parent, ch.is_spine, commit=False)
+        done += n
+        gm.set_P(done)
+    root0 = int(r["argmax"][n - 1].item())
+    log(f"prefill done, P={gm.P}")
+
+    # ---- staging buffers of a step (device resident)
+    cur_tok = torch.zeros(B, dtype=torch.int32, device=dev)
+    cur_par = torch.zeros(B, dtype=torch.int32, device=dev)
+    cur_spn = torch.zeros(B, dtype=torch.uint8, device=dev)
+    next_root = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def one_step():
+        gm.verify_step_fused(cur_tok, cur_par, cur_spn, B, P_max, next_root=next_root)
+
+    # ---- rehearsal (untimed): fixes the inputs of every step.  Planted drafts follow the model's own
+    # continuation, so they depend on what earlier steps accepted; this pass runs the same entry point
+    # as the timed pass, reads the outcome back each step and records the trees.
+    trees, toks, P_hist, acc_hist = [], [], [], []
+    root = root0
+    for t in range(total):
+        tree = make_tree(tree_kind, t)
+        tk = gi.draft_tokens_uniform(args.seed * 7919 + t, tree.parent, shape.vocab, root)
+        if args.drafts == "planted":
+            cont = greedy_lookahead(gm, root, 6)
+            tk = gi.plant_drafts(args.seed * 104729 + t, tree.parent, tree.is_spine, tk, cont, shape.vocab,
+                                 p_spine=0.6, p_branch=0.5, p_grand=0.3)
+        P_hist.append(gm.P)
+        cur_tok.copy_(torch.as_tensor(tk.astype(np.int32)))
+        cur_par.copy_(torch.as_tensor(tree.parent.astype(np.int32)))
+        cur_spn.copy_(torch.as_tensor(tree.is_spine.astype(np.uint8)))
+        one_step()
+        torch.cuda.synchronize()
+        gm.P = int(gm.d_P.item())
+        trees.append(tree)
+        toks.append(tk)
+        acc_hist.append(int(gm.accept_len.item()))
+        root = int(gm.bonus.item())
+    P_final = gm.P
+    assert P_final + B <= cap
+    log(f"rehearsal done: mean accepted drafts/step {np.mean(acc_hist):.2f}, P {P0} -> {P_final}")
+
+    # ---- device-resident inputs of the timed run
+    tok_all = torch.as_tensor(np.stack(toks).astype(np.int32), device=dev)
+    par_all = torch.as_tensor(np.stack([t.parent for t in trees]).astype(np.int32), device=dev)
+    spn_all = torch.as_tensor(np.stack([t.is_spine for t in trees]).astype(np.uint8), device=dev)
+
+    def stage(t):  # tiny device-to-device copies; the root is the previous step's bonus token
+        cur_tok.copy_(tok_all[t])
+        cur_par.copy_(par_all[t])
+        cur_spn.copy_(spn_all[t])
+        if t > 0:
+            cur_tok[0:1].copy_(next_root)
+
+    graph = None
+    if args.graph:
+        try:
+            gm.set_P(P0)
+            stage(0)
+            s = torch.cuda.Stream()
+            s.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(s):
+                one_step()  # warm the stream before capture
+            torch.cuda.current_stream().wait_stream(s)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=s):
+                one_step()
+            torch.cuda.synchronize()
+        except Exception as e:  # capture unavailable: plain launches (still the HIP path)
+            log(f"graph capture failed ({e}); timing plain launches")
+            graph = None
+
+    def run(n_from, n_to):
+        for t in range(n_from, n_to):
+            stage(t)
+            if graph is not None:
+                graph.replay()
+            else:
+                one_step()
+
+    # ---- timed region
+    gm.set_P(P0)
+    run(0, W)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    run(W, total)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    elapsed = t2 - t1
+    P_end = int(gm.d_P.item())
+    if P_end != P_final:
+        log(f"WARNING: replay ended at P={P_end}, rehearsal at P={P_final}")
+    ms_per_step = elapsed / K * 1e3
+    bytes_timed = sum(step_bytes(shape, B, P_hist[t]) for t in range(W, total))
+    achieved = bytes_timed / elapsed / 1e9
+
+    # ---- per-kernel timing with HIP events on the launch stream, over the same steps
+    roofline, kernels = None, None
+    if not args.no_kernel_timing:
+        gm.set_P(P0)
+        for t in range(W):
+            stage(t)
+            one_step()
+        torch.cuda.synchronize()
+        gm.ctx.goose_profile_enable(True)
+        for t in range(W, total):
+            stage(t)
+            one_step()
+        prof = gm.ctx.goose_profile_read()
+        gm.ctx.goose_profile_enable(False)
+        kernels = {k: {"avg_us": ms / max(n, 1) * 1e3, "launches": n} for k, (ms, n) in prof.items() if n}
+        es = 2
+        gu_bytes = 2 * shape.ffn * shape.hidden * es + B * shape.hidden * es + B * shape.ffn * es
+        gu = kernels["gemm_gate_up_swiglu"]
+        ach = gu_bytes / (gu["avg_us"] * 1e-6) / 1e9
+        roofline = {"kernel": "k_gemm_bf16<MT,2,EPI_SWIGLU> (gate/up projection + SwiGLU)", "bound": "hbm",
+                    "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                    "bytes_per_launch": gu_bytes, "avg_us": round(gu["avg_us"], 2)}
+
+    # ---- CPU baseline: the oracle on a bounded sample (two layers + LM head of the same step)
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(shape, gm, args.seed, B, P0, tree_kind, log)
+
+    out = {
+        "metric": "tree-verify steps/s + achieved HBM GB/s, 7B-shape, B=64 spine tree, KV 1024"
+                  if args.workload == "7b_B64_P1024" else f"tree-verify steps/s, {args.workload}",
+        "value": round(K / elapsed, 2), "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": args.workload, "shape": shape.name, "B": B, "P0": P0, "P_end": P_end,
+                   "tree": tree_kind, "drafts": args.drafts, "launch": "hipGraph per step" if graph else "plain",
+                   "mean_accepted_drafts_per_step": round(float(np.mean(acc_hist[W:])), 3)},
+        "draft_tokens_verified_per_s": round(B * K / elapsed, 1),
+        "tokens_emitted_per_s": round(float(np.sum(np.asarray(acc_hist[W:]) + 1)) / elapsed, 1),
+        "achieved_GBps": round(achieved, 1), "hbm_frac": round(achieved / HBM_PEAK_GBPS, 4),
+        "algorithmic_GB_per_step": round(bytes_timed / K / 1e9, 3),
+        "roofline": roofline, "cpu_baseline": cpu, "kernels_avg_us": kernels,
+    }
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(shape, gm, seed, B, P0, tree_kind, log):
+    """Times the NumPy fp64 oracle on two decoder layers and the LM head of one step at this workload's
+    shape (same weights, the device's own prefix KV as input) and scales to the full layer count."""
+    import torch
+    import goose_inputs as gi
+    from oracle import goose_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+
+    def f64(t):
+        return t.detach().to("cpu").to(torch.float64).numpy()
+
+    n_s = 2
+    log("cpu baseline: building the 2-layer oracle sample")
+    layers = [{k: f64(v) for k, v in gi.layer_weights(shape, seed, l, gm.device).items()} for l in range(n_s)]
+    om = orc.OracleModel(shape.n_heads, shape.head_dim, shape.rope_base, shape.rms_eps, layers,
+                         f64(gm.embed), f64(gi.lm_head(shape, seed, gm.device)),
+                         f64(gi.final_norm(shape, seed, gm.device)))
+    cache = [(f64(gm.kcache[l, :, :P0]), f64(gm.vcache[l, :, :P0])) for l in range(n_s)]
+    tree = make_tree(tree_kind, 0)
+    toks = gi.draft_tokens_uniform(seed, tree.parent, shape.vocab, 1)
+    anc, depth = orc.ancestor_mask(tree.parent)
+    allow = np.concatenate([np.ones((B, P0), dtype=bool), anc], axis=1)
+    x = om.embed[toks.astype(np.int64)]
+    ta = time.perf_counter()
+    for l in range(n_s):
+        x, _, _ = orc.decoder_layer(om, om.layers[l], x, cache[l][0], cache[l][1], P0 + depth, allow)
+    tb = time.perf_counter()
+    logits = orc.final_logits(om, x)
+    x_hat = orc.argmax_lowest(logits)
+    orc.greedy_walk(tree.parent, toks, tree.is_spine, x_hat)
+    tc = time.perf_counter()
+    t_step = (tb - ta) / n_s * shape.n_layers + (tc - tb)
+    log(f"cpu baseline: {n_s} layers {tb - ta:.2f}s, head {tc - tb:.2f}s -> {t_step:.1f}s/step on {threads} threads")
+    return {"value": round(1.0 / t_step, 5), "unit": "steps/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n_s} of {shape.n_layers} decoder layers + LM head + walk of one step "
+                      f"(B={B}, P={P0}), layer time scaled linearly to {shape.n_layers} layers",
+            "seconds_measured": round(tc - ta, 2)}
+
+
+if __name__ == "__main__":
+    main()

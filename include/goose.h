@@ -83,6 +83,8 @@ typedef struct {
 typedef struct goose_ctx goose_ctx;
 
 const char* goose_strerror(int status);
+/* Text of the most recent failing HIP runtime call in this process ("" if none): which call, which error. */
+const char* goose_last_hip_error(void);
 
 /* Creates a context with workspace for trees of up to max_B nodes and caches of `cap`
  * slots per head.  Allocates device memory on the current device. */
@@ -186,6 +188,17 @@ int goose_verify_step(goose_ctx* ctx, const goose_model_ptrs* model, const goose
 /* Device-side diagnostics: bit 0 set if any kernel since the last call saw a parent
  * array that is not topological.  Synchronises `stream`. */
 int goose_device_flags(goose_ctx* ctx, void* stream, int32_t* h_flags_out);
+
+/* ---- diagnostics: per-kernel timing --------------------------------------------------------
+ * While enabled, every kernel launch of verify_layer / lm_head_argmax is bracketed by two
+ * hipEvents recorded on the caller's stream (this adds gaps between kernels: use it to time
+ * kernels, not whole steps; do not enable it under stream capture).  goose_profile_read
+ * synchronises the stream, adds the elapsed milliseconds per kernel kind into
+ * h_ms_sum[goose_profile_kinds()] / h_count[...] (HOST arrays) and resets the records. */
+int goose_profile_enable(goose_ctx* ctx, int enable);
+int goose_profile_kinds(void);
+const char* goose_profile_kind_name(int kind);
+int goose_profile_read(goose_ctx* ctx, void* stream, double* h_ms_sum, int32_t* h_count);
 
 #ifdef __cplusplus
 }

@@ -13,10 +13,11 @@ import numpy as np
 _PKG = os.path.dirname(os.path.abspath(__file__))
 
 EXPORTS = [
-    "goose_strerror", "goose_create", "goose_destroy", "goose_check_parent",
+    "goose_strerror", "goose_last_hip_error", "goose_create", "goose_destroy", "goose_check_parent",
     "goose_packed_layer_bytes", "goose_pack_layer", "goose_packed_lm_head_bytes", "goose_pack_lm_head",
     "goose_build_mask", "goose_embed", "goose_verify_layer", "goose_lm_head_argmax",
     "goose_accept", "goose_compact_kv", "goose_verify_step", "goose_device_flags",
+    "goose_profile_enable", "goose_profile_kinds", "goose_profile_kind_name", "goose_profile_read",
 ]
 
 GOOSE_DTYPE_BF16, GOOSE_DTYPE_F32 = 0, 1
@@ -88,6 +89,8 @@ def load_library():
     lib = C.CDLL(path)
     lib.goose_strerror.restype = C.c_char_p
     lib.goose_strerror.argtypes = [C.c_int]
+    lib.goose_last_hip_error.restype = C.c_char_p
+    lib.goose_last_hip_error.argtypes = []
     lib.goose_create.argtypes = [C.POINTER(_Desc), C.c_int, C.c_int, C.POINTER(C.c_void_p)]
     lib.goose_destroy.argtypes = [C.c_void_p]
     lib.goose_destroy.restype = None
@@ -107,9 +110,15 @@ def load_library():
     lib.goose_verify_step.argtypes = [C.c_void_p, C.POINTER(_ModelPtrs), C.POINTER(_StepIO), C.c_int, C.c_int,
                                       C.c_void_p]
     lib.goose_device_flags.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
+    lib.goose_profile_enable.argtypes = [C.c_void_p, C.c_int]
+    lib.goose_profile_kinds.argtypes = []
+    lib.goose_profile_kind_name.argtypes = [C.c_int]
+    lib.goose_profile_kind_name.restype = C.c_char_p
+    lib.goose_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     for name in EXPORTS:
         fn = getattr(lib, name)
-        if name not in ("goose_strerror", "goose_destroy", "goose_packed_layer_bytes", "goose_packed_lm_head_bytes"):
+        if name not in ("goose_strerror", "goose_last_hip_error", "goose_destroy", "goose_packed_layer_bytes", "goose_packed_lm_head_bytes",
+                        "goose_profile_kind_name"):
             fn.restype = C.c_int
     _lib = lib
     return lib
@@ -117,7 +126,11 @@ def load_library():
 
 def _strerror(status):
     try:
-        return load_library().goose_strerror(int(status)).decode()
+        lib = load_library()
+        msg = lib.goose_strerror(int(status)).decode()
+        if status == -5:
+            msg += ": " + lib.goose_last_hip_error().decode()
+        return msg
     except Exception:  # pragma: no cover
         return "?"
 
@@ -218,3 +231,14 @@ class GooseContext:
         out = C.c_int32(0)
         _check(self.lib.goose_device_flags(self._h, _stream(), C.byref(out)), "goose_device_flags")
         return out.value
+
+    def goose_profile_enable(self, enable: bool):
+        _check(self.lib.goose_profile_enable(self._h, 1 if enable else 0), "goose_profile_enable")
+
+    def goose_profile_read(self) -> dict:
+        """{kernel kind: (total ms, launches)} since the last read."""
+        n = self.lib.goose_profile_kinds()
+        ms = (C.c_double * n)()
+        cnt = (C.c_int32 * n)()
+        _check(self.lib.goose_profile_read(self._h, _stream(), ms, cnt), "goose_profile_read")
+        return {self.lib.goose_profile_kind_name(k).decode(): (ms[k], cnt[k]) for k in range(n)}

@@ -6,10 +6,12 @@
 //     rows x 16 inputs = 1 KiB, lane l of a wavefront owning W[nt*32 + l%32][kt*16 + 8*(l/32) .. +7].
 //     One global_load_dwordx4 per lane fetches a whole operand of v_mfma_f32_32x32x16_bf16 and
 //     consecutive kt are consecutive in memory, so each wavefront reads one long contiguous run.
-//   * The M x K activation block is small and shared: the workgroup stages 64-wide K chunks of it
+//   * The M x K activation block is small and shared: the workgroup stages 128-wide K slices of it
 //     in LDS (double buffered) and every wavefront reads its A operands from there.
-//   * 4 wavefronts per workgroup, each owning NT column tiles; split-K over blockIdx.y writes
+//   * 2 or 4 wavefronts per workgroup, one column tile each; split-K over blockIdx.y writes
 //     fp32 partials that the next (reduction / rotary / norm) kernel sums in a fixed order.
+#include <type_traits>
+
 #include "goose_internal.h"
 
 namespace {
@@ -18,7 +20,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int KC = 64;               // k extent of one LDS chunk
+constexpr int KC = 128;              // k extent of one LDS stage
 constexpr int LDS_ROW = KC * 2 + 16;  // bytes; the 16-byte pad staggers rows across banks
 
 // ------------------------------------------------------------------------------------------
@@ -63,153 +65,173 @@ __global__ __launch_bounds__(256) void k_pack_bf16(int mode, const bf16_t* __res
 }
 
 // ------------------------------------------------------------------------------------------
-template <int MT, int NT, int EPI>
-__global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A, int lda,
-                                                   const u32x4* __restrict__ Wp, int ntiles, int ksteps_total,
-                                                   int chunks_per_split, int B, void* __restrict__ out, size_t ldo,
-                                                   size_t split_stride) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2][MT * 32 * LDS_ROW];
+// One workgroup = NW wavefronts, wavefront w owns column tile blockIdx.x*NW + w (32 columns) and
+// all MT row tiles.  blockIdx.y selects the split-K range.  Per stage (KC = 128 inputs):
+//   - every wavefront has the 8 operand loads (8 KiB) of the NEXT stage in flight while it
+//     multiplies the current one (register double buffer),
+//   - the workgroup copies the next A stage global -> registers -> LDS (LDS double buffer),
+//   - one barrier.
+// EPI_SWIGLU: even wavefronts hold gate tiles, odd ones the matching up tiles; the up tile
+// is handed over through LDS and the even wavefront writes h = silu(gate) * up.
+template <int MT, int NW, int EPI>
+__global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict__ A, int lda,
+                                                       const u32x4* __restrict__ Wp, int ntiles, int ksteps_total,
+                                                       int stages_per_split, int B, void* __restrict__ out,
+                                                       size_t ldo, size_t split_stride) {
+  constexpr int NTHR = 64 * NW;
+  constexpr int STEPS = KC / 16;                    // MFMA k-steps per stage
+  constexpr int ASEG = MT * 32 * (KC / 8);           // 16-byte segments of one A stage
+  constexpr int APT = ASEG / NTHR;                   // segments per thread
+  static_assert(ASEG % NTHR == 0, "A stage must divide evenly over the workgroup");
+  constexpr int STAGE_BYTES = MT * 32 * LDS_ROW;
+  constexpr int SWAP_BYTES = (EPI == EPI_SWIGLU) ? (NW / 2) * MT * 16 * 64 * 4 : 0;
+  constexpr int LDS_BYTES = 2 * STAGE_BYTES > SWAP_BYTES ? 2 * STAGE_BYTES : SWAP_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int tile0 = (blockIdx.x * 4 + wave) * NT;
-  const int nchunks_total = ksteps_total >> 2;
-  const int c_begin = blockIdx.y * chunks_per_split;
-  const int c_end = min(c_begin + chunks_per_split, nchunks_total);
-  const int nch = c_end - c_begin;
+  const int tile = blockIdx.x * NW + wave;
+  const bool active = tile < ntiles;
+  // a wavefront past the last tile redoes the last tile (no divergent control flow in the
+  // pipeline, which lets the compiler count outstanding loads exactly) and skips the store
+  const int tile_ld = active ? tile : ntiles - 1;
+  const int nstages_total = ksteps_total / STEPS;
+  const int s_begin = blockIdx.y * stages_per_split;
+  const int s_end = min(s_begin + stages_per_split, nstages_total);
+  const int nst = s_end - s_begin;
 
-  f32x16 acc[MT][NT];
+  f32x16 acc[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mt][t][r] = 0.f;
+    for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
 
-  bool active[NT];
+  // A stage copy: global -> registers -> LDS, APT 16-byte segments per thread
+  u32x4 areg[APT];
+  const bf16_t* a_src[APT];
+  int a_dst[APT];
 #pragma unroll
-  for (int t = 0; t < NT; ++t) active[t] = (tile0 + t) < ntiles;
-
-  // per-thread slots of the cooperative A-chunk copy: MT*32 rows x 8 sixteen-byte segments
-  u32x4 areg[MT];
-  auto load_a = [&](int c) {
+  for (int i = 0; i < APT; ++i) {
+    const int seg = tid + NTHR * i;
+    const int row = seg / (KC / 8), c16 = seg % (KC / 8);
+    a_src[i] = A + (size_t)row * lda + c16 * 8;
+    a_dst[i] = row * LDS_ROW + c16 * 16;
+  }
+  auto load_a = [&](int st) {
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      const int seg = tid + 256 * i;
-      const int row = seg >> 3, c16 = seg & 7;
-      areg[i] = *reinterpret_cast<const u32x4*>(A + (size_t)row * lda + (size_t)c * KC + c16 * 8);
-    }
+    for (int i = 0; i < APT; ++i) areg[i] = *reinterpret_cast<const u32x4*>(a_src[i] + (size_t)st * KC);
   };
   auto store_a = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      const int seg = tid + 256 * i;
-      const int row = seg >> 3, c16 = seg & 7;
-      *reinterpret_cast<u32x4*>(&lds[buf][row * LDS_ROW + c16 * 16]) = areg[i];
-    }
+    for (int i = 0; i < APT; ++i) *reinterpret_cast<u32x4*>(&lds[buf * STAGE_BYTES + a_dst[i]]) = areg[i];
   };
-  u32x4 wreg[2][NT][4];
-  auto load_w = [&](int c, int slot) {
+  // Weight stream: a ring of two stages (16 operand loads = 16 KiB per wavefront).  A slot is
+  // refilled for stage st+2 right after the MFMAs of stage st consumed it, so 8..16 loads stay
+  // in flight per wavefront at all times, independent of the barriers.
+  u32x4 wreg[2][STEPS];
+  const u32x4* wbase = Wp + (size_t)tile_ld * ksteps_total * 64 + lane;
+  auto load_w = [&](int st, int slot) {
+    const u32x4* p = wbase + (size_t)st * STEPS * 64;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      if (active[t]) {
-        const u32x4* p = Wp + ((size_t)(tile0 + t) * ksteps_total + (size_t)c * 4) * 64 + lane;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) wreg[slot][t][s] = __builtin_nontemporal_load(p + s * 64);
-      }
-    }
+    for (int s = 0; s < STEPS; ++s) wreg[slot][s] = __builtin_nontemporal_load(p + s * 64);
   };
-  auto compute = [&](int buf, int slot) {
+  const int a_frag = (lane & 31) * LDS_ROW + (lane >> 5) * 16;
+  // one stage: start the copy of the next A stage, multiply, refill the ring, publish the next A stage
+  // (buf/slot are compile-time so that the register ring is never indexed dynamically)
+  auto stage = [&](auto buf_c, int st, auto next_a, auto refill) {
+    constexpr int buf = decltype(buf_c)::value, slot = buf;
+    if (next_a) load_a(st + 1);
+    __builtin_amdgcn_sched_barrier(0);  // keep the issue order: the scheduler would sink these loads
+    const u32x4* pn = wbase + (size_t)(st + 2) * STEPS * 64;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      bf16x8 a[MT];
+    for (int s = 0; s < STEPS; ++s) {
+      const bf16x8 b = __builtin_bit_cast(bf16x8, wreg[slot][s]);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        const int row = mt * 32 + (lane & 31);
-        a[mt] = *reinterpret_cast<const bf16x8*>(&lds[buf][row * LDS_ROW + s * 32 + (lane >> 5) * 16]);
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(
+            &lds[buf * STAGE_BYTES + mt * 32 * LDS_ROW + a_frag + s * 32]);
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mt], 0, 0, 0);
       }
-#pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        if (active[t]) {
-          const bf16x8 b = __builtin_bit_cast(bf16x8, wreg[slot][t][s]);
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
-            acc[mt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt], b, acc[mt][t], 0, 0, 0);
-        }
-      }
+      if (refill) wreg[slot][s] = __builtin_nontemporal_load(pn + s * 64);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    if (next_a) store_a(buf ^ 1);
+    __syncthreads();
   };
+  const std::true_type yes;
+  const std::integral_constant<int, 0> b0;
+  const std::integral_constant<int, 1> b1;
 
-  if (nch > 0) {
-    load_a(c_begin);
-    load_w(c_begin, 0);
+  if (nst > 0) {
+    load_a(s_begin);
+    load_w(s_begin, 0);
+    if (nst > 1) load_w(s_begin + 1, 1);
     store_a(0);
     __syncthreads();
-    for (int i = 0; i < nch; i += 2) {
-      // even step: compute from (lds 0, wreg 0) while chunk i+1 streams into (lds 1, wreg 1)
-      const bool more1 = (i + 1) < nch;
-      if (more1) { load_a(c_begin + i + 1); load_w(c_begin + i + 1, 1); }
-      compute(0, 0);
-      if (more1) store_a(1);
-      __syncthreads();
-      if (!more1) break;
-      const bool more2 = (i + 2) < nch;
-      if (more2) { load_a(c_begin + i + 2); load_w(c_begin + i + 2, 0); }
-      compute(1, 1);
-      if (more2) store_a(0);
-      __syncthreads();
+    int i = 0;
+    for (; i + 3 < nst; i += 2) {  // steady state: no conditionals inside
+      stage(b0, s_begin + i, yes, yes);
+      stage(b1, s_begin + i + 1, yes, yes);
+    }
+    for (; i < nst; ++i) {  // last one to three stages
+      if (i & 1) stage(b1, s_begin + i, (i + 1) < nst, (i + 2) < nst);
+      else       stage(b0, s_begin + i, (i + 1) < nst, (i + 2) < nst);
     }
   }
 
   // C layout of the 32x32 MFMA: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
   if (EPI == EPI_PARTIAL) {
+    if (!active) return;
     float* o = reinterpret_cast<float*>(out) + blockIdx.y * split_stride;
+    const int col = tile * 32 + (lane & 31);
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      if (!active[t]) continue;
-      const int col = (tile0 + t) * 32 + (lane & 31);
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (row < B) o[(size_t)row * ldo + col] = acc[mt][r];
+      }
+  } else {  // EPI_SWIGLU (the last loop barrier already separates the A stages from this reuse of LDS)
+    float* swap = reinterpret_cast<float*>(lds) + (size_t)(wave >> 1) * MT * 16 * 64;
+    if (active && (wave & 1)) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          if (row < B) o[(size_t)row * ldo + col] = acc[mt][t][r];
-        }
+        for (int r = 0; r < 16; ++r) swap[(mt * 16 + r) * 64 + lane] = acc[mt][r];
     }
-  } else {  // EPI_SWIGLU: tile pair (gate, up) -> h = silu(gate) * up
-    static_assert(EPI != EPI_SWIGLU || NT == 2, "SwiGLU epilogue needs the gate and up tiles in one wavefront");
-    if (active[0] && active[NT - 1]) {
+    __syncthreads();
+    if (active && !(wave & 1)) {
       bf16_t* hq = reinterpret_cast<bf16_t*>(out);
-      const int col = (tile0 >> 1) * 32 + (lane & 31);
+      const int col = (tile >> 1) * 32 + (lane & 31);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int row = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          const float g = acc[mt][0][r], u = acc[mt][NT - 1][r];
+          const float g = acc[mt][r], u = swap[(mt * 16 + r) * 64 + lane];
           if (row < B) hq[(size_t)row * ldo + col] = (bf16_t)(g / (1.0f + __expf(-g)) * u);
         }
     }
   }
 }
 
-template <int MT, int NT, int EPI>
+template <int MT, int NW, int EPI>
 int launch_one(const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit, void* out, size_t ldo,
                size_t split_stride, hipStream_t st) {
-  const int ntiles = Npad / 32, ksteps = Kpad / 16, nchunks = ksteps / 4;
-  const int cps = (nchunks + ksplit - 1) / ksplit;
-  dim3 grid((ntiles + 4 * NT - 1) / (4 * NT), ksplit);
-  hipLaunchKernelGGL((k_gemm_bf16<MT, NT, EPI>), grid, dim3(256), 0, st, (const bf16_t*)A, lda, (const u32x4*)Wp,
-                     ntiles, ksteps, cps, B, out, ldo, split_stride);
+  const int ntiles = Npad / 32, ksteps = Kpad / 16, nstages = Kpad / KC;
+  const int sps = (nstages + ksplit - 1) / ksplit;
+  dim3 grid((ntiles + NW - 1) / NW, ksplit);
+  hipLaunchKernelGGL((k_gemm_bf16<MT, NW, EPI>), grid, dim3(64 * NW), 0, st, (const bf16_t*)A, lda,
+                     (const u32x4*)Wp, ntiles, ksteps, sps, B, out, ldo, split_stride);
   return goose_launch_status();
 }
 
-template <int NT, int EPI>
+template <int NW, int EPI>
 int launch_mt(int MT, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit, void* out,
               size_t ldo, size_t split_stride, hipStream_t st) {
   switch (MT) {
-    case 1: return launch_one<1, NT, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st);
-    case 2: return launch_one<2, NT, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st);
-    case 3: return launch_one<3, NT, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st);
-    case 4: return launch_one<4, NT, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st);
+    case 1: return launch_one<1, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st);
+    case 2: return launch_one<2, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st);
+    case 3: return launch_one<3, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st);
+    case 4: return launch_one<4, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st);
   }
   return GOOSE_ERR_ARG;
 }
@@ -225,28 +247,31 @@ int launch_pack_bf16(int mode, const void* s0, const void* s1, const void* s2, i
   return goose_launch_status();
 }
 
-// Split-K factor: enough workgroups to cover the 256 compute units about twice, but every
-// split keeps at least 4 chunks (256 inputs) so the fp32 partial traffic stays small.
-int pick_ksplit(int Npad, int Kpad, int max_ksplit) {
-  const int ntiles = Npad / 32;
-  const int wgs_n = (ntiles + 3) / 4;  // NT = 1
-  const int nchunks = Kpad / KC;
-  int ks = (384 + wgs_n - 1) / wgs_n;
-  if (ks > nchunks / 4) ks = nchunks / 4;
+// Workgroup width (wavefronts = column tiles per workgroup) and split-K factor for a shape.
+// Streaming needs about 1000 wavefronts with 8 KiB of loads in flight each to keep HBM busy, so
+// split K until tiles * ksplit reaches that, but keep every split at least 4 stages long; use
+// the 4-wide workgroup (more sharing of the staged A block) whenever that still leaves >= 256
+// workgroups.
+void pick_gemm_config(int Npad, int Kpad, int max_ksplit, int* nw_out, int* ksplit_out) {
+  const int ntiles = Npad / 32, nstages = Kpad / KC;
+  int ks = (1024 + ntiles - 1) / ntiles;
+  if (ks > nstages / 4) ks = nstages / 4;
   if (ks > max_ksplit) ks = max_ksplit;
   if (ks < 1) ks = 1;
-  // no empty split: ceil(nchunks / ks) * (ks - 1) < nchunks
-  while (ks > 1 && ((nchunks + ks - 1) / ks) * (ks - 1) >= nchunks) --ks;
-  return ks;
+  while (ks > 1 && ((nstages + ks - 1) / ks) * (ks - 1) >= nstages) --ks;  // no empty split
+  *nw_out = (((ntiles + 3) / 4) * ks >= 256) ? 4 : 2;
+  *ksplit_out = ks;
 }
 
-int launch_gemm_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit,
+int launch_gemm_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw, int ksplit,
                      void* out, size_t ldo, size_t out_split_stride, hipStream_t st) {
-  if (B < 1 || B > GOOSE_MAX_B || (Npad & 31) || (Kpad & 63) || ksplit < 1) return GOOSE_ERR_ARG;
+  if (B < 1 || B > GOOSE_MAX_B || (Npad & 31) || (Kpad % KC) || ksplit < 1) return GOOSE_ERR_ARG;
   const int MT = (B + 31) / 32;
   if (epi == EPI_SWIGLU) {
     if (ksplit != 1 || (Npad & 63)) return GOOSE_ERR_ARG;
+    if (nw == 4) return launch_mt<4, EPI_SWIGLU>(MT, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st);
     return launch_mt<2, EPI_SWIGLU>(MT, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st);
   }
-  return launch_mt<1, EPI_PARTIAL>(MT, A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st);
+  if (nw == 4) return launch_mt<4, EPI_PARTIAL>(MT, A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st);
+  return launch_mt<2, EPI_PARTIAL>(MT, A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st);
 }

@@ -6,7 +6,15 @@
 #include <new>
 #include <vector>
 
+#include <stdio.h>
+
 #include "goose_internal.h"
+
+static char g_last_hip_error[256] = "";
+
+void goose_note_hip_error(hipError_t e, const char* what, int line) {
+  snprintf(g_last_hip_error, sizeof(g_last_hip_error), "%s (%d) at %s:%d", hipGetErrorString(e), (int)e, what, line);
+}
 
 namespace {
 
@@ -17,6 +25,43 @@ int env_int(const char* name, int dflt) {
   const char* v = getenv(name);
   return (v && *v) ? atoi(v) : dflt;
 }
+
+// ---- optional per-kernel timing with HIP events on the caller's stream -----------------------
+enum ProfKind { PK_NORM = 0, PK_GEMM_QKV, PK_ROPE, PK_ATTN, PK_GEMM_O, PK_GEMM_GATE_UP, PK_GEMM_DOWN, PK_LM_HEAD,
+                PK_ARGMAX, PK_MISC, PK_COUNT };
+const char* const kProfNames[PK_COUNT] = {"rmsnorm_residual", "gemm_qkv", "rope_kv_write", "tree_attention", "gemm_o",
+                                          "gemm_gate_up_swiglu", "gemm_down", "gemm_lm_head", "argmax",
+                                          "mask_embed_accept_compact"};
+}  // namespace
+struct goose_prof {
+  bool on = false;
+  std::vector<hipEvent_t> ev;   // pairs: ev[2i] start, ev[2i+1] end
+  std::vector<int> kind;        // kind of pair i
+  size_t used = 0;              // pairs used since the last read
+};
+namespace {
+struct ProfScope {
+  goose_prof* p;
+  hipStream_t st;
+  ProfScope(goose_ctx* c, int kind, hipStream_t s) : p(c->prof && c->prof->on ? c->prof : nullptr), st(s) {
+    if (!p) return;
+    if (p->used * 2 >= p->ev.size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { p = nullptr; return; }
+      p->ev.push_back(a);
+      p->ev.push_back(b);
+      p->kind.push_back(kind);
+    }
+    p->kind[p->used] = kind;
+    (void)hipEventRecord(p->ev[2 * p->used], st);
+  }
+  ~ProfScope() {
+    if (!p) return;
+    (void)hipEventRecord(p->ev[2 * p->used + 1], st);
+    ++p->used;
+  }
+};
+#define PROF(kind) ProfScope prof_scope_(c, kind, st)
 
 void compute_layouts(goose_ctx* c) {
   const goose_model_desc& d = c->d;
@@ -47,8 +92,8 @@ void compute_layouts(goose_ctx* c) {
 }
 
 int dev_alloc(void** p, size_t bytes) {
-  if (hipMalloc(p, bytes) != hipSuccess) return GOOSE_ERR_HIP;
-  if (hipMemset(*p, 0, bytes) != hipSuccess) return GOOSE_ERR_HIP;
+  GOOSE_HIP_TRY(hipMalloc(p, bytes));
+  GOOSE_HIP_TRY(hipMemset(*p, 0, bytes));
   return GOOSE_OK;
 }
 
@@ -58,6 +103,23 @@ int check_tree_args(const goose_ctx* ctx, int B, int P) {
   if (B > ctx->max_B || B > GOOSE_MAX_B) return GOOSE_ERR_CAPACITY;
   if ((long)P + B > ctx->cap) return GOOSE_ERR_CAPACITY;
   return GOOSE_OK;
+}
+
+// Workgroup width / split-K of one projection: heuristic, or "nw,ksplit" from the environment (tuning aid).
+struct GemmCfg { int nw, ks; };
+GemmCfg gemm_cfg(const goose_ctx* c, const char* env_name, int Npad, int Kpad) {
+  GemmCfg g;
+  pick_gemm_config(Npad, Kpad, c->max_ksplit, &g.nw, &g.ks);
+  const char* v = getenv(env_name);
+  if (v && *v) {
+    int nw = 0, ks = 0;
+    if (sscanf(v, "%d,%d", &nw, &ks) == 2 && (nw == 2 || nw == 4) && ks >= 1 && ks <= c->max_ksplit &&
+        ks <= Kpad / 128) {
+      g.nw = nw;
+      g.ks = ks;
+    }
+  }
+  return g;
 }
 
 // Resolves "P from memory if given, else the host value" to a device pointer.
@@ -71,6 +133,8 @@ int resolve_P(goose_ctx* ctx, int P, const int32_t* d_P, hipStream_t st, const i
 }  // namespace
 
 extern "C" {
+
+const char* goose_last_hip_error(void) { return g_last_hip_error; }
 
 const char* goose_strerror(int status) {
   switch (status) {
@@ -116,9 +180,9 @@ int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** o
   c->Bpad = round_up(max_B, 32);
   c->cap = cap;
   c->Hq = d.n_heads * d.head_dim;
-  c->Kh = round_up(d.hidden, 64);
-  c->Kq = round_up(c->Hq, 64);
-  c->Fpad = round_up(d.ffn, 64);
+  c->Kh = round_up(d.hidden, 128);
+  c->Kq = round_up(c->Hq, 128);
+  c->Fpad = round_up(d.ffn, 128);
   c->Vpad = round_up(d.vocab, 32);
   c->max_splits = 32;
   c->max_ksplit = 16;
@@ -149,11 +213,14 @@ int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** o
   if (rc == GOOSE_OK) {
     std::vector<double> f(d.head_dim / 2);
     for (int j = 0; j < d.head_dim / 2; ++j) f[j] = pow((double)d.rope_base, -2.0 * j / d.head_dim);
-    if (hipMemcpy(c->inv_freq, f.data(), f.size() * sizeof(double), hipMemcpyHostToDevice) != hipSuccess)
-      rc = GOOSE_ERR_HIP;
+    hipError_t e = hipMemcpy(c->inv_freq, f.data(), f.size() * sizeof(double), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { goose_note_hip_error(e, "hipMemcpy(inv_freq)", __LINE__); rc = GOOSE_ERR_HIP; }
   }
   // the zero fills above ran on the null stream; callers use their own streams
-  if (rc == GOOSE_OK && hipDeviceSynchronize() != hipSuccess) rc = GOOSE_ERR_HIP;
+  if (rc == GOOSE_OK) {
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) { goose_note_hip_error(e, "hipDeviceSynchronize", __LINE__); rc = GOOSE_ERR_HIP; }
+  }
   if (rc != GOOSE_OK) { goose_destroy(c); return rc; }
   *out = c;
   return GOOSE_OK;
@@ -165,6 +232,10 @@ void goose_destroy(goose_ctx* c) {
                   c->s_mask, c->s_depth, c->s_pos, c->s_x, c->flags, c->s_P};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
+  if (c->prof) {
+    for (hipEvent_t e : c->prof->ev) (void)hipEventDestroy(e);
+    delete c->prof;
+  }
   delete c;
 }
 
@@ -252,42 +323,52 @@ int goose_verify_layer(goose_ctx* c, const void* d_packed_layer, float* d_x, voi
   const int H = d.hidden, Hq = c->Hq;
 
   // x_hat = RMSNorm(x) * g1
-  rc = launch_resid_norm(d.dtype, d_x, H, nullptr, 0, 0, 0, w + c->pl.g1, d.rms_eps, c->xn, c->Kh, B, st);
+  { PROF(PK_NORM);
+    rc = launch_resid_norm(d.dtype, d_x, H, nullptr, 0, 0, 0, w + c->pl.g1, d.rms_eps, c->xn, c->Kh, B, st); }
   if (rc) return rc;
 
   if (d.dtype == GOOSE_DTYPE_BF16) {
     const int Nqkv = round_up(3 * Hq, 32), Nh = round_up(H, 32), Ngu = 2 * round_up(d.ffn, 32);
-    static const int ks_qkv_env = env_int("GOOSE_KSPLIT_QKV", 0), ks_o_env = env_int("GOOSE_KSPLIT_O", 0),
-                     ks_d_env = env_int("GOOSE_KSPLIT_DOWN", 0), splits_env = env_int("GOOSE_ATTN_SPLITS", 0);
-    int ks = ks_qkv_env > 0 ? ks_qkv_env : pick_ksplit(Nqkv, c->Kh, c->max_ksplit);
-    if (ks > c->max_ksplit) ks = c->max_ksplit;
-    rc = launch_gemm_bf16(EPI_PARTIAL, c->xn, c->Kh, w + c->pl.wqkv, Nqkv, c->Kh, B, ks, c->part, c->part_ld, pstride,
-                          st);
+    static const int splits_env = env_int("GOOSE_ATTN_SPLITS", 0);
+    const GemmCfg cq = gemm_cfg(c, "GOOSE_CFG_QKV", Nqkv, c->Kh);
+    int ks = cq.ks;
+    { PROF(PK_GEMM_QKV);
+      rc = launch_gemm_bf16(EPI_PARTIAL, c->xn, c->Kh, w + c->pl.wqkv, Nqkv, c->Kh, B, cq.nw, ks, c->part,
+                            c->part_ld, pstride, st); }
     if (rc) return rc;
-    rc = launch_rope_kv(d.dtype, c->part, ks, pstride, c->part_ld, B, d.n_heads, d.head_dim, d_pos, c->inv_freq, dP,
-                        c->cap, c->q, c->Kq, d_kcache, d_vcache, st);
+    { PROF(PK_ROPE);
+      rc = launch_rope_kv(d.dtype, c->part, ks, pstride, c->part_ld, B, d.n_heads, d.head_dim, d_pos, c->inv_freq,
+                          dP, c->cap, c->q, c->Kq, d_kcache, d_vcache, st); }
     if (rc) return rc;
     int splits = splits_env > 0 ? splits_env : pick_attn_splits(d.n_heads, P + B, c->max_splits);
     if (splits > c->max_splits) splits = c->max_splits;
-    rc = launch_attn_bf16(c->q, c->Kq, d_kcache, d_vcache, d.n_heads, d.head_dim, c->cap, dP, B, d_mask, splits,
-                          c->att_o, c->att_ml, c->Bpad, c->o, c->Kq, st);
+    { PROF(PK_ATTN);
+      rc = launch_attn_bf16(c->q, c->Kq, d_kcache, d_vcache, d.n_heads, d.head_dim, c->cap, dP, B, d_mask, splits,
+                            c->att_o, c->att_ml, c->Bpad, c->o, c->Kq, st); }
     if (rc) return rc;
-    ks = ks_o_env > 0 ? ks_o_env : pick_ksplit(Nh, c->Kq, c->max_ksplit);
-    if (ks > c->max_ksplit) ks = c->max_ksplit;
-    rc = launch_gemm_bf16(EPI_PARTIAL, c->o, c->Kq, w + c->pl.wo, Nh, c->Kq, B, ks, c->part, c->part_ld, pstride, st);
+    const GemmCfg co = gemm_cfg(c, "GOOSE_CFG_O", Nh, c->Kq);
+    ks = co.ks;
+    { PROF(PK_GEMM_O);
+      rc = launch_gemm_bf16(EPI_PARTIAL, c->o, c->Kq, w + c->pl.wo, Nh, c->Kq, B, co.nw, ks, c->part, c->part_ld,
+                            pstride, st); }
     if (rc) return rc;
     // x += attention projection; x_hat = RMSNorm(x) * g2
-    rc = launch_resid_norm(d.dtype, d_x, H, c->part, ks, pstride, c->part_ld, w + c->pl.g2, d.rms_eps, c->xn, c->Kh,
-                           B, st);
+    { PROF(PK_NORM);
+      rc = launch_resid_norm(d.dtype, d_x, H, c->part, ks, pstride, c->part_ld, w + c->pl.g2, d.rms_eps, c->xn,
+                             c->Kh, B, st); }
     if (rc) return rc;
-    rc = launch_gemm_bf16(EPI_SWIGLU, c->xn, c->Kh, w + c->pl.wgu, Ngu, c->Kh, B, 1, c->h, c->Fpad, 0, st);
+    static const int gu_nw = env_int("GOOSE_GU_NW", 2) == 4 ? 4 : 2;
+    { PROF(PK_GEMM_GATE_UP);
+      rc = launch_gemm_bf16(EPI_SWIGLU, c->xn, c->Kh, w + c->pl.wgu, Ngu, c->Kh, B, gu_nw, 1, c->h, c->Fpad, 0, st); }
     if (rc) return rc;
-    ks = ks_d_env > 0 ? ks_d_env : pick_ksplit(Nh, c->Fpad, c->max_ksplit);
-    if (ks > c->max_ksplit) ks = c->max_ksplit;
-    rc = launch_gemm_bf16(EPI_PARTIAL, c->h, c->Fpad, w + c->pl.wd, Nh, c->Fpad, B, ks, c->part, c->part_ld, pstride,
-                          st);
+    const GemmCfg cd = gemm_cfg(c, "GOOSE_CFG_DOWN", Nh, c->Fpad);
+    ks = cd.ks;
+    { PROF(PK_GEMM_DOWN);
+      rc = launch_gemm_bf16(EPI_PARTIAL, c->h, c->Fpad, w + c->pl.wd, Nh, c->Fpad, B, cd.nw, ks, c->part, c->part_ld,
+                            pstride, st); }
     if (rc) return rc;
     // x += MLP output
+    PROF(PK_NORM);
     return launch_resid_norm(d.dtype, d_x, H, c->part, ks, pstride, c->part_ld, nullptr, d.rms_eps, nullptr, 0, B, st);
   }
 
@@ -330,22 +411,26 @@ int goose_lm_head_argmax(goose_ctx* c, const void* d_packed_head, const float* d
   if (rc) return rc;
   float* logits = d_logits_or_null ? d_logits_or_null : c->logits;
   const size_t ld = d_logits_or_null ? (size_t)d.vocab : (size_t)c->Vpad;
+  static const int lm_nw = env_int("GOOSE_LM_NW", 4) == 2 ? 2 : 4;
   if (d.dtype == GOOSE_DTYPE_BF16) {
     if (d_logits_or_null && (d.vocab % 32) != 0) {
       // tiles are 32 columns wide: write into the padded workspace, then copy rows out
-      rc = launch_gemm_bf16(EPI_PARTIAL, c->xn, c->Kh, w + c->ph.wlm, c->Vpad, c->Kh, B, 1, c->logits, c->Vpad, 0, st);
+      rc = launch_gemm_bf16(EPI_PARTIAL, c->xn, c->Kh, w + c->ph.wlm, c->Vpad, c->Kh, B, lm_nw, 1, c->logits, c->Vpad, 0,
+                            st);
       if (rc) return rc;
       GOOSE_HIP_TRY(hipMemcpy2DAsync(d_logits_or_null, (size_t)d.vocab * 4, c->logits, (size_t)c->Vpad * 4,
                                      (size_t)d.vocab * 4, B, hipMemcpyDeviceToDevice, st));
       logits = c->logits;
       return launch_argmax(logits, c->Vpad, d.vocab, B, d_argmax, d_margin_or_null, st);
     }
-    rc = launch_gemm_bf16(EPI_PARTIAL, c->xn, c->Kh, w + c->ph.wlm, c->Vpad, c->Kh, B, 1, logits, ld, 0, st);
+    PROF(PK_LM_HEAD);
+    rc = launch_gemm_bf16(EPI_PARTIAL, c->xn, c->Kh, w + c->ph.wlm, c->Vpad, c->Kh, B, lm_nw, 1, logits, ld, 0, st);
   } else {
     rc = launch_gemm_f32((const float*)c->xn, c->Kh, (const float*)(w + c->ph.wlm), d.vocab, d.hidden, B, logits, ld,
                          st);
   }
   if (rc) return rc;
+  PROF(PK_ARGMAX);
   return launch_argmax(logits, ld, d.vocab, B, d_argmax, d_margin_or_null, st);
 }
 
@@ -410,6 +495,33 @@ int goose_device_flags(goose_ctx* c, void* stream, int32_t* h_flags_out) {
   GOOSE_HIP_TRY(hipMemcpyAsync(h_flags_out, c->flags, sizeof(int32_t), hipMemcpyDeviceToHost, st));
   GOOSE_HIP_TRY(hipStreamSynchronize(st));
   GOOSE_HIP_TRY(hipMemsetAsync(c->flags, 0, sizeof(int32_t), st));
+  return GOOSE_OK;
+}
+
+int goose_profile_enable(goose_ctx* c, int enable) {
+  if (!c) return GOOSE_ERR_ARG;
+  if (!c->prof) c->prof = new (std::nothrow) goose_prof();
+  if (!c->prof) return GOOSE_ERR_ARG;
+  c->prof->on = enable != 0;
+  return GOOSE_OK;
+}
+
+int goose_profile_kinds(void) { return PK_COUNT; }
+
+const char* goose_profile_kind_name(int kind) { return (kind >= 0 && kind < PK_COUNT) ? kProfNames[kind] : ""; }
+
+int goose_profile_read(goose_ctx* c, void* stream, double* h_ms_sum, int32_t* h_count) {
+  if (!c || !h_ms_sum || !h_count) return GOOSE_ERR_ARG;
+  for (int k = 0; k < PK_COUNT; ++k) { h_ms_sum[k] = 0.0; h_count[k] = 0; }
+  if (!c->prof) return GOOSE_OK;
+  GOOSE_HIP_TRY(hipStreamSynchronize(as_stream(stream)));
+  for (size_t i = 0; i < c->prof->used; ++i) {
+    float ms = 0.f;
+    GOOSE_HIP_TRY(hipEventElapsedTime(&ms, c->prof->ev[2 * i], c->prof->ev[2 * i + 1]));
+    h_ms_sum[c->prof->kind[i]] += ms;
+    ++h_count[c->prof->kind[i]];
+  }
+  c->prof->used = 0;
   return GOOSE_OK;
 }
 

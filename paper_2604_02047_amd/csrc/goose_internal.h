@@ -7,13 +7,24 @@
 
 typedef __bf16 bf16_t;
 
-#define GOOSE_HIP_TRY(expr)                    \
-  do {                                         \
-    hipError_t e_ = (expr);                    \
-    if (e_ != hipSuccess) return GOOSE_ERR_HIP; \
+// Remembers the most recent failing HIP call for goose_last_hip_error() (goose_api.hip).
+void goose_note_hip_error(hipError_t e, const char* what, int line);
+
+#define GOOSE_HIP_TRY(expr)                         \
+  do {                                              \
+    hipError_t e_ = (expr);                         \
+    if (e_ != hipSuccess) {                         \
+      goose_note_hip_error(e_, #expr, __LINE__);    \
+      return GOOSE_ERR_HIP;                         \
+    }                                               \
   } while (0)
 
-static inline int goose_launch_status() { return hipGetLastError() == hipSuccess ? GOOSE_OK : GOOSE_ERR_HIP; }
+static inline int goose_launch_status() {
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return GOOSE_OK;
+  goose_note_hip_error(e, "kernel launch", 0);
+  return GOOSE_ERR_HIP;
+}
 
 static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 static inline size_t round_up_sz(size_t x, size_t m) { return (x + m - 1) / m * m; }
@@ -26,15 +37,17 @@ struct PackedHeadLayout {
   size_t gf, wlm, total;
 };
 
+struct goose_prof;
+
 struct goose_ctx {
   goose_model_desc d;
   int max_B;   // as requested
   int Bpad;    // rounded up to 32: row count of every activation buffer
   int cap;     // cache slots per head
   int Hq;      // n_heads * head_dim
-  int Fpad;    // ffn rounded up to 64 (bf16) -- the K extent of the down projection
-  int Kh;      // hidden rounded up to 64
-  int Kq;      // Hq rounded up to 64
+  int Fpad;    // ffn rounded up to 128 -- the K extent of the down projection
+  int Kh;      // hidden rounded up to 128
+  int Kq;      // Hq rounded up to 128
   int Vpad;    // vocab rounded up to 32
   int max_splits;  // attention key splits the workspace is sized for
   int max_ksplit;  // split-K factor the partial buffer is sized for
@@ -59,6 +72,7 @@ struct goose_ctx {
   float* s_x;        // [Bpad][hidden]
   int32_t* flags;    // [1]
   int32_t* s_P;      // [1] holds a host-supplied P for kernels that read it from memory
+  goose_prof* prof;  // optional per-kernel event timing
 };
 
 // ---- small kernels (kernels_small.hip)
@@ -94,9 +108,9 @@ int launch_pack_bf16(int mode, const void* s0, const void* s1, const void* s2, i
                      int Kpad, void* dst, hipStream_t st);
 enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
 // out partials f32 [ksplit][Bpad][ldo] (EPI_PARTIAL) or bf16 h [Bpad][ldo] (EPI_SWIGLU, ksplit must be 1)
-int launch_gemm_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit,
+int launch_gemm_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw, int ksplit,
                      void* out, size_t ldo, size_t out_split_stride, hipStream_t st);
-int pick_ksplit(int Npad, int Kpad, int max_ksplit);
+void pick_gemm_config(int Npad, int Kpad, int max_ksplit, int* nw_out, int* ksplit_out);
 int launch_attn_bf16(const void* q, int ldq, const void* kc, const void* vc, int n_heads, int head_dim, int cap,
                      const int32_t* dP, int B, const uint64_t* mask, int splits, float* att_o, float* att_ml,
                      int Bpad, void* o, int ldo, hipStream_t st);

@@ -61,27 +61,64 @@ __global__ __launch_bounds__(256) void k_embed(const T* __restrict__ E, const in
 
 // ------------------------------------------------------------------------------------------
 // x[m] += sum of S partial GEMM outputs; xn[m] = T(x[m] * rsqrt(mean(x[m]^2) + eps) * g).
+// One workgroup per row, four columns per thread per pass (H is a multiple of 4), all loads of a
+// pass independent so the few rows still pull their partials at full memory parallelism.
 template <typename T>
-__global__ __launch_bounds__(256) void k_resid_norm(float* __restrict__ x, int H, const float* __restrict__ part,
-                                                    int S, size_t part_stride, size_t part_ld,
-                                                    const T* __restrict__ g, float eps, T* __restrict__ xn, int ldxn) {
+__device__ inline void store4(T* p, float a, float b, float c, float d);
+template <>
+__device__ inline void store4<float>(float* p, float a, float b, float c, float d) {
+  *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
+}
+template <>
+__device__ inline void store4<bf16_t>(bf16_t* p, float a, float b, float c, float d) {
+  typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+  bf16x4 v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
+  *reinterpret_cast<bf16x4*>(p) = v;
+}
+
+template <typename T, int NTHR>
+__global__ __launch_bounds__(NTHR) void k_resid_norm(float* __restrict__ x, int H, const float* __restrict__ part,
+                                                     int S, size_t part_stride, size_t part_ld,
+                                                     const T* __restrict__ g, float eps, T* __restrict__ xn,
+                                                     int ldxn) {
+  constexpr int MAXV = 4;  // float4 slots per thread kept in registers (H <= 16 * NTHR)
   const int m = blockIdx.x;
   float* xr = x + (size_t)m * H;
+  const int nvec = H >> 2;
+  float4 v[MAXV];
   float ss = 0.f;
-  for (int c = threadIdx.x; c < H; c += 256) {
-    float v = xr[c];
-    for (int s = 0; s < S; ++s) v += part[s * part_stride + (size_t)m * part_ld + c];
-    if (S > 0) xr[c] = v;
-    ss += v * v;
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int c4 = threadIdx.x + i * NTHR;
+    if (c4 < nvec) {
+      float4 a = *reinterpret_cast<const float4*>(xr + c4 * 4);
+      for (int s = 0; s < S; ++s) {
+        const float4 p = *reinterpret_cast<const float4*>(part + s * part_stride + (size_t)m * part_ld + c4 * 4);
+        a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+      }
+      if (S > 0) *reinterpret_cast<float4*>(xr + c4 * 4) = a;
+      ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+      v[i] = a;
+    }
   }
-  __shared__ float red[4];
+  if (xn == nullptr) return;
+  __shared__ float red[NTHR / 64];
   ss = wave_sum(ss);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
   __syncthreads();
-  if (xn == nullptr) return;
-  const float tot = red[0] + red[1] + red[2] + red[3];
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < NTHR / 64; ++w) tot += red[w];
   const float rstd = 1.0f / sqrtf(tot / (float)H + eps);
-  for (int c = threadIdx.x; c < H; c += 256) xn[(size_t)m * ldxn + c] = (T)((xr[c] * rstd) * to_f32(g[c]));
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int c4 = threadIdx.x + i * NTHR;
+    if (c4 < nvec) {
+      const T* gp = g + c4 * 4;
+      store4<T>(xn + (size_t)m * ldxn + c4 * 4, (v[i].x * rstd) * to_f32(gp[0]), (v[i].y * rstd) * to_f32(gp[1]),
+                (v[i].z * rstd) * to_f32(gp[2]), (v[i].w * rstd) * to_f32(gp[3]));
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -273,12 +310,23 @@ int launch_embed(int dtype, const void* E, const int32_t* tokens, int B, int H, 
 
 int launch_resid_norm(int dtype, float* x, int H, const float* part, int S, size_t part_stride, size_t part_ld,
                       const void* g, float eps, void* xn, int ldxn, int B, hipStream_t st) {
-  if (dtype == GOOSE_DTYPE_BF16)
-    hipLaunchKernelGGL(k_resid_norm<bf16_t>, dim3(B), dim3(256), 0, st, x, H, part, S, part_stride, part_ld,
-                       (const bf16_t*)g, eps, (bf16_t*)xn, ldxn);
-  else
-    hipLaunchKernelGGL(k_resid_norm<float>, dim3(B), dim3(256), 0, st, x, H, part, S, part_stride, part_ld,
-                       (const float*)g, eps, (float*)xn, ldxn);
+  if ((H & 3) || H > 16 * 1024) return GOOSE_ERR_SHAPE;
+  const bool big = H > 4 * 256;  // 1024 threads once a row has more than 1024 columns
+  if (dtype == GOOSE_DTYPE_BF16) {
+    if (big)
+      hipLaunchKernelGGL((k_resid_norm<bf16_t, 1024>), dim3(B), dim3(1024), 0, st, x, H, part, S, part_stride,
+                         part_ld, (const bf16_t*)g, eps, (bf16_t*)xn, ldxn);
+    else
+      hipLaunchKernelGGL((k_resid_norm<bf16_t, 256>), dim3(B), dim3(256), 0, st, x, H, part, S, part_stride, part_ld,
+                         (const bf16_t*)g, eps, (bf16_t*)xn, ldxn);
+  } else {
+    if (big)
+      hipLaunchKernelGGL((k_resid_norm<float, 1024>), dim3(B), dim3(1024), 0, st, x, H, part, S, part_stride, part_ld,
+                         (const float*)g, eps, (float*)xn, ldxn);
+    else
+      hipLaunchKernelGGL((k_resid_norm<float, 256>), dim3(B), dim3(256), 0, st, x, H, part, S, part_stride, part_ld,
+                         (const float*)g, eps, (float*)xn, ldxn);
+  }
   return goose_launch_status();
 }
 
