@@ -97,7 +97,7 @@ def main():
     K = args.steps if args.steps is not None else dflt_steps
     W = args.warmup
     total = K + W
-    cap = P0 + total * 20 + 2 * B
+    cap = (P0 + total * 20 + 2 * B + 63) // 64 * 64
     P_max = cap - B
 
     def log(msg):
@@ -282,7 +282,8 @@ def cpu_baseline(shape, gm, seed, B, P0, tree_kind, log):
     om = orc.OracleModel(shape.n_heads, shape.head_dim, shape.rope_base, shape.rms_eps, layers,
                          f64(gm.embed), f64(gi.lm_head(shape, seed, gm.device)),
                          f64(gi.final_norm(shape, seed, gm.device)))
-    cache = [(f64(gm.kcache[l, :, :P0]), f64(gm.vcache[l, :, :P0])) for l in range(n_s)]
+    vr = gm.v_rows(0, P0)
+    cache = [(f64(gm.kcache[l, :, :P0]), f64(vr[l])) for l in range(n_s)]
     tree = make_tree(tree_kind, 0)
     toks = gi.draft_tokens_uniform(seed, tree.parent, shape.vocab, 1)
     anc, depth = orc.ancestor_mask(tree.parent)

@@ -36,10 +36,11 @@
  * GOOSE_DTYPE_BF16 (MFMA kernels, fp32 accumulation) or GOOSE_DTYPE_F32 (plain fp32
  * kernels for small models).  The residual stream x is always fp32 [B][hidden].
  *
- * KV cache: two allocations, K and V, each T[n_layers][n_heads][cap][head_dim];
- * K is stored after the rotary embedding.  verify_layer writes slots [P, P+B) of its
- * layer, compact_kv rewrites slots [P, P+L] of every layer; slots above P+L hold
- * leftovers afterwards.
+ * KV cache: two allocations.  K is T[n_layers][n_heads][cap][head_dim], stored after the
+ * rotary embedding.  V is stored TRANSPOSED, T[n_layers][n_heads][head_dim][cap], so that the
+ * attention kernel reads 16 contiguous bytes of one head-dim row across slots.  cap must be a
+ * multiple of 64.  verify_layer writes slots [P, P+B) of its layer, compact_kv rewrites
+ * slots [P, P+L] of every layer; slots above P+L hold leftovers afterwards.
  */
 #ifndef GOOSE_H
 #define GOOSE_H
@@ -87,7 +88,7 @@ const char* goose_strerror(int status);
 const char* goose_last_hip_error(void);
 
 /* Creates a context with workspace for trees of up to max_B nodes and caches of `cap`
- * slots per head.  Allocates device memory on the current device. */
+ * slots per head (a multiple of 64).  Allocates device memory on the current device. */
 int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** out);
 void goose_destroy(goose_ctx* ctx);
 
@@ -122,7 +123,8 @@ int goose_build_mask(goose_ctx* ctx, const int32_t* d_parent, int B, int P, cons
 int goose_embed(goose_ctx* ctx, const void* d_embed, const int32_t* d_tokens, int B, float* d_x, void* stream);
 
 /* ---- 3. one decoder layer over the B packed nodes (Alg. 2 line 1, per layer) ------------
- * d_x fp32 [B][hidden], updated in place.  d_kcache/d_vcache: THIS layer's T[n_heads][cap][head_dim].
+ * d_x fp32 [B][hidden], updated in place.  d_kcache: THIS layer's T[n_heads][cap][head_dim];
+ * d_vcache: THIS layer's transposed T[n_heads][head_dim][cap].
  * d_mask/d_pos as written by goose_build_mask.  P from *d_P when d_P != NULL (then the
  * argument P must be an upper bound of *d_P; it sizes the launch), else the argument. */
 int goose_verify_layer(goose_ctx* ctx, const void* d_packed_layer, float* d_x, void* d_kcache, void* d_vcache,
@@ -151,7 +153,7 @@ int goose_accept(goose_ctx* ctx, const int32_t* d_parent, const int32_t* d_token
  * accepted nodes become cache slots P..P+L; valid because a node's K was rotated at
  * P + depth and depth(path[j]) = j).  Exact byte copies.  The paper does not describe
  * cache handling; this is the standard commit of tree speculation.
- * d_kcache_all/d_vcache_all: the whole T[n_layers][n_heads][cap][head_dim] allocations.
+ * d_kcache_all/d_vcache_all: the whole K and (transposed) V allocations, all layers.
  * If d_new_P_or_null != NULL it receives P + L + 1 (it may alias d_P). */
 int goose_compact_kv(goose_ctx* ctx, void* d_kcache_all, void* d_vcache_all, int P, const int32_t* d_P,
                      const int32_t* d_path, const int32_t* d_accept_len, int32_t* d_new_P_or_null, void* stream);

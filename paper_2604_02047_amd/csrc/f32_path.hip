@@ -54,7 +54,7 @@ __global__ __launch_bounds__(64) void k_attn_f32(const float* __restrict__ q, in
   __syncthreads();
   const float scale = 1.0f / sqrtf((float)head_dim);
   const float* kh = kc + (size_t)h * cap * head_dim;
-  const float* vh = vc + (size_t)h * cap * head_dim;
+  const float* vh = vc + (size_t)h * head_dim * cap;  // transposed value cache Vt[head][d][slot]
   float mx = -INFINITY;
   for (int s = lane; s < nk; s += 64) {
     bool vis = s < P;
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(64) void k_attn_f32(const float* __restrict__ q, in
     float acc = 0.f;
     for (int s = 0; s < nk; ++s) {
       const float p = sc[s];
-      if (p != 0.f) acc += p * vh[(size_t)s * head_dim + c];
+      if (p != 0.f) acc += p * vh[(size_t)c * cap + s];
     }
     o[(size_t)i * ldo + h * head_dim + c] = acc / sum;
   }

@@ -160,7 +160,7 @@ int goose_check_parent(const int32_t* h_parent, int B) {
 int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** out) {
   if (!desc || !out) return GOOSE_ERR_ARG;
   *out = nullptr;
-  if (max_B < 1 || max_B > GOOSE_MAX_B || cap < max_B) return GOOSE_ERR_ARG;
+  if (max_B < 1 || max_B > GOOSE_MAX_B || cap < max_B || (cap % 64) != 0) return GOOSE_ERR_ARG;
   const goose_model_desc& d = *desc;
   if (d.n_layers < 1 || d.hidden < 1 || d.n_heads < 1 || d.head_dim < 2 || d.ffn < 1 || d.vocab < 1)
     return GOOSE_ERR_ARG;
@@ -177,7 +177,7 @@ int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** o
   memset(c, 0, sizeof(*c));
   c->d = d;
   c->max_B = max_B;
-  c->Bpad = round_up(max_B, 32);
+  c->Bpad = max_B <= 32 ? 32 : (max_B <= 64 ? 64 : 128);
   c->cap = cap;
   c->Hq = d.n_heads * d.head_dim;
   c->Kh = round_up(d.hidden, 128);

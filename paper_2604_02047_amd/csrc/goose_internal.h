@@ -42,7 +42,7 @@ struct goose_prof;
 struct goose_ctx {
   goose_model_desc d;
   int max_B;   // as requested
-  int Bpad;    // rounded up to 32: row count of every activation buffer
+  int Bpad;    // 32, 64 or 128: row count of every activation buffer
   int cap;     // cache slots per head
   int Hq;      // n_heads * head_dim
   int Fpad;    // ffn rounded up to 128 -- the K extent of the down projection

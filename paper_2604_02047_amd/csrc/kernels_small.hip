@@ -124,12 +124,13 @@ __global__ __launch_bounds__(NTHR) void k_resid_norm(float* __restrict__ x, int 
 // ------------------------------------------------------------------------------------------
 // Sum the split-K partials of the fused q|k|v projection, rotate q and k by the node's
 // position (half-split pairing (j, j+d/2), angle pos * base^(-2j/d)) and store q for the
-// attention kernel and k, v into cache slot P + m.
+// attention kernel, k into cache slot P + m of K[head][slot][d], and v into the TRANSPOSED
+// value cache Vt[head][d][slot].  Grid (node, head); thread j owns the pair (j, j + d/2).
 template <typename T>
 __global__ void k_rope_kv(const float* __restrict__ part, int S, size_t part_stride, size_t part_ld, int n_heads,
                           int head_dim, const int32_t* __restrict__ pos, const double* __restrict__ inv_freq,
                           const int32_t* __restrict__ dP, int cap, T* __restrict__ qout, int ldq,
-                          T* __restrict__ kcache, T* __restrict__ vcache) {
+                          T* __restrict__ kcache, T* __restrict__ vtcache) {
   const int m = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
   const int half = head_dim >> 1;
   const int Hq = n_heads * head_dim;
@@ -159,8 +160,9 @@ __global__ void k_rope_kv(const float* __restrict__ part, int S, size_t part_str
   const size_t row = ((size_t)h * cap + slot) * head_dim + j;
   kcache[row] = (T)k1;
   kcache[row + half] = (T)k2;
-  vcache[row] = (T)v6[4];
-  vcache[row + half] = (T)v6[5];
+  T* vcol = vtcache + ((size_t)h * head_dim + j) * cap + slot;
+  vcol[0] = (T)v6[4];
+  vcol[(size_t)half * cap] = (T)v6[5];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -258,17 +260,16 @@ __global__ __launch_bounds__(128) void k_accept(const int32_t* __restrict__ pare
 }
 
 // ------------------------------------------------------------------------------------------
-// Move cache rows P + path[j] -> P + j, j = 1..L, in every (layer, K|V, head).  One thread
-// owns one 16-byte column chunk of all rows and walks j upward: path[j] >= j, so a row is
-// always read before the same thread can overwrite it.
-__global__ __launch_bounds__(64) void k_compact(uint4* __restrict__ kall, uint4* __restrict__ vall, int n_heads,
-                                                int cap, int row_chunks, const int32_t* __restrict__ dP,
-                                                const int32_t* __restrict__ path,
-                                                const int32_t* __restrict__ accept_len) {
+// Commit of the accepted path: cache slot P + path[j] -> slot P + j, j = 1..L, in every layer and head.
+// K[head][slot][d]: one thread owns one 16-byte column chunk of all rows.  Vt[head][d][slot]: one thread
+// owns one d-row and moves single elements along it.  Either way a thread walks j upward and
+// path[j] >= j, so a slot is always read before the same thread can overwrite it.
+__global__ __launch_bounds__(64) void k_compact_k(uint4* __restrict__ kall, int cap, int row_chunks,
+                                                  const int32_t* __restrict__ dP, const int32_t* __restrict__ path,
+                                                  const int32_t* __restrict__ accept_len) {
   const int c = threadIdx.x;
   if (c >= row_chunks) return;
-  const int lh = blockIdx.x;  // layer * n_heads + head
-  uint4* base = (blockIdx.y == 0 ? kall : vall) + (size_t)lh * cap * row_chunks;
+  uint4* base = kall + (size_t)blockIdx.x * cap * row_chunks;  // blockIdx.x = layer * n_heads + head
   const int P = *dP;
   int L = *accept_len;
   if (L > GOOSE_MAX_B - 1) L = GOOSE_MAX_B - 1;
@@ -276,6 +277,21 @@ __global__ __launch_bounds__(64) void k_compact(uint4* __restrict__ kall, uint4*
     const int src = path[j];
     if (src < j || src >= GOOSE_MAX_B || P + src >= cap) break;  // malformed path: stop, stay in bounds
     if (src != j) base[(size_t)(P + j) * row_chunks + c] = base[(size_t)(P + src) * row_chunks + c];
+  }
+}
+
+template <typename T>
+__global__ void k_compact_vt(T* __restrict__ vall, int cap, int head_dim, const int32_t* __restrict__ dP,
+                             const int32_t* __restrict__ path, const int32_t* __restrict__ accept_len) {
+  const int c = threadIdx.x;  // d index
+  T* base = vall + ((size_t)blockIdx.x * head_dim + c) * cap;
+  const int P = *dP;
+  int L = *accept_len;
+  if (L > GOOSE_MAX_B - 1) L = GOOSE_MAX_B - 1;
+  for (int j = 1; j <= L; ++j) {
+    const int src = path[j];
+    if (src < j || src >= GOOSE_MAX_B || P + src >= cap) break;
+    if (src != j) base[P + j] = base[P + src];
   }
 }
 
@@ -364,9 +380,17 @@ int launch_compact(int elem_bytes, void* kall, void* vall, int n_layers, int n_h
                    const int32_t* dP, const int32_t* path, const int32_t* accept_len, int32_t* new_P,
                    hipStream_t st) {
   const int row_chunks = head_dim * elem_bytes / 16;  // <= 64 for head_dim <= 256 (fp32)
-  hipLaunchKernelGGL(k_compact, dim3(n_layers * n_heads, 2), dim3(64), 0, st, (uint4*)kall, (uint4*)vall, n_heads,
-                     cap, row_chunks, dP, path, accept_len);
+  hipLaunchKernelGGL(k_compact_k, dim3(n_layers * n_heads), dim3(64), 0, st, (uint4*)kall, cap, row_chunks, dP, path,
+                     accept_len);
   int rc = goose_launch_status();
+  if (rc != GOOSE_OK) return rc;
+  if (elem_bytes == 2)
+    hipLaunchKernelGGL(k_compact_vt<bf16_t>, dim3(n_layers * n_heads), dim3(head_dim), 0, st, (bf16_t*)vall, cap,
+                       head_dim, dP, path, accept_len);
+  else
+    hipLaunchKernelGGL(k_compact_vt<float>, dim3(n_layers * n_heads), dim3(head_dim), 0, st, (float*)vall, cap,
+                       head_dim, dP, path, accept_len);
+  rc = goose_launch_status();
   if (rc != GOOSE_OK) return rc;
   if (new_P) {
     hipLaunchKernelGGL(k_new_P, dim3(1), dim3(1), 0, st, dP, accept_len, new_P);

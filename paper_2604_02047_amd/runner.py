@@ -37,9 +37,10 @@ class GooseModel:
         self.ctx.goose_pack_lm_head(gf, wl, self.packed_head)
         torch.cuda.synchronize()
         del wl, gf
-        shape = (desc.n_layers, desc.n_heads, cap, desc.head_dim)
-        self.kcache = torch.zeros(shape, dtype=self.dt, device=self.device)
-        self.vcache = torch.zeros(shape, dtype=self.dt, device=self.device)
+        assert cap % 64 == 0, "cap must be a multiple of 64"
+        # K[layer][head][slot][d]; V is kept transposed, Vt[layer][head][d][slot]
+        self.kcache = torch.zeros((desc.n_layers, desc.n_heads, cap, desc.head_dim), dtype=self.dt, device=self.device)
+        self.vcache = torch.zeros((desc.n_layers, desc.n_heads, desc.head_dim, cap), dtype=self.dt, device=self.device)
         self.P = 0
         i32 = dict(dtype=torch.int32, device=self.device)
         self.d_P = torch.zeros(1, **i32)
@@ -55,6 +56,10 @@ class GooseModel:
 
     def packed_layer(self, l):
         return self.packed_layers[l * self.layer_bytes:(l + 1) * self.layer_bytes]
+
+    def v_rows(self, a, b):
+        """Value rows of slots [a,b) as [layer][head][slot][d] (a copy; the cache itself is transposed)."""
+        return self.vcache[:, :, :, a:b].transpose(2, 3).contiguous()
 
     def set_P(self, P: int):
         self.P = int(P)
@@ -92,7 +97,7 @@ class GooseModel:
         out = {"mask": mask.clone().view(B, W), "depth": self.depth[:B].clone(), "pos": self.pos[:B].clone(),
                "argmax": self.argmax[:B].clone(), "margin": self.margin[:B].clone(), "logits": logits,
                "tail_k": self.kcache[:, :, self.P:self.P + B].clone(),
-               "tail_v": self.vcache[:, :, self.P:self.P + B].clone()}
+               "tail_v": self.v_rows(self.P, self.P + B)}
         if commit:
             new_P = torch.zeros(1, dtype=torch.int32, device=self.device)
             c.goose_compact_kv(self.kcache, self.vcache, self.P, self.path, self.accept_len, new_P)

@@ -93,40 +93,43 @@ def test_compact_kv_bit_exact(dtype):
     from paper_2604_02047_amd import GooseContext, ModelDesc
     dev = "cuda:0"
     shape = gi.SHAPES["tiny"] if dtype == "f32" else gi.SHAPES["tiny_bf16"]
-    cap = 300
+    cap = 320
     c = GooseContext(ModelDesc.from_shape(shape), 128, cap)
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
-    dims = (shape.n_layers, shape.n_heads, cap, shape.head_dim)
+    kdims = (shape.n_layers, shape.n_heads, cap, shape.head_dim)
     rng = np.random.default_rng(1)
     cases = [[0], [0, 1, 2, 3], [0, 2, 3], [0, 5, 9, 64, 127], [0, 127], list(range(0, 128, 1))[:40],
              [0, 3, 4, 5, 6, 40, 41]]
     for n, path in enumerate(cases):
         P = int(rng.integers(0, cap - 128))
-        k = torch.randn(dims, device=dev).to(tdt)
-        v = torch.randn(dims, device=dev).to(tdt)
-        k0, v0 = k.clone(), v.clone()
+        k = torch.randn(kdims, device=dev).to(tdt)
+        v_rows = torch.randn(kdims, device=dev).to(tdt)          # logical [layer][head][slot][d]
+        vt = v_rows.transpose(2, 3).contiguous()                  # stored transposed [layer][head][d][slot]
+        k0, v0 = k.clone(), v_rows.clone()
         L = len(path) - 1
         dpath = torch.full((128,), -1, dtype=torch.int32, device=dev)
         dpath[:L + 1] = torch.tensor(path, dtype=torch.int32)
         dlen = torch.tensor([L], dtype=torch.int32, device=dev)
         newP = torch.zeros(1, dtype=torch.int32, device=dev)
         if n % 2:
-            c.goose_compact_kv(k, v, P, dpath, dlen, newP)
+            c.goose_compact_kv(k, vt, P, dpath, dlen, newP)
         else:  # P from device memory, updated in place
             newP.fill_(P)
-            c.goose_compact_kv(k, v, 0, dpath, dlen, newP, d_P=newP)
+            c.goose_compact_kv(k, vt, 0, dpath, dlen, newP, d_P=newP)
         torch.cuda.synchronize()
+        v = vt.transpose(2, 3)
         assert int(newP.item()) == P + L + 1
         idx = torch.tensor(path, device=dev) + P
         # slots [0,P) untouched, [P, P+L] are the path rows, byte for byte
         assert torch.equal(k[:, :, :P], k0[:, :, :P]) and torch.equal(v[:, :, :P], v0[:, :, :P])
         assert torch.equal(k[:, :, P:P + L + 1], k0[:, :, idx]) and torch.equal(v[:, :, P:P + L + 1], v0[:, :, idx])
         # and identical to the oracle's commit of the same rows
-        cache = [(k0[l, :, :P].double().cpu().numpy(), v0[l, :, :P].double().cpu().numpy()) for l in range(dims[0])]
+        nl = kdims[0]
+        cache = [(k0[l, :, :P].double().cpu().numpy(), v0[l, :, :P].double().cpu().numpy()) for l in range(nl)]
         new_kv = [(k0[l, :, P:P + 128].double().cpu().numpy(), v0[l, :, P:P + 128].double().cpu().numpy())
-                  for l in range(dims[0])]
+                  for l in range(nl)]
         ref = orc.commit_path(cache, new_kv, path)
-        for l in range(dims[0]):
+        for l in range(nl):
             assert np.array_equal(k[l, :, :P + L + 1].double().cpu().numpy(), ref[l][0])
             assert np.array_equal(v[l, :, :P + L + 1].double().cpu().numpy(), ref[l][1])
     c.close()

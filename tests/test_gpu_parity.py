@@ -76,7 +76,7 @@ def _compare_step(shape, gm, om, cache, tokens, tree, tol, check_hidden=True):
     idx = torch.as_tensor([0] + acc, device=gm.device)
     assert gm.P == P + L + 1
     assert torch.equal(gm.kcache[:, :, P:P + L + 1], g["tail_k"][:, :, idx])
-    assert torch.equal(gm.vcache[:, :, P:P + L + 1], g["tail_v"][:, :, idx])
+    assert torch.equal(gm.v_rows(P, P + L + 1), g["tail_v"][:, :, idx])
     return g, o, decisive
 
 
@@ -85,7 +85,7 @@ def _run_cycles(shape_name, n_cycles, P0, trees, seed, oracle_prefill, chunk=16,
     tol = TOL[shape.dtype]
     tm = torch_model(shape, seed=seed, gain_jitter=0.1)
     om = oracle_model(shape, tm)
-    gm = gpu_model(shape, tm, max_B=128, cap=P0 + 128 * (n_cycles + 1))
+    gm = gpu_model(shape, tm, max_B=128, cap=(P0 + 128 * (n_cycles + 1) + 63) // 64 * 64)
     prefix = gi.prefix_tokens(seed, P0, shape.vocab)
     last = _gpu_prefill(gm, prefix, chunk)
     if oracle_prefill:

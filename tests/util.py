@@ -56,11 +56,12 @@ def load_prefix_cache(gm, cache):
     P = cache[0][0].shape[1]
     for l, (k, v) in enumerate(cache):
         gm.kcache[l, :, :P] = torch.from_numpy(k).to(gm.dt).to(gm.device)
-        gm.vcache[l, :, :P] = torch.from_numpy(v).to(gm.dt).to(gm.device)
+        gm.vcache[l, :, :, :P] = torch.from_numpy(v).to(gm.dt).to(gm.device).transpose(1, 2)
     gm.set_P(P)
 
 
 def device_cache_as_oracle(gm, P):
     """The device cache's first P slots as an oracle cache (exact upcast of the stored values)."""
-    return [(gm.kcache[l, :, :P].to(torch.float64).cpu().numpy(), gm.vcache[l, :, :P].to(torch.float64).cpu().numpy())
+    vr = gm.v_rows(0, P)
+    return [(gm.kcache[l, :, :P].to(torch.float64).cpu().numpy(), vr[l].to(torch.float64).cpu().numpy())
             for l in range(gm.desc.n_layers)]
