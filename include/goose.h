@@ -191,6 +191,23 @@ int goose_verify_step(goose_ctx* ctx, const goose_model_ptrs* model, const goose
  * array that is not topological.  Synchronises `stream`. */
 int goose_device_flags(goose_ctx* ctx, void* stream, int32_t* h_flags_out);
 
+/* ---- the projection kernel on its own (unit tests and tuning; bf16 only) ---------------------
+ * out[m][n] = sum_k A[m][k] * W[n][k] for the skinny-M shapes of the pass (M = B <= 128 tree nodes).
+ * goose_pack_matrix re-tiles a row-major bf16 W[N][K] into goose_packed_matrix_bytes(N, K) bytes
+ * (N padded to 32, K to 128, zero filled).  goose_gemm_packed multiplies: d_a is bf16 with
+ * round_up(B,32) readable rows of lda >= round_up(K,128) elements (columns K.. must be finite),
+ * nw = 2 or 4 column tiles per workgroup, ksplit = split-K factor (every split non-empty).
+ * d_partials receives fp32 [ksplit][round_up(B,32)][round_up(N,32)]; the result is the sum over
+ * the first index, rows < B (other rows are not written). */
+size_t goose_packed_matrix_bytes(int N, int K);
+int goose_pack_matrix(const void* d_w, int N, int K, void* d_packed, void* stream);
+int goose_gemm_packed(const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, int ksplit,
+                      float* d_partials, void* stream);
+/* Same product with the fused SwiGLU epilogue: the N rows of W (N a multiple of 64) alternate in blocks
+ * of 32 between gate rows and up rows; d_h bf16 [B][ldh] receives silu(gate) * up, N/2 columns. */
+int goose_gemm_swiglu_packed(const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, void* d_h,
+                             int ldh, void* stream);
+
 /* ---- diagnostics: per-kernel timing --------------------------------------------------------
  * While enabled, every kernel launch of verify_layer / lm_head_argmax is bracketed by two
  * hipEvents recorded on the caller's stream (this adds gaps between kernels: use it to time

@@ -9,6 +9,10 @@ from .binding import (  # noqa: F401
     GooseContext,
     ModelDesc,
     goose_check_parent,
+    goose_packed_matrix_bytes,
+    goose_pack_matrix,
+    goose_gemm_packed,
+    goose_gemm_swiglu_packed,
     lib_path,
     load_library,
     EXPORTS,

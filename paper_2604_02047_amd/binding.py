@@ -17,6 +17,7 @@ EXPORTS = [
     "goose_packed_layer_bytes", "goose_pack_layer", "goose_packed_lm_head_bytes", "goose_pack_lm_head",
     "goose_build_mask", "goose_embed", "goose_verify_layer", "goose_lm_head_argmax",
     "goose_accept", "goose_compact_kv", "goose_verify_step", "goose_device_flags",
+    "goose_packed_matrix_bytes", "goose_pack_matrix", "goose_gemm_packed", "goose_gemm_swiglu_packed",
     "goose_profile_enable", "goose_profile_kinds", "goose_profile_kind_name", "goose_profile_read",
 ]
 
@@ -110,6 +111,12 @@ def load_library():
     lib.goose_verify_step.argtypes = [C.c_void_p, C.POINTER(_ModelPtrs), C.POINTER(_StepIO), C.c_int, C.c_int,
                                       C.c_void_p]
     lib.goose_device_flags.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
+    lib.goose_packed_matrix_bytes.argtypes = [C.c_int, C.c_int]
+    lib.goose_packed_matrix_bytes.restype = C.c_size_t
+    lib.goose_pack_matrix.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+    lib.goose_gemm_packed.argtypes = [C.c_void_p, C.c_int, C.c_void_p] + [C.c_int] * 5 + [C.c_void_p, C.c_void_p]
+    lib.goose_gemm_swiglu_packed.argtypes = [C.c_void_p, C.c_int, C.c_void_p] + [C.c_int] * 4 + [C.c_void_p, C.c_int,
+                                                                                                C.c_void_p]
     lib.goose_profile_enable.argtypes = [C.c_void_p, C.c_int]
     lib.goose_profile_kinds.argtypes = []
     lib.goose_profile_kind_name.argtypes = [C.c_int]
@@ -118,7 +125,7 @@ def load_library():
     for name in EXPORTS:
         fn = getattr(lib, name)
         if name not in ("goose_strerror", "goose_last_hip_error", "goose_destroy", "goose_packed_layer_bytes", "goose_packed_lm_head_bytes",
-                        "goose_profile_kind_name"):
+                        "goose_profile_kind_name", "goose_packed_matrix_bytes"):
             fn.restype = C.c_int
     _lib = lib
     return lib
@@ -146,6 +153,24 @@ def goose_check_parent(parent) -> int:
         return load_library().goose_check_parent(None, 0)
     a = np.ascontiguousarray(np.asarray(parent, dtype=np.int32))
     return load_library().goose_check_parent(a.ctypes.data_as(C.c_void_p), int(a.shape[0]))
+
+
+def goose_packed_matrix_bytes(N: int, K: int) -> int:
+    return int(load_library().goose_packed_matrix_bytes(N, K))
+
+
+def goose_pack_matrix(w, N, K, packed):
+    _check(load_library().goose_pack_matrix(_ptr(w), N, K, _ptr(packed), _stream()), "goose_pack_matrix")
+
+
+def goose_gemm_packed(a, lda, packed, N, K, B, nw, ksplit, partials):
+    _check(load_library().goose_gemm_packed(_ptr(a), lda, _ptr(packed), N, K, B, nw, ksplit, _ptr(partials), _stream()),
+           "goose_gemm_packed")
+
+
+def goose_gemm_swiglu_packed(a, lda, packed, N, K, B, nw, h, ldh):
+    _check(load_library().goose_gemm_swiglu_packed(_ptr(a), lda, _ptr(packed), N, K, B, nw, _ptr(h), ldh, _stream()),
+           "goose_gemm_swiglu_packed")
 
 
 def _ptr(t):

@@ -498,6 +498,40 @@ int goose_device_flags(goose_ctx* c, void* stream, int32_t* h_flags_out) {
   return GOOSE_OK;
 }
 
+// ---- the projection kernel on its own (unit tests, tuning) -----------------------------------
+size_t goose_packed_matrix_bytes(int N, int K) {
+  if (N < 1 || K < 1) return 0;
+  return (size_t)round_up(N, 32) * round_up(K, 128) * 2;
+}
+
+int goose_pack_matrix(const void* d_w, int N, int K, void* d_packed, void* stream) {
+  if (!d_w || !d_packed || N < 1 || K < 1) return GOOSE_ERR_ARG;
+  return launch_pack_bf16(PACK_PLAIN, d_w, nullptr, nullptr, N, K, round_up(N, 32), round_up(K, 128), d_packed,
+                          as_stream(stream));
+}
+
+int goose_gemm_swiglu_packed(const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, void* d_h,
+                             int ldh, void* stream) {
+  if (!d_a || !d_packed || !d_h || N < 64 || (N % 64) != 0 || K < 1) return GOOSE_ERR_ARG;
+  if (B < 1 || B > GOOSE_MAX_B || (nw != 2 && nw != 4)) return GOOSE_ERR_ARG;
+  const int Kpad = round_up(K, 128);
+  if (lda < Kpad || (lda % 8) != 0 || ldh < N / 2) return GOOSE_ERR_ARG;
+  return launch_gemm_bf16(EPI_SWIGLU, d_a, lda, d_packed, N, Kpad, B, nw, 1, d_h, (size_t)ldh, 0, as_stream(stream));
+}
+
+int goose_gemm_packed(const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, int ksplit,
+                      float* d_partials, void* stream) {
+  if (!d_a || !d_packed || !d_partials || N < 1 || K < 1) return GOOSE_ERR_ARG;
+  if (B < 1 || B > GOOSE_MAX_B || (nw != 2 && nw != 4) || ksplit < 1) return GOOSE_ERR_ARG;
+  const int Npad = round_up(N, 32), Kpad = round_up(K, 128);
+  if (lda < Kpad || (lda % 8) != 0) return GOOSE_ERR_ARG;
+  const int nstages = Kpad / 128;
+  if (ksplit > nstages || ((nstages + ksplit - 1) / ksplit) * (ksplit - 1) >= nstages) return GOOSE_ERR_ARG;
+  const int rows = round_up(B, 32);
+  return launch_gemm_bf16(EPI_PARTIAL, d_a, lda, d_packed, Npad, Kpad, B, nw, ksplit, d_partials, (size_t)Npad,
+                          (size_t)rows * Npad, as_stream(stream));
+}
+
 int goose_profile_enable(goose_ctx* c, int enable) {
   if (!c) return GOOSE_ERR_ARG;
   if (!c->prof) c->prof = new (std::nothrow) goose_prof();

@@ -1,0 +1,82 @@
+"""The skinny-M projection kernel alone against an fp64 product of the same bf16 inputs."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2604_02047_amd as g
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(B, N, K, nw, ks, seed=0):
+    dev = "cuda:0"
+    gen = torch.Generator(device="cpu").manual_seed(seed)
+    Kp, Np, rows = (K + 127) // 128 * 128, (N + 31) // 32 * 32, (B + 31) // 32 * 32
+    a = torch.zeros((rows, Kp), dtype=torch.bfloat16)
+    a[:B, :K] = (torch.randn((B, K), generator=gen)).to(torch.bfloat16)
+    w = (torch.randn((N, K), generator=gen) * 0.05).to(torch.bfloat16)
+    ref = a[:B, :K].double().numpy() @ w.double().numpy().T
+    packed = torch.zeros(g.goose_packed_matrix_bytes(N, K), dtype=torch.uint8, device=dev)
+    g.goose_pack_matrix(w.to(dev), N, K, packed)
+    part = torch.full((ks, rows, Np), float("nan"), dtype=torch.float32, device=dev)
+    g.goose_gemm_packed(a.to(dev), Kp, packed, N, K, B, nw, ks, part)
+    torch.cuda.synchronize()
+    out = part[:, :B, :N].double().sum(0).cpu().numpy()
+    scale = np.abs(ref).max()
+    err = np.abs(out - ref).max()
+    # fp32 accumulation of exact bf16 products: only summation-order rounding remains
+    assert err <= 2e-5 * scale * max(1.0, np.sqrt(K) / 16), (B, N, K, nw, ks, err, scale)
+
+
+@pytest.mark.parametrize("B", [1, 16, 33, 64, 80, 128])
+def test_gemm_row_tiles(B):
+    _run(B, 256, 512, 2, 1)
+    _run(B, 288, 1024, 4, 2)
+
+
+@pytest.mark.parametrize("stages,ks", [(1, 1), (2, 1), (2, 2), (3, 1), (3, 3), (4, 2), (5, 1), (5, 2), (6, 3),
+                                       (8, 2), (9, 2), (22, 5), (32, 1), (32, 4), (86, 8)])
+def test_gemm_stage_counts_and_splits(stages, ks):
+    for nw in (2, 4):
+        for B in (64, 16, 96):
+            _run(B, 160, stages * 128, nw, ks, seed=stages)
+
+
+def test_gemm_ragged_shapes():
+    _run(50, 1000, 1000, 4, 2)   # N not a multiple of the 4-tile group, K padded to 1024
+    _run(7, 40, 200, 2, 1)
+    _run(64, 4096, 4096, 4, 8)
+
+
+@pytest.mark.parametrize("B,F,K,nw", [(16, 96, 256, 2), (16, 2752, 1024, 2), (64, 2752, 1024, 4), (80, 352, 640, 2),
+                                       (128, 704, 256, 4), (33, 64, 4096, 2)])
+def test_gemm_swiglu_epilogue(B, F, K, nw):
+    dev = "cuda:0"
+    gen = torch.Generator(device="cpu").manual_seed(F)
+    Kp, rows = (K + 127) // 128 * 128, (B + 31) // 32 * 32
+    a = torch.zeros((rows, Kp), dtype=torch.bfloat16)
+    a[:B, :K] = torch.randn((B, K), generator=gen).to(torch.bfloat16)
+    wg = (torch.randn((F, K), generator=gen) * 0.05).to(torch.bfloat16)
+    wu = (torch.randn((F, K), generator=gen) * 0.05).to(torch.bfloat16)
+    assert F % 32 == 0
+    inter = torch.stack([wg.view(F // 32, 32, K), wu.view(F // 32, 32, K)], dim=1).reshape(2 * F, K).contiguous()
+    gd, ud = a[:B, :K].double() @ wg.double().T, a[:B, :K].double() @ wu.double().T
+    ref = (gd / (1 + torch.exp(-gd)) * ud).numpy()
+    packed = torch.zeros(g.goose_packed_matrix_bytes(2 * F, K), dtype=torch.uint8, device=dev)
+    g.goose_pack_matrix(inter.to(dev), 2 * F, K, packed)
+    h = torch.full((rows, F), float("nan"), dtype=torch.bfloat16, device=dev)
+    g.goose_gemm_swiglu_packed(a.to(dev), Kp, packed, 2 * F, K, B, nw, h, F)
+    torch.cuda.synchronize()
+    out = h[:B].double().cpu().numpy()
+    assert np.abs(out - ref).max() <= 6e-3 * np.abs(ref).max()  # one bf16 rounding of the result
+
+
+def test_gemm_repeated_large_launches_are_stable():
+    """The weight stream is hand scheduled (asynchronous loads awaited by count): hammer the
+    big shapes of the 7B model, where memory latency is longest, and check every launch."""
+    for rep in range(6):
+        _run(64, 4096, 4096, 4, 8, seed=rep)
+        _run(64, 4096, 11008, 4, 8, seed=rep)
+        _run(64, 2048, 4096, 2, 1, seed=rep)
+        _run(16, 4096, 4096, 2, 4, seed=rep)
+        _run(128, 1024, 4096, 4, 2, seed=rep)
