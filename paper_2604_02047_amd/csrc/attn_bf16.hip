@@ -283,11 +283,14 @@ int launch_qt(int QT, dim3 grid, hipStream_t st, const bf16_t* q, int ldq, const
 
 }  // namespace
 
-// Key splits: short prefixes get one 64-key tile per workgroup (latency bound: as parallel as
-// possible); long ones enough splits for about four workgroups per compute unit.
+// Key splits per head: at least two 64-key tiles per workgroup, about one workgroup per compute
+// unit (two for long prefixes).
 int pick_attn_splits(int n_heads, int keys_max, int max_splits) {
-  int s = (keys_max + TK - 1) / TK;
-  const int want = (1024 + n_heads - 1) / n_heads;
+  // one workgroup per CU (256) measured faster than more, shorter splits: a split of one tile has
+  // nothing to overlap its loads with, and every split adds a partial result to merge
+  const int tiles = (keys_max + TK - 1) / TK;
+  int s = (tiles + 1) / 2;
+  const int want = ((tiles > 64 ? 512 : 256) + n_heads - 1) / n_heads;
   if (s > want) s = want;
   if (s > max_splits) s = max_splits;
   if (s < 1) s = 1;

@@ -15,6 +15,7 @@
 #include <type_traits>
 
 #include "goose_internal.h"
+#include <climits>
 
 namespace {
 
@@ -22,8 +23,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int KC = 128;              // k extent of one LDS stage
-constexpr int LDS_ROW = KC * 2 + 16;  // bytes; the 16-byte pad staggers rows across banks
+constexpr int KGRAN = 128;  // granularity of K padding and of split-K ranges (inputs)
 
 // ------------------------------------------------------------------------------------------
 // Re-tile raw row-major bf16 matrices.  Packed row n comes from
@@ -67,121 +67,46 @@ __global__ __launch_bounds__(256) void k_pack_bf16(int mode, const bf16_t* __res
 }
 
 // ------------------------------------------------------------------------------------------
-// One workgroup = NW compute wavefronts + 1 loader wavefront.
-//   * Compute wavefront w owns column tile blockIdx.x*NW + w (32 columns) and all MT row tiles;
-//     blockIdx.y selects the split-K range.  Its only global loads are weight operands, kept in a
-//     register ring of RING stages (8 loads = 8 KiB each): a slot is refilled for stage st+RING
-//     right after the MFMAs of stage st consumed it.  Loads retire in order, so with nothing else
-//     in the wavefront's load queue the compiler can wait for exactly the operand it needs and
-//     RING*8 - 1 loads stay in flight all the time.
-//   * The loader wavefront copies the A stages global -> registers -> LDS, two stages ahead of
-//     the multiply (its waits never stall the weight stream).
-//   * One barrier per stage (KC = 128 inputs) hands LDS buffers back and forth.
+// One workgroup = NW wavefronts, wavefront w owns column tile blockIdx.x*NW + w (32 columns) and
+// all MT row tiles.  blockIdx.y selects the split-K range.  Per stage (KC = 128 inputs; a 256-wide
+// stage, half as many barriers, measured no faster):
+//   - every wavefront has the 8 operand loads (8 KiB) of the NEXT stage in flight while it
+//     multiplies the current one (register double buffer),
+//   - the workgroup copies the next A stage global -> registers -> LDS (LDS double buffer),
+//   - one barrier.
 // EPI_SWIGLU: even wavefronts hold gate tiles, odd ones the matching up tiles; the up tile
 // is handed over through LDS and the even wavefront writes h = silu(gate) * up.
-template <int MT, int NW, int EPI, int RING>
-__global__ __launch_bounds__(64 * (NW + 1)) void k_gemm_bf16(const bf16_t* __restrict__ A, int lda,
-                                                             const u32x4* __restrict__ Wp, int ntiles,
-                                                             int ksteps_total, int stages_per_split, int B,
-                                                             void* __restrict__ out, size_t ldo,
-                                                             size_t split_stride, int dbg) {
-  constexpr int STEPS = KC / 16;               // MFMA k-steps per stage
-  constexpr int APL = MT * 32 * (KC / 8) / 64;  // 16-byte segments of one A stage per loader lane
+// EPI_TOP2: besides the optional plain output, every workgroup reduces its columns to one
+// (largest, second largest, index of largest) triple per row, for the greedy argmax.
+template <int MT, int NW, int EPI, int KC>
+__global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict__ A, int lda,
+                                                       const u32x4* __restrict__ Wp, int ntiles, int ksteps_total,
+                                                       int stages_per_split, int B, void* __restrict__ out,
+                                                       size_t ldo, size_t split_stride,
+                                                       float4* __restrict__ top2, int n_valid) {
+  constexpr int LDS_ROW = KC * 2 + 16;  // bytes; the 16-byte pad staggers rows across banks
+  constexpr int NTHR = 64 * NW;
+  constexpr int STEPS = KC / 16;                    // MFMA k-steps per stage
+  constexpr int ASEG = MT * 32 * (KC / 8);           // 16-byte segments of one A stage
+  constexpr int APT = ASEG / NTHR;                   // segments per thread
+  static_assert(ASEG % NTHR == 0, "A stage must divide evenly over the workgroup");
   constexpr int STAGE_BYTES = MT * 32 * LDS_ROW;
   constexpr int SWAP_BYTES = (EPI == EPI_SWIGLU) ? (NW / 2) * MT * 16 * 64 * 4 : 0;
-  constexpr int LDS_BYTES = 2 * STAGE_BYTES > SWAP_BYTES ? 2 * STAGE_BYTES : SWAP_BYTES;
+  constexpr int CT_ROW = 33;  // floats per row of a transposed-read C tile (odd: conflict-free row scans)
+  constexpr int TOP2_BYTES = (EPI == EPI_TOP2) ? NW * MT * 32 * (CT_ROW * 4 + 16) : 0;
+  constexpr int EPI_BYTES = SWAP_BYTES > TOP2_BYTES ? SWAP_BYTES : TOP2_BYTES;
+  constexpr int LDS_BYTES = 2 * STAGE_BYTES > EPI_BYTES ? 2 * STAGE_BYTES : EPI_BYTES;
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tile = blockIdx.x * NW + wave;
+  const bool active = tile < ntiles;
+  // a wavefront past the last tile redoes the last tile (no divergent control flow in the
+  // pipeline, which lets the compiler count outstanding loads exactly) and skips the store
+  const int tile_ld = active ? tile : ntiles - 1;
   const int nstages_total = ksteps_total / STEPS;
   const int s_begin = blockIdx.y * stages_per_split;
   const int s_end = min(s_begin + stages_per_split, nstages_total);
   const int nst = s_end - s_begin;
-  const std::integral_constant<int, 0> c0;
-  const std::integral_constant<int, 1> c1;
-  const std::integral_constant<int, 2> c2;
-  const std::true_type yes;
-
-  if (wave == NW && (dbg & 2)) return;  // DEBUG: no loader, no barriers
-  if (wave == NW) {
-    // ---------------- loader wavefront: A stage st -> LDS buffer st & 1, published by the barrier
-    // that ends stage st - 1.  Registers hold the stage after that one while it is in flight.
-    // lane l copies segment (row l/16 + 4*i, 16-byte column l%16) for i = 0..APL-1
-    const bf16_t* src0 = A + (size_t)(lane >> 4) * lda + (lane & 15) * 8;
-    const int dst0 = (lane >> 4) * LDS_ROW + (lane & 15) * 16;
-    const size_t src_step = (size_t)4 * lda;
-    constexpr int dst_step = 4 * LDS_ROW;
-    // The multiply loop runs an even number of stages; a phantom last stage gets zeros.
-    const int nst2 = (nst + 1) & ~1;
-    if constexpr (APL <= 16) {
-      u32x4 areg[2][APL];
-      auto load_a = [&](int i, auto r_c) {   // stage i of this split, zeros past the end
-        constexpr int r = decltype(r_c)::value;
-        if (i < nst) {
-#pragma unroll
-          for (int k = 0; k < APL; ++k)
-            areg[r][k] = *reinterpret_cast<const u32x4*>(src0 + k * src_step + (size_t)(s_begin + i) * KC);
-        } else {
-#pragma unroll
-          for (int k = 0; k < APL; ++k) areg[r][k] = u32x4{0, 0, 0, 0};
-        }
-      };
-      auto store_a = [&](int buf, auto r_c) {
-        constexpr int r = decltype(r_c)::value;
-#pragma unroll
-        for (int k = 0; k < APL; ++k)
-          *reinterpret_cast<u32x4*>(&lds[buf * STAGE_BYTES + dst0 + k * dst_step]) = areg[r][k];
-      };
-      if (nst > 0) {
-        load_a(0, c0);
-        load_a(1, c1);
-        store_a(0, c0);
-        __syncthreads();
-        // during stage i: fetch stage i+2 into the register set that stage i used, publish stage i+1
-        for (int i = 0; i < nst2; i += 2) {
-          if (i + 2 < nst2) load_a(i + 2, c0);
-          store_a(1, c1);
-          __syncthreads();
-          if (i + 3 < nst2) load_a(i + 3, c1);
-          if (i + 2 < nst2) store_a(0, c0);
-          __syncthreads();
-        }
-      }
-    } else {
-      // tall A blocks (3 or 4 row tiles): one stage of look-ahead, copied in chunks of 16 segments
-      // so that the loader never needs more registers than the compute wavefronts
-      auto copy_stage = [&](int i, int buf) {
-#pragma unroll
-        for (int h = 0; h < APL; h += 16) {
-          u32x4 t[16];
-#pragma unroll
-          for (int k = 0; k < 16; ++k)
-            if (h + k < APL)
-              t[k] = (i < nst) ? *reinterpret_cast<const u32x4*>(src0 + (h + k) * src_step + (size_t)(s_begin + i) * KC)
-                               : u32x4{0, 0, 0, 0};
-#pragma unroll
-          for (int k = 0; k < 16; ++k)
-            if (h + k < APL) *reinterpret_cast<u32x4*>(&lds[buf * STAGE_BYTES + dst0 + (h + k) * dst_step]) = t[k];
-        }
-      };
-      if (nst > 0) {
-        copy_stage(0, 0);
-        __syncthreads();
-        for (int i = 0; i < nst2; ++i) {
-          if (i + 1 < nst2) copy_stage(i + 1, (i + 1) & 1);
-          __syncthreads();
-        }
-      }
-    }
-    if (EPI == EPI_SWIGLU) __syncthreads();  // the epilogue's hand-over barrier
-    return;
-  }
-
-  // ---------------- compute wavefronts
-  const int tile = blockIdx.x * NW + wave;
-  const bool active = tile < ntiles;
-  // a wavefront past the last tile redoes the last tile (no divergent control flow in the
-  // pipeline) and skips the store
-  const int tile_ld = active ? tile : ntiles - 1;
 
   f32x16 acc[MT];
 #pragma unroll
@@ -189,67 +114,77 @@ __global__ __launch_bounds__(64 * (NW + 1)) void k_gemm_bf16(const bf16_t* __res
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
 
-  // Weight stream: a register ring of two stages (16 operand loads = 16 KiB per wavefront), issued
-  // and awaited BY HAND.  These wavefronts have nothing else in their vector-memory queue and loads
-  // retire in order, so "at most 15 loads outstanding" is exactly "the oldest one has arrived":
-  // the ring stays full all the time.  (Left to the compiler, the wait counts are merged
-  // conservatively around the loop and half of the ring drains at every stage.)
-  // The compiler does not know that these registers are written asynchronously, so the code is
-  // shaped to give it no reason to touch them in between: ONE loop block, every register defined
-  // by one asm and consumed by the next wait asm in the same block, no separate tail code.  To
-  // that end the loop always runs an even number of stages and always refills: past the end of
-  // the split the refill re-reads the first KiB of the matrix (always cached) and a phantom odd
-  // stage multiplies zeros staged by the loader.  After the loop everything is awaited before the
-  // registers are reused.
-  static_assert(RING == 2, "the hand-scheduled weight stream is written for a ring of two stages");
-  u32x4 wreg[2][STEPS];
-  const u32x4* wdummy = Wp + lane;
-  const u32x4* wbase = Wp + (size_t)tile_ld * ksteps_total * 64 + lane;
-  auto issue = [&](u32x4& dst, const u32x4* p) {
-    asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(dst) : "v"(p) : "memory");
+  // A stage copy: global -> registers -> LDS, APT 16-byte segments per thread
+  u32x4 areg[APT];
+  const bf16_t* a_src[APT];
+  int a_dst[APT];
+#pragma unroll
+  for (int i = 0; i < APT; ++i) {
+    const int seg = tid + NTHR * i;
+    const int row = seg / (KC / 8), c16 = seg % (KC / 8);
+    a_src[i] = A + (size_t)row * lda + c16 * 8;
+    a_dst[i] = row * LDS_ROW + c16 * 16;
+  }
+  auto load_a = [&](int st) {
+#pragma unroll
+    for (int i = 0; i < APT; ++i) areg[i] = *reinterpret_cast<const u32x4*>(a_src[i] + (size_t)st * KC);
   };
-  auto stage_ptr = [&](int i) { return (i < nst) ? wbase + (size_t)(s_begin + i) * STEPS * 64 : wdummy; };
+  auto store_a = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < APT; ++i) *reinterpret_cast<u32x4*>(&lds[buf * STAGE_BYTES + a_dst[i]]) = areg[i];
+  };
+  // Weight stream: a ring of two stages (16 operand loads = 16 KiB per wavefront).  A slot is
+  // refilled for stage st+2 right after the MFMAs of stage st consumed it, so 8..16 loads stay
+  // in flight per wavefront at all times, independent of the barriers.
+  u32x4 wreg[2][STEPS];
+  const u32x4* wbase = Wp + (size_t)tile_ld * ksteps_total * 64 + lane;
+  auto load_w = [&](int st, int slot) {
+    const u32x4* p = wbase + (size_t)st * STEPS * 64;
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) wreg[slot][s] = __builtin_nontemporal_load(p + s * 64);
+  };
   const int a_frag = (lane & 31) * LDS_ROW + (lane >> 5) * 16;
-  auto half = [&](auto buf_c, int i) {
+  // one stage: start the copy of the next A stage, multiply, refill the ring, publish the next A stage
+  // (buf/slot are compile-time so that the register ring is never indexed dynamically)
+  auto stage = [&](auto buf_c, int st, auto next_a, auto refill) {
     constexpr int buf = decltype(buf_c)::value, slot = buf;
-    const u32x4* pn = stage_ptr(i + 2);
-    const int pstep = (i + 2 < nst) ? 64 : 0;  // the stand-in load keeps hitting the same KiB
+    if (next_a) load_a(st + 1);
+    __builtin_amdgcn_sched_barrier(0);  // keep the issue order: the scheduler would sink these loads
+    const u32x4* pn = wbase + (size_t)(st + 2) * STEPS * 64;
 #pragma unroll
     for (int s = 0; s < STEPS; ++s) {
-      asm volatile("s_waitcnt vmcnt(15)" : "+v"(wreg[slot][s]));
       const bf16x8 b = __builtin_bit_cast(bf16x8, wreg[slot][s]);
-      if (dbg & 1) {  // DEBUG: no LDS reads, no MFMA
-        acc[0][s] += __builtin_bit_cast(f32x16, (u32x4[4]){wreg[slot][s], wreg[slot][s], wreg[slot][s], wreg[slot][s]})[s];
-      } else {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const bf16x8 a = *reinterpret_cast<const bf16x8*>(
             &lds[buf * STAGE_BYTES + mt * 32 * LDS_ROW + a_frag + s * 32]);
         acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mt], 0, 0, 0);
       }
-      }
-      issue(wreg[slot][s], pn + s * pstep);
+      if (refill) wreg[slot][s] = __builtin_nontemporal_load(pn + s * 64);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (!(dbg & 2)) __syncthreads();
+    if (next_a) store_a(buf ^ 1);
+    __syncthreads();
   };
+  const std::true_type yes;
+  const std::integral_constant<int, 0> b0;
+  const std::integral_constant<int, 1> b1;
+
   if (nst > 0) {
-    const int nst2 = (nst + 1) & ~1;
-    {
-      const u32x4* p0 = stage_ptr(0);
-      const u32x4* p1 = stage_ptr(1);
-      const int st1 = (1 < nst) ? 64 : 0;
-#pragma unroll
-      for (int s = 0; s < STEPS; ++s) issue(wreg[0][s], p0 + s * 64);
-#pragma unroll
-      for (int s = 0; s < STEPS; ++s) issue(wreg[1][s], p1 + s * st1);
+    load_a(s_begin);
+    load_w(s_begin, 0);
+    if (nst > 1) load_w(s_begin + 1, 1);
+    store_a(0);
+    __syncthreads();
+    int i = 0;
+    for (; i + 3 < nst; i += 2) {  // steady state: no conditionals inside
+      stage(b0, s_begin + i, yes, yes);
+      stage(b1, s_begin + i + 1, yes, yes);
     }
-    if (!(dbg & 2)) __syncthreads();
-    for (int i = 0; i < nst2; i += 2) {
-      half(c0, i);
-      half(c1, i + 1);
+    for (; i < nst; ++i) {  // last one to three stages
+      if (i & 1) stage(b1, s_begin + i, (i + 1) < nst, (i + 2) < nst);
+      else       stage(b0, s_begin + i, (i + 1) < nst, (i + 2) < nst);
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the stand-in refills still target the ring
-    __builtin_amdgcn_sched_barrier(0);
   }
 
   // C layout of the 32x32 MFMA: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
@@ -264,6 +199,46 @@ __global__ __launch_bounds__(64 * (NW + 1)) void k_gemm_bf16(const bf16_t* __res
         const int row = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         if (row < B) o[(size_t)row * ldo + col] = acc[mt][r];
       }
+  } else if (EPI == EPI_TOP2) {  // (the last loop barrier already separates the A stages from this reuse of LDS)
+    constexpr int ROWS = MT * 32;
+    float* o = reinterpret_cast<float*>(out);
+    float* ct = reinterpret_cast<float*>(lds) + wave * ROWS * CT_ROW;
+    float4* red = reinterpret_cast<float4*>(lds + NW * ROWS * CT_ROW * 4);
+    const int col = tile * 32 + (lane & 31);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (o != nullptr && active && row < B) o[(size_t)row * ldo + col] = acc[mt][r];
+        ct[row * CT_ROW + (lane & 31)] = acc[mt][r];
+      }
+    __syncthreads();
+    // lane = row: scan the tile's 32 columns in ascending order (the lowest index wins a tie)
+    for (int row = lane; row < ROWS; row += 64) {
+      float v1 = -INFINITY, v2 = -INFINITY;
+      int i1 = INT_MAX;
+      const int c_end = active ? min(32, n_valid - tile * 32) : 0;
+      for (int cc = 0; cc < c_end; ++cc) {
+        const float v = ct[row * CT_ROW + cc];
+        if (v > v1) { v2 = v1; v1 = v; i1 = tile * 32 + cc; }
+        else v2 = fmaxf(v2, v);
+      }
+      red[wave * ROWS + row] = make_float4(v1, v2, __int_as_float(i1), 0.f);
+    }
+    __syncthreads();
+    if (wave == 0) {
+      for (int row = lane; row < ROWS; row += 64) {
+        float4 t = red[row];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) {  // column ranges ascend with w
+          const float4 e = red[w * ROWS + row];
+          if (e.x > t.x) { t.y = fmaxf(t.x, e.y); t.x = e.x; t.z = e.z; }
+          else t.y = fmaxf(t.y, e.x);
+        }
+        if (row < B) top2[(size_t)row * gridDim.x + blockIdx.x] = t;
+      }
+    }
   } else {  // EPI_SWIGLU (the last loop barrier already separates the A stages from this reuse of LDS)
     float* swap = reinterpret_cast<float*>(lds) + (size_t)(wave >> 1) * MT * 16 * 64;
     if (active && (wave & 1)) {
@@ -290,25 +265,24 @@ __global__ __launch_bounds__(64 * (NW + 1)) void k_gemm_bf16(const bf16_t* __res
 
 template <int MT, int NW, int EPI>
 int launch_one(const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit, void* out, size_t ldo,
-               size_t split_stride, int ring, hipStream_t st) {
-  const int ntiles = Npad / 32, ksteps = Kpad / 16, nstages = Kpad / KC;
-  const int sps = (nstages + ksplit - 1) / ksplit;
-  dim3 grid((ntiles + NW - 1) / NW, ksplit), block(64 * (NW + 1));
-  (void)ring;
-  static const int dbg = []() { const char* v = getenv("GOOSE_DBG"); return v ? atoi(v) : 0; }();
-  hipLaunchKernelGGL((k_gemm_bf16<MT, NW, EPI, 2>), grid, block, 0, st, (const bf16_t*)A, lda, (const u32x4*)Wp,
-                     ntiles, ksteps, sps, B, out, ldo, split_stride, dbg);
+               size_t split_stride, hipStream_t st, void* top2 = nullptr, int n_valid = 0) {
+  const int ntiles = Npad / 32, ksteps = Kpad / 16;
+  dim3 grid((ntiles + NW - 1) / NW, ksplit);
+  const int granules = Kpad / KGRAN;                      // split-K ranges are multiples of 128 inputs
+  const int gps = (granules + ksplit - 1) / ksplit;       // granules (= stages) per split
+  hipLaunchKernelGGL((k_gemm_bf16<MT, NW, EPI, 128>), grid, dim3(64 * NW), 0, st, (const bf16_t*)A, lda,
+                     (const u32x4*)Wp, ntiles, ksteps, gps, B, out, ldo, split_stride, (float4*)top2, n_valid);
   return goose_launch_status();
 }
 
 template <int NW, int EPI>
 int launch_mt(int MT, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit, void* out,
-              size_t ldo, size_t split_stride, int ring, hipStream_t st) {
+              size_t ldo, size_t split_stride, hipStream_t st, void* top2 = nullptr, int n_valid = 0) {
   switch (MT) {
-    case 1: return launch_one<1, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, ring, st);
-    case 2: return launch_one<2, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, ring, st);
-    case 3: return launch_one<3, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, ring, st);
-    case 4: return launch_one<4, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, ring, st);
+    case 1: return launch_one<1, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st, top2, n_valid);
+    case 2: return launch_one<2, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st, top2, n_valid);
+    case 3: return launch_one<3, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st, top2, n_valid);
+    case 4: return launch_one<4, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st, top2, n_valid);
   }
   return GOOSE_ERR_ARG;
 }
@@ -325,37 +299,40 @@ int launch_pack_bf16(int mode, const void* s0, const void* s1, const void* s2, i
 }
 
 // Workgroup width (wavefronts = column tiles per workgroup) and split-K factor for a shape.
-// Streaming needs about 1000 wavefronts with 8 KiB of loads in flight each to keep HBM busy, so
-// split K until tiles * ksplit reaches that, but keep every split at least 4 stages long; use
-// the 4-wide workgroup (more sharing of the staged A block) whenever that still leaves >= 256
-// workgroups.
+// Measured on MI355X: the stream wants about 768 wavefronts in flight; every extra split costs an
+// fp32 tile written and re-read (and flushed at the kernel boundary), so take the smallest power of
+// two that reaches it, with every split at least 4 stages long; the 4-wide workgroup (more sharing
+// of the staged A block) whenever it leaves enough workgroups.
 void pick_gemm_config(int Npad, int Kpad, int max_ksplit, int* nw_out, int* ksplit_out) {
-  const int ntiles = Npad / 32, nstages = Kpad / KC;
-  int ks = (1024 + ntiles - 1) / ntiles;
-  if (ks > nstages / 4) ks = nstages / 4;
-  if (ks > max_ksplit) ks = max_ksplit;
-  if (ks < 1) ks = 1;
+  const int ntiles = Npad / 32, nstages = Kpad / KGRAN;
+  const int want = (768 + ntiles - 1) / ntiles;
+  int ks = 1;
+  while (ks < want) ks *= 2;
+  while (ks > 1 && (ks > nstages / 4 || ks > max_ksplit)) ks /= 2;
   while (ks > 1 && ((nstages + ks - 1) / ks) * (ks - 1) >= nstages) --ks;  // no empty split
-  *nw_out = (((ntiles + 3) / 4) * ks >= 256) ? 4 : 2;
+  *nw_out = (((ntiles + 3) / 4) * ks >= 160) ? 4 : 2;
   *ksplit_out = ks;
+}
+
+int launch_gemm_top2_bf16(const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw, float* out,
+                          size_t ldo, void* top2, int n_valid, hipStream_t st) {
+  if (B < 1 || B > GOOSE_MAX_B || (Npad & 31) || (Kpad % KGRAN) || !top2 || n_valid < 1 || n_valid > Npad)
+    return GOOSE_ERR_ARG;
+  const int MT = (B + 31) / 32;
+  if (nw == 4) return launch_mt<4, EPI_TOP2>(MT, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st, top2, n_valid);
+  return launch_mt<2, EPI_TOP2>(MT, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st, top2, n_valid);
 }
 
 int launch_gemm_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw, int ksplit,
                      void* out, size_t ldo, size_t out_split_stride, hipStream_t st) {
-  if (B < 1 || B > GOOSE_MAX_B || (Npad & 31) || (Kpad % KC) || ksplit < 1) return GOOSE_ERR_ARG;
+  if (B < 1 || B > GOOSE_MAX_B || (Npad & 31) || (Kpad % KGRAN) || ksplit < 1) return GOOSE_ERR_ARG;
+  if (epi != EPI_PARTIAL && epi != EPI_SWIGLU) return GOOSE_ERR_ARG;
   const int MT = (B + 31) / 32;
-  if (MT == 4) nw = 2;  // 4 row tiles x 4 column wavefronts would exceed the register file (spills)
-  static const int ring = []() {
-    const char* v = getenv("GOOSE_RING");
-    const int r = v ? atoi(v) : 3;
-    return (r >= 2 && r <= 4) ? r : 3;
-  }();
   if (epi == EPI_SWIGLU) {
     if (ksplit != 1 || (Npad & 63)) return GOOSE_ERR_ARG;
-    if (nw == 4) return launch_mt<4, EPI_SWIGLU>(MT, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, ring, st);
-    return launch_mt<2, EPI_SWIGLU>(MT, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, ring, st);
+    if (nw == 4) return launch_mt<4, EPI_SWIGLU>(MT, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st);
+    return launch_mt<2, EPI_SWIGLU>(MT, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st);
   }
-  if (nw == 4)
-    return launch_mt<4, EPI_PARTIAL>(MT, A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, ring, st);
-  return launch_mt<2, EPI_PARTIAL>(MT, A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, ring, st);
+  if (nw == 4) return launch_mt<4, EPI_PARTIAL>(MT, A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st);
+  return launch_mt<2, EPI_PARTIAL>(MT, A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st);
 }

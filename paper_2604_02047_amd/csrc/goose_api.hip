@@ -203,6 +203,7 @@ int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** o
   A((void**)&c->att_o, (size_t)d.n_heads * c->max_splits * c->Bpad * d.head_dim * sizeof(float));
   A((void**)&c->att_ml, (size_t)d.n_heads * c->max_splits * c->Bpad * 2 * sizeof(float));
   A((void**)&c->logits, (size_t)c->Bpad * c->Vpad * sizeof(float));
+  A(&c->top2, (size_t)c->Bpad * (c->Vpad / 64 + 1) * 16);
   A((void**)&c->inv_freq, (size_t)(d.head_dim / 2) * sizeof(double));
   A((void**)&c->s_mask, 128 * 2 * sizeof(uint64_t));
   A((void**)&c->s_depth, 128 * sizeof(int32_t));
@@ -228,7 +229,7 @@ int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** o
 
 void goose_destroy(goose_ctx* c) {
   if (!c) return;
-  void* ptrs[] = {c->xn, c->part, c->q, c->o, c->h, c->att_o, c->att_ml, c->logits, c->inv_freq,
+  void* ptrs[] = {c->xn, c->part, c->q, c->o, c->h, c->att_o, c->att_ml, c->logits, c->top2, c->inv_freq,
                   c->s_mask, c->s_depth, c->s_pos, c->s_x, c->flags, c->s_P};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
@@ -308,23 +309,22 @@ int goose_embed(goose_ctx* c, const void* d_embed, const int32_t* d_tokens, int 
   return launch_embed(c->d.dtype, d_embed, d_tokens, B, c->d.hidden, c->d.vocab, d_x, as_stream(stream));
 }
 
-int goose_verify_layer(goose_ctx* c, const void* d_packed_layer, float* d_x, void* d_kcache, void* d_vcache, int P,
-                       const int32_t* d_P, int B, const uint64_t* d_mask, const int32_t* d_pos, void* stream) {
-  int rc = check_tree_args(c, B, P);
-  if (rc) return rc;
-  if (!d_packed_layer || !d_x || !d_kcache || !d_vcache || !d_mask || !d_pos) return GOOSE_ERR_ARG;
-  hipStream_t st = as_stream(stream);
-  const int32_t* dP;
-  rc = resolve_P(c, P, d_P, st, &dP);
-  if (rc) return rc;
+// One decoder layer.  `xhat_ready`: the operand buffer already holds RMSNorm(x)*g1 (the previous
+// layer's closing kernel wrote it).  `g_next`: gain of the normalisation that follows this layer
+// (the next layer's g1 or the final norm), folded into the closing residual add; null to skip.
+static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, void* d_vcache, int P,
+                      const int32_t* dP, int B, const uint64_t* d_mask, const int32_t* d_pos, hipStream_t st,
+                      bool xhat_ready, const void* g_next) {
+  int rc = GOOSE_OK;
   const goose_model_desc& d = c->d;
-  const char* w = (const char*)d_packed_layer;
   const size_t pstride = (size_t)c->Bpad * c->part_ld;
   const int H = d.hidden, Hq = c->Hq;
 
   // x_hat = RMSNorm(x) * g1
-  { PROF(PK_NORM);
-    rc = launch_resid_norm(d.dtype, d_x, H, nullptr, 0, 0, 0, w + c->pl.g1, d.rms_eps, c->xn, c->Kh, B, st); }
+  if (!xhat_ready) {
+    PROF(PK_NORM);
+    rc = launch_resid_norm(d.dtype, d_x, H, nullptr, 0, 0, 0, w + c->pl.g1, d.rms_eps, c->xn, c->Kh, B, st);
+  }
   if (rc) return rc;
 
   if (d.dtype == GOOSE_DTYPE_BF16) {
@@ -357,7 +357,7 @@ int goose_verify_layer(goose_ctx* c, const void* d_packed_layer, float* d_x, voi
       rc = launch_resid_norm(d.dtype, d_x, H, c->part, ks, pstride, c->part_ld, w + c->pl.g2, d.rms_eps, c->xn,
                              c->Kh, B, st); }
     if (rc) return rc;
-    static const int gu_nw = env_int("GOOSE_GU_NW", 2) == 4 ? 4 : 2;
+    static const int gu_nw = env_int("GOOSE_GU_NW", 4) == 2 ? 2 : 4;
     { PROF(PK_GEMM_GATE_UP);
       rc = launch_gemm_bf16(EPI_SWIGLU, c->xn, c->Kh, w + c->pl.wgu, Ngu, c->Kh, B, gu_nw, 1, c->h, c->Fpad, 0, st); }
     if (rc) return rc;
@@ -367,9 +367,10 @@ int goose_verify_layer(goose_ctx* c, const void* d_packed_layer, float* d_x, voi
       rc = launch_gemm_bf16(EPI_PARTIAL, c->h, c->Fpad, w + c->pl.wd, Nh, c->Fpad, B, cd.nw, ks, c->part, c->part_ld,
                             pstride, st); }
     if (rc) return rc;
-    // x += MLP output
+    // x += MLP output (and the following normalisation when its gain is known)
     PROF(PK_NORM);
-    return launch_resid_norm(d.dtype, d_x, H, c->part, ks, pstride, c->part_ld, nullptr, d.rms_eps, nullptr, 0, B, st);
+    return launch_resid_norm(d.dtype, d_x, H, c->part, ks, pstride, c->part_ld, g_next, d.rms_eps,
+                             g_next ? c->xn : nullptr, g_next ? c->Kh : 0, B, st);
   }
 
   // fp32 storage: plain kernels
@@ -394,43 +395,66 @@ int goose_verify_layer(goose_ctx* c, const void* d_packed_layer, float* d_x, voi
   rc = launch_gemm_f32((const float*)c->h, c->Fpad, (const float*)(w + c->pl.wd), H, d.ffn, B, c->part, c->part_ld,
                        st);
   if (rc) return rc;
-  return launch_resid_norm(d.dtype, d_x, H, c->part, 1, pstride, c->part_ld, nullptr, d.rms_eps, nullptr, 0, B, st);
+  return launch_resid_norm(d.dtype, d_x, H, c->part, 1, pstride, c->part_ld, g_next, d.rms_eps,
+                           g_next ? c->xn : nullptr, g_next ? c->Kh : 0, B, st);
 }
+
+int goose_verify_layer(goose_ctx* c, const void* d_packed_layer, float* d_x, void* d_kcache, void* d_vcache, int P,
+                       const int32_t* d_P, int B, const uint64_t* d_mask, const int32_t* d_pos, void* stream) {
+  int rc = check_tree_args(c, B, P);
+  if (rc) return rc;
+  if (!d_packed_layer || !d_x || !d_kcache || !d_vcache || !d_mask || !d_pos) return GOOSE_ERR_ARG;
+  hipStream_t st = as_stream(stream);
+  const int32_t* dP;
+  rc = resolve_P(c, P, d_P, st, &dP);
+  if (rc) return rc;
+  return layer_impl(c, (const char*)d_packed_layer, d_x, d_kcache, d_vcache, P, dP, B, d_mask, d_pos, st, false,
+                    nullptr);
+}
+
+static int lm_head_impl(goose_ctx* c, const void* d_packed_head, const float* d_x, int B, int32_t* d_argmax,
+                        float* d_logits_or_null, float* d_margin_or_null, hipStream_t st, bool xhat_ready);
 
 int goose_lm_head_argmax(goose_ctx* c, const void* d_packed_head, const float* d_x, int B, int32_t* d_argmax,
                          float* d_logits_or_null, float* d_margin_or_null, void* stream) {
   if (!c || !d_packed_head || !d_x || !d_argmax) return GOOSE_ERR_ARG;
   if (B < 1) return GOOSE_ERR_ARG;
   if (B > c->max_B) return GOOSE_ERR_CAPACITY;
-  hipStream_t st = as_stream(stream);
+  return lm_head_impl(c, d_packed_head, d_x, B, d_argmax, d_logits_or_null, d_margin_or_null, as_stream(stream),
+                      false);
+}
+
+static int lm_head_impl(goose_ctx* c, const void* d_packed_head, const float* d_x, int B, int32_t* d_argmax,
+                        float* d_logits_or_null, float* d_margin_or_null, hipStream_t st, bool xhat_ready) {
   const goose_model_desc& d = c->d;
   const char* w = (const char*)d_packed_head;
   // the residual stream is left untouched: normalise into the operand buffer only
-  int rc = launch_resid_norm(d.dtype, const_cast<float*>(d_x), d.hidden, nullptr, 0, 0, 0, w + c->ph.gf, d.rms_eps,
-                             c->xn, c->Kh, B, st);
+  int rc = GOOSE_OK;
+  if (!xhat_ready)
+    rc = launch_resid_norm(d.dtype, const_cast<float*>(d_x), d.hidden, nullptr, 0, 0, 0, w + c->ph.gf, d.rms_eps,
+                           c->xn, c->Kh, B, st);
   if (rc) return rc;
-  float* logits = d_logits_or_null ? d_logits_or_null : c->logits;
-  const size_t ld = d_logits_or_null ? (size_t)d.vocab : (size_t)c->Vpad;
-  static const int lm_nw = env_int("GOOSE_LM_NW", 4) == 2 ? 2 : 4;
   if (d.dtype == GOOSE_DTYPE_BF16) {
-    if (d_logits_or_null && (d.vocab % 32) != 0) {
-      // tiles are 32 columns wide: write into the padded workspace, then copy rows out
-      rc = launch_gemm_bf16(EPI_PARTIAL, c->xn, c->Kh, w + c->ph.wlm, c->Vpad, c->Kh, B, lm_nw, 1, c->logits, c->Vpad, 0,
-                            st);
-      if (rc) return rc;
+    // the projection kernel reduces its own columns to (max, second, index) per row; logits are
+    // written only on request (through the padded workspace when rows are no multiple of a tile)
+    static const int lm_nw = env_int("GOOSE_LM_NW", 4) == 2 ? 2 : 4;
+    const bool bounce = d_logits_or_null && (d.vocab % 32) != 0;
+    float* out = bounce ? c->logits : d_logits_or_null;
+    const size_t ld = bounce ? (size_t)c->Vpad : (size_t)d.vocab;
+    const int groups = (c->Vpad / 32 + lm_nw - 1) / lm_nw;
+    { PROF(PK_LM_HEAD);
+      rc = launch_gemm_top2_bf16(c->xn, c->Kh, w + c->ph.wlm, c->Vpad, c->Kh, B, lm_nw, out, ld, c->top2, d.vocab, st); }
+    if (rc) return rc;
+    if (bounce)
       GOOSE_HIP_TRY(hipMemcpy2DAsync(d_logits_or_null, (size_t)d.vocab * 4, c->logits, (size_t)c->Vpad * 4,
                                      (size_t)d.vocab * 4, B, hipMemcpyDeviceToDevice, st));
-      logits = c->logits;
-      return launch_argmax(logits, c->Vpad, d.vocab, B, d_argmax, d_margin_or_null, st);
-    }
-    PROF(PK_LM_HEAD);
-    rc = launch_gemm_bf16(EPI_PARTIAL, c->xn, c->Kh, w + c->ph.wlm, c->Vpad, c->Kh, B, lm_nw, 1, logits, ld, 0, st);
-  } else {
-    rc = launch_gemm_f32((const float*)c->xn, c->Kh, (const float*)(w + c->ph.wlm), d.vocab, d.hidden, B, logits, ld,
-                         st);
+    PROF(PK_ARGMAX);
+    return launch_argmax_top2(c->top2, groups, B, d_argmax, d_margin_or_null, st);
   }
+  float* logits = d_logits_or_null ? d_logits_or_null : c->logits;
+  const size_t ld = d_logits_or_null ? (size_t)d.vocab : (size_t)c->Vpad;
+  rc = launch_gemm_f32((const float*)c->xn, c->Kh, (const float*)(w + c->ph.wlm), d.vocab, d.hidden, B, logits, ld, st);
   if (rc) return rc;
-  PROF(PK_ARGMAX);
   return launch_argmax(logits, ld, d.vocab, B, d_argmax, d_margin_or_null, st);
 }
 
@@ -473,14 +497,17 @@ int goose_verify_step(goose_ctx* c, const goose_model_ptrs* m, const goose_step_
   rc = launch_embed(d.dtype, m->d_embed, io->d_tokens, B, d.hidden, d.vocab, c->s_x, st);
   if (rc) return rc;
   const size_t layer_cache = (size_t)d.n_heads * c->cap * d.head_dim * elem_size(d.dtype);
+  // each layer's closing residual add also writes the next normalisation's output
   for (int l = 0; l < d.n_layers; ++l) {
-    rc = goose_verify_layer(c, (const char*)m->d_packed_layers + (size_t)l * c->pl.total, c->s_x,
-                            (char*)m->d_kcache_all + l * layer_cache, (char*)m->d_vcache_all + l * layer_cache, P_max,
-                            io->d_P, B, c->s_mask, c->s_pos, stream);
+    const char* w = (const char*)m->d_packed_layers + (size_t)l * c->pl.total;
+    const void* g_next = (l + 1 < d.n_layers) ? (const void*)(w + c->pl.total + c->pl.g1)
+                                              : (const void*)((const char*)m->d_packed_head + c->ph.gf);
+    rc = layer_impl(c, w, c->s_x, (char*)m->d_kcache_all + l * layer_cache, (char*)m->d_vcache_all + l * layer_cache,
+                    P_max, io->d_P, B, c->s_mask, c->s_pos, st, l > 0, g_next);
     if (rc) return rc;
   }
-  rc = goose_lm_head_argmax(c, m->d_packed_head, c->s_x, B, io->d_argmax, io->d_logits_or_null, io->d_margin_or_null,
-                            stream);
+  rc = lm_head_impl(c, m->d_packed_head, c->s_x, B, io->d_argmax, io->d_logits_or_null, io->d_margin_or_null, st,
+                    true);
   if (rc) return rc;
   rc = launch_accept(io->d_parent, io->d_tokens, io->d_is_spine, io->d_argmax, B, io->d_accept_len, io->d_path,
                      io->d_bonus, io->d_next_root_or_null, st);

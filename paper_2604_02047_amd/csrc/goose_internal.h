@@ -63,7 +63,8 @@ struct goose_ctx {
   void* h;         // T [Bpad][Fpad] SwiGLU output (GEMM operand)
   float* att_o;    // f32 [n_heads][max_splits][Bpad][head_dim]
   float* att_ml;   // f32 [n_heads][max_splits][Bpad][2]
-  float* logits;   // f32 [Bpad][Vpad]  (when the caller does not ask for logits)
+  float* logits;   // f32 [Bpad][Vpad]  (fp32 models; vocabularies that are no multiple of 32)
+  void* top2;      // float4 [Bpad][Vpad/64]  per-workgroup reductions of the LM head
   double* inv_freq;  // f64 [head_dim/2]
   // scratch for goose_verify_step
   uint64_t* s_mask;  // [128][2]
@@ -106,10 +107,16 @@ enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
 // Re-tiles raw [rows][K] bf16 matrices into MFMA-operand order; Npad x Kpad zero padded.
 int launch_pack_bf16(int mode, const void* s0, const void* s1, const void* s2, int rows_each, int K, int Npad,
                      int Kpad, void* dst, hipStream_t st);
-enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
+enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_TOP2 = 2 };
 // out partials f32 [ksplit][Bpad][ldo] (EPI_PARTIAL) or bf16 h [Bpad][ldo] (EPI_SWIGLU, ksplit must be 1)
 int launch_gemm_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw, int ksplit,
                      void* out, size_t ldo, size_t out_split_stride, hipStream_t st);
+// Projection whose workgroups (nw column tiles each) also emit per-row (max, second max, index of
+// max) over their valid columns (< n_valid): top2 is float4 [B][ceil(Npad/32/nw)], index bits in .z.
+// `out` (f32 [B][ldo]) may be null when only the reduction is wanted.
+int launch_gemm_top2_bf16(const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw, float* out,
+                          size_t ldo, void* top2, int n_valid, hipStream_t st);
+int launch_argmax_top2(const void* top2, int n_groups, int B, int32_t* argmax, float* margin, hipStream_t st);
 void pick_gemm_config(int Npad, int Kpad, int max_ksplit, int* nw_out, int* ksplit_out);
 int launch_attn_bf16(const void* q, int ldq, const void* kc, const void* vc, int n_heads, int head_dim, int cap,
                      const int32_t* dP, int B, const uint64_t* mask, int splits, float* att_o, float* att_ml,

@@ -216,6 +216,30 @@ __global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits
   }
 }
 
+// Same from the per-workgroup reductions of the LM-head kernel (groups cover ascending column ranges).
+__global__ __launch_bounds__(64) void k_argmax_top2(const float4* __restrict__ top2, int n_groups,
+                                                    int32_t* __restrict__ argmax, float* __restrict__ margin) {
+  const int m = blockIdx.x;
+  Top2 t = {-INFINITY, -INFINITY, INT_MAX};
+  for (int g = threadIdx.x; g < n_groups; g += 64) {
+    const float4 e = top2[(size_t)m * n_groups + g];
+    Top2 o = {e.x, e.y, __float_as_int(e.z)};
+    t = top2_merge(t, o);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    Top2 o;
+    o.v1 = __shfl_xor(t.v1, off, 64);
+    o.v2 = __shfl_xor(t.v2, off, 64);
+    o.i1 = __shfl_xor(t.i1, off, 64);
+    t = top2_merge(t, o);
+  }
+  if (threadIdx.x == 0) {
+    argmax[m] = t.i1;
+    if (margin) margin[m] = t.v1 - t.v2;
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // Greedy walk (Alg. 2).  Every node whose own edge matches (its token equals the prediction
 // at its parent) bids for its parent with the key (branch?1:0, node index); the lowest key
@@ -366,6 +390,11 @@ int launch_swiglu_f32(const float* gu, size_t ld, int F, float* h, int ldh, int 
 
 int launch_argmax(const float* logits, size_t ld, int V, int B, int32_t* argmax, float* margin, hipStream_t st) {
   hipLaunchKernelGGL(k_argmax, dim3(B), dim3(256), 0, st, logits, ld, V, argmax, margin);
+  return goose_launch_status();
+}
+
+int launch_argmax_top2(const void* top2, int n_groups, int B, int32_t* argmax, float* margin, hipStream_t st) {
+  hipLaunchKernelGGL(k_argmax_top2, dim3(B), dim3(64), 0, st, (const float4*)top2, n_groups, argmax, margin);
   return goose_launch_status();
 }
 
