@@ -34,6 +34,26 @@ WORKLOADS = {
 }
 
 
+COPY_PROBE_BYTES = 256 << 20
+
+
+def recorded_traffic(workload):
+    """HBM bytes per launch of the gate/up kernel from the committed profiler summary of this workload
+    (FETCH_SIZE + WRITE_SIZE, scaled by the copy probe), or None when there is none.  Counters cannot
+    be read from inside this process; the summary names the command that produced it."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                m = line.split()
+                # the SwiGLU epilogue is template argument 3 == 1 of k_gemm_bf16<MT, NW, EPI, KC>
+                if line.startswith("k_gemm_bf16<") and line.split(">")[0].split(",")[2].strip() == "1":
+                    return int(round((float(m[-2]) + float(m[-1])) * 1e6))
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
+
+
 def make_tree(kind, seed):
     import goose_inputs as gi
     return {"spine_7b": lambda: gi.tree_spine_7b(seed), "spine_13b": gi.tree_spine_13b,
@@ -76,6 +96,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch the library's 256 MiB copy kernel (calibrates profiler traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the verification pass of one request does not shard); "
@@ -214,6 +236,15 @@ def main():
     bytes_timed = sum(step_bytes(shape, B, P_hist[t]) for t in range(W, total))
     achieved = bytes_timed / elapsed / 1e9
 
+    if args.copy_probe:
+        from paper_2604_02047_amd.binding import goose_copy_probe
+        src = torch.ones(COPY_PROBE_BYTES, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            goose_copy_probe(src, dst, COPY_PROBE_BYTES)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- per-kernel timing with HIP events on the launch stream, over the same steps
     roofline, kernels = None, None
     if not args.no_kernel_timing:
@@ -229,14 +260,23 @@ def main():
         prof = gm.ctx.goose_profile_read()
         gm.ctx.goose_profile_enable(False)
         kernels = {k: {"avg_us": ms / max(n, 1) * 1e3, "launches": n} for k, (ms, n) in prof.items() if n}
+        # what a pair of events reads with nothing between them (part of every figure above)
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
+        for a, b in pairs:
+            a.record()
+            b.record()
+        torch.cuda.synchronize()
+        floor_us = float(np.median([a.elapsed_time(b) for a, b in pairs])) * 1e3
         es = 2
         gu_bytes = 2 * shape.ffn * shape.hidden * es + B * shape.hidden * es + B * shape.ffn * es
         gu = kernels["gemm_gate_up_swiglu"]
         ach = gu_bytes / (gu["avg_us"] * 1e-6) / 1e9
-        roofline = {"kernel": "k_gemm_bf16<MT,2,EPI_SWIGLU> (gate/up projection + SwiGLU)", "bound": "hbm",
+        roofline = {"kernel": "k_gemm_bf16<MT,NW,EPI_SWIGLU> (gate/up projection + SwiGLU)", "bound": "hbm",
                     "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
-                    "bytes_per_launch": gu_bytes, "avg_us": round(gu["avg_us"], 2)}
+                    "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(args.workload),
+                    "bytes_per_launch": gu_bytes, "avg_us": round(gu["avg_us"], 2),
+                    "timing": "HIP events around each launch on the launch stream, averaged over the timed steps",
+                    "empty_event_pair_us": round(floor_us, 2)}
 
     # ---- CPU baseline: the oracle on a bounded sample (two layers + LM head of the same step)
     cpu = None
@@ -262,7 +302,7 @@ def main():
 
 
 def cpu_baseline(shape, gm, seed, B, P0, tree_kind, log):
-    """Times the NumPy fp64 oracle on two decoder layers and the LM head of one step at this workload's
+    """Times the NumPy fp64 oracle on a few decoder layers and the LM head of one step at this workload's
     shape (same weights, the device's own prefix KV as input) and scales to the full layer count."""
     import torch
     import goose_inputs as gi
@@ -276,33 +316,36 @@ def cpu_baseline(shape, gm, seed, B, P0, tree_kind, log):
     def f64(t):
         return t.detach().to("cpu").to(torch.float64).numpy()
 
-    n_s = 2
-    log("cpu baseline: building the 2-layer oracle sample")
-    layers = [{k: f64(v) for k, v in gi.layer_weights(shape, seed, l, gm.device).items()} for l in range(n_s)]
-    om = orc.OracleModel(shape.n_heads, shape.head_dim, shape.rope_base, shape.rms_eps, layers,
+    n_s = min(16, shape.n_layers)
+    log(f"cpu baseline: building the {n_s}-layer oracle sample")
+    om = orc.OracleModel(shape.n_heads, shape.head_dim, shape.rope_base, shape.rms_eps, [None] * n_s,
                          f64(gm.embed), f64(gi.lm_head(shape, seed, gm.device)),
                          f64(gi.final_norm(shape, seed, gm.device)))
     vr = gm.v_rows(0, P0)
-    cache = [(f64(gm.kcache[l, :, :P0]), f64(vr[l])) for l in range(n_s)]
     tree = make_tree(tree_kind, 0)
     toks = gi.draft_tokens_uniform(seed, tree.parent, shape.vocab, 1)
     anc, depth = orc.ancestor_mask(tree.parent)
     allow = np.concatenate([np.ones((B, P0), dtype=bool), anc], axis=1)
     x = om.embed[toks.astype(np.int64)]
-    ta = time.perf_counter()
-    for l in range(n_s):
-        x, _, _ = orc.decoder_layer(om, om.layers[l], x, cache[l][0], cache[l][1], P0 + depth, allow)
+    t_layers = 0.0
+    for l in range(n_s):  # one layer's fp64 weights at a time; only the oracle's arithmetic is timed
+        w = {k: f64(v) for k, v in gi.layer_weights(shape, seed, l, gm.device).items()}
+        Kc, Vc = f64(gm.kcache[l, :, :P0]), f64(vr[l])
+        ta = time.perf_counter()
+        x, _, _ = orc.decoder_layer(om, w, x, Kc, Vc, P0 + depth, allow)
+        t_layers += time.perf_counter() - ta
+        del w, Kc, Vc
     tb = time.perf_counter()
     logits = orc.final_logits(om, x)
     x_hat = orc.argmax_lowest(logits)
     orc.greedy_walk(tree.parent, toks, tree.is_spine, x_hat)
     tc = time.perf_counter()
-    t_step = (tb - ta) / n_s * shape.n_layers + (tc - tb)
-    log(f"cpu baseline: {n_s} layers {tb - ta:.2f}s, head {tc - tb:.2f}s -> {t_step:.1f}s/step on {threads} threads")
+    t_step = t_layers / n_s * shape.n_layers + (tc - tb)
+    log(f"cpu baseline: {n_s} layers {t_layers:.2f}s, head {tc - tb:.2f}s -> {t_step:.1f}s/step on {threads} threads")
     return {"value": round(1.0 / t_step, 5), "unit": "steps/s", "cores": int(threads), "kind": "oracle",
             "sample": f"{n_s} of {shape.n_layers} decoder layers + LM head + walk of one step "
                       f"(B={B}, P={P0}), layer time scaled linearly to {shape.n_layers} layers",
-            "seconds_measured": round(tc - ta, 2)}
+            "seconds_measured": round(t_layers + tc - tb, 2)}
 
 
 if __name__ == "__main__":

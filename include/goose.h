@@ -219,6 +219,11 @@ int goose_profile_kinds(void);
 const char* goose_profile_kind_name(int kind);
 int goose_profile_read(goose_ctx* ctx, void* stream, double* h_ms_sum, int32_t* h_count);
 
+/* Profiling aid: a plain streaming copy of `bytes` (a multiple of 16) from d_src to d_dst, both
+ * DEVICE, non-overlapping.  It reads and writes exactly `bytes` of HBM once each, which calibrates
+ * hardware traffic counters read for the other kernels in the same profiler run. */
+int goose_copy_probe(const void* d_src, void* d_dst, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

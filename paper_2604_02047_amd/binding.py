@@ -19,6 +19,7 @@ EXPORTS = [
     "goose_accept", "goose_compact_kv", "goose_verify_step", "goose_device_flags",
     "goose_packed_matrix_bytes", "goose_pack_matrix", "goose_gemm_packed", "goose_gemm_swiglu_packed",
     "goose_profile_enable", "goose_profile_kinds", "goose_profile_kind_name", "goose_profile_read",
+    "goose_copy_probe",
 ]
 
 GOOSE_DTYPE_BF16, GOOSE_DTYPE_F32 = 0, 1
@@ -171,6 +172,10 @@ def goose_gemm_packed(a, lda, packed, N, K, B, nw, ksplit, partials):
 def goose_gemm_swiglu_packed(a, lda, packed, N, K, B, nw, h, ldh):
     _check(load_library().goose_gemm_swiglu_packed(_ptr(a), lda, _ptr(packed), N, K, B, nw, _ptr(h), ldh, _stream()),
            "goose_gemm_swiglu_packed")
+
+
+def goose_copy_probe(src, dst, nbytes):
+    _check(load_library().goose_copy_probe(_ptr(src), _ptr(dst), C.c_size_t(nbytes), _stream()), "goose_copy_probe")
 
 
 def _ptr(t):

@@ -559,6 +559,11 @@ int goose_gemm_packed(const void* d_a, int lda, const void* d_packed, int N, int
                           (size_t)rows * Npad, as_stream(stream));
 }
 
+int goose_copy_probe(const void* d_src, void* d_dst, size_t bytes, void* stream) {
+  if (!d_src || !d_dst || bytes < 16 || (bytes % 16) != 0) return GOOSE_ERR_ARG;
+  return launch_copy_probe(d_src, d_dst, bytes, as_stream(stream));
+}
+
 int goose_profile_enable(goose_ctx* c, int enable) {
   if (!c) return GOOSE_ERR_ARG;
   if (!c->prof) c->prof = new (std::nothrow) goose_prof();

@@ -393,6 +393,16 @@ int launch_argmax(const float* logits, size_t ld, int V, int B, int32_t* argmax,
   return goose_launch_status();
 }
 
+// Plain streaming copy of n 16-byte words (profiling aid: a kernel of exactly known HBM traffic).
+__global__ __launch_bounds__(256) void k_copy_probe(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+int launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st) {
+  hipLaunchKernelGGL(k_copy_probe, dim3(2048), dim3(256), 0, st, (const uint4*)src, (uint4*)dst, bytes / 16);
+  return goose_launch_status();
+}
+
 int launch_argmax_top2(const void* top2, int n_groups, int B, int32_t* argmax, float* margin, hipStream_t st) {
   hipLaunchKernelGGL(k_argmax_top2, dim3(B), dim3(64), 0, st, (const float4*)top2, n_groups, argmax, margin);
   return goose_launch_status();

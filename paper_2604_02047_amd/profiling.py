@@ -1,0 +1,93 @@
+"""Text summaries of a rocprofv3 run (its rocpd SQLite output): per-kernel durations, and HBM
+traffic per launch from the FETCH_SIZE / WRITE_SIZE counters, scaled by what the same counter read
+for the library's copy probe (a kernel that moves a known number of bytes) in the same run.
+
+    python -m paper_2604_02047_amd.profiling kernels <run_results.db>
+    python -m paper_2604_02047_amd.profiling traffic <fetch_run.db> <write_run.db> <copy_probe_bytes>
+
+Reads only; prints to stdout.  Nothing here runs on the GPU.
+"""
+import collections
+import re
+import sqlite3
+import sys
+
+
+def short_name(name):
+    name = re.sub(r"\s+", " ", name)
+    m = re.search(r"(k_[a-z0-9_]+?)(?=[A-Z<(]|$)", name)   # also inside a mangled name; drops its suffix
+    if m:
+        t = re.search(re.escape(m.group(1)) + r"(<[^(]*>)", name)
+        return m.group(1) + (t.group(1) if t else "")
+    return re.sub(r"\(.*", "", name)[-60:]
+
+
+def kernel_stats(db):
+    """[(name, calls, avg_us, min_us, max_us, total_ms)] sorted by total time."""
+    c = sqlite3.connect(db)
+    rows = c.execute("select name, count(*), avg(end-start), min(end-start), max(end-start), sum(end-start) "
+                     "from kernels group by name order by sum(end-start) desc").fetchall()
+    return [(short_name(n), k, a / 1e3, lo / 1e3, hi / 1e3, t / 1e6) for n, k, a, lo, hi, t in rows]
+
+
+def print_kernels(db):
+    """Library kernels one per row; everything else (input generation and staging done with torch
+    before the timed region) summed in one row."""
+    rows = kernel_stats(db)
+    tot = sum(r[5] for r in rows)
+    print(f"{'kernel':64s} {'calls':>7s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'total_ms':>9s} {'%':>6s}")
+    other_calls, other_ms = 0, 0.0
+    for n, k, a, lo, hi, t in rows:
+        if not n.startswith("k_"):
+            other_calls, other_ms = other_calls + k, other_ms + t
+            continue
+        print(f"{n[:64]:64s} {k:7d} {a:9.2f} {lo:9.2f} {hi:9.2f} {t:9.2f} {100 * t / tot:6.2f}")
+    print(f"{'(kernels of other libraries: setup and staging)':64s} {other_calls:7d} {'':9s} {'':9s} {'':9s} "
+          f"{other_ms:9.2f} {100 * other_ms / tot:6.2f}")
+
+
+def counter_per_kernel(db, counter):
+    """{(kernel, workgroups_x, grid_y): (launches, mean counter value per launch, mean duration us)}."""
+    c = sqlite3.connect(db)
+    q = ("select k.name, k.grid_x, k.grid_y, k.workgroup_x, p.dispatch_id, sum(p.counter_value), k.end - k.start "
+         "from pmc_events p join kernels k on p.dispatch_id = k.dispatch_id where p.counter_name = ? "
+         "group by p.dispatch_id")
+    acc = collections.defaultdict(list)
+    for name, gx, gy, wx, _, val, dur in c.execute(q, (counter,)):
+        acc[(short_name(name), gx // wx if wx else gx, gy)].append((val, dur))
+    return {k: (len(v), sum(x for x, _ in v) / len(v), sum(d for _, d in v) / len(v) / 1e3) for k, v in acc.items()}
+
+
+def print_traffic(fetch_db, write_db, probe_bytes):
+    fetch = counter_per_kernel(fetch_db, "FETCH_SIZE")
+    write = counter_per_kernel(write_db, "WRITE_SIZE")
+    pf = [v for k, v in fetch.items() if k[0].startswith("k_copy_probe")]
+    pw = [v for k, v in write.items() if k[0].startswith("k_copy_probe")]
+    if not pf or not pw:
+        raise SystemExit("no k_copy_probe dispatch in the run: cannot calibrate")
+    # the counters are documented in KiB; the probe says what one byte of HBM traffic reads as
+    f_unit = probe_bytes / pf[0][1]
+    w_unit = probe_bytes / pw[0][1]
+    print(f"copy probe of {probe_bytes} bytes: FETCH_SIZE reads {pf[0][1]:.1f} -> {f_unit:.2f} bytes per count "
+          f"(1024 if it counted KiB exactly); WRITE_SIZE reads {pw[0][1]:.1f} -> {w_unit:.2f} bytes per count")
+    print(f"{'kernel':52s} {'wgs_x':>6s} {'gy':>3s} {'n':>5s} {'avg_us':>8s} {'fetch_MB':>10s} {'write_MB':>10s}")
+    for key in sorted(fetch, key=lambda k: -fetch[k][0] * fetch[k][2]):
+        if not key[0].startswith("k_"):
+            continue
+        n, fv, dur = fetch[key]
+        wv = write.get(key, (0, float('nan'), 0))[1]
+        print(f"{key[0][:52]:52s} {key[1]:6d} {key[2]:3d} {n:5d} {dur:8.1f} {fv * f_unit / 1e6:10.2f} "
+              f"{wv * w_unit / 1e6:10.2f}")
+
+
+def main(argv):
+    if len(argv) >= 3 and argv[1] == "kernels":
+        print_kernels(argv[2])
+    elif len(argv) >= 5 and argv[1] == "traffic":
+        print_traffic(argv[2], argv[3], int(argv[4]))
+    else:
+        raise SystemExit(__doc__)
+
+
+if __name__ == "__main__":
+    main(sys.argv)
