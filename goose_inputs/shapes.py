@@ -1,6 +1,6 @@
 """Model shapes of the benchmark configurations (random-init Llama-style decoders).
 
-The paper evaluates Vicuna-7B/13B/33B (Sec. 6 "Setup"); the shapes below are
+The paper evaluates Vicuna-7B/13B/33B (Sec. 5.1 "Setup"); the shapes below are
 those architectures' public dimensions.  Trained weights are not used: every
 tensor is random-init from a seed (see weights.py).
 """

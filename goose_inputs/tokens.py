@@ -2,7 +2,7 @@
 
 Draft tokens are inputs to verification (the draft side of Sec. 4 is not part
 of the verified path).  Siblings always carry distinct tokens, as the paper's
-tree construction drops duplicates (Sec. 4.2, Alg. 1 remark).
+tree construction drops duplicates (Sec. 4.2, Alg. BuildSpineTree remark).
 """
 import numpy as np
 

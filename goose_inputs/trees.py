@@ -3,9 +3,9 @@
 A tree is the input the draft side hands to verification: node 0 is the root
 (the anchor token of the cycle, Sec. 4), parent[0] = -1 and parent[i] < i.
 `is_spine[i]` = 1 tags a context-match (spine) node, 0 a transition (branch)
-node, the two source tags of Alg. 2.  The shapes follow the spine-tree family
-of Alg. 1 (deep chain + wider branches near the root); budgets and depths are
-the benchmark configurations', not produced by running Alg. 1.
+node, the two source tags of Alg. UnifiedGreedyWalk.  The shapes follow the spine-tree family
+of Alg. BuildSpineTree (deep chain + wider branches near the root); budgets and depths are
+the benchmark configurations', not produced by running Alg. BuildSpineTree.
 Nothing here computes masks, depths or positions.
 """
 from dataclasses import dataclass
@@ -32,7 +32,7 @@ def _mk(parent, is_spine) -> Tree:
 
 
 def tree_single() -> Tree:
-    """Root only: one ordinary decoding step (the fallback case of Alg. 3)."""
+    """Root only: one ordinary decoding step (the fallback case of Alg. "Decoding Loop")."""
     return _mk([-1], [1])
 
 
@@ -95,7 +95,7 @@ def tree_spine_stress() -> Tree:
 
 def tree_balanced(B: int = 128, fanout=(4, 3, 2, 2, 2)) -> Tree:
     """Breadth-first balanced tree with the given per-level fan-out, cut at B nodes
-    (the isotropic control shape of Sec. 6)."""
+    (the isotropic control shape of Sec. 5.3)."""
     parent = [-1]
     level = [0]
     for f in fanout:

@@ -3,7 +3,7 @@
  *
  * One call sequence verifies one draft tree in one pass of the target model
  * (Goose, Sec. 4, stage 2 "one forward pass scores every candidate" and stage 3
- * "greedy walk"; Alg. 2):
+ * "greedy walk"; Alg. UnifiedGreedyWalk):
  *
  *   goose_build_mask  ->  goose_embed  ->  goose_verify_layer x n_layers
  *   ->  goose_lm_head_argmax  ->  goose_accept  ->  goose_compact_kv
@@ -27,7 +27,7 @@
  * position P + depth (Sec. 4 "tree attention mask": each node attends only to its
  * root-to-node ancestors).
  *
- * Model: pre-norm Llama-style decoder (the architecture the paper evaluates, Sec. 6):
+ * Model: pre-norm Llama-style decoder (the architecture the paper evaluates, Sec. 5.1):
  * RMSNorm x*rsqrt(mean(x^2)+eps)*g, rotary embedding on q,k with half-split pairing
  * (j, j+d/2) and angle pos*base^(-2j/d), scores/sqrt(d), softmax, SwiGLU MLP, untied LM
  * head, no biases, n_kv_heads == n_heads.  Raw weight matrices are row-major [out][in].
@@ -122,7 +122,7 @@ int goose_build_mask(goose_ctx* ctx, const int32_t* d_parent, int B, int P, cons
 /* ---- 2. embedding gather: x[i][:] = fp32(E[tokens[i]][:]).  d_embed: T[vocab][hidden]. */
 int goose_embed(goose_ctx* ctx, const void* d_embed, const int32_t* d_tokens, int B, float* d_x, void* stream);
 
-/* ---- 3. one decoder layer over the B packed nodes (Alg. 2 line 1, per layer) ------------
+/* ---- 3. one decoder layer over the B packed nodes (Alg. UnifiedGreedyWalk line 1, per layer) ------------
  * d_x fp32 [B][hidden], updated in place.  d_kcache: THIS layer's T[n_heads][cap][head_dim];
  * d_vcache: THIS layer's transposed T[n_heads][head_dim][cap].
  * d_mask/d_pos as written by goose_build_mask.  P from *d_P when d_P != NULL (then the
@@ -131,13 +131,13 @@ int goose_verify_layer(goose_ctx* ctx, const void* d_packed_layer, float* d_x, v
                        int P, const int32_t* d_P, int B, const uint64_t* d_mask, const int32_t* d_pos,
                        void* stream);
 
-/* ---- 4. final norm + LM head + per-node argmax (Alg. 2 line 2) ------------------------
+/* ---- 4. final norm + LM head + per-node argmax (Alg. UnifiedGreedyWalk line 2) ------------------------
  * d_argmax int32 [B]: greedy prediction at every node, lowest index on ties.
  * d_logits_or_null fp32 [B][vocab]; d_margin_or_null fp32 [B] = top-1 minus top-2 logit. */
 int goose_lm_head_argmax(goose_ctx* ctx, const void* d_packed_head, const float* d_x, int B, int32_t* d_argmax,
                          float* d_logits_or_null, float* d_margin_or_null, void* stream);
 
-/* ---- 5. greedy walk (Alg. 2 lines 3-13; Sec. 4.2) -------------------------------------
+/* ---- 5. greedy walk (Alg. UnifiedGreedyWalk lines 3-13; Sec. 4.2) -------------------------------------
  * From the root, step to the child whose draft token equals the prediction at the current
  * node; spine-tagged children are examined before branch children, lower node index first
  * within a tag; stop when no child matches.  d_is_spine_or_null: uint8 [B] (NULL = all spine).

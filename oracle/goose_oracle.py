@@ -1,18 +1,18 @@
-"""CPU oracle for tree verification (Goose, Sec. 4 and Alg. 2).  TEST INFRASTRUCTURE ONLY.
+"""CPU oracle for tree verification (Goose, Sec. 4 and Alg. UnifiedGreedyWalk).  TEST INFRASTRUCTURE ONLY.
 
 A plain, slow, fp64 NumPy statement of what the verification step computes.
 It shares no code with the HIP library and must never be imported by the
 product path; only tests, the smoke check and the benchmark's CPU-baseline
 leg call it.
 
-What is verified (Sec. 1 and Sec. 4, "tree attention mask"; Alg. 2):
+What is verified (Sec. 1 and Sec. 4, "tree attention mask"; Alg. UnifiedGreedyWalk):
   * the target model scores every node i of a draft tree as if the plain
     sequence  prefix + tokens on the root->i path  had been fed causally;
-  * x_hat[i] = argmax of node i's logits (Alg. 2, greedy prediction per node);
+  * x_hat[i] = argmax of node i's logits (Alg. UnifiedGreedyWalk, greedy prediction per node);
   * a walk from the root follows the child whose draft token equals x_hat of
     the current node (spine child checked before branch children), stops when
     no child matches, and returns the accepted nodes plus the bonus token
-    x_hat[last node] (Alg. 2; Sec. 4.2);
+    x_hat[last node] (Alg. UnifiedGreedyWalk; Sec. 4.2);
   * the accepted path (root included) becomes the new end of the KV cache.
 
 Two routes to the per-node logits are kept on purpose:
@@ -21,7 +21,7 @@ Two routes to the per-node logits are kept on purpose:
                            positions P + depth (the method).
 
 The model is a pre-norm Llama-style decoder (the paper runs stock Llama /
-Vicuna checkpoints, Sec. 6 "Setup"; it prints no model equations, so the
+Vicuna checkpoints, Sec. 5.1 "Setup"; it prints no model equations, so the
 conventions are those of that architecture and are pinned in the tests
 against an independent library implementation of it):
 RMSNorm x*rsqrt(mean(x^2)+eps)*g, rotary embedding with half-split pairing
@@ -240,7 +240,7 @@ def top2_margin(logits):
 
 
 def greedy_walk(parent, tokens, is_spine, x_hat):
-    """Alg. 2: follow matching children from the root, spine child before branch children.
+    """Alg. UnifiedGreedyWalk: follow matching children from the root, spine child before branch children.
     Returns (accepted node list without the root, bonus token)."""
     B = len(parent)
     children = [[] for _ in range(B)]

@@ -241,7 +241,7 @@ __global__ __launch_bounds__(64) void k_argmax_top2(const float4* __restrict__ t
 }
 
 // ------------------------------------------------------------------------------------------
-// Greedy walk (Alg. 2).  Every node whose own edge matches (its token equals the prediction
+// Greedy walk (Alg. UnifiedGreedyWalk).  Every node whose own edge matches (its token equals the prediction
 // at its parent) bids for its parent with the key (branch?1:0, node index); the lowest key
 // wins, i.e. spine children before branch children, lower index first.  Thread 0 then follows
 // the winners from the root; node indices grow along any path, so the walk is finite.

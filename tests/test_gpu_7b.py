@@ -4,7 +4,7 @@ and single layers of the 13B / 33B shapes.
 The 7B step is checked twice.  Piecewise, at the one-layer tolerance: every decoder layer from the
 device's own input to that layer (input rows and the layer's stored KV prefix are handed to the
 oracle; output rows, the update on its own scale and the new KV rows are compared), the LM head on
-the final hidden rows, the walk (Alg. 2) and the compaction bit-exactly; the device-resident entry
+the final hidden rows, the walk (Alg. UnifiedGreedyWalk) and the compaction bit-exactly; the device-resident entry
 point the benchmark replays is then required to reproduce the same step bit for bit.  And as a
 whole, all 32 layers on both sides from the same stored prefix, at the depth-scaled tolerance.
 """

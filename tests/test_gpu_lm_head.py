@@ -1,6 +1,6 @@
 """LM head with the fused per-row top-2 reduction: ragged vocabularies, ties, logits on and off.
 
-The prediction rule is the greedy argmax of the target distribution (Sec. 2.1, Alg. 2); ties go to
+The prediction rule is the greedy argmax of the target distribution (Sec. 4.2, Alg. UnifiedGreedyWalk); ties go to
 the lowest token id on both sides.
 """
 import numpy as np

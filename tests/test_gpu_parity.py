@@ -72,7 +72,7 @@ def _compare_step(shape, gm, om, cache, tokens, tree, tol, check_hidden=True):
     # predictions agree wherever the oracle's decision is not a near-tie
     safe = o["margin"] > 2 * tol * scale
     assert np.array_equal(g["argmax"].cpu().numpy()[safe], o["x_hat"][safe])
-    # the walk on the kernel's own predictions is exactly Alg. 2 ...
+    # the walk on the kernel's own predictions is exactly Alg. UnifiedGreedyWalk ...
     acc, bonus = orc.greedy_walk(tree.parent, tokens, tree.is_spine, g["argmax"].cpu().numpy())
     assert g["accept_len"] == len(acc) and g["bonus"] == bonus
     assert g["path"].tolist() == [0] + acc + [-1] * (B - 1 - len(acc))

@@ -1,7 +1,7 @@
 """Pin of the oracle's whole-model forward against an independent library implementation.
 
 The paper runs stock Llama-family checkpoints through the Hugging Face
-Transformers stack (Sec. 6 "Setup", App. C hardware/software table).  Loading
+Transformers stack (Sec. 5.1 "Setup", App. C hardware/software table).  Loading
 the same random-init weights into that library's Llama model and comparing
 logits pins every convention the oracle had to choose (norm, rotary pairing,
 score scale, SwiGLU, weight orientation), for the plain causal run and for the

@@ -5,8 +5,8 @@
   3. the packed tree pass equals one plain causal run per root-to-node path
      (Sec. 1: every path is scored in one forward pass) -- brute force;
   4. accepted tokens + bonus over several cycles equal plain greedy decoding
-     (the lossless property, Sec. 1 and Sec. 6 "identical output").
-Plus cheap structural checks on the mask, the walk (Alg. 2) and the KV commit.
+     (the lossless property, Sec. 1 and Sec. 5.2 "identical output").
+Plus cheap structural checks on the mask, the walk (Alg. UnifiedGreedyWalk) and the KV commit.
 """
 import json
 import os
