@@ -158,6 +158,46 @@ def test_7b_whole_step_against_the_oracle():
     gm.ctx.close()
 
 
+@pytest.mark.timeout(900)
+def test_7b_hundred_cycles_walk_and_compaction_bit_exact():
+    """100 consecutive cycles at the benchmark shape with planted drafts: every cycle's walk equals
+    Alg. UnifiedGreedyWalk on the kernel's own predictions, and the committed cache rows are, byte for
+    byte, the rows the layers wrote for the accepted path."""
+    from paper_2604_02047_amd import ModelDesc
+    from paper_2604_02047_amd.runner import GooseModel
+    shape, seed, B, P0, n_cycles = gi.SHAPES["7b"], 0, 64, 1024, 100
+    dev = torch.device("cuda:0")
+    cap = (P0 + n_cycles * 20 + 2 * B + 63) // 64 * 64
+    gm = GooseModel(ModelDesc.from_shape(shape), B, cap, lambda l: gi.layer_weights(shape, seed, l, dev),
+                    gi.embedding(shape, seed, dev), gi.lm_head(shape, seed, dev), gi.final_norm(shape, seed, dev))
+    prefix = gi.prefix_tokens(seed, P0, shape.vocab)
+    root = int(_gpu_prefill(gm, prefix, B)["argmax"][-1].item())
+    accepted, multi = 0, 0
+    for t in range(n_cycles):
+        tree = gi.tree_spine_7b(t)
+        tokens = gi.draft_tokens_uniform(seed * 7919 + t, tree.parent, shape.vocab, root)
+        tokens = gi.plant_drafts(seed * 104729 + t, tree.parent, tree.is_spine, tokens, _lookahead(gm, root, 6),
+                                 shape.vocab, p_spine=0.6, p_branch=0.5, p_grand=0.3)
+        P = gm.P
+        g = gm.verify_step_calls(tokens, tree.parent, tree.is_spine, commit=True)
+        acc, bonus = orc.greedy_walk(tree.parent, tokens, tree.is_spine, g["argmax"].cpu().numpy())
+        L = len(acc)
+        assert (g["accept_len"], g["bonus"]) == (L, bonus), f"cycle {t}"
+        assert g["path"].tolist() == [0] + acc + [-1] * (B - 1 - L), f"cycle {t}"
+        assert gm.P == P + L + 1
+        idx = torch.as_tensor([0] + acc, device=dev)
+        assert torch.equal(gm.kcache[:, :, P:P + L + 1], g["tail_k"][:, :, idx]), f"cycle {t}"
+        assert torch.equal(gm.v_rows(P, P + L + 1), g["tail_v"][:, :, idx]), f"cycle {t}"
+        accepted += L
+        multi += any(a != j + 1 for j, a in enumerate(acc))   # a path that leaves the spine moves rows
+        root = bonus
+        if t % 20 == 19:
+            print(f"cycle {t + 1}: P={gm.P}, accepted so far {accepted}", flush=True)
+    assert accepted >= n_cycles and multi >= 5
+    assert gm.ctx.goose_device_flags() == 0
+    gm.ctx.close()
+
+
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("name,B,P0,tree_fn", [
     ("13b", 80, 320, gi.tree_spine_13b),
