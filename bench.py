@@ -321,7 +321,7 @@ def cpu_baseline(shape, gm, seed, B, P0, tree_kind, log):
     om = orc.OracleModel(shape.n_heads, shape.head_dim, shape.rope_base, shape.rms_eps, [None] * n_s,
                          f64(gm.embed), f64(gi.lm_head(shape, seed, gm.device)),
                          f64(gi.final_norm(shape, seed, gm.device)))
-    vr = gm.v_rows(0, P0)
+    kr, vr = gm.k_rows(0, P0), gm.v_rows(0, P0)
     tree = make_tree(tree_kind, 0)
     toks = gi.draft_tokens_uniform(seed, tree.parent, shape.vocab, 1)
     anc, depth = orc.ancestor_mask(tree.parent)
@@ -330,7 +330,7 @@ def cpu_baseline(shape, gm, seed, B, P0, tree_kind, log):
     t_layers = 0.0
     for l in range(n_s):  # one layer's fp64 weights at a time; only the oracle's arithmetic is timed
         w = {k: f64(v) for k, v in gi.layer_weights(shape, seed, l, gm.device).items()}
-        Kc, Vc = f64(gm.kcache[l, :, :P0]), f64(vr[l])
+        Kc, Vc = f64(kr[l]), f64(vr[l])
         ta = time.perf_counter()
         x, _, _ = orc.decoder_layer(om, w, x, Kc, Vc, P0 + depth, allow)
         t_layers += time.perf_counter() - ta

@@ -36,11 +36,17 @@
  * GOOSE_DTYPE_BF16 (MFMA kernels, fp32 accumulation) or GOOSE_DTYPE_F32 (plain fp32
  * kernels for small models).  The residual stream x is always fp32 [B][hidden].
  *
- * KV cache: two allocations.  K is T[n_layers][n_heads][cap][head_dim], stored after the
- * rotary embedding.  V is stored TRANSPOSED, T[n_layers][n_heads][head_dim][cap], so that the
- * attention kernel reads 16 contiguous bytes of one head-dim row across slots.  cap must be a
- * multiple of 64.  verify_layer writes slots [P, P+B) of its layer, compact_kv rewrites
- * slots [P, P+L] of every layer; slots above P+L hold leftovers afterwards.
+ * KV cache: two allocations of n_layers * n_heads * cap * head_dim elements each, one head's
+ * cap * head_dim elements contiguous, cap a multiple of 64.  K is stored after the rotary embedding.
+ *   GOOSE_DTYPE_F32:  K[layer][head][slot][d];  V TRANSPOSED, Vt[layer][head][d][slot].
+ *   GOOSE_DTYPE_BF16: both in MFMA OPERAND ORDER, in blocks of 32 slots, so that the attention
+ *   kernel streams them with one coalesced 16-byte load per lane and no re-arrangement.
+ *   With g = slot, kk = g % 32, c = head-dim column, the element offset inside one head is
+ *     K: (((g/32)*(d/16) + c/16)*64 + i + 32*((c/8)%2))*8 + c%8,
+ *        i = ((kk/4)%4)*8 + (kk/16)*4 + kk%4      (the MFMA row that carries key kk of a block)
+ *     V: ((((g/32)*(d/32) + c/32)*2 + (kk/8)%2)*64 + c%32 + 32*(kk/16))*8 + kk%8.
+ * verify_layer writes slots [P, P+B) of its layer, compact_kv rewrites slots [P, P+L] of every
+ * layer; slots above P+L hold leftovers afterwards (never read: every kernel masks by P).
  */
 #ifndef GOOSE_H
 #define GOOSE_H
@@ -123,8 +129,8 @@ int goose_build_mask(goose_ctx* ctx, const int32_t* d_parent, int B, int P, cons
 int goose_embed(goose_ctx* ctx, const void* d_embed, const int32_t* d_tokens, int B, float* d_x, void* stream);
 
 /* ---- 3. one decoder layer over the B packed nodes (Alg. UnifiedGreedyWalk line 1, per layer) ------------
- * d_x fp32 [B][hidden], updated in place.  d_kcache: THIS layer's T[n_heads][cap][head_dim];
- * d_vcache: THIS layer's transposed T[n_heads][head_dim][cap].
+ * d_x fp32 [B][hidden], updated in place.  d_kcache / d_vcache: THIS layer's part of the two
+ * cache allocations (n_heads * cap * head_dim elements each, layout above).
  * d_mask/d_pos as written by goose_build_mask.  P from *d_P when d_P != NULL (then the
  * argument P must be an upper bound of *d_P; it sizes the launch), else the argument. */
 int goose_verify_layer(goose_ctx* ctx, const void* d_packed_layer, float* d_x, void* d_kcache, void* d_vcache,
@@ -153,7 +159,7 @@ int goose_accept(goose_ctx* ctx, const int32_t* d_parent, const int32_t* d_token
  * accepted nodes become cache slots P..P+L; valid because a node's K was rotated at
  * P + depth and depth(path[j]) = j).  Exact byte copies.  The paper does not describe
  * cache handling; this is the standard commit of tree speculation.
- * d_kcache_all/d_vcache_all: the whole K and (transposed) V allocations, all layers.
+ * d_kcache_all/d_vcache_all: the whole K and V allocations, all layers (layout above).
  * If d_new_P_or_null != NULL it receives P + L + 1 (it may alias d_P). */
 int goose_compact_kv(goose_ctx* ctx, void* d_kcache_all, void* d_vcache_all, int P, const int32_t* d_P,
                      const int32_t* d_path, const int32_t* d_accept_len, int32_t* d_new_P_or_null, void* stream);

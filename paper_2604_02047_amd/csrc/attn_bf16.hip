@@ -1,80 +1,262 @@
 // Tree-masked attention of the B draft-node queries over the cached prefix plus their own
-// ancestors (Sec. 4, tree attention mask), bf16 operands, fp32 softmax, for gfx950.
+// ancestors (Sec. 4, tree attention mask), fused with the rotary embedding of q and k and the
+// write of the new K/V rows; bf16 operands, fp32 softmax, for gfx950.
 //
-// All B queries of a head share the same keys, so the B nodes are the N dimension of an MFMA
-// and every K/V byte fetched from HBM is used B times.  Cache layout: K[head][slot][d] and
-// V TRANSPOSED, Vt[head][d][slot], so that both MFMA operands are 16 contiguous bytes per lane.
-// Work decomposition:
-//   grid = (key splits, heads); a workgroup has one wavefront per 32-query tile.
-//   The workgroup stages 64-key tiles of K and Vt in LDS (double buffered: the next tile is
-//   on its way global -> registers while the current one is multiplied).
-//   Per 32-key sub-tile a wavefront computes
+// All B queries of a head share the same keys, so the B nodes are the N dimension of an MFMA and
+// every K/V byte fetched from HBM is used B times.  The caches are stored in MFMA OPERAND ORDER
+// (see goose.h): a 32-key block of one head is D/16 x 1 KiB of K and D/16 x 1 KiB of V, each
+// 1 KiB piece being the 64 lanes x 16 bytes of one operand load.  A wavefront therefore streams
+// its key blocks global -> registers -> MFMA with perfectly coalesced loads: no LDS staging, no
+// barriers.
+//
+// Per 32-key block and 32-query tile:
 //     S^T[key][query]  = K . Q^T          (v_mfma_f32_32x32x16_bf16, rows = keys)
-//     online softmax over keys: in this layout each lane owns ONE query (column l%32) and 16
-//     keys, so the running max / sum / rescale are per-lane scalars plus one exchange with the
-//     twin lane l^32;
-//     O^T[d][query]   += Vt . P^T         (rows = head-dim, columns = the same queries).
-//   The MFMA row <-> key assignment is chosen so that the 16 scores a lane holds are 16
-//   consecutive keys: the probabilities feed the second MFMA straight from registers.
-// Splits write (max, sum, unnormalised O) partials; k_attn_merge combines them in fixed order.
-#include <type_traits>
+//     online softmax over keys: each lane owns ONE query (column l%32) and 16 keys, so the
+//     running max / sum / rescale are per-lane scalars plus one exchange with the twin lane l^32;
+//     O^T[d][query]   += V^T . P^T        (rows = head-dim, columns = the same queries).
+// The MFMA row <-> key assignment (sigma, baked into the K block layout) makes the 16 scores a
+// lane holds 16 consecutive keys, so the probabilities feed the second MFMA from registers.
+//
+// Work decomposition: grid = (key splits, heads); a workgroup = NQH query tiles x NG key groups
+// of one wavefront each.  The prefix blocks [0, ceil(P/32)) are dealt to splits and groups; the
+// LAST split also owns the tree itself: it sums the split-K slices of the k|v projections of the
+// B nodes, rotates k, stores both into LDS (for this pass) and into cache slots P+i (for later
+// cycles), and attends to them under the ancestor mask.  Every wavefront rotates its own q
+// operand from the projection slices (lane-local: the rotation pairs (j, j+d/2) live in the same
+// lane).  Groups are merged through LDS; splits write (max, sum, unnormalised O) partials that
+// k_attn_merge combines in fixed order (a single split writes the normalised bf16 rows itself).
 
 #include "goose_internal.h"
 
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int TK = 64;             // keys per staged tile
 constexpr float NEG_BIG = -1e30f;  // finite stand-in for -inf: keeps exp2(m_old - m_new) well defined
+constexpr int TAIL_COST = 3;       // a tree block costs the last split about this many prefix blocks
 
-template <int D, int QT>
-__global__ __launch_bounds__(64 * QT) void k_attn_bf16(const bf16_t* __restrict__ q, int ldq,
-                                                       const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vt,
-                                                       int cap, const int32_t* __restrict__ dP, int B,
-                                                       const uint64_t* __restrict__ mask, float* __restrict__ att_o,
-                                                       float* __restrict__ att_ml, int Bpad) {
-  constexpr int NTHR = 64 * QT;
-  constexpr int KROW = D * 2 + 16;       // bytes per staged K row
-  constexpr int VROW = TK * 2 + 16;      // bytes per staged Vt row
-  constexpr int KCH = TK * (D / 8);      // 16-byte chunks of a K tile
-  constexpr int VCH = D * (TK / 8);      // 16-byte chunks of a Vt tile
-  constexpr int KPT = KCH / NTHR, VPT = VCH / NTHR;
-  static_assert(KCH % NTHR == 0 && VCH % NTHR == 0, "tile must divide over the workgroup");
-  constexpr int KBYTES = TK * KROW, VBYTES = D * VROW;
-  __shared__ __attribute__((aligned(16))) unsigned char Ks[2][KBYTES];
-  __shared__ __attribute__((aligned(16))) unsigned char Vs[2][VBYTES];
+// lane row i of the first MFMA carries key sigma(i) of its block; inverse below
+__device__ __host__ inline int sigma_inv(int kk) { return (((kk >> 2) & 3) << 3) | ((kk >> 4) << 2) | (kk & 3); }
 
-  const int tid = threadIdx.x, lane = tid & 63, qt = tid >> 6;
+// element offset of chunk (s, hh) of key slot g in the operand-ordered K cache of one head
+template <int D>
+__device__ inline size_t k_chunk_off(int g, int s, int hh) {
+  return (((size_t)(g >> 5) * (D / 16) + s) * 64 + sigma_inv(g & 31) + 32 * hh) * 8;
+}
+// element offset of (slot g, column c) in the operand-ordered V cache of one head
+template <int D>
+__device__ inline size_t v_elem_off(int g, int c) {
+  const int kk = g & 31;
+  return ((((size_t)(g >> 5) * (D / 32) + (c >> 5)) * 2 + ((kk >> 3) & 1)) * 64 + (c & 31) + 32 * (kk >> 4)) * 8 +
+         (kk & 7);
+}
+
+template <int D, int NG, int NQH>
+__global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
+    const float* __restrict__ part, int ks, size_t part_stride, size_t part_ld, int n_heads,
+    const float2* __restrict__ cs, bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, int cap,
+    const int32_t* __restrict__ dP, int B, const uint64_t* __restrict__ mask, float* __restrict__ att_o,
+    float* __restrict__ att_ml, int Bpad, bf16_t* __restrict__ o_out, int ldo) {
+  constexpr int NTHR = 64 * NG * NQH;
+  constexpr int NS = D / 16;               // operand loads (1 KiB pieces) per block, for K and for V
+  constexpr int TROWS = NQH * 32;          // tree rows the LDS buffers hold (>= B for this instantiation)
+  constexpr int KROW = D * 2 + 16;         // bytes per K / Q row in LDS (padded)
+  constexpr int VROW = TROWS * 2 + 16;     // bytes per V^T row in LDS (padded)
+  constexpr int TAIL_BYTES = 2 * TROWS * KROW + D * VROW;  // tree keys, tree values, rotated queries
+  constexpr int OREGS = (D / 32) * 16;                     // accumulator floats per lane
+  constexpr int MERGE_BYTES = (NG / 2) * NQH * (OREGS + 2) * 64 * 4;
+  constexpr int LDS_BYTES = TAIL_BYTES > MERGE_BYTES ? TAIL_BYTES : MERGE_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
+  unsigned char* Kt = lds;                  // tree keys   [i][c]  (rotated)
+  unsigned char* Vt = lds + TROWS * KROW;   // tree values [c][i]  (transposed)
+  unsigned char* Qs = Vt + D * VROW;        // rotated queries [i][c]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = wave % NG, qh = wave / NG;  // key group, query tile
   const int split = blockIdx.x, nsplit = gridDim.x, h = blockIdx.y;
-  const int P = *dP;
-  int Ktot = P + B;
-  if (Ktot > cap) Ktot = cap;
-  // 32-key units dealt evenly to the splits
-  const int units = (Ktot + 31) >> 5;
-  const int k_begin = (int)(((long)units * split) / nsplit) << 5;
-  int k_end = (int)(((long)units * (split + 1)) / nsplit) << 5;
-  if (k_end > Ktot) k_end = Ktot;
-
   const int l31 = lane & 31, hh = lane >> 5;
-  const int qi = qt * 32 + l31;
-  // row i = l31 of the first MFMA carries key sigma(i) so that register r of lane (q, hh) is key hh*16 + r
-  const int sigma = ((l31 >> 2) & 1) * 16 + (l31 & 3) + 4 * (l31 >> 3);
+  const int Hq = n_heads * D;
+  int P = *dP;
+  if (P > cap - B) P = cap - B;  // callers guarantee P + B <= cap; never index outside the cache
+  if (P < 0) P = 0;
+  const bool last = split == nsplit - 1;
 
-  bf16x8 qf[D / 16];
+  // ---- prefix blocks of this split, then of this key group
+  const int nbp = (P + 31) >> 5, nbt = (B + 31) >> 5;
+  int b_lo, b_hi;
+  if (nsplit == 1) {
+    b_lo = 0; b_hi = nbp;
+  } else {
+    const int tc = nbt * TAIL_COST;
+    const int per = (nbp + tc + nsplit - 1) / nsplit;
+    int pl = per - tc;
+    pl = pl < 0 ? 0 : (pl > nbp ? nbp : pl);
+    const int rest = nbp - pl;  // dealt evenly to splits 0 .. nsplit-2
+    if (last) { b_lo = rest; b_hi = nbp; }
+    else {
+      b_lo = (int)(((long)rest * split) / (nsplit - 1));
+      b_hi = (int)(((long)rest * (split + 1)) / (nsplit - 1));
+    }
+  }
+  const int nb_split = b_hi - b_lo;
+  const int blk0 = b_lo + (nb_split * g) / NG;
+  const int nblk = b_lo + (nb_split * (g + 1)) / NG - blk0;
+  // This wavefront's block sequence: its prefix blocks (operands from the cache), then, in the
+  // last split, the tree blocks t = g, g+NG, .. (operands from LDS).
+  const int ntail = last ? (nbt - g + NG - 1) / NG : 0;
+  const int total = nblk + (ntail > 0 ? ntail : 0);
+
+  const bf16_t* kh = kc + (size_t)h * cap * D;
+  const bf16_t* vh = vc + (size_t)h * cap * D;
+  // One block of operands in registers.  The K pieces are free again after the first MFMA chain
+  // and the V pieces after the second, so the next block's loads are issued right there: they fly
+  // during the softmax and the second chain (the loop below exists once: code executed once per
+  // wavefront is all instruction-issue time, so the kernel is kept short).
+  u32x4 kreg[NS], vreg[NS];
+  auto fetch_k = [&](int idx) {
+    if (idx < nblk) {
+      const u32x4* kp = reinterpret_cast<const u32x4*>(kh + (size_t)(blk0 + idx) * 32 * D) + lane;
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s)
-    qf[s] = *reinterpret_cast<const bf16x8*>(q + (size_t)qi * ldq + h * D + s * 16 + hh * 8);
+      for (int s = 0; s < NS; ++s) kreg[s] = kp[s * 64];
+    } else {
+      const int t = g + NG * (idx - nblk);
+      const unsigned char* kp = Kt + (t * 32 + ((l31 >> 2) & 1) * 16 + (l31 & 3) + 4 * (l31 >> 3)) * KROW + hh * 16;
+#pragma unroll
+      for (int s = 0; s < NS; ++s) kreg[s] = *reinterpret_cast<const u32x4*>(kp + s * 32);
+    }
+  };
+  auto fetch_v = [&](int idx) {
+    if (idx < nblk) {
+      const u32x4* vp = reinterpret_cast<const u32x4*>(vh + (size_t)(blk0 + idx) * 32 * D) + lane;
+#pragma unroll
+      for (int s = 0; s < NS; ++s) vreg[s] = vp[s * 64];
+    } else {
+      const int t = g + NG * (idx - nblk);
+      const unsigned char* vp = Vt + l31 * VROW + (t * 32 + hh * 16) * 2;
+#pragma unroll
+      for (int s = 0; s < NS; ++s) vreg[s] = *reinterpret_cast<const u32x4*>(vp + (s >> 1) * 32 * VROW + (s & 1) * 16);
+    }
+  };
+  // the first block is on its way while q (and the tree's k, v) are prepared
+  if (nblk > 0) { fetch_k(0); fetch_v(0); }
 
-  const int W = (B + 63) >> 6;
+  // ---- q of all query tiles (every split), k and v of the tree (last split): sum the split-K
+  // slices, rotate q and k, bf16 into LDS.  One item = 4 columns j0.. and their rotation partners
+  // j0+d/2..: 16 neighbouring lanes read 256 contiguous bytes of a projection row.  The loads of
+  // the first two slices of all of a thread's items are issued together: the buffer was written
+  // by another kernel, so every dependent load is a trip to memory.
+  const int rows = nbt * 32;
+  constexpr int NIT = TROWS * (D / 8) / NTHR;
+  static_assert(TROWS * (D / 8) % NTHR == 0 && NIT >= 1, "items must divide over the workgroup");
+  {
+    const float* prow[NIT];
+    f32x4 acc[NIT][6];  // q lo/hi, k lo/hi, v lo/hi
+    bool kv[NIT];
+#pragma unroll
+    for (int u = 0; u < NIT; ++u) {
+      const int it = tid + u * NTHR;
+      const int i = it / (D / 8), j0 = (it % (D / 8)) * 4;
+      prow[u] = part + (size_t)i * part_ld + h * D + j0;  // row i < Bpad exists in the buffer
+      kv[u] = last && i < B;
+    }
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    const bool two = ks > 1;
+#pragma unroll
+    for (int u = 0; u < NIT; ++u) {
+      const float* p1 = prow[u] + part_stride;
+#pragma unroll
+      for (int w = 0; w < 3; ++w) {
+        const bool on = w == 0 || kv[u];
+        f32x4 a = on ? *reinterpret_cast<const f32x4*>(prow[u] + w * Hq) : zero4;
+        f32x4 b = on ? *reinterpret_cast<const f32x4*>(prow[u] + w * Hq + D / 2) : zero4;
+        if (on && two) {
+          a += *reinterpret_cast<const f32x4*>(p1 + w * Hq);
+          b += *reinterpret_cast<const f32x4*>(p1 + w * Hq + D / 2);
+        }
+        acc[u][2 * w] = a;
+        acc[u][2 * w + 1] = b;
+      }
+    }
+    for (int sl = 2; sl < ks; ++sl) {
+#pragma unroll
+      for (int u = 0; u < NIT; ++u) {
+        const float* p = prow[u] + sl * part_stride;
+#pragma unroll
+        for (int w = 0; w < 3; ++w)
+          if (w == 0 || kv[u]) {
+            acc[u][2 * w] += *reinterpret_cast<const f32x4*>(p + w * Hq);
+            acc[u][2 * w + 1] += *reinterpret_cast<const f32x4*>(p + w * Hq + D / 2);
+          }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < NIT; ++u) {
+      const int it = tid + u * NTHR;
+      const int i = it / (D / 8), j0 = (it % (D / 8)) * 4;
+      const f32x4 c01 = *reinterpret_cast<const f32x4*>(cs + (size_t)i * (D / 2) + j0);      // cos,sin of j0, j0+1
+      const f32x4 c23 = *reinterpret_cast<const f32x4*>(cs + (size_t)i * (D / 2) + j0 + 2);  // ... j0+2, j0+3
+      const float co[4] = {c01[0], c01[2], c23[0], c23[2]}, si[4] = {c01[1], c01[3], c23[1], c23[3]};
+      bf16x4 rl, rh;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        rl[e] = (__bf16)(acc[u][0][e] * co[e] - acc[u][1][e] * si[e]);
+        rh[e] = (__bf16)(acc[u][1][e] * co[e] + acc[u][0][e] * si[e]);
+      }
+      *reinterpret_cast<bf16x4*>(Qs + i * KROW + j0 * 2) = rl;
+      *reinterpret_cast<bf16x4*>(Qs + i * KROW + (j0 + D / 2) * 2) = rh;
+      if (last && i < rows) {  // rows of the tree's blocks beyond B are zero (kv false)
+        bf16x4 kl, kh4, vl, vh4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          kl[e] = (__bf16)(acc[u][2][e] * co[e] - acc[u][3][e] * si[e]);
+          kh4[e] = (__bf16)(acc[u][3][e] * co[e] + acc[u][2][e] * si[e]);
+          vl[e] = (__bf16)acc[u][4][e];
+          vh4[e] = (__bf16)acc[u][5][e];
+        }
+        if (kv[u]) {
+          // key row of slot P+i into the cache: columns j0..j0+3 sit in chunk (j0/16, (j0/8)%2) at j0%8
+          bf16_t* kw = const_cast<bf16_t*>(kh);
+          *reinterpret_cast<bf16x4*>(kw + k_chunk_off<D>(P + i, j0 >> 4, (j0 >> 3) & 1) + (j0 & 7)) = kl;
+          *reinterpret_cast<bf16x4*>(kw + k_chunk_off<D>(P + i, (j0 + D / 2) >> 4, (j0 >> 3) & 1) + (j0 & 7)) = kh4;
+        }
+        *reinterpret_cast<bf16x4*>(Kt + i * KROW + j0 * 2) = kl;
+        *reinterpret_cast<bf16x4*>(Kt + i * KROW + (j0 + D / 2) * 2) = kh4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          *reinterpret_cast<__bf16*>(Vt + (j0 + e) * VROW + i * 2) = vl[e];
+          *reinterpret_cast<__bf16*>(Vt + (j0 + D / 2 + e) * VROW + i * 2) = vh4[e];
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- this wavefront's q operand and ancestor row
+  const int qi = qh * 32 + l31;
+  bf16x8 qf[NS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(Qs + qi * KROW + (16 * s + 8 * hh) * 2);
   uint64_t mw0 = 0, mw1 = 0;
   if (qi < B) {
+    const int W = (B + 63) >> 6;
     mw0 = mask[(size_t)qi * W];
     if (W > 1) mw1 = mask[(size_t)qi * W + 1];
+  }
+  if (nblk == 0 && total > 0) { fetch_k(0); fetch_v(0); }  // a tree block first: it is in LDS only now
+
+  // ---- the tree's values into the cache, node index fastest so that neighbouring lanes fill
+  // neighbouring bytes (the keys went out above)
+  if (last) {
+    bf16_t* vw = const_cast<bf16_t*>(vh);
+    for (int it = tid; it < rows * D; it += NTHR) {
+      const int i = it % rows, c = it / rows;
+      if (i < B) vw[v_elem_off<D>(P + i, c)] = *reinterpret_cast<const bf16_t*>(Vt + c * VROW + i * 2);
+    }
   }
 
   f32x16 oacc[D / 32];
@@ -85,157 +267,136 @@ __global__ __launch_bounds__(64 * QT) void k_attn_bf16(const bf16_t* __restrict_
   float m_run = NEG_BIG, l_run = 0.f;
   const float scale = 1.4426950408889634f / sqrtf((float)D);  // log2(e) / sqrt(d): softmax in base 2
 
-  const bf16_t* kh = kc + (size_t)h * cap * D;
-  const bf16_t* vh = vt + (size_t)h * D * cap;
+  for (int idx = 0; idx < total; ++idx) {
+    // visibility of this lane's 16 keys
+    bool masked = false, ragged = false;
+    unsigned vis = 0xFFFFu;
+    if (idx >= nblk) {  // tree block: the ancestor bits of nodes j0 .. j0+15
+      masked = true;
+      const int j0 = (g + NG * (idx - nblk)) * 32 + hh * 16;
+      vis = (unsigned)(j0 < 64 ? mw0 >> j0 : mw1 >> (j0 - 64)) & 0xFFFFu;
+    } else {
+      const int nvalid = P - (blk0 + idx) * 32;  // >= 32 except in the ragged last prefix block
+      if (nvalid < 32) {
+        // stale slots at or beyond P may hold anything: scores are replaced, values zeroed
+        masked = ragged = true;
+        const int mine = nvalid - hh * 16;
+        vis = mine >= 16 ? 0xFFFFu : (mine <= 0 ? 0u : ((1u << mine) - 1u));
+      }
+    }
+    f32x16 sacc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[s]), qf[s], sacc, 0, 0, 0);
+    if (idx + 1 < total) fetch_k(idx + 1);
+    if (masked) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[r] = ((vis >> r) & 1u) ? sacc[r] : NEG_BIG;  // also drops NaNs of stale keys
+    }
+    float tmax = NEG_BIG;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      sacc[r] = fmaxf(sacc[r] * scale, NEG_BIG);
+      tmax = fmaxf(tmax, sacc[r]);
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float m_new = fmaxf(m_run, tmax);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    const bool grew = m_new > m_run;
+    m_run = m_new;
+    float p[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) p[r] = __builtin_amdgcn_exp2f(sacc[r] - m_new);
+    if (masked) {  // a fully masked row has m_new == NEG_BIG: exp2(0) must not count
+#pragma unroll
+      for (int r = 0; r < 16; ++r) p[r] = ((vis >> r) & 1u) ? p[r] : 0.f;
+    }
+    if (ragged) {  // stale values -> 0 (here `vis` depends on the key half only, as the V operand's keys do)
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const unsigned bits = (vis >> ((s & 1) * 8)) & 0xFFu;
+        u16x8 e = __builtin_bit_cast(u16x8, vreg[s]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+          if (!((bits >> k) & 1u)) e[k] = 0;
+        vreg[s] = __builtin_bit_cast(u32x4, e);
+      }
+    }
+    float psum = 0.f;
+    bf16x8 pf[2];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      psum += p[r];
+      pf[r >> 3][r & 7] = (__bf16)p[r];
+    }
+    l_run = l_run * alpha + psum;
+    // the running maximum settles after a few blocks: skip the rescale of O when no lane's maximum grew
+    if (__builtin_amdgcn_ballot_w64(grew) != 0) {
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+    }
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vreg[dt * 2 + j]), pf[j],
+                                                           oacc[dt], 0, 0, 0);
+    if (idx + 1 < total) fetch_v(idx + 1);
+  }
 
-  // Tile copy global -> registers -> LDS.  Every load is issued unconditionally (a chunk past
-  // the end of the split re-reads the split's first keys, always in bounds) so that all 16 loads
-  // of a thread are in flight together; keys at or beyond k_end are zeroed on the way into LDS.
-  u32x4 kreg[KPT], vreg[VPT];
-  auto load_tile = [&](int key0) {
+  // ---- merge the key groups of a query tile through LDS (pairwise, fixed order)
+  if (NG > 1) {
+    __syncthreads();  // every wavefront is done with the tree and query buffers
+    float* mbuf = reinterpret_cast<float*>(lds);
+    constexpr int WFLOATS = (OREGS + 2) * 64;
 #pragma unroll
-    for (int i = 0; i < KPT; ++i) {
-      const int ch = tid + NTHR * i;
-      const int row = ch / (D / 8), c = ch % (D / 8);
-      const int key = (key0 + row < k_end) ? key0 + row : k_begin;
-      kreg[i] = *reinterpret_cast<const u32x4*>(kh + (size_t)key * D + c * 8);
-    }
-#pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-      const int ch = tid + NTHR * i;
-      const int row = ch / (TK / 8), c = ch % (TK / 8);
-      const int key = (key0 + c * 8 < k_end) ? key0 + c * 8 : k_begin;
-      vreg[i] = *reinterpret_cast<const u32x4*>(vh + (size_t)row * cap + key);
-    }
-  };
-  auto store_tile = [&](int buf, int key0) {
-    const bool ragged = key0 + TK > k_end;  // only the last tile of a split
-#pragma unroll
-    for (int i = 0; i < KPT; ++i) {
-      const int ch = tid + NTHR * i;
-      const int row = ch / (D / 8), c = ch % (D / 8);
-      u32x4 v = kreg[i];
-      if (ragged && key0 + row >= k_end) v = u32x4{0, 0, 0, 0};
-      *reinterpret_cast<u32x4*>(&Ks[buf][row * KROW + c * 16]) = v;
-    }
-#pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-      const int ch = tid + NTHR * i;
-      const int row = ch / (TK / 8), c = ch % (TK / 8);
-      u32x4 v = vreg[i];
-      if (ragged) {
-        const int key = key0 + c * 8;
-        u16x8 e = __builtin_bit_cast(u16x8, v);
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-          if (key + j >= k_end) e[j] = 0;
-        v = __builtin_bit_cast(u32x4, e);
-      }
-      *reinterpret_cast<u32x4*>(&Vs[buf][row * VROW + c * 16]) = v;
-    }
-  };
-
-  auto compute_tile = [&](auto buf_c, int key0) {
-    constexpr int buf = decltype(buf_c)::value;
-#pragma unroll
-    for (int sub = 0; sub < TK / 32; ++sub) {
-      const int kb = key0 + sub * 32;
-      if (kb >= k_end) break;
-      f32x16 sacc;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
-#pragma unroll
-      for (int s = 0; s < D / 16; ++s) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[buf][(sub * 32 + sigma) * KROW + s * 32 + hh * 16]);
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], sacc, 0, 0, 0);
-      }
-      // scores -> probabilities.  Sub-tiles that lie wholly inside the prefix need no mask at all
-      // (wave-uniform test); only the few tail sub-tiles take the masked path.
-      const int kfirst = kb + hh * 16;  // this lane's 16 keys are kfirst .. kfirst+15
-      float tmax = NEG_BIG;
-      unsigned vis = 0xFFFFu;
-      const bool masked = kb + 32 > P;
-      if (!masked) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          sacc[r] *= scale;
-          tmax = fmaxf(tmax, sacc[r]);
-        }
-      } else {
-        // 16 visibility bits: keys below P are visible, key P+j is visible iff bit j of the ancestor row
-        const int j0 = kfirst - P;
-        if (j0 >= 0) {
-          const uint64_t lo = j0 < 64 ? (mw0 >> j0) | (j0 ? mw1 << (64 - j0) : 0ull) : (j0 < 128 ? mw1 >> (j0 - 64) : 0ull);
-          vis = (unsigned)lo & 0xFFFFu;
-        } else if (j0 > -16) {
-          const int np = -j0;  // 1..15 prefix keys first
-          vis = (((1u << np) - 1u) | ((unsigned)mw0 << np)) & 0xFFFFu;
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          sacc[r] = ((vis >> r) & 1u) ? sacc[r] * scale : NEG_BIG;
-          tmax = fmaxf(tmax, sacc[r]);
-        }
-      }
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-      const float m_new = fmaxf(m_run, tmax);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      const bool grew = m_new > m_run;
-      m_run = m_new;
-      float psum = 0.f;
-      bf16x8 pf[2];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float p = __builtin_amdgcn_exp2f(sacc[r] - m_new);
-        if (masked) p = ((vis >> r) & 1u) ? p : 0.f;  // a fully masked row has m_new == NEG_BIG: exp2(0) must not count
-        psum += p;
-        pf[r >> 3][r & 7] = (__bf16)p;
-      }
-      l_run = l_run * alpha + psum;
-      // the running maximum settles after a few tiles: skip the rescale of O when no lane's maximum grew
-      if (__builtin_amdgcn_ballot_w64(grew) != 0) {
+    for (int half = NG / 2; half >= 1; half >>= 1) {
+      if (g >= half && g < 2 * half) {
+        float* dst = mbuf + (size_t)(qh * (NG / 2) + (g - half)) * WFLOATS + lane;
+        dst[0] = m_run;
+        dst[64] = l_run;
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+          for (int r = 0; r < 16; ++r) dst[64 * (2 + dt * 16 + r)] = oacc[dt][r];
       }
+      __syncthreads();
+      if (g < half) {
+        const float* src = mbuf + (size_t)(qh * (NG / 2) + g) * WFLOATS + lane;
+        const float mo = src[0], lo = src[64];
+        const float m_new = fmaxf(m_run, mo);
+        const float a = __builtin_amdgcn_exp2f(m_run - m_new), b = __builtin_amdgcn_exp2f(mo - m_new);
+        m_run = m_new;
+        l_run = l_run * a + lo * b;
 #pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt) {
+        for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(
-              &Vs[buf][(dt * 32 + l31) * VROW + (sub * 32 + hh * 16 + j * 8) * 2]);
-          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[j], oacc[dt], 0, 0, 0);
-        }
+          for (int r = 0; r < 16; ++r) oacc[dt][r] = oacc[dt][r] * a + src[64 * (2 + dt * 16 + r)] * b;
       }
-    }
-  };
-  const std::integral_constant<int, 0> b0;
-  const std::integral_constant<int, 1> b1;
-
-  const int ntiles = (k_end - k_begin + TK - 1) / TK;
-  if (ntiles > 0) {
-    load_tile(k_begin);
-    store_tile(0, k_begin);
-    __syncthreads();
-    for (int t = 0; t < ntiles; t += 2) {
-      const int key0 = k_begin + t * TK;
-      const bool more1 = (t + 1) < ntiles;
-      if (more1) load_tile(key0 + TK);
-      compute_tile(b0, key0);
-      if (more1) store_tile(1, key0 + TK);
-      __syncthreads();
-      if (!more1) break;
-      const bool more2 = (t + 2) < ntiles;
-      if (more2) load_tile(key0 + 2 * TK);
-      compute_tile(b1, key0 + TK);
-      if (more2) store_tile(0, key0 + 2 * TK);
-      __syncthreads();
+      if (half > 1) __syncthreads();
     }
   }
+  if (g != 0) return;
 
+  // ---- output: C layout of O^T, register r of lane (q, hh) is d = dt*32 + 8*(r/4) + 4*hh + r%4
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  if (qi < B) {
+  if (qi >= B) return;
+  if (nsplit == 1) {
+    const float inv = 1.0f / l_tot;
+    bf16_t* orow = o_out + (size_t)qi * ldo + h * D;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        bf16x4 v = {(__bf16)(oacc[dt][a * 4] * inv), (__bf16)(oacc[dt][a * 4 + 1] * inv),
+                    (__bf16)(oacc[dt][a * 4 + 2] * inv), (__bf16)(oacc[dt][a * 4 + 3] * inv)};
+        *reinterpret_cast<bf16x4*>(orow + dt * 32 + a * 8 + hh * 4) = v;
+      }
+  } else {
     const size_t base = ((size_t)h * nsplit + split) * Bpad + qi;
     if (hh == 0) {
       att_ml[base * 2] = m_run;
@@ -268,52 +429,77 @@ __global__ void k_attn_merge(const float* __restrict__ att_o, const float* __res
   o[(size_t)qi * ldo + h * D + c] = (bf16_t)(num / den);
 }
 
-template <int D>
-int launch_qt(int QT, dim3 grid, hipStream_t st, const bf16_t* q, int ldq, const bf16_t* kc, const bf16_t* vt, int cap,
-              const int32_t* dP, int B, const uint64_t* mask, float* att_o, float* att_ml, int Bpad) {
-  switch (QT) {
-    case 1: hipLaunchKernelGGL((k_attn_bf16<D, 1>), grid, dim3(64), 0, st, q, ldq, kc, vt, cap, dP, B, mask, att_o, att_ml, Bpad); break;
-    case 2: hipLaunchKernelGGL((k_attn_bf16<D, 2>), grid, dim3(128), 0, st, q, ldq, kc, vt, cap, dP, B, mask, att_o, att_ml, Bpad); break;
-    case 3: hipLaunchKernelGGL((k_attn_bf16<D, 4>), grid, dim3(256), 0, st, q, ldq, kc, vt, cap, dP, B, mask, att_o, att_ml, Bpad); break;
-    case 4: hipLaunchKernelGGL((k_attn_bf16<D, 4>), grid, dim3(256), 0, st, q, ldq, kc, vt, cap, dP, B, mask, att_o, att_ml, Bpad); break;
-    default: return GOOSE_ERR_ARG;
-  }
+// (cos, sin) of pos[m] * base^(-2j/d) for every node m and pair j: the angle is reduced in double,
+// then evaluated in float (|error| ~ 1e-7 rad at any position).
+__global__ void k_rope_table(const int32_t* __restrict__ pos, const double* __restrict__ inv_freq, int half,
+                             float2* __restrict__ cs) {
+  const int m = blockIdx.x, j = threadIdx.x;
+  double ang = (double)pos[m] * inv_freq[j];
+  const double two_pi = 6.283185307179586476925286766559;
+  ang -= two_pi * rint(ang / two_pi);
+  float sn, c;
+  sincosf((float)ang, &sn, &c);
+  cs[(size_t)m * half + j] = make_float2(c, sn);
+}
+
+struct AttnArgs {
+  const float* part; int ks; size_t part_stride, part_ld; int n_heads;
+  const float2* cs; bf16_t* kc; bf16_t* vc; int cap; const int32_t* dP; int B; const uint64_t* mask;
+  float* att_o; float* att_ml; int Bpad; bf16_t* o; int ldo;
+};
+
+template <int D, int NG, int NQH>
+int launch_cfg(dim3 grid, hipStream_t st, const AttnArgs& a) {
+  hipLaunchKernelGGL((k_attn_fused<D, NG, NQH>), grid, dim3(64 * NG * NQH), 0, st, a.part, a.ks, a.part_stride,
+                     a.part_ld, a.n_heads, a.cs, a.kc, a.vc, a.cap, a.dP, a.B, a.mask, a.att_o, a.att_ml, a.Bpad, a.o,
+                     a.ldo);
   return goose_launch_status();
+}
+
+template <int D>
+int launch_d(int QT, int ng, dim3 grid, hipStream_t st, const AttnArgs& a) {
+  // one wavefront per (query tile, key group); at most 8 wavefronts per workgroup
+  if (QT == 1) return ng == 4 ? launch_cfg<D, 4, 1>(grid, st, a) : launch_cfg<D, 2, 1>(grid, st, a);
+  if (QT == 2) return ng == 4 ? launch_cfg<D, 4, 2>(grid, st, a) : launch_cfg<D, 2, 2>(grid, st, a);
+  return launch_cfg<D, 2, 4>(grid, st, a);
 }
 
 }  // namespace
 
-// Key splits per head: at least two 64-key tiles per workgroup, about one workgroup per compute
-// unit (two for long prefixes).
+int launch_rope_table(const int32_t* pos, const double* inv_freq, int B, int head_dim, void* cs, hipStream_t st) {
+  hipLaunchKernelGGL(k_rope_table, dim3(B), dim3(head_dim / 2), 0, st, pos, inv_freq, head_dim / 2, (float2*)cs);
+  return goose_launch_status();
+}
+
+// Key splits per head for a pass over `keys_max` keys: about two 32-key blocks per wavefront
+// (4 key groups per workgroup); fewer, longer splits measured better than more, shorter ones
+// (every split adds a partial result and a workgroup's fixed cost), more are needed only to
+// spread long prefixes over the chip.
 int pick_attn_splits(int n_heads, int keys_max, int max_splits) {
-  // one workgroup per CU (256) measured faster than more, shorter splits: a split of one tile has
-  // nothing to overlap its loads with, and every split adds a partial result to merge
-  const int tiles = (keys_max + TK - 1) / TK;
-  int s = (tiles + 1) / 2;
-  const int want = ((tiles > 64 ? 512 : 256) + n_heads - 1) / n_heads;
+  const int blocks = (keys_max + 31) / 32;
+  int s = (blocks + 7) / 8;
+  const int want = (1024 + n_heads - 1) / n_heads;
   if (s > want) s = want;
   if (s > max_splits) s = max_splits;
   if (s < 1) s = 1;
   return s;
 }
 
-int launch_attn_bf16(const void* q, int ldq, const void* kc, const void* vt, int n_heads, int head_dim, int cap,
-                     const int32_t* dP, int B, const uint64_t* mask, int splits, float* att_o, float* att_ml,
-                     int Bpad, void* o, int ldo, hipStream_t st) {
+int launch_attn_bf16(const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs, void* kc, void* vc,
+                     int n_heads, int head_dim, int cap, const int32_t* dP, int B, const uint64_t* mask, int splits,
+                     int key_groups, float* att_o, float* att_ml, int Bpad, void* o, int ldo, hipStream_t st) {
   const int QT = (B + 31) / 32;
-  // a 3-tile tree runs the 4-wavefront kernel, which reads query rows up to 128 (the workspace has them)
-  if ((QT == 3 ? 4 : QT) * 32 > Bpad) return GOOSE_ERR_ARG;
+  // a 3-tile tree runs the 4-tile kernel, which reads projection rows up to 128 (the workspace has them)
+  if ((QT >= 3 ? 4 : QT) * 32 > Bpad || B > GOOSE_MAX_B || (cap & 31)) return GOOSE_ERR_ARG;
+  if (splits < 1 || (key_groups != 2 && key_groups != 4)) return GOOSE_ERR_ARG;
+  AttnArgs a{part, ks, part_stride, part_ld, n_heads, (const float2*)cs, (bf16_t*)kc, (bf16_t*)vc, cap, dP, B, mask,
+             att_o, att_ml, Bpad, (bf16_t*)o, ldo};
   dim3 grid(splits, n_heads);
   int rc;
-  if (head_dim == 128)
-    rc = launch_qt<128>(QT, grid, st, (const bf16_t*)q, ldq, (const bf16_t*)kc, (const bf16_t*)vt, cap, dP, B, mask,
-                        att_o, att_ml, Bpad);
-  else if (head_dim == 64)
-    rc = launch_qt<64>(QT, grid, st, (const bf16_t*)q, ldq, (const bf16_t*)kc, (const bf16_t*)vt, cap, dP, B, mask,
-                       att_o, att_ml, Bpad);
-  else
-    return GOOSE_ERR_SHAPE;
-  if (rc != GOOSE_OK) return rc;
+  if (head_dim == 128) rc = launch_d<128>(QT, key_groups, grid, st, a);
+  else if (head_dim == 64) rc = launch_d<64>(QT, key_groups, grid, st, a);
+  else return GOOSE_ERR_SHAPE;
+  if (rc != GOOSE_OK || splits == 1) return rc;
   hipLaunchKernelGGL(k_attn_merge, dim3(B, n_heads), dim3(head_dim), 0, st, att_o, att_ml, splits, Bpad, head_dim,
                      (bf16_t*)o, ldo);
   return goose_launch_status();

@@ -205,6 +205,7 @@ int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** o
   A((void**)&c->logits, (size_t)c->Bpad * c->Vpad * sizeof(float));
   A(&c->top2, (size_t)c->Bpad * (c->Vpad / 64 + 1) * 16);
   A((void**)&c->inv_freq, (size_t)(d.head_dim / 2) * sizeof(double));
+  A(&c->rope_cs, (size_t)GOOSE_MAX_B * (d.head_dim / 2) * 2 * sizeof(float));
   A((void**)&c->s_mask, 128 * 2 * sizeof(uint64_t));
   A((void**)&c->s_depth, 128 * sizeof(int32_t));
   A((void**)&c->s_pos, 128 * sizeof(int32_t));
@@ -229,7 +230,7 @@ int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** o
 
 void goose_destroy(goose_ctx* c) {
   if (!c) return;
-  void* ptrs[] = {c->xn, c->part, c->q, c->o, c->h, c->att_o, c->att_ml, c->logits, c->top2, c->inv_freq,
+  void* ptrs[] = {c->xn, c->part, c->q, c->o, c->h, c->att_o, c->att_ml, c->logits, c->top2, c->inv_freq, c->rope_cs,
                   c->s_mask, c->s_depth, c->s_pos, c->s_x, c->flags, c->s_P};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
@@ -336,15 +337,13 @@ static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, v
       rc = launch_gemm_bf16(EPI_PARTIAL, c->xn, c->Kh, w + c->pl.wqkv, Nqkv, c->Kh, B, cq.nw, ks, c->part,
                             c->part_ld, pstride, st); }
     if (rc) return rc;
-    { PROF(PK_ROPE);
-      rc = launch_rope_kv(d.dtype, c->part, ks, pstride, c->part_ld, B, d.n_heads, d.head_dim, d_pos, c->inv_freq,
-                          dP, c->cap, c->q, c->Kq, d_kcache, d_vcache, st); }
-    if (rc) return rc;
+    // rotary embedding of q and k, KV rows of the tree into the cache, tree attention: one kernel
+    static const int ng_env = env_int("GOOSE_ATTN_NG", 4) == 2 ? 2 : 4;
     int splits = splits_env > 0 ? splits_env : pick_attn_splits(d.n_heads, P + B, c->max_splits);
     if (splits > c->max_splits) splits = c->max_splits;
     { PROF(PK_ATTN);
-      rc = launch_attn_bf16(c->q, c->Kq, d_kcache, d_vcache, d.n_heads, d.head_dim, c->cap, dP, B, d_mask, splits,
-                            c->att_o, c->att_ml, c->Bpad, c->o, c->Kq, st); }
+      rc = launch_attn_bf16(c->part, ks, pstride, c->part_ld, c->rope_cs, d_kcache, d_vcache, d.n_heads, d.head_dim,
+                            c->cap, dP, B, d_mask, splits, ng_env, c->att_o, c->att_ml, c->Bpad, c->o, c->Kq, st); }
     if (rc) return rc;
     const GemmCfg co = gemm_cfg(c, "GOOSE_CFG_O", Nh, c->Kq);
     ks = co.ks;
@@ -408,6 +407,11 @@ int goose_verify_layer(goose_ctx* c, const void* d_packed_layer, float* d_x, voi
   const int32_t* dP;
   rc = resolve_P(c, P, d_P, st, &dP);
   if (rc) return rc;
+  if (c->d.dtype == GOOSE_DTYPE_BF16) {
+    PROF(PK_ROPE);
+    rc = launch_rope_table(d_pos, c->inv_freq, B, c->d.head_dim, c->rope_cs, st);
+    if (rc) return rc;
+  }
   return layer_impl(c, (const char*)d_packed_layer, d_x, d_kcache, d_vcache, P, dP, B, d_mask, d_pos, st, false,
                     nullptr);
 }
@@ -496,6 +500,11 @@ int goose_verify_step(goose_ctx* c, const goose_model_ptrs* m, const goose_step_
   if (rc) return rc;
   rc = launch_embed(d.dtype, m->d_embed, io->d_tokens, B, d.hidden, d.vocab, c->s_x, st);
   if (rc) return rc;
+  if (d.dtype == GOOSE_DTYPE_BF16) {  // the tree's rotary angles, once for all layers
+    PROF(PK_ROPE);
+    rc = launch_rope_table(c->s_pos, c->inv_freq, B, d.head_dim, c->rope_cs, st);
+    if (rc) return rc;
+  }
   const size_t layer_cache = (size_t)d.n_heads * c->cap * d.head_dim * elem_size(d.dtype);
   // each layer's closing residual add also writes the next normalisation's output
   for (int l = 0; l < d.n_layers; ++l) {

@@ -66,6 +66,7 @@ struct goose_ctx {
   float* logits;   // f32 [Bpad][Vpad]  (fp32 models; vocabularies that are no multiple of 32)
   void* top2;      // float4 [Bpad][Vpad/64]  per-workgroup reductions of the LM head
   double* inv_freq;  // f64 [head_dim/2]
+  void* rope_cs;     // float2 [128][head_dim/2]  (cos, sin) of the current tree's positions
   // scratch for goose_verify_step
   uint64_t* s_mask;  // [128][2]
   int32_t* s_depth;  // [128]
@@ -119,7 +120,11 @@ int launch_gemm_top2_bf16(const void* A, int lda, const void* Wp, int Npad, int 
 int launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
 int launch_argmax_top2(const void* top2, int n_groups, int B, int32_t* argmax, float* margin, hipStream_t st);
 void pick_gemm_config(int Npad, int Kpad, int max_ksplit, int* nw_out, int* ksplit_out);
-int launch_attn_bf16(const void* q, int ldq, const void* kc, const void* vc, int n_heads, int head_dim, int cap,
-                     const int32_t* dP, int B, const uint64_t* mask, int splits, float* att_o, float* att_ml,
-                     int Bpad, void* o, int ldo, hipStream_t st);
+// (cos, sin) of every node's rotary angles: cs is float2 [B][head_dim/2].
+int launch_rope_table(const int32_t* pos, const double* inv_freq, int B, int head_dim, void* cs, hipStream_t st);
+// Fused rotary embedding + KV-tail write + tree attention.  part: the q|k|v projection as `ks`
+// split-K slices of f32 [Bpad][part_ld]; kc/vc: this layer's operand-ordered caches; o: bf16 [B][ldo].
+int launch_attn_bf16(const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs, void* kc, void* vc,
+                     int n_heads, int head_dim, int cap, const int32_t* dP, int B, const uint64_t* mask, int splits,
+                     int key_groups, float* att_o, float* att_ml, int Bpad, void* o, int ldo, hipStream_t st);
 int pick_attn_splits(int n_heads, int keys_max, int max_splits);

@@ -304,6 +304,38 @@ __global__ __launch_bounds__(64) void k_compact_k(uint4* __restrict__ kall, int 
   }
 }
 
+// The same for bf16 caches in MFMA operand order (32-key blocks; the layouts are spelled out in
+// goose.h): thread c moves chunk c of the K row (16 bytes) and column c of the V row (2 bytes).
+template <int D>
+__global__ __launch_bounds__(D) void k_compact_tiled(bf16_t* __restrict__ kall, bf16_t* __restrict__ vall, int cap,
+                                                     const int32_t* __restrict__ dP,
+                                                     const int32_t* __restrict__ path,
+                                                     const int32_t* __restrict__ accept_len) {
+  const int c = threadIdx.x;
+  bf16_t* kb = kall + (size_t)blockIdx.x * cap * D;  // blockIdx.x = layer * n_heads + head
+  bf16_t* vb = vall + (size_t)blockIdx.x * cap * D;
+  const int P = *dP;
+  int L = *accept_len;
+  if (L > GOOSE_MAX_B - 1) L = GOOSE_MAX_B - 1;
+  auto k_off = [](int g, int ch) {  // chunk ch = 2*s + hh of slot g
+    const int kk = g & 31, i = (((kk >> 2) & 3) << 3) | ((kk >> 4) << 2) | (kk & 3);
+    return (((size_t)(g >> 5) * (D / 16) + (ch >> 1)) * 64 + i + 32 * (ch & 1)) * 8;
+  };
+  auto v_off = [](int g, int col) {
+    const int kk = g & 31;
+    return ((((size_t)(g >> 5) * (D / 32) + (col >> 5)) * 2 + ((kk >> 3) & 1)) * 64 + (col & 31) + 32 * (kk >> 4)) * 8 +
+           (kk & 7);
+  };
+  for (int j = 1; j <= L; ++j) {
+    const int src = path[j];
+    if (src < j || src >= GOOSE_MAX_B || P + src >= cap) break;  // malformed path: stop, stay in bounds
+    if (src == j) continue;
+    if (c < D / 8)
+      *reinterpret_cast<uint4*>(kb + k_off(P + j, c)) = *reinterpret_cast<const uint4*>(kb + k_off(P + src, c));
+    vb[v_off(P + j, c)] = vb[v_off(P + src, c)];
+  }
+}
+
 template <typename T>
 __global__ void k_compact_vt(T* __restrict__ vall, int cap, int head_dim, const int32_t* __restrict__ dP,
                              const int32_t* __restrict__ path, const int32_t* __restrict__ accept_len) {
@@ -418,18 +450,27 @@ int launch_accept(const int32_t* parent, const int32_t* tokens, const uint8_t* i
 int launch_compact(int elem_bytes, void* kall, void* vall, int n_layers, int n_heads, int cap, int head_dim,
                    const int32_t* dP, const int32_t* path, const int32_t* accept_len, int32_t* new_P,
                    hipStream_t st) {
-  const int row_chunks = head_dim * elem_bytes / 16;  // <= 64 for head_dim <= 256 (fp32)
-  hipLaunchKernelGGL(k_compact_k, dim3(n_layers * n_heads), dim3(64), 0, st, (uint4*)kall, cap, row_chunks, dP, path,
-                     accept_len);
-  int rc = goose_launch_status();
-  if (rc != GOOSE_OK) return rc;
-  if (elem_bytes == 2)
-    hipLaunchKernelGGL(k_compact_vt<bf16_t>, dim3(n_layers * n_heads), dim3(head_dim), 0, st, (bf16_t*)vall, cap,
-                       head_dim, dP, path, accept_len);
-  else
+  int rc;
+  if (elem_bytes == 2) {  // bf16: operand-ordered blocks
+    if (head_dim == 128)
+      hipLaunchKernelGGL(k_compact_tiled<128>, dim3(n_layers * n_heads), dim3(128), 0, st, (bf16_t*)kall, (bf16_t*)vall,
+                         cap, dP, path, accept_len);
+    else if (head_dim == 64)
+      hipLaunchKernelGGL(k_compact_tiled<64>, dim3(n_layers * n_heads), dim3(64), 0, st, (bf16_t*)kall, (bf16_t*)vall,
+                         cap, dP, path, accept_len);
+    else
+      return GOOSE_ERR_SHAPE;
+    rc = goose_launch_status();
+  } else {  // fp32: K[head][slot][d], Vt[head][d][slot]
+    const int row_chunks = head_dim * elem_bytes / 16;  // <= 64 for head_dim <= 256
+    hipLaunchKernelGGL(k_compact_k, dim3(n_layers * n_heads), dim3(64), 0, st, (uint4*)kall, cap, row_chunks, dP, path,
+                       accept_len);
+    rc = goose_launch_status();
+    if (rc != GOOSE_OK) return rc;
     hipLaunchKernelGGL(k_compact_vt<float>, dim3(n_layers * n_heads), dim3(head_dim), 0, st, (float*)vall, cap,
                        head_dim, dP, path, accept_len);
-  rc = goose_launch_status();
+    rc = goose_launch_status();
+  }
   if (rc != GOOSE_OK) return rc;
   if (new_P) {
     hipLaunchKernelGGL(k_new_P, dim3(1), dim3(1), 0, st, dP, accept_len, new_P);

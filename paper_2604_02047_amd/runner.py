@@ -7,6 +7,7 @@ synthetic generators can both feed it.
 import numpy as np
 import torch
 
+from . import layout
 from .binding import GooseContext, ModelDesc
 
 
@@ -38,9 +39,15 @@ class GooseModel:
         torch.cuda.synchronize()
         del wl, gf
         assert cap % 64 == 0, "cap must be a multiple of 64"
-        # K[layer][head][slot][d]; V is kept transposed, Vt[layer][head][d][slot]
-        self.kcache = torch.zeros((desc.n_layers, desc.n_heads, cap, desc.head_dim), dtype=self.dt, device=self.device)
-        self.vcache = torch.zeros((desc.n_layers, desc.n_heads, desc.head_dim, cap), dtype=self.dt, device=self.device)
+        # One head's cache is cap * head_dim elements.  fp32 models: K[slot][d] and V transposed, Vt[d][slot];
+        # bf16 models: 32-key blocks in MFMA operand order (layout.py), kept here as flat vectors.
+        self.tiled = desc.dtype == "bf16"
+        if self.tiled:
+            self.kcache = torch.zeros((desc.n_layers, desc.n_heads, cap * desc.head_dim), dtype=self.dt, device=self.device)
+            self.vcache = torch.zeros_like(self.kcache)
+        else:
+            self.kcache = torch.zeros((desc.n_layers, desc.n_heads, cap, desc.head_dim), dtype=self.dt, device=self.device)
+            self.vcache = torch.zeros((desc.n_layers, desc.n_heads, desc.head_dim, cap), dtype=self.dt, device=self.device)
         self.P = 0
         i32 = dict(dtype=torch.int32, device=self.device)
         self.d_P = torch.zeros(1, **i32)
@@ -57,9 +64,31 @@ class GooseModel:
     def packed_layer(self, l):
         return self.packed_layers[l * self.layer_bytes:(l + 1) * self.layer_bytes]
 
+    def _slots(self, a, b):
+        return torch.arange(a, b, device=self.device)
+
+    def k_rows(self, a, b):
+        """Key rows of slots [a,b) as [layer][head][slot][d] (a copy in logical order)."""
+        if not self.tiled:
+            return self.kcache[:, :, a:b].clone()
+        return self.kcache[:, :, layout.k_offsets(self._slots(a, b), self.desc.head_dim)]
+
     def v_rows(self, a, b):
-        """Value rows of slots [a,b) as [layer][head][slot][d] (a copy; the cache itself is transposed)."""
-        return self.vcache[:, :, :, a:b].transpose(2, 3).contiguous()
+        """Value rows of slots [a,b) as [layer][head][slot][d] (a copy in logical order)."""
+        if not self.tiled:
+            return self.vcache[:, :, :, a:b].transpose(2, 3).contiguous()
+        return self.vcache[:, :, layout.v_offsets(self._slots(a, b), self.desc.head_dim)]
+
+    def write_rows(self, l, k, v):
+        """Stores logical rows k, v [head][n][d] of layer l into slots [0,n) (values cast to the cache type)."""
+        n = k.shape[1]
+        k, v = k.to(self.dt).to(self.device), v.to(self.dt).to(self.device)
+        if not self.tiled:
+            self.kcache[l, :, :n] = k
+            self.vcache[l, :, :, :n] = v.transpose(1, 2)
+        else:
+            self.kcache[l][:, layout.k_offsets(self._slots(0, n), self.desc.head_dim)] = k
+            self.vcache[l][:, layout.v_offsets(self._slots(0, n), self.desc.head_dim)] = v
 
     def set_P(self, P: int):
         self.P = int(P)
@@ -96,7 +125,7 @@ class GooseModel:
         c.goose_accept(p, t, s, self.argmax, B, self.accept_len, self.path, self.bonus)
         out = {"mask": mask.clone().view(B, W), "depth": self.depth[:B].clone(), "pos": self.pos[:B].clone(),
                "argmax": self.argmax[:B].clone(), "margin": self.margin[:B].clone(), "logits": logits,
-               "tail_k": self.kcache[:, :, self.P:self.P + B].clone(),
+               "tail_k": self.k_rows(self.P, self.P + B),
                "tail_v": self.v_rows(self.P, self.P + B)}
         if commit:
             new_P = torch.zeros(1, dtype=torch.int32, device=self.device)

@@ -74,7 +74,7 @@ def test_7b_step_in_the_benchmark_configuration():
         print(f"oracle layer {l}", flush=True)
         w = {k: to_f64(v) for k, v in gi.layer_weights(shape, seed, l, dev).items()}
         x_in = (x_embed if l == 0 else hidden[l - 1]).double().cpu().numpy()
-        Kc = gm.kcache[l, :, :P].double().cpu().numpy()
+        Kc = gm.k_rows(0, P)[l].double().cpu().numpy()
         Vc = gm.v_rows(0, P)[l].double().cpu().numpy()
         x_out, k_new, v_new = orc.decoder_layer(om, w, x_in, Kc, Vc, P + depth, allow)
         got = hidden[l].double().cpu().numpy()
@@ -121,7 +121,7 @@ def test_7b_step_in_the_benchmark_configuration():
     L = len(acc)
     assert int(gm.d_P.item()) == P + L + 1
     idx = torch.as_tensor([0] + acc, device=dev)
-    assert torch.equal(gm.kcache[:, :, P:P + L + 1], g["tail_k"][:, :, idx])
+    assert torch.equal(gm.k_rows(P, P + L + 1), g["tail_k"][:, :, idx])
     assert torch.equal(gm.v_rows(P, P + L + 1), g["tail_v"][:, :, idx])
     assert gm.ctx.goose_device_flags() == 0
     gm.ctx.close()
@@ -186,7 +186,7 @@ def test_7b_hundred_cycles_walk_and_compaction_bit_exact():
         assert g["path"].tolist() == [0] + acc + [-1] * (B - 1 - L), f"cycle {t}"
         assert gm.P == P + L + 1
         idx = torch.as_tensor([0] + acc, device=dev)
-        assert torch.equal(gm.kcache[:, :, P:P + L + 1], g["tail_k"][:, :, idx]), f"cycle {t}"
+        assert torch.equal(gm.k_rows(P, P + L + 1), g["tail_k"][:, :, idx]), f"cycle {t}"
         assert torch.equal(gm.v_rows(P, P + L + 1), g["tail_v"][:, :, idx]), f"cycle {t}"
         accepted += L
         multi += any(a != j + 1 for j, a in enumerate(acc))   # a path that leaves the spine moves rows

@@ -102,10 +102,20 @@ def test_compact_kv_bit_exact(dtype):
              [0, 3, 4, 5, 6, 40, 41]]
     for n, path in enumerate(cases):
         P = int(rng.integers(0, cap - 128))
-        k = torch.randn(kdims, device=dev).to(tdt)
-        v_rows = torch.randn(kdims, device=dev).to(tdt)          # logical [layer][head][slot][d]
-        vt = v_rows.transpose(2, 3).contiguous()                  # stored transposed [layer][head][d][slot]
-        k0, v0 = k.clone(), v_rows.clone()
+        k0 = torch.randn(kdims, device=dev).to(tdt)              # logical [layer][head][slot][d]
+        v0 = torch.randn(kdims, device=dev).to(tdt)
+        if dtype == "f32":   # stored as K[slot][d] and V transposed [d][slot]
+            k, vt = k0.clone(), v0.transpose(2, 3).contiguous()
+        else:                # stored in operand-ordered 32-key blocks
+            from paper_2604_02047_amd import layout
+            slots = torch.arange(cap, device=dev)
+            ko, vo = layout.k_offsets(slots, shape.head_dim), layout.v_offsets(slots, shape.head_dim)
+            assert sorted(ko.flatten().tolist()) == list(range(cap * shape.head_dim))   # a permutation of the cache
+            assert sorted(vo.flatten().tolist()) == list(range(cap * shape.head_dim))
+            k = torch.zeros((kdims[0], kdims[1], cap * shape.head_dim), dtype=tdt, device=dev)
+            vt = torch.zeros_like(k)
+            k[:, :, ko] = k0
+            vt[:, :, vo] = v0
         L = len(path) - 1
         dpath = torch.full((128,), -1, dtype=torch.int32, device=dev)
         dpath[:L + 1] = torch.tensor(path, dtype=torch.int32)
@@ -117,7 +127,10 @@ def test_compact_kv_bit_exact(dtype):
             newP.fill_(P)
             c.goose_compact_kv(k, vt, 0, dpath, dlen, newP, d_P=newP)
         torch.cuda.synchronize()
-        v = vt.transpose(2, 3)
+        if dtype == "f32":
+            v = vt.transpose(2, 3)
+        else:
+            k, v = k[:, :, ko], vt[:, :, vo]
         assert int(newP.item()) == P + L + 1
         idx = torch.tensor(path, device=dev) + P
         # slots [0,P) untouched, [P, P+L] are the path rows, byte for byte

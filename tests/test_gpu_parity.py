@@ -84,7 +84,7 @@ def _compare_step(shape, gm, om, cache, tokens, tree, tol, check_hidden=True):
     L = len(acc)
     idx = torch.as_tensor([0] + acc, device=gm.device)
     assert gm.P == P + L + 1
-    assert torch.equal(gm.kcache[:, :, P:P + L + 1], g["tail_k"][:, :, idx])
+    assert torch.equal(gm.k_rows(P, P + L + 1), g["tail_k"][:, :, idx])
     assert torch.equal(gm.v_rows(P, P + L + 1), g["tail_v"][:, :, idx])
     return g, o, decisive
 
@@ -100,7 +100,7 @@ def _run_cycles(shape_name, n_cycles, P0, trees, seed, oracle_prefill, chunk=16,
     if oracle_prefill:
         cache = orc.prefill(om, prefix)           # fully independent state
         for l, (k, v) in enumerate(cache):        # chain prefill on the GPU == causal prefill of the oracle
-            gk = gm.kcache[l, :, :P0].double().cpu().numpy()
+            gk = gm.k_rows(0, P0)[l].double().cpu().numpy()
             assert np.abs(gk - k).max() <= tol * np.abs(k).max()
     else:
         cache = device_cache_as_oracle(gm, P0)    # the device's stored bytes are the oracle's input

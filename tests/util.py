@@ -55,13 +55,12 @@ def load_prefix_cache(gm, cache):
     """Copies an oracle cache (list of (K,V) float64 [n_h,P,d]) into the device cache (rounded to its type)."""
     P = cache[0][0].shape[1]
     for l, (k, v) in enumerate(cache):
-        gm.kcache[l, :, :P] = torch.from_numpy(k).to(gm.dt).to(gm.device)
-        gm.vcache[l, :, :, :P] = torch.from_numpy(v).to(gm.dt).to(gm.device).transpose(1, 2)
+        gm.write_rows(l, torch.from_numpy(k), torch.from_numpy(v))
     gm.set_P(P)
 
 
 def device_cache_as_oracle(gm, P):
     """The device cache's first P slots as an oracle cache (exact upcast of the stored values)."""
-    vr = gm.v_rows(0, P)
-    return [(gm.kcache[l, :, :P].to(torch.float64).cpu().numpy(), vr[l].to(torch.float64).cpu().numpy())
+    kr, vr = gm.k_rows(0, P), gm.v_rows(0, P)
+    return [(kr[l].to(torch.float64).cpu().numpy(), vr[l].to(torch.float64).cpu().numpy())
             for l in range(gm.desc.n_layers)]
