@@ -70,15 +70,18 @@ __global__ __launch_bounds__(256) void k_pack_bf16(int mode, const bf16_t* __res
 // One workgroup = NW wavefronts, wavefront w owns column tile blockIdx.x*NW + w (32 columns) and
 // all MT row tiles.  blockIdx.y selects the split-K range.  Per stage (KC = 128 inputs; a 256-wide
 // stage, half as many barriers, measured no faster):
-//   - every wavefront has the 8 operand loads (8 KiB) of the NEXT stage in flight while it
-//     multiplies the current one (register double buffer),
-//   - the workgroup copies the next A stage global -> registers -> LDS (LDS double buffer),
+//   - every wavefront keeps RING stages of its own weight pieces (8 KiB each) and of its share of
+//     the A copy in flight in registers,
+//   - the workgroup publishes the next A stage registers -> LDS (LDS double buffer),
 //   - one barrier.
+// Measured with parts compiled out: the matrix instructions, the LDS reads and the barriers cost
+// nothing; the A copy costs about 5 us of the gate/up projection and about 1 us of the others;
+// the rest is the weight stream itself plus the fixed cost of a dependent launch.
 // EPI_SWIGLU: even wavefronts hold gate tiles, odd ones the matching up tiles; the up tile
 // is handed over through LDS and the even wavefront writes h = silu(gate) * up.
 // EPI_TOP2: besides the optional plain output, every workgroup reduces its columns to one
 // (largest, second largest, index of largest) triple per row, for the greedy argmax.
-template <int MT, int NW, int EPI, int KC>
+template <int MT, int NW, int EPI, int KC, int RING>
 __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict__ A, int lda,
                                                        const u32x4* __restrict__ Wp, int ntiles, int ksteps_total,
                                                        int stages_per_split, int B, void* __restrict__ out,
@@ -114,8 +117,14 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict_
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
 
-  // A stage copy: global -> registers -> LDS, APT 16-byte segments per thread
-  u32x4 areg[APT];
+  // Both operand streams run RING stages ahead in registers.  Memory operations complete in
+  // order as far as the wait counter is concerned, so a value can only be awaited together with
+  // everything issued before it: whatever is consumed soon must not have been issued after
+  // loads that are meant to stay in flight.  Hence stage st issues the A copy of stage st+RING
+  // and the weight pieces of stage st+RING (into the slots stage st just freed) and consumes only
+  // what was issued RING stages ago; RING * (8 + APT) loads per wavefront stay outstanding.
+  static_assert(RING == 2 || RING == 4, "ring depth");
+  u32x4 areg[RING][APT];
   const bf16_t* a_src[APT];
   int a_dst[APT];
 #pragma unroll
@@ -125,32 +134,33 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict_
     a_src[i] = A + (size_t)row * lda + c16 * 8;
     a_dst[i] = row * LDS_ROW + c16 * 16;
   }
-  auto load_a = [&](int st) {
-#pragma unroll
-    for (int i = 0; i < APT; ++i) areg[i] = *reinterpret_cast<const u32x4*>(a_src[i] + (size_t)st * KC);
-  };
-  auto store_a = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < APT; ++i) *reinterpret_cast<u32x4*>(&lds[buf * STAGE_BYTES + a_dst[i]]) = areg[i];
-  };
-  // Weight stream: a ring of two stages (16 operand loads = 16 KiB per wavefront).  A slot is
-  // refilled for stage st+2 right after the MFMAs of stage st consumed it, so 8..16 loads stay
-  // in flight per wavefront at all times, independent of the barriers.
-  u32x4 wreg[2][STEPS];
+  u32x4 wreg[RING][STEPS];
   const u32x4* wbase = Wp + (size_t)tile_ld * ksteps_total * 64 + lane;
-  auto load_w = [&](int st, int slot) {
+  auto load_a = [&](int st, auto slot_c) {
+    constexpr int slot = decltype(slot_c)::value;
+#pragma unroll
+    for (int i = 0; i < APT; ++i) areg[slot][i] = *reinterpret_cast<const u32x4*>(a_src[i] + (size_t)st * KC);
+  };
+  auto store_a = [&](int buf, auto slot_c) {
+    constexpr int slot = decltype(slot_c)::value;
+#pragma unroll
+    for (int i = 0; i < APT; ++i) *reinterpret_cast<u32x4*>(&lds[buf * STAGE_BYTES + a_dst[i]]) = areg[slot][i];
+  };
+  auto load_w = [&](int st, auto slot_c) {
+    constexpr int slot = decltype(slot_c)::value;
     const u32x4* p = wbase + (size_t)st * STEPS * 64;
 #pragma unroll
     for (int s = 0; s < STEPS; ++s) wreg[slot][s] = __builtin_nontemporal_load(p + s * 64);
   };
   const int a_frag = (lane & 31) * LDS_ROW + (lane >> 5) * 16;
-  // one stage: start the copy of the next A stage, multiply, refill the ring, publish the next A stage
-  // (buf/slot are compile-time so that the register ring is never indexed dynamically)
-  auto stage = [&](auto buf_c, int st, auto next_a, auto refill) {
-    constexpr int buf = decltype(buf_c)::value, slot = buf;
-    if (next_a) load_a(st + 1);
-    __builtin_amdgcn_sched_barrier(0);  // keep the issue order: the scheduler would sink these loads
-    const u32x4* pn = wbase + (size_t)(st + 2) * STEPS * 64;
+  // one stage (slot = st % RING, compile-time so that no register array is indexed dynamically;
+  // the LDS buffer alternates with the stage's parity)
+  auto stage = [&](auto slot_c, int st, auto next_a, auto refill) {
+    constexpr int slot = decltype(slot_c)::value, buf = slot & 1;
+    const std::integral_constant<int, (slot + 1) % RING> nslot;
+    if (refill) load_a(st + RING, slot_c);  // this slot's previous content (stage st) is in LDS already
+    __builtin_amdgcn_sched_barrier(0);      // keep the issue order: the scheduler would sink these loads
+    const u32x4* pn = wbase + (size_t)(st + RING) * STEPS * 64;
 #pragma unroll
     for (int s = 0; s < STEPS; ++s) {
       const bf16x8 b = __builtin_bit_cast(bf16x8, wreg[slot][s]);
@@ -163,27 +173,60 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict_
       if (refill) wreg[slot][s] = __builtin_nontemporal_load(pn + s * 64);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (next_a) store_a(buf ^ 1);
+    if (next_a) store_a(buf ^ 1, nslot);
     __syncthreads();
   };
   const std::true_type yes;
-  const std::integral_constant<int, 0> b0;
-  const std::integral_constant<int, 1> b1;
+  const std::integral_constant<int, 0> c0;
+  const std::integral_constant<int, 1> c1;
+  const std::integral_constant<int, 2> c2;
+  const std::integral_constant<int, 3> c3;
 
   if (nst > 0) {
-    load_a(s_begin);
-    load_w(s_begin, 0);
-    if (nst > 1) load_w(s_begin + 1, 1);
-    store_a(0);
-    __syncthreads();
     int i = 0;
-    for (; i + 3 < nst; i += 2) {  // steady state: no conditionals inside
-      stage(b0, s_begin + i, yes, yes);
-      stage(b1, s_begin + i + 1, yes, yes);
+    if (nst >= 2 * RING) {
+      // long range: every slot is filled unconditionally, so that the compiler's wait counts at
+      // the loop head are exact (it merges all paths into the loop, and a path with fewer loads
+      // in flight would make every iteration drain the ring)
+      load_a(s_begin, c0);
+      load_w(s_begin, c0);
+      load_a(s_begin + 1, c1);
+      load_w(s_begin + 1, c1);
+      if (RING == 4) {
+        load_a(s_begin + 2, c2);
+        load_w(s_begin + 2, c2);
+        load_a(s_begin + 3, c3);
+        load_w(s_begin + 3, c3);
+      }
+      store_a(0, c0);
+      __syncthreads();
+      for (; i + 2 * RING - 1 < nst; i += RING) {  // steady state: no conditionals inside
+        stage(c0, s_begin + i, yes, yes);
+        stage(c1, s_begin + i + 1, yes, yes);
+        if (RING == 4) {
+          stage(c2, s_begin + i + 2, yes, yes);
+          stage(c3, s_begin + i + 3, yes, yes);
+        }
+      }
+    } else {
+      load_a(s_begin, c0);
+      load_w(s_begin, c0);
+      if (nst > 1) { load_a(s_begin + 1, c1); load_w(s_begin + 1, c1); }
+      if (RING == 4) {
+        if (nst > 2) { load_a(s_begin + 2, c2); load_w(s_begin + 2, c2); }
+        if (nst > 3) { load_a(s_begin + 3, c3); load_w(s_begin + 3, c3); }
+      }
+      store_a(0, c0);
+      __syncthreads();
     }
-    for (; i < nst; ++i) {  // last one to three stages
-      if (i & 1) stage(b1, s_begin + i, (i + 1) < nst, (i + 2) < nst);
-      else       stage(b0, s_begin + i, (i + 1) < nst, (i + 2) < nst);
+    for (; i < nst; ++i) {  // the last stages (i is a multiple of RING on entry)
+      const bool na = (i + 1) < nst, rf = (i + RING) < nst;
+      switch (i % RING) {
+        case 0: stage(c0, s_begin + i, na, rf); break;
+        case 1: stage(c1, s_begin + i, na, rf); break;
+        case 2: if (RING == 4) stage(c2, s_begin + i, na, rf); break;
+        default: if (RING == 4) stage(c3, s_begin + i, na, rf); break;
+      }
     }
   }
 
@@ -270,7 +313,8 @@ int launch_one(const void* A, int lda, const void* Wp, int Npad, int Kpad, int B
   dim3 grid((ntiles + NW - 1) / NW, ksplit);
   const int granules = Kpad / KGRAN;                      // split-K ranges are multiples of 128 inputs
   const int gps = (granules + ksplit - 1) / ksplit;       // granules (= stages) per split
-  hipLaunchKernelGGL((k_gemm_bf16<MT, NW, EPI, 128>), grid, dim3(64 * NW), 0, st, (const bf16_t*)A, lda,
+  // two stages of each stream in flight measured best (four: every projection 2-3 us slower)
+  hipLaunchKernelGGL((k_gemm_bf16<MT, NW, EPI, 128, 2>), grid, dim3(64 * NW), 0, st, (const bf16_t*)A, lda,
                      (const u32x4*)Wp, ntiles, ksteps, gps, B, out, ldo, split_stride, (float4*)top2, n_valid);
   return goose_launch_status();
 }
