@@ -159,31 +159,41 @@ def main():
     # ---- rehearsal (untimed): fixes the inputs of every step.  Planted drafts follow the model's own
     # continuation, so they depend on what earlier steps accepted; this pass runs the same entry point
     # as the timed pass, reads the outcome back each step and records the trees.
-    trees, toks, P_hist, acc_hist = [], [], [], []
-    root = root0
-    for t in range(total):
-        tree = make_tree(tree_kind, t)
-        tk = gi.draft_tokens_uniform(args.seed * 7919 + t, tree.parent, shape.vocab, root)
-        if args.drafts == "planted":
-            cont = greedy_lookahead(gm, root, 6)
-            tk = gi.plant_drafts(args.seed * 104729 + t, tree.parent, tree.is_spine, tk, cont, shape.vocab,
-                                 p_spine=0.6, p_branch=0.5, p_grand=0.3)
-        P_hist.append(gm.P)
-        cur_tok.copy_(torch.as_tensor(tk.astype(np.int32)))
-        cur_par.copy_(torch.as_tensor(tree.parent.astype(np.int32)))
-        cur_spn.copy_(torch.as_tensor(tree.is_spine.astype(np.uint8)))
-        one_step()
-        torch.cuda.synchronize()
-        gm.P = int(gm.d_P.item())
-        trees.append(tree)
-        toks.append(tk)
-        acc_hist.append(int(gm.accept_len.item()))
-        root = int(gm.bonus.item())
-    P_final = gm.P
-    assert P_final + B <= cap
-    log(f"rehearsal done: mean accepted drafts/step {np.mean(acc_hist):.2f}, P {P0} -> {P_final}")
-    # a serving loop knows how far a request can grow; here the rehearsal fixed it exactly
-    bound["P_max"] = min(P_max, P_final)
+    # The launches are sized from an upper bound of the device-resident P (it picks the number of
+    # key splits, hence the order of the attention sums): a serving loop knows how far a request
+    # can grow; here the bound is a guess of 3 slots per step, checked by the rehearsal itself and
+    # widened if the walk outgrew it.  Rehearsal and timed run use the same bound.
+    bound["P_max"] = min(P_max, P0 + 3 * total)
+    while True:
+        trees, toks, P_hist, acc_hist = [], [], [], []
+        root = root0
+        gm.set_P(P0)
+        for t in range(total):
+            tree = make_tree(tree_kind, t)
+            tk = gi.draft_tokens_uniform(args.seed * 7919 + t, tree.parent, shape.vocab, root)
+            if args.drafts == "planted":
+                cont = greedy_lookahead(gm, root, 6)
+                tk = gi.plant_drafts(args.seed * 104729 + t, tree.parent, tree.is_spine, tk, cont, shape.vocab,
+                                     p_spine=0.6, p_branch=0.5, p_grand=0.3)
+            P_hist.append(gm.P)
+            cur_tok.copy_(torch.as_tensor(tk.astype(np.int32)))
+            cur_par.copy_(torch.as_tensor(tree.parent.astype(np.int32)))
+            cur_spn.copy_(torch.as_tensor(tree.is_spine.astype(np.uint8)))
+            one_step()
+            torch.cuda.synchronize()
+            gm.P = int(gm.d_P.item())
+            trees.append(tree)
+            toks.append(tk)
+            acc_hist.append(int(gm.accept_len.item()))
+            root = int(gm.bonus.item())
+        P_final = gm.P
+        assert P_final + B <= cap
+        if max(P_hist) <= bound["P_max"] or bound["P_max"] == P_max:
+            break
+        log(f"P reached {max(P_hist)} > bound {bound['P_max']}: rehearsing again with a wider bound")
+        bound["P_max"] = min(P_max, bound["P_max"] + 3 * total)
+    log(f"rehearsal done: mean accepted drafts/step {np.mean(acc_hist):.2f}, P {P0} -> {P_final} "
+        f"(launch bound {bound['P_max']})")
 
     # ---- device-resident inputs of the timed run
     tok_all = torch.as_tensor(np.stack(toks).astype(np.int32), device=dev)
@@ -235,7 +245,8 @@ def main():
     elapsed = t2 - t1
     P_end = int(gm.d_P.item())
     if P_end != P_final:
-        log(f"WARNING: replay ended at P={P_end}, rehearsal at P={P_final}")
+        log(f"ERROR: replay ended at P={P_end}, rehearsal at P={P_final}")
+        sys.exit(4)
     ms_per_step = elapsed / K * 1e3
     bytes_timed = sum(step_bytes(shape, B, P_hist[t]) for t in range(W, total))
     achieved = bytes_timed / elapsed / 1e9
