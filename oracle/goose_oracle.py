@@ -239,6 +239,31 @@ def top2_margin(logits):
     return part[:, -1] - part[:, -2]
 
 
+def harvest_topk(logits, tokens, K, table_ids=None, table_scores=None, vocab=None):
+    """Harvest of a cycle's logits into the unigram successor tables (Sec. 4 stage 2; App. C,
+    "adjacency table", tier 1, and "logit harvesting"): for every tree node i -- accepted or not --
+    row tokens[i] of the two dense [vocab, K] tables receives the K most likely successors of that
+    token according to node i's distribution: their ids, and as scores their softmax probabilities.
+
+    Readings where the paper is silent: entries are ordered by decreasing logit, equal logits by
+    increasing token id; when several nodes of the tree carry the same token, the node with the
+    highest index writes last and wins; rows of other tokens are left as they were.
+    Returns (ids int32 [vocab, K], scores float64 [vocab, K]); fresh tables hold id -1, score 0."""
+    logits = np.asarray(logits, F64)
+    B, V = logits.shape
+    vocab = V if vocab is None else vocab
+    ids = np.full((vocab, K), -1, np.int32) if table_ids is None else np.array(table_ids, np.int32)
+    scores = np.zeros((vocab, K), F64) if table_scores is None else np.array(table_scores, F64)
+    prob = softmax_rows(logits)
+    for i in range(B):
+        t = int(tokens[i])
+        # decreasing logit, then increasing id: sort ids by the pair (-logit, id)
+        order = sorted(range(V), key=lambda v: (-logits[i, v], v))[:K]
+        ids[t, :] = order
+        scores[t, :] = prob[i, order]
+    return ids, scores
+
+
 def greedy_walk(parent, tokens, is_spine, x_hat):
     """Alg. UnifiedGreedyWalk: follow matching children from the root, spine child before branch children.
     Returns (accepted node list without the root, bonus token)."""
