@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--harvest", type=int, default=0, metavar="K",
+                    help="also harvest every cycle's logits into [vocab][K] successor tables (not part of the headline step)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch the library's 256 MiB copy kernel (calibrates profiler traffic counters)")
     args = ap.parse_args()
@@ -153,8 +155,14 @@ def main():
 
     bound = {"P_max": P_max}  # upper bound of the device-resident P that sizes the launches
 
+    succ_ids = succ_sc = None
+    if args.harvest:
+        succ_ids = torch.full((shape.vocab, args.harvest), -1, dtype=torch.int32, device=dev)
+        succ_sc = torch.zeros((shape.vocab, args.harvest), dtype=torch.float32, device=dev)
+
     def one_step():
-        gm.verify_step_fused(cur_tok, cur_par, cur_spn, B, bound["P_max"], next_root=next_root)
+        gm.verify_step_fused(cur_tok, cur_par, cur_spn, B, bound["P_max"], next_root=next_root, succ_ids=succ_ids,
+                             succ_scores=succ_sc)
 
     # ---- rehearsal (untimed): fixes the inputs of every step.  Planted drafts follow the model's own
     # continuation, so they depend on what earlier steps accepted; this pass runs the same entry point
@@ -306,7 +314,8 @@ def main():
         "dtype": shape.dtype, "data": "synthetic",
         "config": {"workload": args.workload, "shape": shape.name, "B": B, "P0": P0, "P_end": P_end,
                    "tree": tree_kind, "drafts": args.drafts, "launch": "hipGraph per step" if graph else "plain",
-                   "mean_accepted_drafts_per_step": round(float(np.mean(acc_hist[W:])), 3)},
+                   "mean_accepted_drafts_per_step": round(float(np.mean(acc_hist[W:])), 3),
+                   "harvest_top_k": args.harvest},
         "draft_tokens_verified_per_s": round(B * K / elapsed, 1),
         "tokens_emitted_per_s": round(float(np.sum(np.asarray(acc_hist[W:]) + 1)) / elapsed, 1),
         "achieved_GBps": round(achieved, 1), "hbm_frac": round(achieved / HBM_PEAK_GBPS, 4),

@@ -188,10 +188,25 @@ typedef struct {
   int32_t* d_next_root_or_null;
   float* d_logits_or_null;   /* [B][vocab] */
   float* d_margin_or_null;   /* [B] */
+  int32_t* d_succ_ids_or_null;    /* [vocab][harvest_k]: harvest this cycle's logits (goose_harvest_topk) */
+  float* d_succ_scores_or_null;   /* [vocab][harvest_k], required with d_succ_ids_or_null */
+  int32_t harvest_k;              /* 1..16 when harvesting */
 } goose_step_io;
 
 int goose_verify_step(goose_ctx* ctx, const goose_model_ptrs* model, const goose_step_io* io, int B, int P_max,
                       void* stream);
+
+/* ---- 7. logit harvest (Sec. 4 stage 2 "verify and harvest"; App. C "adjacency table", tier 1, and
+ * "logit harvesting"; Alg. "Decoding Loop", the update of the table from all logits of a cycle) ----
+ * For every node i < B -- accepted or not -- row d_tokens[i] of the two dense successor tables
+ * receives the K most likely next tokens under node i's logits: d_succ_ids int32 [vocab][K], ordered
+ * by decreasing logit (equal logits: increasing id), and d_succ_scores f32 [vocab][K], their softmax
+ * probabilities.  When several nodes carry the same token the highest node index wins; rows of other
+ * tokens are untouched; a token outside [0, vocab) writes nothing.  d_logits: f32 [B][ld] DEVICE,
+ * ld >= vocab.  1 <= K <= 16 (the paper uses 10).  The tier-2 (two-token context) table is host-side
+ * hashing and not part of this library. */
+int goose_harvest_topk(goose_ctx* ctx, const float* d_logits, size_t ld, const int32_t* d_tokens, int B, int K,
+                       int32_t* d_succ_ids, float* d_succ_scores, void* stream);
 
 /* Device-side diagnostics: bit 0 set if any kernel since the last call saw a parent
  * array that is not topological.  Synchronises `stream`. */

@@ -19,7 +19,7 @@ EXPORTS = [
     "goose_accept", "goose_compact_kv", "goose_verify_step", "goose_device_flags",
     "goose_packed_matrix_bytes", "goose_pack_matrix", "goose_gemm_packed", "goose_gemm_swiglu_packed",
     "goose_profile_enable", "goose_profile_kinds", "goose_profile_kind_name", "goose_profile_read",
-    "goose_copy_probe",
+    "goose_copy_probe", "goose_harvest_topk",
 ]
 
 GOOSE_DTYPE_BF16, GOOSE_DTYPE_F32 = 0, 1
@@ -49,7 +49,8 @@ class _ModelPtrs(C.Structure):
 class _StepIO(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("d_tokens", "d_parent", "d_is_spine", "d_P", "d_argmax", "d_accept_len",
                                           "d_path", "d_bonus", "d_next_root_or_null", "d_logits_or_null",
-                                          "d_margin_or_null")]
+                                          "d_margin_or_null", "d_succ_ids_or_null", "d_succ_scores_or_null")] + \
+               [("harvest_k", C.c_int32)]
 
 
 @dataclass
@@ -242,6 +243,10 @@ class GooseContext:
         _check(self.lib.goose_lm_head_argmax(self._h, _ptr(packed_head), _ptr(x), B, _ptr(argmax), _ptr(logits),
                                              _ptr(margin), _stream()), "goose_lm_head_argmax")
 
+    def goose_harvest_topk(self, logits, ld, tokens, B, K, succ_ids, succ_scores):
+        _check(self.lib.goose_harvest_topk(self._h, _ptr(logits), C.c_size_t(ld), _ptr(tokens), B, K, _ptr(succ_ids),
+                                           _ptr(succ_scores), _stream()), "goose_harvest_topk")
+
     def goose_accept(self, parent, tokens, is_spine, argmax, B, accept_len, path, bonus):
         _check(self.lib.goose_accept(self._h, _ptr(parent), _ptr(tokens), _ptr(is_spine), _ptr(argmax), B,
                                      _ptr(accept_len), _ptr(path), _ptr(bonus), _stream()), "goose_accept")
@@ -253,8 +258,9 @@ class GooseContext:
     def goose_verify_step(self, model: dict, io: dict, B, P_max):
         m = _ModelPtrs(*[model[n].data_ptr() for n in ("embed", "packed_layers", "packed_head", "kcache", "vcache")])
         names = ("tokens", "parent", "is_spine", "P", "argmax", "accept_len", "path", "bonus", "next_root", "logits",
-                 "margin")
-        s = _StepIO(*[(io[n].data_ptr() if io.get(n) is not None else None) for n in names])
+                 "margin", "succ_ids", "succ_scores")
+        s = _StepIO(*[(io[n].data_ptr() if io.get(n) is not None else None) for n in names],
+                    int(io.get("harvest_k") or 0))
         _check(self.lib.goose_verify_step(self._h, C.byref(m), C.byref(s), B, P_max, _stream()), "goose_verify_step")
 
     def goose_device_flags(self) -> int:

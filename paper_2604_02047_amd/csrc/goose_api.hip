@@ -28,10 +28,10 @@ int env_int(const char* name, int dflt) {
 
 // ---- optional per-kernel timing with HIP events on the caller's stream -----------------------
 enum ProfKind { PK_NORM = 0, PK_GEMM_QKV, PK_ROPE, PK_ATTN, PK_GEMM_O, PK_GEMM_GATE_UP, PK_GEMM_DOWN, PK_LM_HEAD,
-                PK_ARGMAX, PK_MISC, PK_COUNT };
-const char* const kProfNames[PK_COUNT] = {"rmsnorm_residual", "gemm_qkv", "rope_kv_write", "tree_attention", "gemm_o",
+                PK_ARGMAX, PK_HARVEST, PK_MISC, PK_COUNT };
+const char* const kProfNames[PK_COUNT] = {"rmsnorm_residual", "gemm_qkv", "rope_table", "tree_attention", "gemm_o",
                                           "gemm_gate_up_swiglu", "gemm_down", "gemm_lm_head", "argmax",
-                                          "mask_embed_accept_compact"};
+                                          "harvest_topk", "mask_embed_accept_compact"};
 }  // namespace
 struct goose_prof {
   bool on = false;
@@ -416,8 +416,15 @@ int goose_verify_layer(goose_ctx* c, const void* d_packed_layer, float* d_x, voi
                     nullptr);
 }
 
+struct HarvestArgs {  // optional harvest of the logits into the successor tables
+  const int32_t* tokens = nullptr;
+  int K = 0;
+  int32_t* ids = nullptr;
+  float* scores = nullptr;
+};
 static int lm_head_impl(goose_ctx* c, const void* d_packed_head, const float* d_x, int B, int32_t* d_argmax,
-                        float* d_logits_or_null, float* d_margin_or_null, hipStream_t st, bool xhat_ready);
+                        float* d_logits_or_null, float* d_margin_or_null, hipStream_t st, bool xhat_ready,
+                        const HarvestArgs& hv);
 
 int goose_lm_head_argmax(goose_ctx* c, const void* d_packed_head, const float* d_x, int B, int32_t* d_argmax,
                          float* d_logits_or_null, float* d_margin_or_null, void* stream) {
@@ -425,11 +432,12 @@ int goose_lm_head_argmax(goose_ctx* c, const void* d_packed_head, const float* d
   if (B < 1) return GOOSE_ERR_ARG;
   if (B > c->max_B) return GOOSE_ERR_CAPACITY;
   return lm_head_impl(c, d_packed_head, d_x, B, d_argmax, d_logits_or_null, d_margin_or_null, as_stream(stream),
-                      false);
+                      false, HarvestArgs());
 }
 
 static int lm_head_impl(goose_ctx* c, const void* d_packed_head, const float* d_x, int B, int32_t* d_argmax,
-                        float* d_logits_or_null, float* d_margin_or_null, hipStream_t st, bool xhat_ready) {
+                        float* d_logits_or_null, float* d_margin_or_null, hipStream_t st, bool xhat_ready,
+                        const HarvestArgs& hv) {
   const goose_model_desc& d = c->d;
   const char* w = (const char*)d_packed_head;
   // the residual stream is left untouched: normalise into the operand buffer only
@@ -442,9 +450,10 @@ static int lm_head_impl(goose_ctx* c, const void* d_packed_head, const float* d_
     // the projection kernel reduces its own columns to (max, second, index) per row; logits are
     // written only on request (through the padded workspace when rows are no multiple of a tile)
     static const int lm_nw = env_int("GOOSE_LM_NW", 4) == 2 ? 2 : 4;
+    // (the harvest needs them too: into the workspace then)
     const bool bounce = d_logits_or_null && (d.vocab % 32) != 0;
-    float* out = bounce ? c->logits : d_logits_or_null;
-    const size_t ld = bounce ? (size_t)c->Vpad : (size_t)d.vocab;
+    float* out = (bounce || (!d_logits_or_null && hv.ids)) ? c->logits : d_logits_or_null;
+    const size_t ld = out == c->logits ? (size_t)c->Vpad : (size_t)d.vocab;
     const int groups = (c->Vpad / 32 + lm_nw - 1) / lm_nw;
     { PROF(PK_LM_HEAD);
       rc = launch_gemm_top2_bf16(c->xn, c->Kh, w + c->ph.wlm, c->Vpad, c->Kh, B, lm_nw, out, ld, c->top2, d.vocab, st); }
@@ -452,14 +461,28 @@ static int lm_head_impl(goose_ctx* c, const void* d_packed_head, const float* d_
     if (bounce)
       GOOSE_HIP_TRY(hipMemcpy2DAsync(d_logits_or_null, (size_t)d.vocab * 4, c->logits, (size_t)c->Vpad * 4,
                                      (size_t)d.vocab * 4, B, hipMemcpyDeviceToDevice, st));
-    PROF(PK_ARGMAX);
-    return launch_argmax_top2(c->top2, groups, B, d_argmax, d_margin_or_null, st);
+    { PROF(PK_ARGMAX);
+      rc = launch_argmax_top2(c->top2, groups, B, d_argmax, d_margin_or_null, st); }
+    if (rc || !hv.ids) return rc;
+    PROF(PK_HARVEST);
+    return launch_harvest_topk(out, ld, d.vocab, hv.tokens, B, hv.K, d.vocab, hv.ids, hv.scores, st);
   }
   float* logits = d_logits_or_null ? d_logits_or_null : c->logits;
   const size_t ld = d_logits_or_null ? (size_t)d.vocab : (size_t)c->Vpad;
   rc = launch_gemm_f32((const float*)c->xn, c->Kh, (const float*)(w + c->ph.wlm), d.vocab, d.hidden, B, logits, ld, st);
   if (rc) return rc;
-  return launch_argmax(logits, ld, d.vocab, B, d_argmax, d_margin_or_null, st);
+  rc = launch_argmax(logits, ld, d.vocab, B, d_argmax, d_margin_or_null, st);
+  if (rc || !hv.ids) return rc;
+  return launch_harvest_topk(logits, ld, d.vocab, hv.tokens, B, hv.K, d.vocab, hv.ids, hv.scores, st);
+}
+
+int goose_harvest_topk(goose_ctx* c, const float* d_logits, size_t ld, const int32_t* d_tokens, int B, int K,
+                       int32_t* d_succ_ids, float* d_succ_scores, void* stream) {
+  if (!c || !d_logits || !d_tokens || !d_succ_ids || !d_succ_scores) return GOOSE_ERR_ARG;
+  if (B < 1 || K < 1 || K > 16 || ld < (size_t)c->d.vocab) return GOOSE_ERR_ARG;
+  if (B > GOOSE_MAX_B) return GOOSE_ERR_CAPACITY;
+  return launch_harvest_topk(d_logits, ld, c->d.vocab, d_tokens, B, K, c->d.vocab, d_succ_ids, d_succ_scores,
+                             as_stream(stream));
 }
 
 int goose_accept(goose_ctx* c, const int32_t* d_parent, const int32_t* d_tokens, const uint8_t* d_is_spine_or_null,
@@ -515,8 +538,16 @@ int goose_verify_step(goose_ctx* c, const goose_model_ptrs* m, const goose_step_
                     P_max, io->d_P, B, c->s_mask, c->s_pos, st, l > 0, g_next);
     if (rc) return rc;
   }
+  HarvestArgs hv;
+  if (io->d_succ_ids_or_null) {
+    if (!io->d_succ_scores_or_null || io->harvest_k < 1 || io->harvest_k > 16) return GOOSE_ERR_ARG;
+    hv.tokens = io->d_tokens;
+    hv.K = io->harvest_k;
+    hv.ids = io->d_succ_ids_or_null;
+    hv.scores = io->d_succ_scores_or_null;
+  }
   rc = lm_head_impl(c, m->d_packed_head, c->s_x, B, io->d_argmax, io->d_logits_or_null, io->d_margin_or_null, st,
-                    true);
+                    true, hv);
   if (rc) return rc;
   rc = launch_accept(io->d_parent, io->d_tokens, io->d_is_spine, io->d_argmax, B, io->d_accept_len, io->d_path,
                      io->d_bonus, io->d_next_root_or_null, st);

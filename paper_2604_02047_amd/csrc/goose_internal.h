@@ -117,6 +117,8 @@ int launch_gemm_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, 
 // `out` (f32 [B][ldo]) may be null when only the reduction is wanted.
 int launch_gemm_top2_bf16(const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw, float* out,
                           size_t ldo, void* top2, int n_valid, hipStream_t st);
+int launch_harvest_topk(const float* logits, size_t ld, int V, const int32_t* tokens, int B, int K, int table_rows,
+                        int32_t* succ_ids, float* succ_scores, hipStream_t st);
 int launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
 int launch_argmax_top2(const void* top2, int n_groups, int B, int32_t* argmax, float* margin, hipStream_t st);
 void pick_gemm_config(int Npad, int Kpad, int max_ksplit, int* nw_out, int* ksplit_out);

@@ -241,6 +241,177 @@ __global__ __launch_bounds__(64) void k_argmax_top2(const float4* __restrict__ t
 }
 
 // ------------------------------------------------------------------------------------------
+// Logit harvest (Sec. 4 stage 2; App. C, adjacency table tier 1): row tokens[m] of the dense
+// [vocab][K] successor tables receives the K most likely next tokens of node m (ids, ordered by
+// decreasing logit, equal logits by increasing id) and their softmax probabilities.  When several
+// nodes carry the same token the highest node index writes (the others skip the store).
+// One workgroup per node, two passes over its row:
+//   1. every thread finds the best (logit, id) pair of its strided share and an online
+//      log-sum-exp; the K-th best of the 256 thread-bests, tau, is a lower bound of the K-th best
+//      of the row (there are K pairs at or above it);
+//   2. the pairs at or above tau -- K of them plus a few -- are appended to a short list in LDS,
+//      from which K rounds of a workgroup-wide maximum pop the winners in order.
+// A row whose list would overflow (many pairs above tau inside one thread's share) takes the
+// plain route instead: every thread keeps its best KMAX pairs in sorted registers.
+__device__ inline bool cand_before(float av, int ai, float bv, int bi) { return av > bv || (av == bv && ai < bi); }
+
+// Workgroup-wide best of every thread's (v, i); all 256 threads call it.  s_v/s_i: 4-entry LDS scratch.
+__device__ inline void block_best(float& v, int& i, float* s_v, int* s_i) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const float ov = __shfl_xor(v, off, 64);
+    const int oi = __shfl_xor(i, off, 64);
+    if (cand_before(ov, oi, v, i)) { v = ov; i = oi; }
+  }
+  __syncthreads();  // the previous call's readers are done
+  if ((threadIdx.x & 63) == 0) { s_v[threadIdx.x >> 6] = v; s_i[threadIdx.x >> 6] = i; }
+  __syncthreads();
+  v = s_v[0]; i = s_i[0];
+#pragma unroll
+  for (int w = 1; w < 4; ++w)
+    if (cand_before(s_v[w], s_i[w], v, i)) { v = s_v[w]; i = s_i[w]; }
+}
+
+// Sorted insert of (v, c) into a thread's best-first list of N pairs.
+template <int N>
+__device__ inline void list_insert(float (&tv)[N], int (&ti)[N], float v, int c) {
+  if (!cand_before(v, c, tv[N - 1], ti[N - 1])) return;
+  tv[N - 1] = v;
+  ti[N - 1] = c;
+#pragma unroll
+  for (int j = N - 1; j > 0; --j) {
+    if (cand_before(tv[j], ti[j], tv[j - 1], ti[j - 1])) {
+      const float fv = tv[j]; tv[j] = tv[j - 1]; tv[j - 1] = fv;
+      const int fi = ti[j]; ti[j] = ti[j - 1]; ti[j - 1] = fi;
+    }
+  }
+}
+
+// K rounds: the workgroup's best head wins, its owner pops it, thread 0 stores the winner.
+template <int N>
+__device__ inline void pop_rounds(float (&tv)[N], int (&ti)[N], int K, bool writes, int tok, float M, float S,
+                                  int32_t* succ_ids, float* succ_scores, float* s_v, int* s_i) {
+  for (int k = 0; k < K; ++k) {
+    float bv = tv[0];
+    int bi = ti[0];
+    block_best(bv, bi, s_v, s_i);
+    if (ti[0] == bi && bi != INT_MAX) {  // token ids are unique: exactly one owner
+#pragma unroll
+      for (int j = 0; j < N - 1; ++j) { tv[j] = tv[j + 1]; ti[j] = ti[j + 1]; }
+      tv[N - 1] = -INFINITY;
+      ti[N - 1] = INT_MAX;
+    }
+    if (threadIdx.x == 0 && writes) {
+      const bool real = bi != INT_MAX;
+      succ_ids[(size_t)tok * K + k] = real ? bi : -1;
+      succ_scores[(size_t)tok * K + k] = real ? __expf(bv - M) / S : 0.f;
+    }
+  }
+}
+
+template <int KMAX>
+__global__ __launch_bounds__(256) void k_harvest_topk(const float* __restrict__ logits, size_t ld, int V,
+                                                      const int32_t* __restrict__ tokens, int B, int K, int table_rows,
+                                                      int32_t* __restrict__ succ_ids,
+                                                      float* __restrict__ succ_scores) {
+  constexpr int DEPTH = 16;   // loads in flight per thread: the row was written by the previous kernel
+  constexpr int LIST = 4;     // list entries per thread on the short route
+  constexpr int CAP = 256 * LIST;
+  __shared__ float s_v[4];
+  __shared__ int s_i[4];
+  __shared__ float s_m[4], s_s[4];
+  __shared__ float c_v[CAP];
+  __shared__ int c_i[CAP];
+  __shared__ int c_n, s_dup;
+  const int m = blockIdx.x, tid = threadIdx.x;
+  const float* row = logits + (size_t)m * ld;
+  if (tid == 0) { c_n = 0; s_dup = 0; }
+
+  // ---- pass 1: thread-best pair and log-sum-exp
+  float bv = -INFINITY, mx = -INFINITY, sm = 0.f;
+  int bi = INT_MAX;
+  for (int c0 = tid; c0 < V; c0 += 256 * DEPTH) {
+    float vals[DEPTH];
+#pragma unroll
+    for (int u = 0; u < DEPTH; ++u) vals[u] = (c0 + u * 256 < V) ? row[c0 + u * 256] : NAN;
+#pragma unroll
+    for (int u = 0; u < DEPTH; ++u) {
+      const float v = vals[u];
+      if (!(v == v)) continue;  // past the row, or NaN: not a candidate
+      if (v > mx) { sm = sm * __expf(mx - v) + 1.f; mx = v; }
+      else sm += __expf(v - mx);
+      if (v > bv) { bv = v; bi = c0 + u * 256; }  // ids ascend within a thread: '>' keeps the lowest
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const float om = __shfl_xor(mx, off, 64), os = __shfl_xor(sm, off, 64);
+    const float nm = fmaxf(mx, om);
+    sm = (nm == -INFINITY) ? 0.f : sm * __expf(mx - nm) + os * __expf(om - nm);
+    mx = nm;
+  }
+  if ((tid & 63) == 0) { s_m[tid >> 6] = mx; s_s[tid >> 6] = sm; }
+  // does this node write?  (a valid token, and no later node with the same token)
+  const int tok = tokens[m];
+  __syncthreads();
+  if (tid > m && tid < B && tokens[tid] == tok) s_dup = 1;
+  const float M = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+  float S = 0.f;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) S += (s_m[w] == -INFINITY) ? 0.f : s_s[w] * __expf(s_m[w] - M);
+
+  // ---- tau: the K-th best of the thread-bests
+  float tau_v = -INFINITY;
+  int tau_i = INT_MAX;
+  for (int k = 0; k < K; ++k) {
+    float wv = bv;
+    int wi = bi;
+    block_best(wv, wi, s_v, s_i);
+    if (wi == bi && bi != INT_MAX) { bv = -INFINITY; bi = INT_MAX; }
+    tau_v = wv;
+    tau_i = wi;  // (-inf, INT_MAX) once the thread-bests run out: then every pair qualifies
+  }
+  const bool writes = tok >= 0 && tok < table_rows && s_dup == 0;  // s_dup settled by the barriers above
+
+  // ---- pass 2: pairs at or above tau into the list
+  for (int c0 = tid; c0 < V; c0 += 256 * DEPTH) {
+    float vals[DEPTH];
+#pragma unroll
+    for (int u = 0; u < DEPTH; ++u) vals[u] = (c0 + u * 256 < V) ? row[c0 + u * 256] : NAN;
+#pragma unroll
+    for (int u = 0; u < DEPTH; ++u) {
+      const float v = vals[u];
+      const int c = c0 + u * 256;
+      if (v == v && !cand_before(tau_v, tau_i, v, c)) {
+        const int pos = atomicAdd(&c_n, 1);
+        if (pos < CAP) { c_v[pos] = v; c_i[pos] = c; }
+      }
+    }
+  }
+  __syncthreads();
+  const int n = c_n;
+  if (n <= CAP) {
+    float tv[LIST];
+    int ti[LIST];
+#pragma unroll
+    for (int j = 0; j < LIST; ++j) { tv[j] = -INFINITY; ti[j] = INT_MAX; }
+    for (int e = tid; e < n; e += 256) list_insert<LIST>(tv, ti, c_v[e], c_i[e]);
+    pop_rounds<LIST>(tv, ti, K, writes, tok, M, S, succ_ids, succ_scores, s_v, s_i);
+    return;
+  }
+  // ---- plain route (wave-uniform: n is shared)
+  float tv[KMAX];
+  int ti[KMAX];
+#pragma unroll
+  for (int j = 0; j < KMAX; ++j) { tv[j] = -INFINITY; ti[j] = INT_MAX; }
+  for (int c = tid; c < V; c += 256) {
+    const float v = row[c];
+    if (v == v) list_insert<KMAX>(tv, ti, v, c);
+  }
+  pop_rounds<KMAX>(tv, ti, K, writes, tok, M, S, succ_ids, succ_scores, s_v, s_i);
+}
+
+// ------------------------------------------------------------------------------------------
 // Greedy walk (Alg. UnifiedGreedyWalk).  Every node whose own edge matches (its token equals the prediction
 // at its parent) bids for its parent with the key (branch?1:0, node index); the lowest key
 // wins, i.e. spine children before branch children, lower index first.  Thread 0 then follows
@@ -437,6 +608,14 @@ int launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st) 
 
 int launch_argmax_top2(const void* top2, int n_groups, int B, int32_t* argmax, float* margin, hipStream_t st) {
   hipLaunchKernelGGL(k_argmax_top2, dim3(B), dim3(64), 0, st, (const float4*)top2, n_groups, argmax, margin);
+  return goose_launch_status();
+}
+
+int launch_harvest_topk(const float* logits, size_t ld, int V, const int32_t* tokens, int B, int K, int table_rows,
+                        int32_t* succ_ids, float* succ_scores, hipStream_t st) {
+  if (K < 1 || K > 16) return GOOSE_ERR_ARG;
+  hipLaunchKernelGGL(k_harvest_topk<16>, dim3(B), dim3(256), 0, st, logits, ld, V, tokens, B, K, table_rows, succ_ids,
+                     succ_scores);
   return goose_launch_status();
 }
 

@@ -139,8 +139,10 @@ class GooseModel:
         return out
 
     # ---- one step through goose_verify_step (P lives on the device)
-    def verify_step_fused(self, t, p, s, B, P_max, next_root=None, logits=None, margin=None):
+    def verify_step_fused(self, t, p, s, B, P_max, next_root=None, logits=None, margin=None, succ_ids=None,
+                          succ_scores=None):
         io = {"tokens": t, "parent": p, "is_spine": s, "P": self.d_P, "argmax": self.argmax,
               "accept_len": self.accept_len, "path": self.path, "bonus": self.bonus, "next_root": next_root,
-              "logits": logits, "margin": margin}
+              "logits": logits, "margin": margin, "succ_ids": succ_ids, "succ_scores": succ_scores,
+              "harvest_k": 0 if succ_ids is None else succ_ids.shape[1]}
         self.ctx.goose_verify_step(self.model_ptrs(), io, B, P_max)
