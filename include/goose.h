@@ -208,6 +208,45 @@ int goose_verify_step(goose_ctx* ctx, const goose_model_ptrs* model, const goose
 int goose_harvest_topk(goose_ctx* ctx, const float* d_logits, size_t ld, const int32_t* d_tokens, int B, int K,
                        int32_t* d_succ_ids, float* d_succ_scores, void* stream);
 
+/* ---- 8. the draft side of a cycle (HOST functions on HOST memory; no GPU work) ---------------
+ * goose_context_match (the n-gram lookup described under Alg. "Decoding Loop", App. B.2): for every
+ * query length n in h_lens, the most recent earlier occurrence of the last n tokens of h_seq; the
+ * draft chain is the continuation after the match of the largest n that matched (at most max_len
+ * tokens, never past the end of the sequence); *h_consensus = 1 iff at least two lengths matched
+ * and two of them agree on the first continuation token.  h_draft: [max_len], *h_m tokens valid.
+ *
+ * goose_spine_budget: lines 1-3 of Alg. BuildSpineTree (b_s spine nodes, b_r root branches, b_rho
+ * spine-level branches) in double precision.
+ *
+ * goose_build_spine_tree: Alg. BuildSpineTree on the one-token successor tables (host mirror of
+ * what goose_harvest_topk writes: ids int32 [vocab][K], scores f32 [vocab][K]).  Node 0 is the
+ * anchor; creation order (root, spine, root branches, spine branches by spine position with the
+ * harmonic allocation floor(b_rho * (1/i) / H_{b_s}), then the breadth-first extension) is the node
+ * order and is topological.  A successor is skipped if its id < 0, its score < min_score, or its
+ * token is already a child of the node (this covers the spine continuation); the extension visits
+ * branch leaves first-in first-out and appends one successor per visit while budget remains, down
+ * to branch depth D.  Outputs: h_tokens/h_parent/h_is_spine [B], *h_n <= B nodes written.
+ * The two-token table tier and the score-proportional re-weighting of branch widths (App. C) are
+ * not implemented.
+ *
+ * goose_spine_ratio_tier / goose_ema_update: Sec. 4.3 and the hyperparameter table of App. C
+ * (tiers 0.15 / 0.30 / 0.50 at 0.2 and 0.4; p <- (1-alpha) p + alpha * accepted/offered, unchanged
+ * when no spine node was offered). */
+int goose_context_match(const int32_t* h_seq, int n_seq, const int32_t* h_lens, int n_lens, int max_len,
+                        int32_t* h_draft, int32_t* h_m, int32_t* h_consensus);
+int goose_spine_budget(int B, int m, double r, double rho, int32_t* b_s, int32_t* b_r, int32_t* b_rho);
+int goose_build_spine_tree(int32_t anchor, const int32_t* h_draft, int m, const int32_t* h_succ_ids,
+                           const float* h_succ_scores, int vocab, int K, int B, double r, double rho, int D,
+                           double min_score, int32_t* h_tokens, int32_t* h_parent, uint8_t* h_is_spine,
+                           int32_t* h_n);
+/* Routing of a cycle (Alg. "Decoding Loop"): a non-empty draft chain that is long (>= bypass_len) or
+ * has consensus is verified as a plain chain (bypass); otherwise any draft source gives a spine
+ * tree; with none the cycle is one autoregressive step. */
+enum { GOOSE_MODE_AR = 0, GOOSE_MODE_TREE = 1, GOOSE_MODE_BYPASS = 2 };
+int goose_cycle_mode(int m, int consensus, int bypass_len, int anchor_has_successors);
+double goose_spine_ratio_tier(double p_hat);
+double goose_ema_update(double p_hat, int accepted_spine, int offered_spine, double alpha);
+
 /* Device-side diagnostics: bit 0 set if any kernel since the last call saw a parent
  * array that is not topological.  Synchronises `stream`. */
 int goose_device_flags(goose_ctx* ctx, void* stream, int32_t* h_flags_out);

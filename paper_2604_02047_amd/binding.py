@@ -20,6 +20,8 @@ EXPORTS = [
     "goose_packed_matrix_bytes", "goose_pack_matrix", "goose_gemm_packed", "goose_gemm_swiglu_packed",
     "goose_profile_enable", "goose_profile_kinds", "goose_profile_kind_name", "goose_profile_read",
     "goose_copy_probe", "goose_harvest_topk",
+    "goose_context_match", "goose_spine_budget", "goose_build_spine_tree", "goose_spine_ratio_tier", "goose_ema_update",
+    "goose_cycle_mode",
 ]
 
 GOOSE_DTYPE_BF16, GOOSE_DTYPE_F32 = 0, 1
@@ -124,8 +126,18 @@ def load_library():
     lib.goose_profile_kind_name.argtypes = [C.c_int]
     lib.goose_profile_kind_name.restype = C.c_char_p
     lib.goose_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+    lib.goose_context_match.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 3
+    lib.goose_spine_budget.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double] + [C.c_void_p] * 3
+    lib.goose_build_spine_tree.argtypes = [C.c_int32, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+                                           C.c_int, C.c_double, C.c_double, C.c_int, C.c_double] + [C.c_void_p] * 4
+    lib.goose_spine_ratio_tier.argtypes = [C.c_double]
+    lib.goose_spine_ratio_tier.restype = C.c_double
+    lib.goose_ema_update.argtypes = [C.c_double, C.c_int, C.c_int, C.c_double]
+    lib.goose_ema_update.restype = C.c_double
     for name in EXPORTS:
         fn = getattr(lib, name)
+        if name in ("goose_spine_ratio_tier", "goose_ema_update"):
+            continue
         if name not in ("goose_strerror", "goose_last_hip_error", "goose_destroy", "goose_packed_layer_bytes", "goose_packed_lm_head_bytes",
                         "goose_profile_kind_name", "goose_packed_matrix_bytes"):
             fn.restype = C.c_int
@@ -155,6 +167,59 @@ def goose_check_parent(parent) -> int:
         return load_library().goose_check_parent(None, 0)
     a = np.ascontiguousarray(np.asarray(parent, dtype=np.int32))
     return load_library().goose_check_parent(a.ctypes.data_as(C.c_void_p), int(a.shape[0]))
+
+
+def _np_i32(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def goose_context_match(seq, lens=(3, 4, 5), max_len=20):
+    """Host n-gram lookup; returns (draft chain as an int32 array, consensus flag)."""
+    seq, lens = _np_i32(seq), _np_i32(lens)
+    draft = np.zeros(max_len, np.int32)
+    m, cons = C.c_int32(0), C.c_int32(0)
+    _check(load_library().goose_context_match(seq.ctypes.data, len(seq), lens.ctypes.data, len(lens), max_len,
+                                              draft.ctypes.data, C.addressof(m), C.addressof(cons)),
+           "goose_context_match")
+    return draft[:m.value].copy(), bool(cons.value)
+
+
+def goose_spine_budget(B, m, r, rho):
+    out = (C.c_int32 * 3)()
+    base = C.addressof(out)
+    _check(load_library().goose_spine_budget(B, m, r, rho, base, base + 4, base + 8), "goose_spine_budget")
+    return out[0], out[1], out[2]
+
+
+def goose_build_spine_tree(anchor, draft, succ_ids, succ_scores, B, r, rho=0.5, D=6, min_score=0.01):
+    """Host tree builder on host tables (numpy int32 [V][K], float32 [V][K]); returns (tokens, parent, is_spine)."""
+    draft = _np_i32(draft)
+    assert succ_ids.dtype == np.int32 and succ_scores.dtype == np.float32
+    assert succ_ids.flags.c_contiguous and succ_scores.flags.c_contiguous and succ_ids.shape == succ_scores.shape
+    V, K = succ_ids.shape
+    tok, par, spn = np.zeros(B, np.int32), np.zeros(B, np.int32), np.zeros(B, np.uint8)
+    n = C.c_int32(0)
+    _check(load_library().goose_build_spine_tree(int(anchor), draft.ctypes.data, len(draft), succ_ids.ctypes.data,
+                                                 succ_scores.ctypes.data, V, K, B, r, rho, D, min_score,
+                                                 tok.ctypes.data, par.ctypes.data, spn.ctypes.data, C.addressof(n)),
+           "goose_build_spine_tree")
+    return tok[:n.value].copy(), par[:n.value].copy(), spn[:n.value].copy()
+
+
+MODE_AR, MODE_TREE, MODE_BYPASS = 0, 1, 2
+
+
+def goose_cycle_mode(m, consensus, bypass_len, anchor_has_successors) -> int:
+    return int(load_library().goose_cycle_mode(int(m), int(bool(consensus)), int(bypass_len),
+                                               int(bool(anchor_has_successors))))
+
+
+def goose_spine_ratio_tier(p_hat):
+    return float(load_library().goose_spine_ratio_tier(p_hat))
+
+
+def goose_ema_update(p_hat, accepted_spine, offered_spine, alpha=0.3):
+    return float(load_library().goose_ema_update(p_hat, accepted_spine, offered_spine, alpha))
 
 
 def goose_packed_matrix_bytes(N: int, K: int) -> int:

@@ -1,0 +1,66 @@
+"""Whole decoding cycles on the GPU path (Alg. "Decoding Loop"): context match -> routing -> spine tree
+-> verification + harvest -> walk -> commit.  The generated stream must equal plain greedy decoding
+(the paper's lossless property, Sec. 1 / Sec. 5.2), and fewer model calls than tokens must be spent."""
+import numpy as np
+import pytest
+import torch
+
+import goose_inputs as gi
+from oracle import goose_oracle as orc
+from util import gpu_model, oracle_model, torch_model
+
+pytestmark = pytest.mark.gpu
+
+
+def _prompt(vocab, seed):
+    pat = gi.prefix_tokens(seed, 12, vocab).tolist()
+    return pat * 3 + pat[:5]
+
+
+@pytest.mark.parametrize("min_score", [0.0, 0.01])
+def test_tiny_fp32_decoding_is_lossless_against_the_oracle(min_score):
+    from paper_2604_02047_amd.decoder import GooseDecoder
+    shape = gi.SHAPES["tiny"]
+    tm = torch_model(shape, seed=4, gain_jitter=0.1)
+    om = oracle_model(shape, tm)
+    gm = gpu_model(shape, tm, max_B=64, cap=512)
+    prompt = _prompt(shape.vocab, 3)
+    dec = GooseDecoder(gm, B=24, K=10, min_score=min_score)
+    y = dec.generate(prompt, 100)
+    ref = list(orc.greedy_decode(om, prompt, len(y)))[:len(y)]
+    ref_logits, _ = orc.causal_logits(om, prompt + ref[:-1])
+    margins = orc.top2_margin(ref_logits[len(prompt) - 1:])
+    tol = 1e-4 * np.abs(ref_logits).max()                # the fp32 logit tolerance: only closer calls may differ
+    same = next((i for i in range(len(y)) if y[i] != ref[i]), len(y))
+    assert same == len(y) or margins[same] < 2 * tol, (same, float(margins[same]), tol)
+    assert same > 50
+    modes = {t["mode"] for t in dec.trace}
+    assert len(dec.trace) < len(y)                       # something was accepted
+    if min_score == 0.0:
+        assert 1 in modes and max(t["nodes"] for t in dec.trace) == 24     # full spine trees were built and verified
+    assert gm.ctx.goose_device_flags() == 0
+    gm.ctx.close()
+
+
+def test_small_bf16_decoding_equals_its_own_autoregressive_decoding():
+    from paper_2604_02047_amd.decoder import GooseDecoder
+    shape = gi.SHAPES["small_bf16"]
+    tm = torch_model(shape, seed=6, gain_jitter=0.1)
+    prompt = _prompt(shape.vocab, 5)
+    # plain greedy decoding through the same library: one single-node cycle per token
+    gm = gpu_model(shape, tm, max_B=128, cap=512)
+    ar = GooseDecoder(gm, B=60, min_score=2.0)            # a threshold no score reaches and no n-gram length: AR only
+    ar.lens = (10 ** 6,)
+    y_ar = ar.generate(prompt, 90)
+    assert all(t["mode"] == 0 and t["nodes"] == 1 for t in ar.trace)
+    gm.ctx.close()
+    gm = gpu_model(shape, tm, max_B=128, cap=512)
+    dec = GooseDecoder(gm, B=60, min_score=0.0)
+    y = dec.generate(prompt, 90)
+    n = min(len(y), len(y_ar))
+    same = next((i for i in range(n) if y[i] != y_ar[i]), n)
+    # bf16 near-ties can be decided differently by launches of different shape; long agreement is the check
+    assert same >= 40, (same, y[:same + 2], y_ar[:same + 2])
+    assert len(dec.trace) < len(y) and {t["mode"] for t in dec.trace} >= {1}
+    assert sum(t["accepted"] for t in dec.trace) >= 10
+    gm.ctx.close()
