@@ -19,14 +19,24 @@ class ModelShape:
     rope_base: float = 10000.0
     rms_eps: float = 1e-5
     dtype: str = "bf16"  # storage type of weights and KV cache: "bf16" or "f32"
+    n_kv_heads: int = 0  # key/value heads (grouped-query attention); 0 = as many as query heads
+    qk_norm: bool = False  # RMSNorm over head_dim on q and k before the rotary embedding
 
     @property
     def qkv_dim(self) -> int:
         return self.n_heads * self.head_dim
 
+    @property
+    def kv_heads(self) -> int:
+        return self.n_kv_heads or self.n_heads
+
+    @property
+    def kv_dim(self) -> int:
+        return self.kv_heads * self.head_dim
+
     def layer_param_count(self) -> int:
-        h, q, f = self.hidden, self.qkv_dim, self.ffn
-        return 3 * q * h + h * q + 3 * f * h
+        h, q, kv, f = self.hidden, self.qkv_dim, self.kv_dim, self.ffn
+        return q * h + 2 * kv * h + h * q + 3 * f * h
 
     def weight_bytes_per_layer(self) -> int:
         return self.layer_param_count() * (2 if self.dtype == "bf16" else 4)
@@ -42,6 +52,14 @@ SHAPES = {
     "7b": ModelShape("7b", 32, 4096, 32, 128, 11008, 32000),
     "13b": ModelShape("13b", 40, 5120, 40, 128, 13824, 32000),
     "33b": ModelShape("33b", 60, 6656, 52, 128, 17920, 32000),
+    # the grouped-query models the paper also evaluates (Sec. 5.1): public dimensions of Llama-3-8B and Qwen3-8B
+    "llama3_8b": ModelShape("llama3_8b", 32, 4096, 32, 128, 14336, 128256, rope_base=500000.0, n_kv_heads=8),
+    "qwen3_8b": ModelShape("qwen3_8b", 36, 4096, 32, 128, 12288, 151936, rope_base=1000000.0, rms_eps=1e-6,
+                           n_kv_heads=8, qk_norm=True),
+    # oracle-scale models with the same structure
+    "tiny_gqa_bf16": ModelShape("tiny_gqa_bf16", 2, 256, 4, 64, 688, 1024, dtype="bf16", n_kv_heads=2),
+    "small_gqa_qknorm_bf16": ModelShape("small_gqa_qknorm_bf16", 3, 1024, 8, 128, 2752, 4096, dtype="bf16",
+                                        n_kv_heads=2, qk_norm=True, rms_eps=1e-6),
 }
 
 

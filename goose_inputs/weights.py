@@ -15,7 +15,7 @@ _M32 = 0xFFFFFFFF
 
 # tensor ids inside one layer; global id = layer * 16 + local id
 TENSOR_IDS = {
-    "wq": 0, "wk": 1, "wv": 2, "wo": 3, "wg": 4, "wu": 5, "wd": 6, "g1": 7, "g2": 8,
+    "wq": 0, "wk": 1, "wv": 2, "wo": 3, "wg": 4, "wu": 5, "wd": 6, "g1": 7, "g2": 8, "gq": 9, "gk": 10,
 }
 _EMBED_ID = 1_000_000
 _LMHEAD_ID = 1_000_001
@@ -78,13 +78,14 @@ def _torch_dtype(shape_dtype: str) -> torch.dtype:
     return torch.bfloat16 if shape_dtype == "bf16" else torch.float32
 
 
-def norm_gain(shape, seed: int, tensor_id: int, jitter: float, device="cpu") -> torch.Tensor:
+def norm_gain(shape, seed: int, tensor_id: int, jitter: float, device="cpu", width: int = 0) -> torch.Tensor:
     """RMSNorm gain: all ones (benchmark configs) or 1 + jitter*z (tests that must
-    notice a dropped or misplaced gain)."""
+    notice a dropped or misplaced gain).  `width` defaults to the hidden size."""
     dt = _torch_dtype(shape.dtype)
+    width = width or shape.hidden
     if jitter == 0.0:
-        return torch.ones(shape.hidden, dtype=dt, device=device)
-    z = gen_normal(seed, tensor_id, (shape.hidden,), jitter, torch.float32, device)
+        return torch.ones(width, dtype=dt, device=device)
+    z = gen_normal(seed, tensor_id, (width,), jitter, torch.float32, device)
     return (1.0 + z).to(dt)
 
 
@@ -92,15 +93,18 @@ def layer_weights(shape, seed: int, layer: int, device="cpu", std: float = 0.02,
                   gain_jitter: float = 0.0) -> dict:
     """All tensors of one decoder layer, stored [out, in] like the projection y = x W^T."""
     dt = _torch_dtype(shape.dtype)
-    h, q, f = shape.hidden, shape.qkv_dim, shape.ffn
+    h, q, kv, f = shape.hidden, shape.qkv_dim, shape.kv_dim, shape.ffn
     base = layer * 16
-    dims = {"wq": (q, h), "wk": (q, h), "wv": (q, h), "wo": (h, q),
+    dims = {"wq": (q, h), "wk": (kv, h), "wv": (kv, h), "wo": (h, q),
             "wg": (f, h), "wu": (f, h), "wd": (h, f)}
     out = {}
     for name, d in dims.items():
         out[name] = gen_normal(seed, base + TENSOR_IDS[name], d, std, dt, device)
     out["g1"] = norm_gain(shape, seed, base + TENSOR_IDS["g1"], gain_jitter, device)
     out["g2"] = norm_gain(shape, seed, base + TENSOR_IDS["g2"], gain_jitter, device)
+    if shape.qk_norm:
+        out["gq"] = norm_gain(shape, seed, base + TENSOR_IDS["gq"], gain_jitter, device, width=shape.head_dim)
+        out["gk"] = norm_gain(shape, seed, base + TENSOR_IDS["gk"], gain_jitter, device, width=shape.head_dim)
     return out
 
 

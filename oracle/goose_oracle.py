@@ -40,8 +40,11 @@ class OracleModel:
     """Weights as float64 arrays.  `layers[l]` is a dict with wq wk wv wo wg wu wd g1 g2;
     it may be any sequence (also a lazy one) so that large models stream layer by layer."""
 
-    def __init__(self, n_heads, head_dim, rope_base, rms_eps, layers, embed, lm_head, final_norm):
+    def __init__(self, n_heads, head_dim, rope_base, rms_eps, layers, embed, lm_head, final_norm,
+                 n_kv_heads=None, qk_norm=False):
         self.n_heads = int(n_heads)
+        self.n_kv_heads = int(n_kv_heads or n_heads)   # grouped-query attention: query head h reads KV head h // group
+        self.qk_norm = bool(qk_norm)                   # RMSNorm over head_dim on q and k (gains gq, gk) before RoPE
         self.head_dim = int(head_dim)
         self.rope_base = float(rope_base)
         self.rms_eps = float(rms_eps)
@@ -83,26 +86,31 @@ def softmax_rows(s):
 
 
 def attention(q, K, V, allow):
-    """q [T,n_h,d]; K,V [n_h,S,d]; allow bool [T,S] (True = query t may see slot s) -> [T,n_h,d]."""
+    """q [T,n_h,d]; K,V [n_kv,S,d] with n_kv dividing n_h (query head h uses KV head h // (n_h/n_kv));
+    allow bool [T,S] (True = query t may see slot s) -> [T,n_h,d]."""
     T, n_h, d = q.shape
+    group = n_h // K.shape[0]
     out = np.empty_like(q)
     for h in range(n_h):
-        s = q[:, h, :] @ K[h].T / np.sqrt(F64(d))
+        s = q[:, h, :] @ K[h // group].T / np.sqrt(F64(d))
         s = np.where(allow, s, -np.inf)
-        out[:, h, :] = softmax_rows(s) @ V[h]
+        out[:, h, :] = softmax_rows(s) @ V[h // group]
     return out
 
 
 def decoder_layer(model, w, x, Kc, Vc, pos, allow):
     """One pre-norm block over T new rows.
-    x [T,H]; Kc,Vc [n_h,P,d] cached (K already rotated); pos [T]; allow [T,P+T].
-    Returns (x_out [T,H], k_new [n_h,T,d] rotated, v_new [n_h,T,d])."""
+    x [T,H]; Kc,Vc [n_kv,P,d] cached (K already rotated); pos [T]; allow [T,P+T].
+    Returns (x_out [T,H], k_new [n_kv,T,d] rotated, v_new [n_kv,T,d])."""
     T = x.shape[0]
-    n_h, d = model.n_heads, model.head_dim
+    n_h, n_kv, d = model.n_heads, model.n_kv_heads, model.head_dim
     xn = rmsnorm(x, w["g1"], model.rms_eps)
     q = (xn @ w["wq"].T).reshape(T, n_h, d)
-    k = (xn @ w["wk"].T).reshape(T, n_h, d)
-    v = (xn @ w["wv"].T).reshape(T, n_h, d)
+    k = (xn @ w["wk"].T).reshape(T, n_kv, d)
+    v = (xn @ w["wv"].T).reshape(T, n_kv, d)
+    if model.qk_norm:                                   # per head, over head_dim, before the rotation
+        q = rmsnorm(q, w["gq"], model.rms_eps)
+        k = rmsnorm(k, w["gk"], model.rms_eps)
     q = rope(q, pos, model.rope_base)
     k = rope(k, pos, model.rope_base)
     k_new = np.ascontiguousarray(k.transpose(1, 0, 2))
@@ -121,7 +129,7 @@ def final_logits(model, x):
 
 
 def empty_cache(model):
-    z = np.zeros((model.n_heads, 0, model.head_dim), F64)
+    z = np.zeros((model.n_kv_heads, 0, model.head_dim), F64)
     return [(z.copy(), z.copy()) for _ in range(model.n_layers)]
 
 

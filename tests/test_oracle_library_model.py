@@ -27,7 +27,7 @@ def _hf_model(shape, tm):
     cfg = LlamaConfig(
         vocab_size=shape.vocab, hidden_size=shape.hidden, intermediate_size=shape.ffn,
         num_hidden_layers=shape.n_layers, num_attention_heads=shape.n_heads,
-        num_key_value_heads=shape.n_heads, head_dim=shape.head_dim, rms_norm_eps=shape.rms_eps,
+        num_key_value_heads=shape.kv_heads, head_dim=shape.head_dim, rms_norm_eps=shape.rms_eps,
         rope_theta=shape.rope_base, max_position_embeddings=4096, tie_word_embeddings=False,
         attention_bias=False, mlp_bias=False, hidden_act="silu", attn_implementation="eager")
     m = LlamaForCausalLM(cfg).double().eval()
@@ -88,3 +88,49 @@ def test_tree_logits_match_library_with_explicit_mask(models):
     with torch.no_grad():
         ref = hf(input_ids=ids, attention_mask=add, position_ids=torch.tensor(pos)[None]).logits[0, P:].numpy()
     np.testing.assert_allclose(mine, ref, rtol=0, atol=ATOL)
+
+
+# ---- the grouped-query and QK-norm variants (the other model families of Sec. 5.1) ------------------
+def _hf_qwen3(shape, tm):
+    from transformers import Qwen3Config, Qwen3ForCausalLM
+    cfg = Qwen3Config(
+        vocab_size=shape.vocab, hidden_size=shape.hidden, intermediate_size=shape.ffn,
+        num_hidden_layers=shape.n_layers, num_attention_heads=shape.n_heads,
+        num_key_value_heads=shape.kv_heads, head_dim=shape.head_dim, rms_norm_eps=shape.rms_eps,
+        rope_theta=shape.rope_base, max_position_embeddings=4096, tie_word_embeddings=False,
+        attention_bias=False, hidden_act="silu", attn_implementation="eager", use_sliding_window=False)
+    m = Qwen3ForCausalLM(cfg).double().eval()
+    sd = {"model.embed_tokens.weight": tm["embed"], "lm_head.weight": tm["lm_head"],
+          "model.norm.weight": tm["final_norm"]}
+    names = {"wq": "self_attn.q_proj", "wk": "self_attn.k_proj", "wv": "self_attn.v_proj",
+             "wo": "self_attn.o_proj", "wg": "mlp.gate_proj", "wu": "mlp.up_proj", "wd": "mlp.down_proj",
+             "g1": "input_layernorm", "g2": "post_attention_layernorm", "gq": "self_attn.q_norm",
+             "gk": "self_attn.k_norm"}
+    for l, lw in enumerate(tm["layers"]):
+        for k, v in lw.items():
+            sd[f"model.layers.{l}.{names[k]}.weight"] = v
+    missing, unexpected = m.load_state_dict({k: v.double() for k, v in sd.items()}, strict=False)
+    assert not [k for k in missing if "rotary" not in k] and not unexpected
+    return m
+
+
+@pytest.mark.parametrize("kind", ["gqa", "gqa_qknorm"])
+def test_grouped_query_and_qk_norm_match_library(kind):
+    base = gi.SHAPES["tiny"]
+    shape = gi.ModelShape("t", 2, base.hidden, 4, 64, base.ffn, base.vocab, dtype="f32", n_kv_heads=2,
+                          qk_norm=(kind == "gqa_qknorm"), rms_eps=1e-6 if kind == "gqa_qknorm" else 1e-5)
+    tm = torch_model(shape, seed=8, gain_jitter=0.2)
+    om = oracle_model(shape, tm)
+    hf = _hf_qwen3(shape, tm) if shape.qk_norm else _hf_model(shape, tm)
+    toks = gi.prefix_tokens(9, 33, shape.vocab)
+    mine, _ = orc.causal_logits(om, toks)
+    with torch.no_grad():
+        ref = hf(input_ids=torch.from_numpy(toks.astype(np.int64))[None]).logits[0].numpy()
+    assert np.abs(ref).max() > 0.05
+    np.testing.assert_allclose(mine, ref, rtol=0, atol=ATOL)
+    # and the tree pass stays consistent with per-path causal runs for these variants
+    tree = gi.tree_random(9, seed=2, spine_len=3)
+    dt = gi.draft_tokens_uniform(3, tree.parent, shape.vocab, root_token=5)
+    packed, _ = orc.tree_logits(om, orc.prefill(om, toks), dt, tree.parent)
+    brute = orc.path_logits_bruteforce(om, toks, dt, tree.parent)
+    np.testing.assert_allclose(packed, brute, rtol=0, atol=1e-10)

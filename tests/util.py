@@ -40,7 +40,8 @@ def torch_model(shape, seed=0, gain_jitter=0.0, device="cpu"):
 def oracle_model(shape, tm) -> orc.OracleModel:
     layers = [{k: to_f64(v) for k, v in lw.items()} for lw in tm["layers"]]
     return orc.OracleModel(shape.n_heads, shape.head_dim, shape.rope_base, shape.rms_eps,
-                           layers, to_f64(tm["embed"]), to_f64(tm["lm_head"]), to_f64(tm["final_norm"]))
+                           layers, to_f64(tm["embed"]), to_f64(tm["lm_head"]), to_f64(tm["final_norm"]),
+                           n_kv_heads=shape.kv_heads, qk_norm=shape.qk_norm)
 
 
 def gpu_model(shape, tm, max_B, cap):
