@@ -31,6 +31,8 @@ WORKLOADS = {
     "7b_stress_B128_P16384": ("7b", 128, 16384, "spine_stress", 50),
     "7b_balanced_B128_P16384": ("7b", 128, 16384, "balanced", 50),
     "small_B64_P200": ("small_bf16", 64, 200, "spine_7b", 20),
+    "llama3_8b_B64_P1024": ("llama3_8b", 64, 1024, "spine_7b", 100),
+    "qwen3_8b_B64_P1024": ("qwen3_8b", 64, 1024, "spine_7b", 100),
 }
 
 
@@ -66,8 +68,8 @@ def step_bytes(shape, B, P):
     es = 2 if shape.dtype == "bf16" else 4
     w = shape.n_layers * shape.layer_param_count() * es
     head = shape.vocab * shape.hidden * es
-    kv_prefix = 2 * P * shape.qkv_dim * es * shape.n_layers
-    kv_tail = 2 * 2 * B * shape.qkv_dim * es * shape.n_layers
+    kv_prefix = 2 * P * shape.kv_dim * es * shape.n_layers
+    kv_tail = 2 * 2 * B * shape.kv_dim * es * shape.n_layers
     return w + head + kv_prefix + kv_tail
 
 
@@ -344,7 +346,7 @@ def cpu_baseline(shape, gm, seed, B, P0, tree_kind, log):
     log(f"cpu baseline: building the {n_s}-layer oracle sample")
     om = orc.OracleModel(shape.n_heads, shape.head_dim, shape.rope_base, shape.rms_eps, [None] * n_s,
                          f64(gm.embed), f64(gi.lm_head(shape, seed, gm.device)),
-                         f64(gi.final_norm(shape, seed, gm.device)))
+                         f64(gi.final_norm(shape, seed, gm.device)), n_kv_heads=shape.kv_heads, qk_norm=shape.qk_norm)
     kr, vr = gm.k_rows(0, P0), gm.v_rows(0, P0)
     tree = make_tree(tree_kind, 0)
     toks = gi.draft_tokens_uniform(seed, tree.parent, shape.vocab, 1)

@@ -30,15 +30,16 @@
  * Model: pre-norm Llama-style decoder (the architecture the paper evaluates, Sec. 5.1):
  * RMSNorm x*rsqrt(mean(x^2)+eps)*g, rotary embedding on q,k with half-split pairing
  * (j, j+d/2) and angle pos*base^(-2j/d), scores/sqrt(d), softmax, SwiGLU MLP, untied LM
- * head, no biases, n_kv_heads == n_heads.  Raw weight matrices are row-major [out][in].
+ * head, no biases; optionally grouped-query attention and a per-head norm of q and k (the
+ * other model families of Sec. 5.1).  Raw weight matrices are row-major [out][in].
  *
  * Storage types.  desc.dtype selects the storage type T of weights, KV cache and gains:
  * GOOSE_DTYPE_BF16 (MFMA kernels, fp32 accumulation) or GOOSE_DTYPE_F32 (plain fp32
  * kernels for small models).  The residual stream x is always fp32 [B][hidden].
  *
- * KV cache: two allocations of n_layers * n_heads * cap * head_dim elements each, one head's
+ * KV cache: two allocations of n_layers * n_kv_heads * cap * head_dim elements each, one KV head's
  * cap * head_dim elements contiguous, cap a multiple of 64.  K is stored after the rotary embedding.
- *   GOOSE_DTYPE_F32:  K[layer][head][slot][d];  V TRANSPOSED, Vt[layer][head][d][slot].
+ *   GOOSE_DTYPE_F32:  K[layer][kv head][slot][d];  V TRANSPOSED, Vt[layer][kv head][d][slot].
  *   GOOSE_DTYPE_BF16: both in MFMA OPERAND ORDER, in blocks of 32 slots, so that the attention
  *   kernel streams them with one coalesced 16-byte load per lane and no re-arrangement.
  *   With g = slot, kk = g % 32, c = head-dim column, the element offset inside one head is
@@ -74,17 +75,23 @@ enum { GOOSE_MAX_B = 128 };
 typedef struct {
   int32_t n_layers, hidden, n_heads, head_dim, ffn, vocab;
   float rope_base, rms_eps;
-  int32_t dtype; /* GOOSE_DTYPE_* */
+  int32_t dtype;      /* GOOSE_DTYPE_* */
+  int32_t n_kv_heads; /* key/value heads; 0 = n_heads.  Must divide n_heads: query head h reads KV head
+                         h / (n_heads / n_kv_heads) (grouped-query attention; bf16 models only) */
+  int32_t qk_norm;    /* != 0: RMSNorm over head_dim (gains gq, gk, eps = rms_eps) on every head of q and k
+                         before the rotary embedding (bf16 models only) */
 } goose_model_desc;
 
 /* Raw weights of one decoder layer as a checkpoint stores them: device pointers,
  * row-major [out][in] of the model's storage type. */
 typedef struct {
-  const void *wq, *wk, *wv; /* [n_heads*head_dim][hidden] */
+  const void *wq;           /* [n_heads*head_dim][hidden] */
+  const void *wk, *wv;      /* [n_kv_heads*head_dim][hidden] */
   const void *wo;           /* [hidden][n_heads*head_dim] */
   const void *wg, *wu;      /* [ffn][hidden] */
   const void *wd;           /* [hidden][ffn] */
   const void *g1, *g2;      /* [hidden] RMSNorm gains before attention / before the MLP */
+  const void *gq, *gk;      /* [head_dim] gains of the q / k head norms; read only when desc.qk_norm */
 } goose_layer_weights;
 
 typedef struct goose_ctx goose_ctx;
@@ -130,7 +137,7 @@ int goose_embed(goose_ctx* ctx, const void* d_embed, const int32_t* d_tokens, in
 
 /* ---- 3. one decoder layer over the B packed nodes (Alg. UnifiedGreedyWalk line 1, per layer) ------------
  * d_x fp32 [B][hidden], updated in place.  d_kcache / d_vcache: THIS layer's part of the two
- * cache allocations (n_heads * cap * head_dim elements each, layout above).
+ * cache allocations (n_kv_heads * cap * head_dim elements each, layout above).
  * d_mask/d_pos as written by goose_build_mask.  P from *d_P when d_P != NULL (then the
  * argument P must be an upper bound of *d_P; it sizes the launch), else the argument. */
 int goose_verify_layer(goose_ctx* ctx, const void* d_packed_layer, float* d_x, void* d_kcache, void* d_vcache,

@@ -36,11 +36,11 @@ class GooseError(RuntimeError):
 class _Desc(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("ffn", C.c_int32), ("vocab", C.c_int32), ("rope_base", C.c_float), ("rms_eps", C.c_float),
-                ("dtype", C.c_int32)]
+                ("dtype", C.c_int32), ("n_kv_heads", C.c_int32), ("qk_norm", C.c_int32)]
 
 
 class _LayerWeights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2")]
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2", "gq", "gk")]
 
 
 class _ModelPtrs(C.Structure):
@@ -66,14 +66,22 @@ class ModelDesc:
     rope_base: float = 10000.0
     rms_eps: float = 1e-5
     dtype: str = "bf16"
+    n_kv_heads: int = 0
+    qk_norm: bool = False
+
+    @property
+    def kv_heads(self):
+        return self.n_kv_heads or self.n_heads
 
     @classmethod
     def from_shape(cls, s):
-        return cls(s.n_layers, s.hidden, s.n_heads, s.head_dim, s.ffn, s.vocab, s.rope_base, s.rms_eps, s.dtype)
+        return cls(s.n_layers, s.hidden, s.n_heads, s.head_dim, s.ffn, s.vocab, s.rope_base, s.rms_eps, s.dtype,
+                   getattr(s, "n_kv_heads", 0), getattr(s, "qk_norm", False))
 
     def _c(self):
         return _Desc(self.n_layers, self.hidden, self.n_heads, self.head_dim, self.ffn, self.vocab,
-                     self.rope_base, self.rms_eps, GOOSE_DTYPE_BF16 if self.dtype == "bf16" else GOOSE_DTYPE_F32)
+                     self.rope_base, self.rms_eps, GOOSE_DTYPE_BF16 if self.dtype == "bf16" else GOOSE_DTYPE_F32,
+                     self.n_kv_heads, int(self.qk_norm))
 
 
 _lib = None
@@ -285,7 +293,8 @@ class GooseContext:
 
     # ---- packing
     def goose_pack_layer(self, raw: dict, packed_layer):
-        w = _LayerWeights(*[raw[n].data_ptr() for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2")])
+        w = _LayerWeights(*[(raw[n].data_ptr() if n in raw else None)
+                            for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2", "gq", "gk")])
         _check(self.lib.goose_pack_layer(self._h, C.byref(w), _ptr(packed_layer), _stream()), "goose_pack_layer")
 
     def goose_pack_lm_head(self, gf, wlm, packed_head):

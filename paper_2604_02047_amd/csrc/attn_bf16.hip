@@ -58,10 +58,11 @@ __device__ inline size_t v_elem_off(int g, int c) {
 
 template <int D, int NG, int NQH>
 __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
-    const float* __restrict__ part, int ks, size_t part_stride, size_t part_ld, int n_heads,
+    const float* __restrict__ part, int ks, size_t part_stride, size_t part_ld, int n_heads, int n_kv_heads,
     const float2* __restrict__ cs, bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, int cap,
-    const int32_t* __restrict__ dP, int B, const uint64_t* __restrict__ mask, float* __restrict__ att_o,
-    float* __restrict__ att_ml, int Bpad, bf16_t* __restrict__ o_out, int ldo) {
+    const int32_t* __restrict__ dP, int B, const uint64_t* __restrict__ mask, const bf16_t* __restrict__ gq,
+    const bf16_t* __restrict__ gk, float eps, float* __restrict__ att_o, float* __restrict__ att_ml, int Bpad,
+    bf16_t* __restrict__ o_out, int ldo) {
   constexpr int NTHR = 64 * NG * NQH;
   constexpr int NS = D / 16;               // operand loads (1 KiB pieces) per block, for K and for V
   constexpr int TROWS = NQH * 32;          // tree rows the LDS buffers hold (>= B for this instantiation)
@@ -80,7 +81,12 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   const int g = wave % NG, qh = wave / NG;  // key group, query tile
   const int split = blockIdx.x, nsplit = gridDim.x, h = blockIdx.y;
   const int l31 = lane & 31, hh = lane >> 5;
-  const int Hq = n_heads * D;
+  // grouped queries: `group` query heads share KV head kvh; their projections sit at columns
+  // [0,Hq) q, [Hq, Hq+Hkv) k, [Hq+Hkv, Hq+2Hkv) v of the fused projection
+  const int group = n_heads / n_kv_heads, kvh = h / group;
+  const int Hq = n_heads * D, Hkv = n_kv_heads * D;
+  const int kcol = Hq + kvh * D - h * D, vcol = kcol + Hkv;  // relative to this head's q columns
+  const bool tail_writer = (h % group) == 0;                  // one head of the group stores the tree's K/V
   int P = *dP;
   if (P > cap - B) P = cap - B;  // callers guarantee P + B <= cap; never index outside the cache
   if (P < 0) P = 0;
@@ -111,8 +117,8 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   const int ntail = last ? (nbt - g + NG - 1) / NG : 0;
   const int total = nblk + (ntail > 0 ? ntail : 0);
 
-  const bf16_t* kh = kc + (size_t)h * cap * D;
-  const bf16_t* vh = vc + (size_t)h * cap * D;
+  const bf16_t* kh = kc + (size_t)kvh * cap * D;
+  const bf16_t* vh = vc + (size_t)kvh * cap * D;
   // One block of operands in registers.  The K pieces are free again after the first MFMA chain
   // and the V pieces after the second, so the next block's loads are issued right there: they fly
   // during the softmax and the second chain (the loop below exists once: code executed once per
@@ -172,11 +178,12 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
 #pragma unroll
       for (int w = 0; w < 3; ++w) {
         const bool on = w == 0 || kv[u];
-        f32x4 a = on ? *reinterpret_cast<const f32x4*>(prow[u] + w * Hq) : zero4;
-        f32x4 b = on ? *reinterpret_cast<const f32x4*>(prow[u] + w * Hq + D / 2) : zero4;
+        const int col = w == 0 ? 0 : (w == 1 ? kcol : vcol);
+        f32x4 a = on ? *reinterpret_cast<const f32x4*>(prow[u] + col) : zero4;
+        f32x4 b = on ? *reinterpret_cast<const f32x4*>(prow[u] + col + D / 2) : zero4;
         if (on && two) {
-          a += *reinterpret_cast<const f32x4*>(p1 + w * Hq);
-          b += *reinterpret_cast<const f32x4*>(p1 + w * Hq + D / 2);
+          a += *reinterpret_cast<const f32x4*>(p1 + col);
+          b += *reinterpret_cast<const f32x4*>(p1 + col + D / 2);
         }
         acc[u][2 * w] = a;
         acc[u][2 * w + 1] = b;
@@ -189,9 +196,33 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
 #pragma unroll
         for (int w = 0; w < 3; ++w)
           if (w == 0 || kv[u]) {
-            acc[u][2 * w] += *reinterpret_cast<const f32x4*>(p + w * Hq);
-            acc[u][2 * w + 1] += *reinterpret_cast<const f32x4*>(p + w * Hq + D / 2);
+            const int col = w == 0 ? 0 : (w == 1 ? kcol : vcol);
+            acc[u][2 * w] += *reinterpret_cast<const f32x4*>(p + col);
+            acc[u][2 * w + 1] += *reinterpret_cast<const f32x4*>(p + col + D / 2);
           }
+      }
+    }
+    if (gq != nullptr) {
+      // per-head RMSNorm of q and k over the head's D columns: the D/8 items of a row sit in
+      // neighbouring lanes, so the sum of squares is a short butterfly
+#pragma unroll
+      for (int u = 0; u < NIT; ++u) {
+        const int j0 = ((tid + u * NTHR) % (D / 8)) * 4;
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+          float ss = 0.f;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) ss += acc[u][2 * w][e] * acc[u][2 * w][e] + acc[u][2 * w + 1][e] * acc[u][2 * w + 1][e];
+#pragma unroll
+          for (int off = 1; off < D / 8; off <<= 1) ss += __shfl_xor(ss, off, 64);
+          const float rstd = 1.0f / sqrtf(ss / (float)D + eps);
+          const bf16_t* g = w == 0 ? gq : gk;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc[u][2 * w][e] *= rstd * (float)g[j0 + e];
+            acc[u][2 * w + 1][e] *= rstd * (float)g[j0 + D / 2 + e];
+          }
+        }
       }
     }
 #pragma unroll
@@ -218,7 +249,7 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
           vl[e] = (__bf16)acc[u][4][e];
           vh4[e] = (__bf16)acc[u][5][e];
         }
-        if (kv[u]) {
+        if (kv[u] && tail_writer) {
           // key row of slot P+i into the cache: columns j0..j0+3 sit in chunk (j0/16, (j0/8)%2) at j0%8
           bf16_t* kw = const_cast<bf16_t*>(kh);
           *reinterpret_cast<bf16x4*>(kw + k_chunk_off<D>(P + i, j0 >> 4, (j0 >> 3) & 1) + (j0 & 7)) = kl;
@@ -251,7 +282,7 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
 
   // ---- the tree's values into the cache, node index fastest so that neighbouring lanes fill
   // neighbouring bytes (the keys went out above)
-  if (last) {
+  if (last && tail_writer) {
     bf16_t* vw = const_cast<bf16_t*>(vh);
     for (int it = tid; it < rows * D; it += NTHR) {
       const int i = it % rows, c = it / rows;
@@ -443,16 +474,17 @@ __global__ void k_rope_table(const int32_t* __restrict__ pos, const double* __re
 }
 
 struct AttnArgs {
-  const float* part; int ks; size_t part_stride, part_ld; int n_heads;
+  const float* part; int ks; size_t part_stride, part_ld; int n_heads, n_kv;
   const float2* cs; bf16_t* kc; bf16_t* vc; int cap; const int32_t* dP; int B; const uint64_t* mask;
+  const bf16_t* gq; const bf16_t* gk; float eps;
   float* att_o; float* att_ml; int Bpad; bf16_t* o; int ldo;
 };
 
 template <int D, int NG, int NQH>
 int launch_cfg(dim3 grid, hipStream_t st, const AttnArgs& a) {
   hipLaunchKernelGGL((k_attn_fused<D, NG, NQH>), grid, dim3(64 * NG * NQH), 0, st, a.part, a.ks, a.part_stride,
-                     a.part_ld, a.n_heads, a.cs, a.kc, a.vc, a.cap, a.dP, a.B, a.mask, a.att_o, a.att_ml, a.Bpad, a.o,
-                     a.ldo);
+                     a.part_ld, a.n_heads, a.n_kv, a.cs, a.kc, a.vc, a.cap, a.dP, a.B, a.mask, a.gq, a.gk, a.eps,
+                     a.att_o, a.att_ml, a.Bpad, a.o, a.ldo);
   return goose_launch_status();
 }
 
@@ -486,14 +518,16 @@ int pick_attn_splits(int n_heads, int keys_max, int max_splits) {
 }
 
 int launch_attn_bf16(const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs, void* kc, void* vc,
-                     int n_heads, int head_dim, int cap, const int32_t* dP, int B, const uint64_t* mask, int splits,
-                     int key_groups, float* att_o, float* att_ml, int Bpad, void* o, int ldo, hipStream_t st) {
+                     int n_heads, int n_kv_heads, int head_dim, int cap, const int32_t* dP, int B,
+                     const uint64_t* mask, int splits, int key_groups, const void* gq, const void* gk, float eps,
+                     float* att_o, float* att_ml, int Bpad, void* o, int ldo, hipStream_t st) {
+  if (n_kv_heads < 1 || n_heads % n_kv_heads != 0 || (gq == nullptr) != (gk == nullptr)) return GOOSE_ERR_ARG;
   const int QT = (B + 31) / 32;
   // a 3-tile tree runs the 4-tile kernel, which reads projection rows up to 128 (the workspace has them)
   if ((QT >= 3 ? 4 : QT) * 32 > Bpad || B > GOOSE_MAX_B || (cap & 31)) return GOOSE_ERR_ARG;
   if (splits < 1 || (key_groups != 2 && key_groups != 4)) return GOOSE_ERR_ARG;
-  AttnArgs a{part, ks, part_stride, part_ld, n_heads, (const float2*)cs, (bf16_t*)kc, (bf16_t*)vc, cap, dP, B, mask,
-             att_o, att_ml, Bpad, (bf16_t*)o, ldo};
+  AttnArgs a{part, ks, part_stride, part_ld, n_heads, n_kv_heads, (const float2*)cs, (bf16_t*)kc, (bf16_t*)vc, cap,
+             dP, B, mask, (const bf16_t*)gq, (const bf16_t*)gk, eps, att_o, att_ml, Bpad, (bf16_t*)o, ldo};
   dim3 grid(splits, n_heads);
   int rc;
   if (head_dim == 128) rc = launch_d<128>(QT, key_groups, grid, st, a);

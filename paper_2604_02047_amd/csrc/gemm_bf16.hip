@@ -28,12 +28,12 @@ constexpr int KGRAN = 128;  // granularity of K padding and of split-K ranges (i
 // ------------------------------------------------------------------------------------------
 // Re-tile raw row-major bf16 matrices.  Packed row n comes from
 //   PACK_PLAIN   : s0 row n
-//   PACK_QKV     : q|k|v stacked: source n / rows_each, row n % rows_each
+//   PACK_QKV     : q|k|v stacked: rows_each rows of s0, then rows_kv rows of s1, then rows_kv rows of s2
 //   PACK_GATE_UP : blocks of 32 rows alternate gate (s0) / up (s1): block b -> (b&1 ? up : gate) rows (b>>1)*32..
 // Rows and columns outside the source are zero.
 __global__ __launch_bounds__(256) void k_pack_bf16(int mode, const bf16_t* __restrict__ s0,
                                                    const bf16_t* __restrict__ s1, const bf16_t* __restrict__ s2,
-                                                   int rows_each, int K, int ktiles, size_t total,
+                                                   int rows_each, int rows_kv, int K, int ktiles, size_t total,
                                                    uint4* __restrict__ dst) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // one 16-byte lane slot
   if (idx >= total) return;
@@ -44,13 +44,13 @@ __global__ __launch_bounds__(256) void k_pack_bf16(int mode, const bf16_t* __res
   const int n = nt * 32 + (lane & 31);
   const int k0 = kt * 16 + (lane >> 5) * 8;
   const bf16_t* src = nullptr;
-  int row = 0;
+  int row = 0, limit = rows_each;
   if (mode == PACK_PLAIN) {
     src = s0; row = n;
-  } else if (mode == PACK_QKV) {
-    const int which = n / rows_each;
-    row = n % rows_each;
-    src = which == 0 ? s0 : (which == 1 ? s1 : (which == 2 ? s2 : nullptr));
+  } else if (mode == PACK_QKV) {  // q rows, then k rows, then v rows (k and v may be narrower: grouped queries)
+    if (n < rows_each) { src = s0; row = n; }
+    else if (n < rows_each + rows_kv) { src = s1; row = n - rows_each; limit = rows_kv; }
+    else if (n < rows_each + 2 * rows_kv) { src = s2; row = n - rows_each - rows_kv; limit = rows_kv; }
   } else {
     const int blk = n >> 5;
     row = (blk >> 1) * 32 + (n & 31);
@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void k_pack_bf16(int mode, const bf16_t* __res
   }
   union { uint4 u; bf16_t e[8]; } v;
   v.u = make_uint4(0, 0, 0, 0);
-  if (src != nullptr && row < rows_each) {
+  if (src != nullptr && row < limit) {
 #pragma unroll
     for (int e = 0; e < 8; ++e)
       if (k0 + e < K) v.e[e] = src[(size_t)row * K + k0 + e];
@@ -334,11 +334,12 @@ int launch_mt(int MT, const void* A, int lda, const void* Wp, int Npad, int Kpad
 }  // namespace
 
 int launch_pack_bf16(int mode, const void* s0, const void* s1, const void* s2, int rows_each, int K, int Npad,
-                     int Kpad, void* dst, hipStream_t st) {
+                     int Kpad, void* dst, hipStream_t st, int rows_kv) {
+  if (rows_kv <= 0) rows_kv = rows_each;
   const size_t total = (size_t)(Npad / 32) * (Kpad / 16) * 64;
   const unsigned blocks = (unsigned)((total + 255) / 256);
   hipLaunchKernelGGL(k_pack_bf16, dim3(blocks), dim3(256), 0, st, mode, (const bf16_t*)s0, (const bf16_t*)s1,
-                     (const bf16_t*)s2, rows_each, K, Kpad / 16, total, (uint4*)dst);
+                     (const bf16_t*)s2, rows_each, rows_kv, K, Kpad / 16, total, (uint4*)dst);
   return goose_launch_status();
 }
 

@@ -71,9 +71,11 @@ void compute_layouts(goose_ctx* c) {
   PackedLayout& p = c->pl;
   p.g1 = off; off = round_up_sz(off + (size_t)d.hidden * es, A);
   p.g2 = off; off = round_up_sz(off + (size_t)d.hidden * es, A);
+  p.gq = off; off = round_up_sz(off + (size_t)d.head_dim * es, A);
+  p.gk = off; off = round_up_sz(off + (size_t)d.head_dim * es, A);
   if (d.dtype == GOOSE_DTYPE_BF16) {
     const size_t f32r = (size_t)round_up(d.ffn, 32);
-    p.wqkv = off; off = round_up_sz(off + (size_t)round_up(3 * c->Hq, 32) * c->Kh * 2, A);
+    p.wqkv = off; off = round_up_sz(off + (size_t)round_up(c->Hq + 2 * c->Hkv, 32) * c->Kh * 2, A);
     p.wo = off;   off = round_up_sz(off + (size_t)round_up(d.hidden, 32) * c->Kq * 2, A);
     p.wgu = off;  off = round_up_sz(off + 2 * f32r * c->Kh * 2, A);
     p.wd = off;   off = round_up_sz(off + (size_t)round_up(d.hidden, 32) * c->Fpad * 2, A);
@@ -167,10 +169,14 @@ int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** o
   if (d.dtype != GOOSE_DTYPE_BF16 && d.dtype != GOOSE_DTYPE_F32) return GOOSE_ERR_ARG;
   if (!(d.rope_base > 1.0f) || !(d.rms_eps >= 0.0f)) return GOOSE_ERR_ARG;
   if (d.head_dim % 8 != 0 || d.head_dim > 256) return GOOSE_ERR_SHAPE;
+  const int n_kv = d.n_kv_heads > 0 ? d.n_kv_heads : d.n_heads;
+  if (n_kv > d.n_heads || d.n_heads % n_kv != 0) return GOOSE_ERR_SHAPE;
   if (d.dtype == GOOSE_DTYPE_BF16) {
     // MFMA kernels: 16-byte vector access to rows, two head sizes
     if (d.head_dim != 64 && d.head_dim != 128) return GOOSE_ERR_SHAPE;
     if (d.hidden % 8 != 0 || d.ffn % 8 != 0) return GOOSE_ERR_SHAPE;
+  } else if (n_kv != d.n_heads || d.qk_norm) {
+    return GOOSE_ERR_SHAPE;  // the fp32 path is the plain multi-head model only
   }
   goose_ctx* c = new (std::nothrow) goose_ctx();
   if (!c) return GOOSE_ERR_ARG;
@@ -180,6 +186,8 @@ int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** o
   c->Bpad = max_B <= 32 ? 32 : (max_B <= 64 ? 64 : 128);
   c->cap = cap;
   c->Hq = d.n_heads * d.head_dim;
+  c->n_kv = n_kv;
+  c->Hkv = n_kv * d.head_dim;
   c->Kh = round_up(d.hidden, 128);
   c->Kq = round_up(c->Hq, 128);
   c->Fpad = round_up(d.ffn, 128);
@@ -189,7 +197,7 @@ int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** o
   compute_layouts(c);
 
   const size_t es = elem_size(d.dtype);
-  size_t widest = (size_t)round_up(3 * c->Hq, 32);
+  size_t widest = (size_t)round_up(c->Hq + 2 * c->Hkv, 32);
   if ((size_t)2 * c->Fpad > widest) widest = (size_t)2 * c->Fpad;
   if ((size_t)c->Kh > widest) widest = c->Kh;
   c->part_ld = widest;
@@ -255,8 +263,13 @@ int goose_pack_layer(goose_ctx* c, const goose_layer_weights* w, void* d_packed,
   GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.g1, w->g1, d.hidden * es, D2D, st));
   GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.g2, w->g2, d.hidden * es, D2D, st));
   if (d.dtype == GOOSE_DTYPE_BF16) {
-    int rc = launch_pack_bf16(PACK_QKV, w->wq, w->wk, w->wv, c->Hq, d.hidden, round_up(3 * c->Hq, 32), c->Kh,
-                              base + c->pl.wqkv, st);
+    if (d.qk_norm) {
+      if (!w->gq || !w->gk) return GOOSE_ERR_ARG;
+      GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.gq, w->gq, d.head_dim * elem_size(d.dtype), hipMemcpyDeviceToDevice, st));
+      GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.gk, w->gk, d.head_dim * elem_size(d.dtype), hipMemcpyDeviceToDevice, st));
+    }
+    int rc = launch_pack_bf16(PACK_QKV, w->wq, w->wk, w->wv, c->Hq, d.hidden, round_up(c->Hq + 2 * c->Hkv, 32), c->Kh,
+                              base + c->pl.wqkv, st, c->Hkv);
     if (rc) return rc;
     rc = launch_pack_bf16(PACK_PLAIN, w->wo, nullptr, nullptr, d.hidden, c->Hq, round_up(d.hidden, 32), c->Kq,
                           base + c->pl.wo, st);
@@ -329,7 +342,7 @@ static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, v
   if (rc) return rc;
 
   if (d.dtype == GOOSE_DTYPE_BF16) {
-    const int Nqkv = round_up(3 * Hq, 32), Nh = round_up(H, 32), Ngu = 2 * round_up(d.ffn, 32);
+    const int Nqkv = round_up(Hq + 2 * c->Hkv, 32), Nh = round_up(H, 32), Ngu = 2 * round_up(d.ffn, 32);
     static const int splits_env = env_int("GOOSE_ATTN_SPLITS", 0);
     const GemmCfg cq = gemm_cfg(c, "GOOSE_CFG_QKV", Nqkv, c->Kh);
     int ks = cq.ks;
@@ -342,8 +355,10 @@ static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, v
     int splits = splits_env > 0 ? splits_env : pick_attn_splits(d.n_heads, P + B, c->max_splits);
     if (splits > c->max_splits) splits = c->max_splits;
     { PROF(PK_ATTN);
-      rc = launch_attn_bf16(c->part, ks, pstride, c->part_ld, c->rope_cs, d_kcache, d_vcache, d.n_heads, d.head_dim,
-                            c->cap, dP, B, d_mask, splits, ng_env, c->att_o, c->att_ml, c->Bpad, c->o, c->Kq, st); }
+      rc = launch_attn_bf16(c->part, ks, pstride, c->part_ld, c->rope_cs, d_kcache, d_vcache, d.n_heads, c->n_kv,
+                            d.head_dim, c->cap, dP, B, d_mask, splits, ng_env, d.qk_norm ? w + c->pl.gq : nullptr,
+                            d.qk_norm ? w + c->pl.gk : nullptr, d.rms_eps, c->att_o, c->att_ml, c->Bpad, c->o,
+                            c->Kq, st); }
     if (rc) return rc;
     const GemmCfg co = gemm_cfg(c, "GOOSE_CFG_O", Nh, c->Kq);
     ks = co.ks;
@@ -504,7 +519,7 @@ int goose_compact_kv(goose_ctx* c, void* d_kcache_all, void* d_vcache_all, int P
   int rc = resolve_P(c, P, d_P, st, &dP);
   if (rc) return rc;
   const goose_model_desc& d = c->d;
-  return launch_compact((int)elem_size(d.dtype), d_kcache_all, d_vcache_all, d.n_layers, d.n_heads, c->cap,
+  return launch_compact((int)elem_size(d.dtype), d_kcache_all, d_vcache_all, d.n_layers, c->n_kv, c->cap,
                         d.head_dim, dP, d_path, d_accept_len, d_new_P_or_null, st);
 }
 
@@ -528,7 +543,7 @@ int goose_verify_step(goose_ctx* c, const goose_model_ptrs* m, const goose_step_
     rc = launch_rope_table(c->s_pos, c->inv_freq, B, d.head_dim, c->rope_cs, st);
     if (rc) return rc;
   }
-  const size_t layer_cache = (size_t)d.n_heads * c->cap * d.head_dim * elem_size(d.dtype);
+  const size_t layer_cache = (size_t)c->n_kv * c->cap * d.head_dim * elem_size(d.dtype);
   // each layer's closing residual add also writes the next normalisation's output
   for (int l = 0; l < d.n_layers; ++l) {
     const char* w = (const char*)m->d_packed_layers + (size_t)l * c->pl.total;
@@ -552,7 +567,7 @@ int goose_verify_step(goose_ctx* c, const goose_model_ptrs* m, const goose_step_
   rc = launch_accept(io->d_parent, io->d_tokens, io->d_is_spine, io->d_argmax, B, io->d_accept_len, io->d_path,
                      io->d_bonus, io->d_next_root_or_null, st);
   if (rc) return rc;
-  return launch_compact((int)elem_size(d.dtype), m->d_kcache_all, m->d_vcache_all, d.n_layers, d.n_heads, c->cap,
+  return launch_compact((int)elem_size(d.dtype), m->d_kcache_all, m->d_vcache_all, d.n_layers, c->n_kv, c->cap,
                         d.head_dim, io->d_P, io->d_path, io->d_accept_len, io->d_P, st);
 }
 

@@ -31,7 +31,7 @@ static inline size_t round_up_sz(size_t x, size_t m) { return (x + m - 1) / m * 
 
 // Byte offsets of the pieces of a packed layer / packed head blob.
 struct PackedLayout {
-  size_t g1, g2, wqkv, wo, wgu, wd, total;
+  size_t g1, g2, gq, gk, wqkv, wo, wgu, wd, total;
 };
 struct PackedHeadLayout {
   size_t gf, wlm, total;
@@ -45,6 +45,8 @@ struct goose_ctx {
   int Bpad;    // 32, 64 or 128: row count of every activation buffer
   int cap;     // cache slots per head
   int Hq;      // n_heads * head_dim
+  int n_kv;    // key/value heads
+  int Hkv;     // n_kv * head_dim
   int Fpad;    // ffn rounded up to 128 -- the K extent of the down projection
   int Kh;      // hidden rounded up to 128
   int Kq;      // Hq rounded up to 128
@@ -106,8 +108,9 @@ int launch_attn_f32(const float* q, int ldq, const float* kc, const float* vc, i
 // ---- bf16 path (gemm_bf16.hip, attn_bf16.hip)
 enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
 // Re-tiles raw [rows][K] bf16 matrices into MFMA-operand order; Npad x Kpad zero padded.
+// rows_each: rows of s0 (and of s1, s2 unless rows_kv > 0: then s1 and s2 have rows_kv rows each)
 int launch_pack_bf16(int mode, const void* s0, const void* s1, const void* s2, int rows_each, int K, int Npad,
-                     int Kpad, void* dst, hipStream_t st);
+                     int Kpad, void* dst, hipStream_t st, int rows_kv = 0);
 enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_TOP2 = 2 };
 // out partials f32 [ksplit][Bpad][ldo] (EPI_PARTIAL) or bf16 h [Bpad][ldo] (EPI_SWIGLU, ksplit must be 1)
 int launch_gemm_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw, int ksplit,
@@ -127,6 +130,7 @@ int launch_rope_table(const int32_t* pos, const double* inv_freq, int B, int hea
 // Fused rotary embedding + KV-tail write + tree attention.  part: the q|k|v projection as `ks`
 // split-K slices of f32 [Bpad][part_ld]; kc/vc: this layer's operand-ordered caches; o: bf16 [B][ldo].
 int launch_attn_bf16(const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs, void* kc, void* vc,
-                     int n_heads, int head_dim, int cap, const int32_t* dP, int B, const uint64_t* mask, int splits,
-                     int key_groups, float* att_o, float* att_ml, int Bpad, void* o, int ldo, hipStream_t st);
+                     int n_heads, int n_kv_heads, int head_dim, int cap, const int32_t* dP, int B,
+                     const uint64_t* mask, int splits, int key_groups, const void* gq, const void* gk, float eps,
+                     float* att_o, float* att_ml, int Bpad, void* o, int ldo, hipStream_t st);
 int pick_attn_splits(int n_heads, int keys_max, int max_splits);

@@ -42,12 +42,13 @@ class GooseModel:
         # One head's cache is cap * head_dim elements.  fp32 models: K[slot][d] and V transposed, Vt[d][slot];
         # bf16 models: 32-key blocks in MFMA operand order (layout.py), kept here as flat vectors.
         self.tiled = desc.dtype == "bf16"
+        kvh = desc.kv_heads  # caches hold key/value heads (fewer than query heads under grouped queries)
         if self.tiled:
-            self.kcache = torch.zeros((desc.n_layers, desc.n_heads, cap * desc.head_dim), dtype=self.dt, device=self.device)
+            self.kcache = torch.zeros((desc.n_layers, kvh, cap * desc.head_dim), dtype=self.dt, device=self.device)
             self.vcache = torch.zeros_like(self.kcache)
         else:
-            self.kcache = torch.zeros((desc.n_layers, desc.n_heads, cap, desc.head_dim), dtype=self.dt, device=self.device)
-            self.vcache = torch.zeros((desc.n_layers, desc.n_heads, desc.head_dim, cap), dtype=self.dt, device=self.device)
+            self.kcache = torch.zeros((desc.n_layers, kvh, cap, desc.head_dim), dtype=self.dt, device=self.device)
+            self.vcache = torch.zeros((desc.n_layers, kvh, desc.head_dim, cap), dtype=self.dt, device=self.device)
         self.P = 0
         i32 = dict(dtype=torch.int32, device=self.device)
         self.d_P = torch.zeros(1, **i32)

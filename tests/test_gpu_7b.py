@@ -203,12 +203,15 @@ def test_7b_hundred_cycles_walk_and_compaction_bit_exact():
     ("13b", 80, 320, gi.tree_spine_13b),
     ("33b", 80, 200, gi.tree_spine_33b),
     ("7b", 128, 450, gi.tree_spine_stress),
+    ("llama3_8b", 64, 333, lambda: gi.tree_spine_7b(1)),
+    ("qwen3_8b", 80, 250, gi.tree_spine_13b),
 ])
 def test_single_layer_of_the_larger_shapes(name, B, P0, tree_fn):
     """One decoder layer with the projection sizes of the larger models (and a small vocabulary),
     every output compared element by element."""
     full = gi.SHAPES[name]
-    shape = gi.ModelShape(f"{name}_1layer", 1, full.hidden, full.n_heads, full.head_dim, full.ffn, 4096)
+    import dataclasses
+    shape = dataclasses.replace(full, name=f"{name}_1layer", n_layers=1, vocab=4096)
     tm = torch_model(shape, seed=3, gain_jitter=0.1, device="cuda:0")
     tm = {k: ([{n: t.cpu() for n, t in lw.items()} for lw in v] if k == "layers" else v.cpu()) for k, v in tm.items()}
     om = oracle_model(shape, tm)

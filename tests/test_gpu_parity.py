@@ -160,7 +160,8 @@ def test_tiny_fp32_empty_prefix_and_big_trees():
     gm.ctx.close()
 
 
-@pytest.mark.parametrize("shape_name,P0,chunk", [("tiny_bf16", 128, 16), ("small_bf16", 200, 50)])
+@pytest.mark.parametrize("shape_name,P0,chunk", [("tiny_bf16", 128, 16), ("small_bf16", 200, 50),
+                                                 ("tiny_gqa_bf16", 100, 32), ("small_gqa_qknorm_bf16", 210, 70)])
 def test_bf16_cycles_match_the_oracle(shape_name, P0, chunk):
     """bf16 MFMA path; the oracle starts every cycle from the device's own stored cache bytes."""
     trees = [gi.tree_tiny_spine(), gi.tree_spine_7b(0), gi.tree_random(33, 4, spine_len=8), gi.tree_spine_13b(),
@@ -168,6 +169,7 @@ def test_bf16_cycles_match_the_oracle(shape_name, P0, chunk):
     _run_cycles(shape_name, 7, P0, trees, seed=2, oracle_prefill=False, chunk=chunk)
 
 
-def test_bf16_independent_prefill_stays_within_tolerance():
+@pytest.mark.parametrize("shape_name", ["small_bf16", "small_gqa_qknorm_bf16"])
+def test_bf16_independent_prefill_stays_within_tolerance(shape_name):
     trees = [gi.tree_spine_7b(3), gi.tree_tiny_spine()]
-    _run_cycles("small_bf16", 2, 96, trees, seed=5, oracle_prefill=True, chunk=32)
+    _run_cycles(shape_name, 2, 96, trees, seed=5, oracle_prefill=True, chunk=32)
