@@ -504,14 +504,15 @@ int launch_rope_table(const int32_t* pos, const double* inv_freq, int B, int hea
 }
 
 // Key splits per head for a pass over `keys_max` keys: about two 32-key blocks per wavefront
-// (4 key groups per workgroup); fewer, longer splits measured better than more, shorter ones
-// (every split adds a partial result and a workgroup's fixed cost), more are needed only to
-// spread long prefixes over the chip.
+// (4 key groups per workgroup), but never more workgroups than compute units.  Measured: a
+// workgroup's fixed cost (projection slices, rotation, merge) and its LDS footprint (one or two
+// workgroups per compute unit) make a second round of workgroups cost more than longer splits
+// -- 7B P=16384 B=128: 93 us at 8 splits, 143 us at 32; 33B P=4096: 56 us at 4, 88 us at 17.
 int pick_attn_splits(int n_heads, int keys_max, int max_splits) {
   const int blocks = (keys_max + 31) / 32;
   int s = (blocks + 7) / 8;
-  const int want = (1024 + n_heads - 1) / n_heads;
-  if (s > want) s = want;
+  const int fit = 256 / n_heads;
+  if (s > fit) s = fit;
   if (s > max_splits) s = max_splits;
   if (s < 1) s = 1;
   return s;
