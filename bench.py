@@ -100,6 +100,10 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--harvest", type=int, default=0, metavar="K",
                     help="also harvest every cycle's logits into [vocab][K] successor tables (not part of the headline step)")
+    ap.add_argument("--requests", type=int, default=1, metavar="N",
+                    help="N requests with trees of --request-budget nodes verified per step in one pass "
+                         "(goose_verify_step_batched), timed beside the same requests verified one after the other")
+    ap.add_argument("--request-budget", type=int, default=32)
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch the library's 256 MiB copy kernel (calibrates profiler traffic counters)")
     args = ap.parse_args()
@@ -128,6 +132,9 @@ def main():
 
     def log(msg):
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+    if args.requests > 1:
+        return bench_batched(args, shape, P0, K, W, log)
 
     t0 = time.time()
     gm = GooseModel(ModelDesc.from_shape(shape), B, cap,
@@ -324,6 +331,112 @@ def main():
         "algorithmic_GB_per_step": round(bytes_timed / K / 1e9, 3),
         "roofline": roofline, "cpu_baseline": cpu, "kernels_avg_us": kernels,
     }
+    print(json.dumps(out), flush=True)
+
+
+def bench_batched(args, shape, P0, K, W, log):
+    """Cross-request batched verification (the batch sweep of App. D): N requests, each with its own KV
+    cache (prefix P0) and a tree of `request_budget` nodes with random draft tokens, share one pass
+    over the weights per step.  Timed as one HIP graph per step, beside the same requests verified one
+    after the other through goose_verify_step.  Prints one JSON line; value = request-steps/s."""
+    import torch
+    import goose_inputs as gi
+    from paper_2604_02047_amd import ModelDesc
+    from paper_2604_02047_amd.runner import GooseModel
+
+    dev = torch.device("cuda:0")
+    n, Br = args.requests, args.request_budget
+    rows = n * ((Br + 31) // 32 * 32)
+    total = K + W
+    cap = (P0 + 2 * total * 2 + 2 * Br + 63) // 64 * 64   # random drafts: a request grows by about one slot per step
+    P_max = cap - Br
+    gm = GooseModel(ModelDesc.from_shape(shape), rows, cap, lambda l: gi.layer_weights(shape, args.seed, l, dev),
+                    gi.embedding(shape, args.seed, dev), gi.lm_head(shape, args.seed, dev),
+                    gi.final_norm(shape, args.seed, dev))
+    i32 = dict(dtype=torch.int32, device=dev)
+    reqs = []
+    for r in range(n):
+        kc, vc = torch.zeros_like(gm.kcache), torch.zeros_like(gm.vcache)
+        gm.kcache, gm.vcache = kc, vc
+        gm.set_P(0)
+        prefix = gi.prefix_tokens(args.seed + 31 * r, P0, shape.vocab)
+        done = 0
+        while done < P0:
+            m = min(rows, P0 - done)
+            ch = gi.tree_chain(m)
+            out = gm.verify_step_calls(prefix[done:done + m], ch.parent, ch.is_spine, commit=False)
+            done += m
+            gm.set_P(done)
+        tree = gi.tree_random(Br, seed=r, spine_len=min(8, Br - 1))
+        tokens = gi.draft_tokens_uniform(args.seed + r, tree.parent, shape.vocab, int(out["argmax"][m - 1].item()))
+        t, p, s = gm.stage_tree(tokens, tree.parent, tree.is_spine)
+        reqs.append({"tokens": t.clone(), "parent": p.clone(), "is_spine": s.clone(), "B": Br, "P_max": P_max,
+                     "kcache": kc, "vcache": vc, "P": torch.full((1,), P0, **i32), "accept_len": torch.zeros(1, **i32),
+                     "path": torch.zeros(rows, **i32), "bonus": torch.zeros(1, **i32),
+                     "next_root": torch.zeros(1, **i32)})
+    log(f"{n} requests prefilled to P={P0}, {Br} nodes each ({rows} rows per pass)")
+    argmax_all = torch.zeros(rows, **i32)
+
+    def batched():
+        gm.ctx.goose_verify_step_batched(gm.model_ptrs(), reqs, argmax_all)
+        for q in reqs:
+            q["tokens"][0:1].copy_(q["next_root"])
+
+    def one_by_one():
+        for q in reqs:
+            gm.kcache, gm.vcache = q["kcache"], q["vcache"]
+            gm.ctx.goose_verify_step(gm.model_ptrs(), {
+                "tokens": q["tokens"], "parent": q["parent"], "is_spine": q["is_spine"], "P": q["P"],
+                "argmax": argmax_all, "accept_len": q["accept_len"], "path": q["path"], "bonus": q["bonus"],
+                "next_root": q["next_root"], "logits": None, "margin": None, "succ_ids": None, "succ_scores": None,
+                "harvest_k": 0}, Br, P_max)
+            q["tokens"][0:1].copy_(q["next_root"])
+
+    def timed(fn):
+        for q in reqs:
+            q["P"].fill_(P0)
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            fn()
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            fn()
+        torch.cuda.synchronize()
+        for q in reqs:
+            q["P"].fill_(P0)
+        for _ in range(W):
+            g.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(K):
+            g.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t1
+        P_end = [int(q["P"].item()) for q in reqs]
+        assert max(P_end) <= P_max, (P_end, P_max)
+        return dt, P_end
+
+    dt_b, P_b = timed(batched)
+    dt_s, P_s = timed(one_by_one)
+    if P_b != P_s:
+        log(f"ERROR: batched run ended at P={P_b}, one-by-one at P={P_s}")
+        sys.exit(4)
+    es = 2
+    w_bytes = (shape.n_layers * shape.layer_param_count() + shape.vocab * shape.hidden) * es
+    kv_bytes = n * shape.n_layers * 2 * shape.kv_dim * es * (P0 + (sum(P_b) / n - P0) / 2 + 2 * Br)
+    out = {"metric": f"batched tree-verify request-steps/s, {args.workload}, {n} requests x {Br} nodes",
+           "value": round(n * K / dt_b, 2), "unit": "request-steps/s", "n_gpus": 1, "steps": K, "warmup": W,
+           "ms_per_step": round(dt_b / K * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": shape.dtype, "data": "synthetic",
+           "config": {"workload": args.workload, "shape": shape.name, "requests": n, "B_per_request": Br,
+                      "rows_per_pass": rows, "P0": P0, "P_end": P_b, "drafts": "random", "launch": "hipGraph per step"},
+           "one_by_one_ms_per_step": round(dt_s / K * 1e3, 4), "speedup_over_one_by_one": round(dt_s / dt_b, 3),
+           "draft_tokens_verified_per_s": round(n * Br * K / dt_b, 1),
+           "achieved_GBps": round((w_bytes + kv_bytes) / (dt_b / K) / 1e9, 1),
+           "hbm_frac": round((w_bytes + kv_bytes) / (dt_b / K) / 1e9 / HBM_PEAK_GBPS, 4)}
     print(json.dumps(out), flush=True)
 
 

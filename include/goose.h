@@ -203,6 +203,32 @@ typedef struct {
 int goose_verify_step(goose_ctx* ctx, const goose_model_ptrs* model, const goose_step_io* io, int B, int P_max,
                       void* stream);
 
+/* ---- 6b. several requests in one pass (the batch sweep of App. D: trees of different requests share
+ * every weight read; masks, positions, caches and cache lengths stay per request) ---------------
+ * The rows of the requests are stacked, each request starting at a multiple of 32 rows; the sum of
+ * the rounded-up B must not exceed round_up(max_B, 32).  Projections, norms and the LM head run once
+ * over all rows; attention, walk and compaction run per request on its own caches.  bf16 models only.
+ * d_argmax_all: int32 [round_up(max_B,32)], receives every row's prediction (request r's rows start
+ * at the sum of round_up(B, 32) of the requests before it).  All pointers DEVICE; P of a request is
+ * read from *d_P (P_max: host upper bound, as in goose_verify_step) and updated in place. */
+#define GOOSE_MAX_REQUESTS 16
+typedef struct {
+  const int32_t* d_tokens;   /* [B] */
+  const int32_t* d_parent;   /* [B] */
+  const uint8_t* d_is_spine; /* [B] or NULL */
+  int32_t B;
+  int32_t P_max;
+  void* d_kcache_all;        /* this request's caches, all layers */
+  void* d_vcache_all;
+  int32_t* d_P;              /* [1] in/out */
+  int32_t* d_accept_len;     /* [1] out */
+  int32_t* d_path;           /* [B] out */
+  int32_t* d_bonus;          /* [1] out */
+  int32_t* d_next_root_or_null;
+} goose_request;
+int goose_verify_step_batched(goose_ctx* ctx, const goose_model_ptrs* model, const goose_request* reqs, int n_req,
+                              int32_t* d_argmax_all, void* stream);
+
 /* ---- 7. logit harvest (Sec. 4 stage 2 "verify and harvest"; App. C "adjacency table", tier 1, and
  * "logit harvesting"; Alg. "Decoding Loop", the update of the table from all logits of a cycle) ----
  * For every node i < B -- accepted or not -- row d_tokens[i] of the two dense successor tables

@@ -21,7 +21,7 @@ EXPORTS = [
     "goose_profile_enable", "goose_profile_kinds", "goose_profile_kind_name", "goose_profile_read",
     "goose_copy_probe", "goose_harvest_topk",
     "goose_context_match", "goose_spine_budget", "goose_build_spine_tree", "goose_spine_ratio_tier", "goose_ema_update",
-    "goose_cycle_mode",
+    "goose_cycle_mode", "goose_verify_step_batched",
 ]
 
 GOOSE_DTYPE_BF16, GOOSE_DTYPE_F32 = 0, 1
@@ -53,6 +53,13 @@ class _StepIO(C.Structure):
                                           "d_path", "d_bonus", "d_next_root_or_null", "d_logits_or_null",
                                           "d_margin_or_null", "d_succ_ids_or_null", "d_succ_scores_or_null")] + \
                [("harvest_k", C.c_int32)]
+
+
+class _Request(C.Structure):
+    _fields_ = [("d_tokens", C.c_void_p), ("d_parent", C.c_void_p), ("d_is_spine", C.c_void_p), ("B", C.c_int32),
+                ("P_max", C.c_int32), ("d_kcache_all", C.c_void_p), ("d_vcache_all", C.c_void_p), ("d_P", C.c_void_p),
+                ("d_accept_len", C.c_void_p), ("d_path", C.c_void_p), ("d_bonus", C.c_void_p),
+                ("d_next_root_or_null", C.c_void_p)]
 
 
 @dataclass
@@ -123,6 +130,8 @@ def load_library():
     lib.goose_verify_step.argtypes = [C.c_void_p, C.POINTER(_ModelPtrs), C.POINTER(_StepIO), C.c_int, C.c_int,
                                       C.c_void_p]
     lib.goose_device_flags.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
+    lib.goose_verify_step_batched.argtypes = [C.c_void_p, C.POINTER(_ModelPtrs), C.POINTER(_Request), C.c_int,
+                                              C.c_void_p, C.c_void_p]
     lib.goose_packed_matrix_bytes.argtypes = [C.c_int, C.c_int]
     lib.goose_packed_matrix_bytes.restype = C.c_size_t
     lib.goose_pack_matrix.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
@@ -336,6 +345,21 @@ class GooseContext:
         s = _StepIO(*[(io[n].data_ptr() if io.get(n) is not None else None) for n in names],
                     int(io.get("harvest_k") or 0))
         _check(self.lib.goose_verify_step(self._h, C.byref(m), C.byref(s), B, P_max, _stream()), "goose_verify_step")
+
+    def goose_verify_step_batched(self, model: dict, requests: list, argmax_all):
+        """requests: dicts with tokens, parent, is_spine (or None), B, P_max, kcache, vcache, P, accept_len, path,
+        bonus, next_root (or None) -- device tensors / ints."""
+        m = _ModelPtrs(model["embed"].data_ptr(), model["packed_layers"].data_ptr(), model["packed_head"].data_ptr(),
+                       None, None)
+        arr = (_Request * len(requests))()
+        for i, q in enumerate(requests):
+            def p(name):
+                t = q.get(name)
+                return None if t is None else t.data_ptr()
+            arr[i] = _Request(p("tokens"), p("parent"), p("is_spine"), int(q["B"]), int(q["P_max"]), p("kcache"),
+                              p("vcache"), p("P"), p("accept_len"), p("path"), p("bonus"), p("next_root"))
+        _check(self.lib.goose_verify_step_batched(self._h, C.byref(m), arr, len(requests), _ptr(argmax_all),
+                                                  _stream()), "goose_verify_step_batched")
 
     def goose_device_flags(self) -> int:
         out = C.c_int32(0)

@@ -56,13 +56,30 @@ __device__ inline size_t v_elem_off(int g, int c) {
          (kk & 7);
 }
 
+// what the kernels need of one request (see AttnSeg); the table travels as a kernel argument
+struct SegDev {
+  int32_t row0, B;
+  bf16_t* kc;
+  bf16_t* vc;
+  const int32_t* dP;
+  const uint64_t* mask;
+};
+struct SegTable { SegDev s[ATTN_MAX_SEGS]; };
+
 template <int D, int NG, int NQH>
 __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
-    const float* __restrict__ part, int ks, size_t part_stride, size_t part_ld, int n_heads, int n_kv_heads,
-    const float2* __restrict__ cs, bf16_t* __restrict__ kc, bf16_t* __restrict__ vc, int cap,
-    const int32_t* __restrict__ dP, int B, const uint64_t* __restrict__ mask, const bf16_t* __restrict__ gq,
-    const bf16_t* __restrict__ gk, float eps, float* __restrict__ att_o, float* __restrict__ att_ml, int Bpad,
-    bf16_t* __restrict__ o_out, int ldo) {
+    const float* part, int ks, size_t part_stride, size_t part_ld, int n_heads, int n_kv_heads, const float2* cs,
+    int cap, const bf16_t* __restrict__ gq, const bf16_t* __restrict__ gk, float eps, float* __restrict__ att_o,
+    float* __restrict__ att_ml, int Bpad, bf16_t* o_out, int ldo, const SegTable segs) {
+  // this workgroup's request: its rows of the stacked buffers, its caches, length and mask
+  const SegDev& sg = segs.s[blockIdx.z];
+  const int B = sg.B, row0 = sg.row0;
+  bf16_t* const kc = sg.kc;
+  bf16_t* const vc = sg.vc;
+  const uint64_t* const mask = sg.mask;
+  part += (size_t)row0 * part_ld;
+  cs += (size_t)row0 * (D / 2);
+  o_out += (size_t)row0 * ldo;
   constexpr int NTHR = 64 * NG * NQH;
   constexpr int NS = D / 16;               // operand loads (1 KiB pieces) per block, for K and for V
   constexpr int TROWS = NQH * 32;          // tree rows the LDS buffers hold (>= B for this instantiation)
@@ -87,7 +104,7 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   const int Hq = n_heads * D, Hkv = n_kv_heads * D;
   const int kcol = Hq + kvh * D - h * D, vcol = kcol + Hkv;  // relative to this head's q columns
   const bool tail_writer = (h % group) == 0;                  // one head of the group stores the tree's K/V
-  int P = *dP;
+  int P = *sg.dP;
   if (P > cap - B) P = cap - B;  // callers guarantee P + B <= cap; never index outside the cache
   if (P < 0) P = 0;
   const bool last = split == nsplit - 1;
@@ -428,7 +445,7 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
         *reinterpret_cast<bf16x4*>(orow + dt * 32 + a * 8 + hh * 4) = v;
       }
   } else {
-    const size_t base = ((size_t)h * nsplit + split) * Bpad + qi;
+    const size_t base = ((size_t)h * nsplit + split) * Bpad + row0 + qi;
     if (hh == 0) {
       att_ml[base * 2] = m_run;
       att_ml[base * 2 + 1] = l_tot;
@@ -446,8 +463,10 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
 
 // o[q][h*D + c] = sum_s 2^(m_s - m) O_s[c] / sum_s 2^(m_s - m) l_s, splits taken in index order.
 __global__ void k_attn_merge(const float* __restrict__ att_o, const float* __restrict__ att_ml, int nsplit, int Bpad,
-                             int D, bf16_t* __restrict__ o, int ldo) {
-  const int qi = blockIdx.x, h = blockIdx.y, c = threadIdx.x;
+                             int D, bf16_t* __restrict__ o, int ldo, const SegTable segs) {
+  const SegDev& sg = segs.s[blockIdx.z];
+  if ((int)blockIdx.x >= sg.B) return;
+  const int qi = sg.row0 + blockIdx.x, h = blockIdx.y, c = threadIdx.x;
   float mmax = NEG_BIG;
   for (int s = 0; s < nsplit; ++s) mmax = fmaxf(mmax, att_ml[(((size_t)h * nsplit + s) * Bpad + qi) * 2]);
   float num = 0.f, den = 0.f;
@@ -475,25 +494,24 @@ __global__ void k_rope_table(const int32_t* __restrict__ pos, const double* __re
 
 struct AttnArgs {
   const float* part; int ks; size_t part_stride, part_ld; int n_heads, n_kv;
-  const float2* cs; bf16_t* kc; bf16_t* vc; int cap; const int32_t* dP; int B; const uint64_t* mask;
-  const bf16_t* gq; const bf16_t* gk; float eps;
+  const float2* cs; int cap; const bf16_t* gq; const bf16_t* gk; float eps;
   float* att_o; float* att_ml; int Bpad; bf16_t* o; int ldo;
 };
 
 template <int D, int NG, int NQH>
-int launch_cfg(dim3 grid, hipStream_t st, const AttnArgs& a) {
+int launch_cfg(dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable& t) {
   hipLaunchKernelGGL((k_attn_fused<D, NG, NQH>), grid, dim3(64 * NG * NQH), 0, st, a.part, a.ks, a.part_stride,
-                     a.part_ld, a.n_heads, a.n_kv, a.cs, a.kc, a.vc, a.cap, a.dP, a.B, a.mask, a.gq, a.gk, a.eps,
-                     a.att_o, a.att_ml, a.Bpad, a.o, a.ldo);
+                     a.part_ld, a.n_heads, a.n_kv, a.cs, a.cap, a.gq, a.gk, a.eps, a.att_o, a.att_ml, a.Bpad, a.o,
+                     a.ldo, t);
   return goose_launch_status();
 }
 
 template <int D>
-int launch_d(int QT, int ng, dim3 grid, hipStream_t st, const AttnArgs& a) {
+int launch_d(int QT, int ng, dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable& t) {
   // one wavefront per (query tile, key group); at most 8 wavefronts per workgroup
-  if (QT == 1) return ng == 4 ? launch_cfg<D, 4, 1>(grid, st, a) : launch_cfg<D, 2, 1>(grid, st, a);
-  if (QT == 2) return ng == 4 ? launch_cfg<D, 4, 2>(grid, st, a) : launch_cfg<D, 2, 2>(grid, st, a);
-  return launch_cfg<D, 2, 4>(grid, st, a);
+  if (QT == 1) return ng == 4 ? launch_cfg<D, 4, 1>(grid, st, a, t) : launch_cfg<D, 2, 1>(grid, st, a, t);
+  if (QT == 2) return ng == 4 ? launch_cfg<D, 4, 2>(grid, st, a, t) : launch_cfg<D, 2, 2>(grid, st, a, t);
+  return launch_cfg<D, 2, 4>(grid, st, a, t);
 }
 
 }  // namespace
@@ -518,24 +536,46 @@ int pick_attn_splits(int n_heads, int keys_max, int max_splits) {
   return s;
 }
 
-int launch_attn_bf16(const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs, void* kc, void* vc,
-                     int n_heads, int n_kv_heads, int head_dim, int cap, const int32_t* dP, int B,
-                     const uint64_t* mask, int splits, int key_groups, const void* gq, const void* gk, float eps,
-                     float* att_o, float* att_ml, int Bpad, void* o, int ldo, hipStream_t st) {
+int launch_attn_bf16(const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs, int n_heads,
+                     int n_kv_heads, int head_dim, int cap, const AttnSeg* segs, int nseg, int splits_or_0,
+                     int max_splits, int key_groups, const void* gq, const void* gk, float eps, float* att_o,
+                     float* att_ml, int Bpad, void* o, int ldo, hipStream_t st) {
   if (n_kv_heads < 1 || n_heads % n_kv_heads != 0 || (gq == nullptr) != (gk == nullptr)) return GOOSE_ERR_ARG;
-  const int QT = (B + 31) / 32;
-  // a 3-tile tree runs the 4-tile kernel, which reads projection rows up to 128 (the workspace has them)
-  if ((QT >= 3 ? 4 : QT) * 32 > Bpad || B > GOOSE_MAX_B || (cap & 31)) return GOOSE_ERR_ARG;
-  if (splits < 1 || (key_groups != 2 && key_groups != 4)) return GOOSE_ERR_ARG;
-  AttnArgs a{part, ks, part_stride, part_ld, n_heads, n_kv_heads, (const float2*)cs, (bf16_t*)kc, (bf16_t*)vc, cap,
-             dP, B, mask, (const bf16_t*)gq, (const bf16_t*)gk, eps, att_o, att_ml, Bpad, (bf16_t*)o, ldo};
-  dim3 grid(splits, n_heads);
-  int rc;
-  if (head_dim == 128) rc = launch_d<128>(QT, key_groups, grid, st, a);
-  else if (head_dim == 64) rc = launch_d<64>(QT, key_groups, grid, st, a);
-  else return GOOSE_ERR_SHAPE;
-  if (rc != GOOSE_OK || splits == 1) return rc;
-  hipLaunchKernelGGL(k_attn_merge, dim3(B, n_heads), dim3(head_dim), 0, st, att_o, att_ml, splits, Bpad, head_dim,
-                     (bf16_t*)o, ldo);
-  return goose_launch_status();
+  if (nseg < 1 || nseg > ATTN_MAX_SEGS || max_splits < 1 || (key_groups != 2 && key_groups != 4) || (cap & 31))
+    return GOOSE_ERR_ARG;
+  if (head_dim != 128 && head_dim != 64) return GOOSE_ERR_SHAPE;
+  const AttnArgs a{part, ks, part_stride, part_ld, n_heads, n_kv_heads, (const float2*)cs, cap, (const bf16_t*)gq,
+                   (const bf16_t*)gk, eps, att_o, att_ml, Bpad, (bf16_t*)o, ldo};
+  // a 3-tile tree runs the 4-tile kernel, which reads projection rows up to row0 + 128
+  auto tiles_of = [](int B) { const int qt = (B + 31) / 32; return qt >= 3 ? 4 : qt; };
+  for (int r = 0; r < nseg; ++r) {
+    const AttnSeg& g = segs[r];
+    if (g.B < 1 || g.B > GOOSE_MAX_B || g.row0 < 0 || (g.row0 & 31) || g.row0 + tiles_of(g.B) * 32 > Bpad ||
+        g.P_max < 0 || g.P_max + g.B > cap || !g.kc || !g.vc || !g.dP || !g.mask)
+      return GOOSE_ERR_ARG;
+  }
+  // one launch per class of tree size (1, 2, or 3-4 query tiles): the class fixes the workgroup shape
+  for (int cls : {1, 2, 4}) {
+    SegTable t{};
+    int n = 0, keys_max = 0, b_max = 0;
+    for (int r = 0; r < nseg; ++r) {
+      const AttnSeg& g = segs[r];
+      if (tiles_of(g.B) != cls) continue;
+      t.s[n++] = SegDev{g.row0, g.B, (bf16_t*)g.kc, (bf16_t*)g.vc, g.dP, g.mask};
+      keys_max = g.P_max + g.B > keys_max ? g.P_max + g.B : keys_max;
+      b_max = g.B > b_max ? g.B : b_max;
+    }
+    if (n == 0) continue;
+    int splits = splits_or_0 > 0 ? splits_or_0 : pick_attn_splits(n_heads * n, keys_max, max_splits);
+    if (splits > max_splits) splits = max_splits;
+    const dim3 grid(splits, n_heads, n);
+    int rc = head_dim == 128 ? launch_d<128>(cls, key_groups, grid, st, a, t) : launch_d<64>(cls, key_groups, grid, st, a, t);
+    if (rc != GOOSE_OK) return rc;
+    if (splits == 1) continue;
+    hipLaunchKernelGGL(k_attn_merge, dim3(b_max, n_heads, n), dim3(head_dim), 0, st, att_o, att_ml, splits, Bpad,
+                       head_dim, (bf16_t*)o, ldo, t);
+    rc = goose_launch_status();
+    if (rc != GOOSE_OK) return rc;
+  }
+  return GOOSE_OK;
 }

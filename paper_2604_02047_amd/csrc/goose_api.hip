@@ -326,9 +326,13 @@ int goose_embed(goose_ctx* c, const void* d_embed, const int32_t* d_tokens, int 
 // One decoder layer.  `xhat_ready`: the operand buffer already holds RMSNorm(x)*g1 (the previous
 // layer's closing kernel wrote it).  `g_next`: gain of the normalisation that follows this layer
 // (the next layer's g1 or the final norm), folded into the closing residual add; null to skip.
+// A batch of requests shares every projection (their rows are stacked, each request starting at a
+// multiple of 32 rows); in the attention every request is a slice of the grid with its own caches,
+// mask and length (`segs`; none = the single request given by the plain arguments).
+static_assert(GOOSE_MAX_REQUESTS <= ATTN_MAX_SEGS, "a batch must fit the attention's request table");
 static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, void* d_vcache, int P,
                       const int32_t* dP, int B, const uint64_t* d_mask, const int32_t* d_pos, hipStream_t st,
-                      bool xhat_ready, const void* g_next) {
+                      bool xhat_ready, const void* g_next, const AttnSeg* segs = nullptr, int nseg = 0) {
   int rc = GOOSE_OK;
   const goose_model_desc& d = c->d;
   const size_t pstride = (size_t)c->Bpad * c->part_ld;
@@ -352,13 +356,13 @@ static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, v
     if (rc) return rc;
     // rotary embedding of q and k, KV rows of the tree into the cache, tree attention: one kernel
     static const int ng_env = env_int("GOOSE_ATTN_NG", 4) == 2 ? 2 : 4;
-    int splits = splits_env > 0 ? splits_env : pick_attn_splits(d.n_heads, P + B, c->max_splits);
-    if (splits > c->max_splits) splits = c->max_splits;
+    const AttnSeg whole{0, B, P, d_kcache, d_vcache, dP, d_mask};
+    if (nseg == 0) { segs = &whole; nseg = 1; }
     { PROF(PK_ATTN);
-      rc = launch_attn_bf16(c->part, ks, pstride, c->part_ld, c->rope_cs, d_kcache, d_vcache, d.n_heads, c->n_kv,
-                            d.head_dim, c->cap, dP, B, d_mask, splits, ng_env, d.qk_norm ? w + c->pl.gq : nullptr,
-                            d.qk_norm ? w + c->pl.gk : nullptr, d.rms_eps, c->att_o, c->att_ml, c->Bpad, c->o,
-                            c->Kq, st); }
+      rc = launch_attn_bf16(c->part, ks, pstride, c->part_ld, c->rope_cs, d.n_heads, c->n_kv, d.head_dim, c->cap, segs,
+                            nseg, splits_env, c->max_splits, ng_env, d.qk_norm ? w + c->pl.gq : nullptr,
+                            d.qk_norm ? w + c->pl.gk : nullptr, d.rms_eps, c->att_o, c->att_ml, c->Bpad, c->o, c->Kq,
+                            st); }
     if (rc) return rc;
     const GemmCfg co = gemm_cfg(c, "GOOSE_CFG_O", Nh, c->Kq);
     ks = co.ks;
@@ -387,7 +391,8 @@ static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, v
                              g_next ? c->xn : nullptr, g_next ? c->Kh : 0, B, st);
   }
 
-  // fp32 storage: plain kernels
+  // fp32 storage: plain kernels (one request)
+  if (nseg > 1) return GOOSE_ERR_SHAPE;
   const float* xn = (const float*)c->xn;
   rc = launch_gemm_f32(xn, c->Kh, (const float*)(w + c->pl.wqkv), 3 * Hq, H, B, c->part, c->part_ld, st);
   if (rc) return rc;
@@ -569,6 +574,65 @@ int goose_verify_step(goose_ctx* c, const goose_model_ptrs* m, const goose_step_
   if (rc) return rc;
   return launch_compact((int)elem_size(d.dtype), m->d_kcache_all, m->d_vcache_all, d.n_layers, c->n_kv, c->cap,
                         d.head_dim, io->d_P, io->d_path, io->d_accept_len, io->d_P, st);
+}
+
+int goose_verify_step_batched(goose_ctx* c, const goose_model_ptrs* m, const goose_request* reqs, int n_req,
+                              int32_t* d_argmax_all, void* stream) {
+  if (!c || !m || !reqs || !d_argmax_all || n_req < 1 || n_req > GOOSE_MAX_REQUESTS) return GOOSE_ERR_ARG;
+  if (!m->d_embed || !m->d_packed_layers || !m->d_packed_head) return GOOSE_ERR_ARG;
+  const goose_model_desc& d = c->d;
+  if (d.dtype != GOOSE_DTYPE_BF16) return GOOSE_ERR_SHAPE;
+  hipStream_t st = as_stream(stream);
+  AttnSeg segs[GOOSE_MAX_REQUESTS];
+  int rows = 0;
+  for (int r = 0; r < n_req; ++r) {
+    const goose_request& q = reqs[r];
+    int rc = check_tree_args(c, q.B, q.P_max);
+    if (rc) return rc;
+    if (!q.d_tokens || !q.d_parent || !q.d_P || !q.d_kcache_all || !q.d_vcache_all || !q.d_accept_len || !q.d_path ||
+        !q.d_bonus)
+      return GOOSE_ERR_ARG;
+    segs[r] = AttnSeg{rows, q.B, q.P_max, nullptr, nullptr, q.d_P, c->s_mask + (size_t)rows * 2};
+    rows += round_up(q.B, 32);
+  }
+  if (rows > c->Bpad || rows > round_up(c->max_B, 32)) return GOOSE_ERR_CAPACITY;
+  int rc;
+  for (int r = 0; r < n_req; ++r) {
+    const goose_request& q = reqs[r];
+    const int row0 = segs[r].row0;
+    rc = launch_build_mask(q.d_parent, q.B, q.d_P, c->s_mask + (size_t)row0 * 2, c->s_depth + row0, c->s_pos + row0,
+                           c->flags, st);
+    if (rc) return rc;
+    rc = launch_embed(d.dtype, m->d_embed, q.d_tokens, q.B, d.hidden, d.vocab, c->s_x + (size_t)row0 * d.hidden, st);
+    if (rc) return rc;
+  }
+  // rows between requests keep stale (finite) values: they ride through the projections unused
+  rc = launch_rope_table(c->s_pos, c->inv_freq, rows, d.head_dim, c->rope_cs, st);
+  if (rc) return rc;
+  const size_t layer_cache = (size_t)c->n_kv * c->cap * d.head_dim * elem_size(d.dtype);
+  for (int l = 0; l < d.n_layers; ++l) {
+    const char* w = (const char*)m->d_packed_layers + (size_t)l * c->pl.total;
+    const void* g_next = (l + 1 < d.n_layers) ? (const void*)(w + c->pl.total + c->pl.g1)
+                                              : (const void*)((const char*)m->d_packed_head + c->ph.gf);
+    for (int r = 0; r < n_req; ++r) {
+      segs[r].kc = (char*)reqs[r].d_kcache_all + l * layer_cache;
+      segs[r].vc = (char*)reqs[r].d_vcache_all + l * layer_cache;
+    }
+    rc = layer_impl(c, w, c->s_x, nullptr, nullptr, 0, nullptr, rows, nullptr, c->s_pos, st, l > 0, g_next, segs, n_req);
+    if (rc) return rc;
+  }
+  rc = lm_head_impl(c, m->d_packed_head, c->s_x, rows, d_argmax_all, nullptr, nullptr, st, true, HarvestArgs());
+  if (rc) return rc;
+  for (int r = 0; r < n_req; ++r) {
+    const goose_request& q = reqs[r];
+    rc = launch_accept(q.d_parent, q.d_tokens, q.d_is_spine, d_argmax_all + segs[r].row0, q.B, q.d_accept_len, q.d_path,
+                       q.d_bonus, q.d_next_root_or_null, st);
+    if (rc) return rc;
+    rc = launch_compact((int)elem_size(d.dtype), q.d_kcache_all, q.d_vcache_all, d.n_layers, c->n_kv, c->cap,
+                        d.head_dim, q.d_P, q.d_path, q.d_accept_len, q.d_P, st);
+    if (rc) return rc;
+  }
+  return GOOSE_OK;
 }
 
 int goose_device_flags(goose_ctx* c, void* stream, int32_t* h_flags_out) {

@@ -127,10 +127,23 @@ int launch_argmax_top2(const void* top2, int n_groups, int B, int32_t* argmax, f
 void pick_gemm_config(int Npad, int Kpad, int max_ksplit, int* nw_out, int* ksplit_out);
 // (cos, sin) of every node's rotary angles: cs is float2 [B][head_dim/2].
 int launch_rope_table(const int32_t* pos, const double* inv_freq, int B, int head_dim, void* cs, hipStream_t st);
-// Fused rotary embedding + KV-tail write + tree attention.  part: the q|k|v projection as `ks`
-// split-K slices of f32 [Bpad][part_ld]; kc/vc: this layer's operand-ordered caches; o: bf16 [B][ldo].
-int launch_attn_bf16(const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs, void* kc, void* vc,
-                     int n_heads, int n_kv_heads, int head_dim, int cap, const int32_t* dP, int B,
-                     const uint64_t* mask, int splits, int key_groups, const void* gq, const void* gk, float eps,
-                     float* att_o, float* att_ml, int Bpad, void* o, int ldo, hipStream_t st);
+// One request's share of an attention launch: its rows [row0, row0 + B) of the stacked projections,
+// this layer's operand-ordered caches, its cache length and its ancestor bitmask (words per row =
+// ceil(B/64)); P_max bounds *dP and sizes the launch.
+struct AttnSeg {
+  int32_t row0, B, P_max;
+  void* kc;
+  void* vc;
+  const int32_t* dP;
+  const uint64_t* mask;
+};
+enum { ATTN_MAX_SEGS = 16 };
+// Fused rotary embedding + KV-tail write + tree attention of `nseg` requests.  part: the q|k|v
+// projection as `ks` split-K slices of f32 [Bpad][part_ld]; cs: rotary table of all rows;
+// o: bf16 [Bpad][ldo].  Requests with the same number of 32-row query tiles share one launch
+// (grid z = request).  splits_or_0: key splits per head, 0 = chosen here (at most max_splits).
+int launch_attn_bf16(const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs, int n_heads,
+                     int n_kv_heads, int head_dim, int cap, const AttnSeg* segs, int nseg, int splits_or_0,
+                     int max_splits, int key_groups, const void* gq, const void* gk, float eps, float* att_o,
+                     float* att_ml, int Bpad, void* o, int ldo, hipStream_t st);
 int pick_attn_splits(int n_heads, int keys_max, int max_splits);
