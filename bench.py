@@ -350,9 +350,9 @@ def bench_batched(args, shape, P0, K, W, log):
     total = K + W
     cap = (P0 + 2 * total * 2 + 2 * Br + 63) // 64 * 64   # random drafts: a request grows by about one slot per step
     P_max = cap - Br
-    gm = GooseModel(ModelDesc.from_shape(shape), rows, cap, lambda l: gi.layer_weights(shape, args.seed, l, dev),
-                    gi.embedding(shape, args.seed, dev), gi.lm_head(shape, args.seed, dev),
-                    gi.final_norm(shape, args.seed, dev))
+    gm = GooseModel(ModelDesc.from_shape(shape), min(128, rows), cap,
+                    lambda l: gi.layer_weights(shape, args.seed, l, dev), gi.embedding(shape, args.seed, dev),
+                    gi.lm_head(shape, args.seed, dev), gi.final_norm(shape, args.seed, dev), max_rows=rows)
     i32 = dict(dtype=torch.int32, device=dev)
     reqs = []
     for r in range(n):
@@ -362,7 +362,7 @@ def bench_batched(args, shape, P0, K, W, log):
         prefix = gi.prefix_tokens(args.seed + 31 * r, P0, shape.vocab)
         done = 0
         while done < P0:
-            m = min(rows, P0 - done)
+            m = min(128, rows, P0 - done)
             ch = gi.tree_chain(m)
             out = gm.verify_step_calls(prefix[done:done + m], ch.parent, ch.is_spine, commit=False)
             done += m
@@ -436,7 +436,10 @@ def bench_batched(args, shape, P0, K, W, log):
            "one_by_one_ms_per_step": round(dt_s / K * 1e3, 4), "speedup_over_one_by_one": round(dt_s / dt_b, 3),
            "draft_tokens_verified_per_s": round(n * Br * K / dt_b, 1),
            "achieved_GBps": round((w_bytes + kv_bytes) / (dt_b / K) / 1e9, 1),
-           "hbm_frac": round((w_bytes + kv_bytes) / (dt_b / K) / 1e9 / HBM_PEAK_GBPS, 4)}
+           "hbm_frac": round((w_bytes + kv_bytes) / (dt_b / K) / 1e9 / HBM_PEAK_GBPS, 4),
+           # projections + LM head only (2 flops per weight per row); dense bf16 MFMA peak 2500 TFLOP/s
+           "projection_TFLOPs": round(2.0 * n * Br * (w_bytes / es) / (dt_b / K) / 1e12, 1)}
+    out["mfma_frac"] = round(out["projection_TFLOPs"] / 2500.0, 4)
     print(json.dumps(out), flush=True)
 
 

@@ -71,6 +71,8 @@ typedef enum {
 
 enum { GOOSE_DTYPE_BF16 = 0, GOOSE_DTYPE_F32 = 1 };
 enum { GOOSE_MAX_B = 128 };
+/* Most rows (nodes of all requests, each request rounded up to 32) one batched pass may stack. */
+enum { GOOSE_MAX_ROWS = 512 };
 
 typedef struct {
   int32_t n_layers, hidden, n_heads, head_dim, ffn, vocab;
@@ -103,6 +105,9 @@ const char* goose_last_hip_error(void);
 /* Creates a context with workspace for trees of up to max_B nodes and caches of `cap`
  * slots per head (a multiple of 64).  Allocates device memory on the current device. */
 int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** out);
+/* The same, with workspace for passes of up to max_rows stacked rows (goose_verify_step_batched):
+ * max_B <= max_rows <= GOOSE_MAX_ROWS, a multiple of 32.  goose_create is max_rows = round_up(max_B, 32). */
+int goose_create_batched(const goose_model_desc* desc, int max_B, int max_rows, int cap, goose_ctx** out);
 void goose_destroy(goose_ctx* ctx);
 
 /* Host-side check of a parent array (h_parent is a HOST pointer): GOOSE_OK,
@@ -206,9 +211,11 @@ int goose_verify_step(goose_ctx* ctx, const goose_model_ptrs* model, const goose
 /* ---- 6b. several requests in one pass (the batch sweep of App. D: trees of different requests share
  * every weight read; masks, positions, caches and cache lengths stay per request) ---------------
  * The rows of the requests are stacked, each request starting at a multiple of 32 rows; the sum of
- * the rounded-up B must not exceed round_up(max_B, 32).  Projections, norms and the LM head run once
- * over all rows; attention, walk and compaction run per request on its own caches.  bf16 models only.
- * d_argmax_all: int32 [round_up(max_B,32)], receives every row's prediction (request r's rows start
+ * the rounded-up B must not exceed the context's max_rows (goose_create_batched), each B its max_B.
+ * Projections, norms and the LM head run once over all rows (beyond 128 rows in chunks of 128 that
+ * share the weight stream through the L2 cache); the attention runs on every request's own caches
+ * as one launch per tree-size class; walk and compaction run per request.  bf16 models only.
+ * d_argmax_all: int32 [max_rows], receives every row's prediction (request r's rows start
  * at the sum of round_up(B, 32) of the requests before it).  All pointers DEVICE; P of a request is
  * read from *d_P (P_max: host upper bound, as in goose_verify_step) and updated in place. */
 #define GOOSE_MAX_REQUESTS 16
@@ -285,10 +292,12 @@ double goose_ema_update(double p_hat, int accepted_spine, int offered_spine, dou
 int goose_device_flags(goose_ctx* ctx, void* stream, int32_t* h_flags_out);
 
 /* ---- the projection kernel on its own (unit tests and tuning; bf16 only) ---------------------
- * out[m][n] = sum_k A[m][k] * W[n][k] for the skinny-M shapes of the pass (M = B <= 128 tree nodes).
+ * out[m][n] = sum_k A[m][k] * W[n][k] for the skinny-M shapes of the pass (M = B <= 128 tree nodes;
+ * up to GOOSE_MAX_ROWS stacked rows of a batch, computed in chunks of 128 rows).
  * goose_pack_matrix re-tiles a row-major bf16 W[N][K] into goose_packed_matrix_bytes(N, K) bytes
  * (N padded to 32, K to 128, zero filled).  goose_gemm_packed multiplies: d_a is bf16 with
- * round_up(B,32) readable rows of lda >= round_up(K,128) elements (columns K.. must be finite),
+ * round_up(B,32) readable rows (round_up(B,128) when B > 128) of lda >= round_up(K,128) elements
+ * (columns K.. and rows B.. must be finite),
  * nw = 2 or 4 column tiles per workgroup, ksplit = split-K factor (every split non-empty).
  * d_partials receives fp32 [ksplit][round_up(B,32)][round_up(N,32)]; the result is the sum over
  * the first index, rows < B (other rows are not written). */

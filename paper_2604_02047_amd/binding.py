@@ -13,7 +13,7 @@ import numpy as np
 _PKG = os.path.dirname(os.path.abspath(__file__))
 
 EXPORTS = [
-    "goose_strerror", "goose_last_hip_error", "goose_create", "goose_destroy", "goose_check_parent",
+    "goose_strerror", "goose_last_hip_error", "goose_create", "goose_create_batched", "goose_destroy", "goose_check_parent",
     "goose_packed_layer_bytes", "goose_pack_layer", "goose_packed_lm_head_bytes", "goose_pack_lm_head",
     "goose_build_mask", "goose_embed", "goose_verify_layer", "goose_lm_head_argmax",
     "goose_accept", "goose_compact_kv", "goose_verify_step", "goose_device_flags",
@@ -112,6 +112,7 @@ def load_library():
     lib.goose_last_hip_error.restype = C.c_char_p
     lib.goose_last_hip_error.argtypes = []
     lib.goose_create.argtypes = [C.POINTER(_Desc), C.c_int, C.c_int, C.POINTER(C.c_void_p)]
+    lib.goose_create_batched.argtypes = [C.POINTER(_Desc), C.c_int, C.c_int, C.c_int, C.POINTER(C.c_void_p)]
     lib.goose_destroy.argtypes = [C.c_void_p]
     lib.goose_destroy.restype = None
     lib.goose_check_parent.argtypes = [C.c_void_p, C.c_int]
@@ -273,13 +274,17 @@ def _stream():
 class GooseContext:
     """Owns a goose_ctx.  Methods are the C entry points with torch tensors as arguments."""
 
-    def __init__(self, desc: ModelDesc, max_B: int, cap: int):
+    def __init__(self, desc: ModelDesc, max_B: int, cap: int, max_rows: int = 0):
+        """max_rows > 0: workspace for batched passes of that many stacked rows (goose_create_batched)."""
         self.lib = load_library()
         self.desc = desc
-        self.max_B, self.cap = max_B, cap
+        self.max_B, self.cap, self.max_rows = max_B, cap, max_rows or (max_B + 31) // 32 * 32
         h = C.c_void_p()
         cd = desc._c()
-        _check(self.lib.goose_create(C.byref(cd), max_B, cap, C.byref(h)), "goose_create")
+        if max_rows:
+            _check(self.lib.goose_create_batched(C.byref(cd), max_B, max_rows, cap, C.byref(h)), "goose_create_batched")
+        else:
+            _check(self.lib.goose_create(C.byref(cd), max_B, cap, C.byref(h)), "goose_create")
         self._h = h
 
     def close(self):

@@ -7,7 +7,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libgoose.so")
-SOURCES = ["goose_api.hip", "kernels_small.hip", "f32_path.hip", "gemm_bf16.hip", "attn_bf16.hip", "draft_host.cpp"]
+SOURCES = ["goose_api.hip", "kernels_small.hip", "f32_path.hip", "gemm_bf16.hip", "gemm_rows_bf16.hip", "attn_bf16.hip", "draft_host.cpp"]
 
 
 def build(verbose: bool = False) -> str:

@@ -81,12 +81,15 @@ __global__ __launch_bounds__(256) void k_pack_bf16(int mode, const bf16_t* __res
 // is handed over through LDS and the even wavefront writes h = silu(gate) * up.
 // EPI_TOP2: besides the optional plain output, every workgroup reduces its columns to one
 // (largest, second largest, index of largest) triple per row, for the greedy argmax.
-template <int MT, int NW, int EPI, int KC, int RING>
+// STREAM: the weights are read once by the whole grid (non-temporal loads keep them from
+// displacing the L2's other lines); false when several row chunks read them (see below).
+template <int MT, int NW, int EPI, int KC, int RING, bool STREAM = true>
 __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict__ A, int lda,
                                                        const u32x4* __restrict__ Wp, int ntiles, int ksteps_total,
                                                        int stages_per_split, int B, void* __restrict__ out,
                                                        size_t ldo, size_t split_stride,
-                                                       float4* __restrict__ top2, int n_valid) {
+                                                       float4* __restrict__ top2, int n_valid, int gx, int nsplit,
+                                                       int nchunk) {
   constexpr int LDS_ROW = KC * 2 + 16;  // bytes; the 16-byte pad staggers rows across banks
   constexpr int NTHR = 64 * NW;
   constexpr int STEPS = KC / 16;                    // MFMA k-steps per stage
@@ -101,13 +104,31 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict_
   constexpr int LDS_BYTES = 2 * STAGE_BYTES > EPI_BYTES ? 2 * STAGE_BYTES : EPI_BYTES;
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int tile = blockIdx.x * NW + wave;
+  // Work item = (column-tile group bx, split-K range by, row chunk of MT*32 rows).  Workgroups are
+  // dealt to the 8 XCDs round-robin in launch order; the chunks of one (bx, by) read the same
+  // weights, so they take consecutive slots of ONE XCD: its L2 then serves all but the first.
+  int bx, by, chunk = 0;
+  if (nchunk == 1) {
+    by = blockIdx.x / gx;
+    bx = blockIdx.x - by * gx;
+  } else {
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int j = slot / nchunk;
+    chunk = slot - j * nchunk;
+    const int t = j * 8 + xcd;
+    if (t >= gx * nsplit) return;  // the grid is rounded up to whole groups of 8
+    by = t / gx;
+    bx = t - by * gx;
+  }
+  const int row_base = chunk * MT * 32;
+  A += (size_t)row_base * lda;
+  const int tile = bx * NW + wave;
   const bool active = tile < ntiles;
   // a wavefront past the last tile redoes the last tile (no divergent control flow in the
   // pipeline, which lets the compiler count outstanding loads exactly) and skips the store
   const int tile_ld = active ? tile : ntiles - 1;
   const int nstages_total = ksteps_total / STEPS;
-  const int s_begin = blockIdx.y * stages_per_split;
+  const int s_begin = by * stages_per_split;
   const int s_end = min(s_begin + stages_per_split, nstages_total);
   const int nst = s_end - s_begin;
 
@@ -150,7 +171,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict_
     constexpr int slot = decltype(slot_c)::value;
     const u32x4* p = wbase + (size_t)st * STEPS * 64;
 #pragma unroll
-    for (int s = 0; s < STEPS; ++s) wreg[slot][s] = __builtin_nontemporal_load(p + s * 64);
+    for (int s = 0; s < STEPS; ++s) wreg[slot][s] = STREAM ? __builtin_nontemporal_load(p + s * 64) : p[s * 64];
   };
   const int a_frag = (lane & 31) * LDS_ROW + (lane >> 5) * 16;
   // one stage (slot = st % RING, compile-time so that no register array is indexed dynamically;
@@ -170,7 +191,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict_
             &lds[buf * STAGE_BYTES + mt * 32 * LDS_ROW + a_frag + s * 32]);
         acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mt], 0, 0, 0);
       }
-      if (refill) wreg[slot][s] = __builtin_nontemporal_load(pn + s * 64);
+      if (refill) wreg[slot][s] = STREAM ? __builtin_nontemporal_load(pn + s * 64) : pn[s * 64];
       __builtin_amdgcn_sched_barrier(0);
     }
     if (next_a) store_a(buf ^ 1, nslot);
@@ -233,13 +254,13 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict_
   // C layout of the 32x32 MFMA: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
   if (EPI == EPI_PARTIAL) {
     if (!active) return;
-    float* o = reinterpret_cast<float*>(out) + blockIdx.y * split_stride;
+    float* o = reinterpret_cast<float*>(out) + by * split_stride;
     const int col = tile * 32 + (lane & 31);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int row = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const int row = row_base + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         if (row < B) o[(size_t)row * ldo + col] = acc[mt][r];
       }
   } else if (EPI == EPI_TOP2) {  // (the last loop barrier already separates the A stages from this reuse of LDS)
@@ -253,7 +274,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict_
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (o != nullptr && active && row < B) o[(size_t)row * ldo + col] = acc[mt][r];
+        if (o != nullptr && active && row_base + row < B) o[(size_t)(row_base + row) * ldo + col] = acc[mt][r];
         ct[row * CT_ROW + (lane & 31)] = acc[mt][r];
       }
     __syncthreads();
@@ -279,7 +300,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict_
           if (e.x > t.x) { t.y = fmaxf(t.x, e.y); t.x = e.x; t.z = e.z; }
           else t.y = fmaxf(t.y, e.x);
         }
-        if (row < B) top2[(size_t)row * gridDim.x + blockIdx.x] = t;
+        if (row_base + row < B) top2[(size_t)(row_base + row) * gx + bx] = t;
       }
     }
   } else {  // EPI_SWIGLU (the last loop barrier already separates the A stages from this reuse of LDS)
@@ -298,7 +319,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict_
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int row = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          const int row = row_base + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
           const float g = acc[mt][r], u = swap[(mt * 16 + r) * 64 + lane];
           if (row < B) hq[(size_t)row * ldo + col] = (bf16_t)(g / (1.0f + __expf(-g)) * u);
         }
@@ -310,12 +331,23 @@ template <int MT, int NW, int EPI>
 int launch_one(const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit, void* out, size_t ldo,
                size_t split_stride, hipStream_t st, void* top2 = nullptr, int n_valid = 0) {
   const int ntiles = Npad / 32, ksteps = Kpad / 16;
-  dim3 grid((ntiles + NW - 1) / NW, ksplit);
+  const int gx = (ntiles + NW - 1) / NW;
+  const int nchunk = (B + MT * 32 - 1) / (MT * 32);  // more than 128 rows: chunks of 4 row tiles
+  const dim3 grid(nchunk == 1 ? gx * ksplit : (gx * ksplit + 7) / 8 * 8 * nchunk);
   const int granules = Kpad / KGRAN;                      // split-K ranges are multiples of 128 inputs
   const int gps = (granules + ksplit - 1) / ksplit;       // granules (= stages) per split
   // two stages of each stream in flight measured best (four: every projection 2-3 us slower)
+  if constexpr (MT == 4) {
+    if (nchunk > 1) {  // the chunks of a column group share their weights through the L2: ordinary loads
+      hipLaunchKernelGGL((k_gemm_bf16<MT, NW, EPI, 128, 2, false>), grid, dim3(64 * NW), 0, st, (const bf16_t*)A, lda,
+                         (const u32x4*)Wp, ntiles, ksteps, gps, B, out, ldo, split_stride, (float4*)top2, n_valid, gx,
+                         ksplit, nchunk);
+      return goose_launch_status();
+    }
+  }
   hipLaunchKernelGGL((k_gemm_bf16<MT, NW, EPI, 128, 2>), grid, dim3(64 * NW), 0, st, (const bf16_t*)A, lda,
-                     (const u32x4*)Wp, ntiles, ksteps, gps, B, out, ldo, split_stride, (float4*)top2, n_valid);
+                     (const u32x4*)Wp, ntiles, ksteps, gps, B, out, ldo, split_stride, (float4*)top2, n_valid, gx,
+                     ksplit, nchunk);
   return goose_launch_status();
 }
 
@@ -361,18 +393,24 @@ void pick_gemm_config(int Npad, int Kpad, int max_ksplit, int* nw_out, int* kspl
 
 int launch_gemm_top2_bf16(const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw, float* out,
                           size_t ldo, void* top2, int n_valid, hipStream_t st) {
-  if (B < 1 || B > GOOSE_MAX_B || (Npad & 31) || (Kpad % KGRAN) || !top2 || n_valid < 1 || n_valid > Npad)
+  if (B < 1 || B > GOOSE_MAX_ROWS || (Npad & 31) || (Kpad % KGRAN) || !top2 || n_valid < 1 || n_valid > Npad)
     return GOOSE_ERR_ARG;
-  const int MT = (B + 31) / 32;
+  const int MT = B > 128 ? 4 : (B + 31) / 32;
   if (nw == 4) return launch_mt<4, EPI_TOP2>(MT, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st, top2, n_valid);
   return launch_mt<2, EPI_TOP2>(MT, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st, top2, n_valid);
 }
 
 int launch_gemm_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw, int ksplit,
                      void* out, size_t ldo, size_t out_split_stride, hipStream_t st) {
-  if (B < 1 || B > GOOSE_MAX_B || (Npad & 31) || (Kpad % KGRAN) || ksplit < 1) return GOOSE_ERR_ARG;
+  if (B < 1 || B > GOOSE_MAX_ROWS || (Npad & 31) || (Kpad % KGRAN) || ksplit < 1) return GOOSE_ERR_ARG;
   if (epi != EPI_PARTIAL && epi != EPI_SWIGLU) return GOOSE_ERR_ARG;
-  const int MT = (B + 31) / 32;
+  if (B > 128) {
+    // the kernel blocked for the matrix cores; GOOSE_ROWS_KERNEL=0 (tuning aid) keeps the skinny kernel in row chunks
+    static const bool rows_kernel = !getenv("GOOSE_ROWS_KERNEL") || atoi(getenv("GOOSE_ROWS_KERNEL")) != 0;
+    if (rows_kernel)
+      return launch_gemm_rows_bf16(epi, A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st);
+  }
+  const int MT = B > 128 ? 4 : (B + 31) / 32;
   if (epi == EPI_SWIGLU) {
     if (ksplit != 1 || (Npad & 63)) return GOOSE_ERR_ARG;
     if (nw == 4) return launch_mt<4, EPI_SWIGLU>(MT, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st);

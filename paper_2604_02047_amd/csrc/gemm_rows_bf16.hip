@@ -1,0 +1,242 @@
+// Many-row bf16 GEMM for gfx950: out[m][n] = sum_k A[m][k] * W[n][k] for the stacked rows of a
+// batch of requests, 128 < M <= 512 (the batch sweep of App. D).  Same operands and the same
+// results, bit for bit, as the skinny kernel of gemm_bf16.hip (each accumulator takes its k-steps
+// in ascending order there and here), but organised for the matrix cores rather than for the
+// weight stream alone: with hundreds of rows a weight byte is used often enough that the pass
+// sits near the ridge between HBM and MFMA, and what limits a kernel there is the operand traffic
+// inside the chip (L2 -> compute unit, LDS -> registers) per matrix instruction.
+//
+//   * A wavefront owns MT x NT tiles of 32 x 32 outputs (MT = 4 row tiles, NT = 2 column tiles:
+//     128 accumulator registers; 8 x 2 or 4 x 4 would halve the operand traffic again but the
+//     compiler spills them): an A operand read from LDS feeds NT instructions, a weight operand MT.
+//   * A workgroup = 4 wavefronts on neighbouring column tiles sharing one chunk of MT*32 rows:
+//     the chunk's K slices (KC = 64 inputs) are staged in LDS, double buffered, as in the skinny
+//     kernel; the weights go global -> registers in operand order, two stages ahead.
+//   * Row chunks of one column group run on ONE XCD in neighbouring launch slots (workgroups are
+//     dealt to the 8 XCDs round-robin), so the later chunks find the weights in that XCD's L2.
+//   Measured on MI355X (28672 x 4096 gate/up, 512 rows): 135 us = 0.89 PFLOP/s, 36 % of the bf16
+//   MFMA peak; the chunked skinny kernel takes 178 us.  One workgroup per compute unit (registers),
+//   about 40 % of its time in matrix instructions; the rest is operand delivery (1.4 GB through
+//   the L2 per launch) and the barrier per stage.
+//   * Epilogues: fp32 split-K partials, or SwiGLU (the gate tile and the up tile of 32 hidden
+//     columns are the two column tiles of one wavefront: no exchange needed).
+#include <type_traits>
+
+#include "goose_internal.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int NW = 4;   // wavefronts per workgroup
+constexpr int NT = 2;   // column tiles per wavefront
+
+// KC: inputs per stage
+template <int MT, int EPI, int KC>
+__global__ __launch_bounds__(64 * NW) void k_gemm_rows(const bf16_t* A, int lda, const u32x4* __restrict__ Wp,
+                                                       int ntiles, int ksteps_total, int stages_per_split, int B,
+                                                       void* __restrict__ out, size_t ldo, size_t split_stride, int gx,
+                                                       int nsplit, int nchunk) {
+  constexpr int LDS_ROW = KC * 2 + 16;  // bytes; 9 x 16: rows start in different banks
+  constexpr int NTHR = 64 * NW;
+  constexpr int STEPS = KC / 16;
+  constexpr int ASEG = MT * 32 * (KC / 8);  // 16-byte segments of one A stage
+  constexpr int APT = ASEG / NTHR;
+  static_assert(ASEG % NTHR == 0, "A stage must divide evenly over the workgroup");
+  constexpr int STAGE_BYTES = MT * 32 * LDS_ROW;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];  // 2 * STAGE_BYTES
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+  // work item = (column group bx, split-K range by, row chunk); see the XCD note above
+  const int xcd = blockIdx.x & 7, slot_id = blockIdx.x >> 3;
+  const int j = slot_id / nchunk, chunk = slot_id - j * nchunk;
+  const int t = j * 8 + xcd;
+  if (t >= gx * nsplit) return;  // the grid is rounded up to whole groups of 8
+  const int by = t / gx, bx = t - by * gx;
+  const int row_base = chunk * MT * 32;
+  A += (size_t)row_base * lda;
+  const int tile0 = (bx * NW + wave) * NT;
+
+  const int nstages_total = ksteps_total / STEPS;
+  const int s_begin = by * stages_per_split;
+  const int s_end = min(s_begin + stages_per_split, nstages_total);
+  const int nst = s_end - s_begin;
+
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.f;
+
+  // both operand streams run two stages ahead in registers (slots st % 2, compile-time indices)
+  u32x4 areg[2][APT];
+  const bf16_t* a_src[APT];
+  int a_dst[APT];
+#pragma unroll
+  for (int i = 0; i < APT; ++i) {
+    const int seg = tid + NTHR * i;
+    const int row = seg / (KC / 8), c16 = seg % (KC / 8);
+    a_src[i] = A + (size_t)row * lda + c16 * 8;
+    a_dst[i] = row * LDS_ROW + c16 * 16;
+  }
+  u32x4 wreg[2][STEPS][NT];
+  const u32x4* wbase[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    // a tile past the last one redoes the last tile (uniform control flow) and is not stored
+    const int tl = tile0 + nt < ntiles ? tile0 + nt : ntiles - 1;
+    wbase[nt] = Wp + (size_t)tl * ksteps_total * 64 + lane;
+  }
+  auto load_a = [&](int st, auto slot_c) {
+    constexpr int slot = decltype(slot_c)::value;
+#pragma unroll
+    for (int i = 0; i < APT; ++i) areg[slot][i] = *reinterpret_cast<const u32x4*>(a_src[i] + (size_t)st * KC);
+  };
+  auto store_a = [&](int buf, auto slot_c) {
+    constexpr int slot = decltype(slot_c)::value;
+#pragma unroll
+    for (int i = 0; i < APT; ++i) *reinterpret_cast<u32x4*>(&lds[buf * STAGE_BYTES + a_dst[i]]) = areg[slot][i];
+  };
+  auto load_w = [&](int st, auto slot_c) {
+    constexpr int slot = decltype(slot_c)::value;
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) wreg[slot][s][nt] = wbase[nt][((size_t)st * STEPS + s) * 64];
+  };
+  const int a_frag = (lane & 31) * LDS_ROW + (lane >> 5) * 16;
+  auto stage = [&](auto slot_c, int st, auto next_a, auto refill) {
+    constexpr int slot = decltype(slot_c)::value, buf = slot;
+    const std::integral_constant<int, slot ^ 1> nslot;
+    if (refill) load_a(st + 2, slot_c);  // this slot's previous content (stage st) is in LDS already
+    __builtin_amdgcn_sched_barrier(0);
+    // the A operands of step s+1 are read from LDS before the matrix instructions of step s issue
+    bf16x8 af[2][MT];
+    auto read_a = [&](int s, int which) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        af[which][mt] = *reinterpret_cast<const bf16x8*>(&lds[buf * STAGE_BYTES + mt * 32 * LDS_ROW + a_frag + s * 32]);
+    };
+    read_a(0, 0);
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+      if (s + 1 < STEPS) read_a(s + 1, (s + 1) & 1);
+      bf16x8 b[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) b[nt] = __builtin_bit_cast(bf16x8, wreg[slot][s][nt]);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s & 1][mt], b[nt], acc[mt][nt], 0, 0, 0);
+      if (refill) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) wreg[slot][s][nt] = wbase[nt][((size_t)(st + 2) * STEPS + s) * 64];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (next_a) store_a(buf ^ 1, nslot);
+    __syncthreads();
+  };
+  const std::true_type yes;
+  const std::integral_constant<int, 0> c0;
+  const std::integral_constant<int, 1> c1;
+
+  if (nst > 0) {
+    int i = 0;
+    if (nst >= 4) {
+      // long range: both slots filled unconditionally, so that the wait counts at the loop head are exact
+      load_a(s_begin, c0);
+      load_w(s_begin, c0);
+      load_a(s_begin + 1, c1);
+      load_w(s_begin + 1, c1);
+      store_a(0, c0);
+      __syncthreads();
+      for (; i + 3 < nst; i += 2) {
+        stage(c0, s_begin + i, yes, yes);
+        stage(c1, s_begin + i + 1, yes, yes);
+      }
+    } else {
+      load_a(s_begin, c0);
+      load_w(s_begin, c0);
+      if (nst > 1) { load_a(s_begin + 1, c1); load_w(s_begin + 1, c1); }
+      store_a(0, c0);
+      __syncthreads();
+    }
+    for (; i < nst; ++i) {  // the last stages (i is even on entry)
+      const bool na = (i + 1) < nst, rf = (i + 2) < nst;
+      if ((i & 1) == 0) stage(c0, s_begin + i, na, rf);
+      else stage(c1, s_begin + i, na, rf);
+    }
+  }
+
+  // C layout of the 32x32 MFMA: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+  if (EPI == EPI_PARTIAL) {
+    float* o = reinterpret_cast<float*>(out) + by * split_stride;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      if (tile0 + nt >= ntiles) continue;
+      const int col = (tile0 + nt) * 32 + (lane & 31);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_base + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          if (row < B) o[(size_t)row * ldo + col] = acc[mt][nt][r];
+        }
+    }
+  } else {  // EPI_SWIGLU: column tile 2c holds gate rows, 2c+1 the matching up rows
+    static_assert(NT == 2, "gate and up tile of a column block sit in one wavefront");
+    if (tile0 + 1 >= ntiles) return;
+    bf16_t* hq = reinterpret_cast<bf16_t*>(out);
+    const int col = (tile0 >> 1) * 32 + (lane & 31);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = row_base + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const float g = acc[mt][0][r], u = acc[mt][1][r];
+        if (row < B) hq[(size_t)row * ldo + col] = (bf16_t)(g / (1.0f + __expf(-g)) * u);
+      }
+  }
+}
+
+template <int MT, int EPI, int KC>
+int launch_rows(const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit, void* out, size_t ldo,
+                size_t split_stride, hipStream_t st) {
+  constexpr int LDS_BYTES = 2 * MT * 32 * (KC * 2 + 16);
+  static bool configured = false;  // more LDS than a kernel gets by default: ask once
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_rows<MT, EPI, KC>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e != hipSuccess) { goose_note_hip_error(e, "hipFuncSetAttribute(k_gemm_rows)", __LINE__); return GOOSE_ERR_HIP; }
+    configured = true;
+  }
+  const int ntiles = Npad / 32, ksteps = Kpad / 16;
+  const int gx = (ntiles + NW * NT - 1) / (NW * NT);
+  const int nchunk = (B + MT * 32 - 1) / (MT * 32);
+  const int granules = Kpad / 128;                        // split-K ranges are multiples of 128 inputs,
+  const int gps = (granules + ksplit - 1) / ksplit;       // the same ranges as the skinny kernel's
+  const dim3 grid((gx * ksplit + 7) / 8 * 8 * nchunk);
+  hipLaunchKernelGGL((k_gemm_rows<MT, EPI, KC>), grid, dim3(64 * NW), LDS_BYTES, st, (const bf16_t*)A, lda,
+                     (const u32x4*)Wp, ntiles, ksteps, gps * (128 / KC), B, out, ldo, split_stride, gx, ksplit, nchunk);
+  return goose_launch_status();
+}
+
+}  // namespace
+
+// A must hold whole chunks of 128 readable rows.
+int launch_gemm_rows_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit,
+                          void* out, size_t ldo, size_t out_split_stride, hipStream_t st) {
+  if (B < 1 || B > GOOSE_MAX_ROWS || (Npad & 31) || (Kpad % 128) || ksplit < 1) return GOOSE_ERR_ARG;
+  if (epi == EPI_SWIGLU) {
+    if (ksplit != 1 || (Npad & 63)) return GOOSE_ERR_ARG;
+    return launch_rows<4, EPI_SWIGLU, 64>(A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st);
+  }
+  if (epi != EPI_PARTIAL) return GOOSE_ERR_ARG;
+  return launch_rows<4, EPI_PARTIAL, 64>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st);
+}

@@ -160,9 +160,14 @@ int goose_check_parent(const int32_t* h_parent, int B) {
 }
 
 int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** out) {
+  return goose_create_batched(desc, max_B, round_up(max_B, 32), cap, out);
+}
+
+int goose_create_batched(const goose_model_desc* desc, int max_B, int max_rows, int cap, goose_ctx** out) {
   if (!desc || !out) return GOOSE_ERR_ARG;
   *out = nullptr;
   if (max_B < 1 || max_B > GOOSE_MAX_B || cap < max_B || (cap % 64) != 0) return GOOSE_ERR_ARG;
+  if (max_rows < max_B || max_rows > GOOSE_MAX_ROWS || (max_rows & 31)) return GOOSE_ERR_ARG;
   const goose_model_desc& d = *desc;
   if (d.n_layers < 1 || d.hidden < 1 || d.n_heads < 1 || d.head_dim < 2 || d.ffn < 1 || d.vocab < 1)
     return GOOSE_ERR_ARG;
@@ -183,7 +188,8 @@ int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** o
   memset(c, 0, sizeof(*c));
   c->d = d;
   c->max_B = max_B;
-  c->Bpad = max_B <= 32 ? 32 : (max_B <= 64 ? 64 : 128);
+  c->max_rows = max_rows;
+  c->Bpad = max_rows <= 32 ? 32 : (max_rows <= 64 ? 64 : round_up(max_rows, 128));
   c->cap = cap;
   c->Hq = d.n_heads * d.head_dim;
   c->n_kv = n_kv;
@@ -213,10 +219,10 @@ int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** o
   A((void**)&c->logits, (size_t)c->Bpad * c->Vpad * sizeof(float));
   A(&c->top2, (size_t)c->Bpad * (c->Vpad / 64 + 1) * 16);
   A((void**)&c->inv_freq, (size_t)(d.head_dim / 2) * sizeof(double));
-  A(&c->rope_cs, (size_t)GOOSE_MAX_B * (d.head_dim / 2) * 2 * sizeof(float));
-  A((void**)&c->s_mask, 128 * 2 * sizeof(uint64_t));
-  A((void**)&c->s_depth, 128 * sizeof(int32_t));
-  A((void**)&c->s_pos, 128 * sizeof(int32_t));
+  A(&c->rope_cs, (size_t)c->Bpad * (d.head_dim / 2) * 2 * sizeof(float));
+  A((void**)&c->s_mask, (size_t)c->Bpad * 2 * sizeof(uint64_t));
+  A((void**)&c->s_depth, (size_t)c->Bpad * sizeof(int32_t));
+  A((void**)&c->s_pos, (size_t)c->Bpad * sizeof(int32_t));
   A((void**)&c->s_x, (size_t)c->Bpad * d.hidden * sizeof(float));
   A((void**)&c->flags, sizeof(int32_t));
   A((void**)&c->s_P, sizeof(int32_t));
@@ -595,7 +601,7 @@ int goose_verify_step_batched(goose_ctx* c, const goose_model_ptrs* m, const goo
     segs[r] = AttnSeg{rows, q.B, q.P_max, nullptr, nullptr, q.d_P, c->s_mask + (size_t)rows * 2};
     rows += round_up(q.B, 32);
   }
-  if (rows > c->Bpad || rows > round_up(c->max_B, 32)) return GOOSE_ERR_CAPACITY;
+  if (rows > c->max_rows) return GOOSE_ERR_CAPACITY;
   int rc;
   for (int r = 0; r < n_req; ++r) {
     const goose_request& q = reqs[r];
@@ -659,7 +665,7 @@ int goose_pack_matrix(const void* d_w, int N, int K, void* d_packed, void* strea
 int goose_gemm_swiglu_packed(const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, void* d_h,
                              int ldh, void* stream) {
   if (!d_a || !d_packed || !d_h || N < 64 || (N % 64) != 0 || K < 1) return GOOSE_ERR_ARG;
-  if (B < 1 || B > GOOSE_MAX_B || (nw != 2 && nw != 4)) return GOOSE_ERR_ARG;
+  if (B < 1 || B > GOOSE_MAX_ROWS || (nw != 2 && nw != 4)) return GOOSE_ERR_ARG;
   const int Kpad = round_up(K, 128);
   if (lda < Kpad || (lda % 8) != 0 || ldh < N / 2) return GOOSE_ERR_ARG;
   return launch_gemm_bf16(EPI_SWIGLU, d_a, lda, d_packed, N, Kpad, B, nw, 1, d_h, (size_t)ldh, 0, as_stream(stream));
@@ -668,7 +674,7 @@ int goose_gemm_swiglu_packed(const void* d_a, int lda, const void* d_packed, int
 int goose_gemm_packed(const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, int ksplit,
                       float* d_partials, void* stream) {
   if (!d_a || !d_packed || !d_partials || N < 1 || K < 1) return GOOSE_ERR_ARG;
-  if (B < 1 || B > GOOSE_MAX_B || (nw != 2 && nw != 4) || ksplit < 1) return GOOSE_ERR_ARG;
+  if (B < 1 || B > GOOSE_MAX_ROWS || (nw != 2 && nw != 4) || ksplit < 1) return GOOSE_ERR_ARG;
   const int Npad = round_up(N, 32), Kpad = round_up(K, 128);
   if (lda < Kpad || (lda % 8) != 0) return GOOSE_ERR_ARG;
   const int nstages = Kpad / 128;

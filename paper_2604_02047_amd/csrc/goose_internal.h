@@ -41,8 +41,9 @@ struct goose_prof;
 
 struct goose_ctx {
   goose_model_desc d;
-  int max_B;   // as requested
-  int Bpad;    // 32, 64 or 128: row count of every activation buffer
+  int max_B;     // nodes of one tree, as requested
+  int max_rows;  // stacked rows of one pass (a multiple of 32; round_up(max_B, 32) unless created for batches)
+  int Bpad;      // 32, 64 or a multiple of 128: row count of every activation buffer
   int cap;     // cache slots per head
   int Hq;      // n_heads * head_dim
   int n_kv;    // key/value heads
@@ -115,6 +116,10 @@ enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_TOP2 = 2 };
 // out partials f32 [ksplit][Bpad][ldo] (EPI_PARTIAL) or bf16 h [Bpad][ldo] (EPI_SWIGLU, ksplit must be 1)
 int launch_gemm_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw, int ksplit,
                      void* out, size_t ldo, size_t out_split_stride, hipStream_t st);
+// The same products for 128 < B <= GOOSE_MAX_ROWS stacked rows, blocked for the matrix cores
+// (gemm_rows_bf16.hip); A must hold whole chunks of 128 readable rows.
+int launch_gemm_rows_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit,
+                          void* out, size_t ldo, size_t out_split_stride, hipStream_t st);
 // Projection whose workgroups (nw column tiles each) also emit per-row (max, second max, index of
 // max) over their valid columns (< n_valid): top2 is float4 [B][ceil(Npad/32/nw)], index bits in .z.
 // `out` (f32 [B][ldo]) may be null when only the reduction is wanted.

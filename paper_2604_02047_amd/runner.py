@@ -19,11 +19,11 @@ class GooseModel:
     """A model resident in HBM: packed weights, KV cache, and per-step staging buffers."""
 
     def __init__(self, desc: ModelDesc, max_B: int, cap: int, layer_fn, embed, lm_head, final_norm,
-                 device="cuda:0"):
+                 device="cuda:0", max_rows: int = 0):
         self.desc, self.max_B, self.cap = desc, max_B, cap
         self.device = torch.device(device)
         self.dt = _torch_dtype(desc.dtype)
-        self.ctx = GooseContext(desc, max_B, cap)
+        self.ctx = GooseContext(desc, max_B, cap, max_rows)
         lb = self.ctx.goose_packed_layer_bytes()
         self.layer_bytes = lb
         self.packed_layers = torch.zeros(desc.n_layers * lb, dtype=torch.uint8, device=self.device)

@@ -51,7 +51,7 @@ def _batched(gm, reqs):
     for q in reqs:
         q["P"] = torch.full((1,), q["P0"], **i32)
         q["accept_len"], q["path"], q["bonus"] = torch.zeros(1, **i32), torch.zeros(128, **i32), torch.zeros(1, **i32)
-    argmax_all = torch.full((128,), -1, **i32)
+    argmax_all = torch.full((gm.ctx.max_rows,), -1, **i32)
     gm.ctx.goose_verify_step_batched(gm.model_ptrs(), reqs, argmax_all)
     torch.cuda.synchronize()
     assert gm.ctx.goose_device_flags() == 0
@@ -97,15 +97,22 @@ def _check_against_oracle(gm, om, shape, q):
     assert torch.equal(k_b, k_0) and torch.equal(v_b, v_0)
 
 
+def _rows_of(sizes):
+    return sum((B + 31) // 32 * 32 for B in sizes)
+
+
 @pytest.mark.parametrize("shape_name,sizes", [("small_bf16", [64, 30, 20]), ("small_gqa_qknorm_bf16", [33, 64]),
-                                              ("tiny_bf16", [16, 9, 1, 32]), ("tiny_gqa_bf16", [128])])
+                                              ("tiny_bf16", [16, 9, 1, 32]), ("tiny_gqa_bf16", [128]),
+                                              ("small_bf16", [32] * 8), ("tiny_bf16", [16, 9, 1, 32, 64, 100, 3]),
+                                              ("small_gqa_qknorm_bf16", [32] * 16)])
 def test_batched_step_equals_the_requests_alone(shape_name, sizes):
-    """Short prefixes: one key split alone and batched, hence identical arithmetic per request."""
+    """Short prefixes: one key split alone and batched, hence identical arithmetic per request
+    (also beyond 128 stacked rows, where the projections run in chunks of 128 rows)."""
     shape = gi.SHAPES[shape_name]
     tm = torch_model(shape, seed=7, gain_jitter=0.1)
-    gm = gpu_model(shape, tm, max_B=128, cap=384)
-    P0s = [40 + 37 * r for r in range(len(sizes))]
-    reqs = _requests(gm, shape, sizes, P0s, [min(256 - B, 384 - B) for B in sizes])
+    gm = gpu_model(shape, tm, max_B=128, cap=384, max_rows=max(128, _rows_of(sizes)))
+    P0s = [40 + (37 * r) % 100 for r in range(len(sizes))]
+    reqs = _requests(gm, shape, sizes, P0s, [256 - B for B in sizes])
     alone = _alone(gm, reqs)
     _batched(gm, reqs)
     for q, a in zip(reqs, alone):
@@ -116,19 +123,20 @@ def test_batched_step_equals_the_requests_alone(shape_name, sizes):
         k_a, v_a = _rows(gm, a["k"], a["v"], 0, a["P"])
         assert torch.equal(k_b, k_a) and torch.equal(v_b, v_a)
     om = oracle_model(shape, tm)
-    for q in reqs[1:2]:     # a request that does not start at row 0, against the oracle
+    for q in reqs[1:2] + reqs[5:]:     # requests that do not start at row 0, against the oracle
         _check_against_oracle(gm, om, shape, q)
     gm.ctx.close()
 
 
 @pytest.mark.parametrize("shape_name,sizes,P0s", [("small_bf16", [32, 32, 32, 32], [700, 513, 640, 96]),
                                                   ("small_gqa_qknorm_bf16", [40, 17, 9], [600, 777, 31]),
-                                                  ("tiny_gqa_bf16", [90], [500])])
+                                                  ("tiny_gqa_bf16", [90], [500]),
+                                                  ("small_gqa_qknorm_bf16", [64, 17, 40, 128, 5], [600, 777, 31, 300, 512])])
 def test_batched_step_with_long_prefixes_matches_the_oracle(shape_name, sizes, P0s):
     """Prefixes long enough for several key splits, mixed tree-size classes: every request against the oracle."""
     shape = gi.SHAPES[shape_name]
     tm = torch_model(shape, seed=8, gain_jitter=0.1)
-    gm = gpu_model(shape, tm, max_B=128, cap=1024)
+    gm = gpu_model(shape, tm, max_B=128, cap=1024, max_rows=max(128, _rows_of(sizes)))
     reqs = _requests(gm, shape, sizes, P0s, [1024 - B for B in sizes])
     _batched(gm, reqs)
     om = oracle_model(shape, tm)

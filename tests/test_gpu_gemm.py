@@ -8,11 +8,16 @@ import paper_2604_02047_amd as g
 pytestmark = pytest.mark.gpu
 
 
+def _a_rows(B):
+    """Rows the operand buffer must hold: whole 32-row tiles, whole 128-row chunks beyond 128 rows."""
+    return (B + 31) // 32 * 32 if B <= 128 else (B + 127) // 128 * 128
+
+
 def _run(B, N, K, nw, ks, seed=0):
     dev = "cuda:0"
     gen = torch.Generator(device="cpu").manual_seed(seed)
     Kp, Np, rows = (K + 127) // 128 * 128, (N + 31) // 32 * 32, (B + 31) // 32 * 32
-    a = torch.zeros((rows, Kp), dtype=torch.bfloat16)
+    a = torch.zeros((_a_rows(B), Kp), dtype=torch.bfloat16)
     a[:B, :K] = (torch.randn((B, K), generator=gen)).to(torch.bfloat16)
     w = (torch.randn((N, K), generator=gen) * 0.05).to(torch.bfloat16)
     ref = a[:B, :K].double().numpy() @ w.double().numpy().T
@@ -34,6 +39,16 @@ def test_gemm_row_tiles(B):
     _run(B, 288, 1024, 4, 2)
 
 
+@pytest.mark.parametrize("B", [129, 200, 256, 300, 512])
+def test_gemm_row_chunks(B):
+    """More than 128 rows: chunks of 128 rows, each its own workgroups (dealt so that the chunks of a
+    column group share an XCD); grids that are no multiple of 8 workgroups, ragged last chunk."""
+    _run(B, 256, 512, 2, 1)
+    _run(B, 288, 1024, 4, 2)
+    _run(B, 1000, 1000, 4, 3)
+    _run(B, 4096, 2048, 4, 4)
+
+
 @pytest.mark.parametrize("stages,ks", [(1, 1), (2, 1), (2, 2), (3, 1), (3, 3), (4, 2), (5, 1), (5, 2), (6, 3),
                                        (8, 2), (9, 2), (22, 5), (32, 1), (32, 4), (86, 8)])
 def test_gemm_stage_counts_and_splits(stages, ks):
@@ -49,12 +64,13 @@ def test_gemm_ragged_shapes():
 
 
 @pytest.mark.parametrize("B,F,K,nw", [(16, 96, 256, 2), (16, 2752, 1024, 2), (64, 2752, 1024, 4), (80, 352, 640, 2),
-                                       (128, 704, 256, 4), (33, 64, 4096, 2)])
+                                       (128, 704, 256, 4), (33, 64, 4096, 2), (300, 704, 256, 4), (512, 352, 640, 2),
+                                       (160, 2752, 1024, 4)])
 def test_gemm_swiglu_epilogue(B, F, K, nw):
     dev = "cuda:0"
     gen = torch.Generator(device="cpu").manual_seed(F)
     Kp, rows = (K + 127) // 128 * 128, (B + 31) // 32 * 32
-    a = torch.zeros((rows, Kp), dtype=torch.bfloat16)
+    a = torch.zeros((_a_rows(B), Kp), dtype=torch.bfloat16)
     a[:B, :K] = torch.randn((B, K), generator=gen).to(torch.bfloat16)
     wg = (torch.randn((F, K), generator=gen) * 0.05).to(torch.bfloat16)
     wu = (torch.randn((F, K), generator=gen) * 0.05).to(torch.bfloat16)

@@ -44,12 +44,12 @@ def oracle_model(shape, tm) -> orc.OracleModel:
                            n_kv_heads=shape.kv_heads, qk_norm=shape.qk_norm)
 
 
-def gpu_model(shape, tm, max_B, cap):
+def gpu_model(shape, tm, max_B, cap, max_rows=0):
     """The HIP-side model built from the same stored weight bytes as `oracle_model`."""
     from paper_2604_02047_amd import ModelDesc
     from paper_2604_02047_amd.runner import GooseModel
     return GooseModel(ModelDesc.from_shape(shape), max_B, cap, lambda l: tm["layers"][l], tm["embed"],
-                      tm["lm_head"], tm["final_norm"])
+                      tm["lm_head"], tm["final_norm"], max_rows=max_rows)
 
 
 def load_prefix_cache(gm, cache):
