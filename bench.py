@@ -33,6 +33,7 @@ WORKLOADS = {
     "small_B64_P200": ("small_bf16", 64, 200, "spine_7b", 20),
     "llama3_8b_B64_P1024": ("llama3_8b", 64, 1024, "spine_7b", 100),
     "qwen3_8b_B64_P1024": ("qwen3_8b", 64, 1024, "spine_7b", 100),
+    "7b_f16_B64_P1024": ("7b_f16", 64, 1024, "spine_7b", 100),
 }
 
 
@@ -65,7 +66,7 @@ def make_tree(kind, seed):
 
 def step_bytes(shape, B, P):
     """Algorithmic HBM bytes of one step: every weight once, the KV prefix once, the tail rows written and read."""
-    es = 2 if shape.dtype == "bf16" else 4
+    es = 4 if shape.dtype == "f32" else 2
     w = shape.n_layers * shape.layer_param_count() * es
     head = shape.vocab * shape.hidden * es
     kv_prefix = 2 * P * shape.kv_dim * es * shape.n_layers

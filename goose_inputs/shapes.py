@@ -18,7 +18,7 @@ class ModelShape:
     vocab: int
     rope_base: float = 10000.0
     rms_eps: float = 1e-5
-    dtype: str = "bf16"  # storage type of weights and KV cache: "bf16" or "f32"
+    dtype: str = "bf16"  # storage type of weights and KV cache: "bf16", "f16" or "f32"
     n_kv_heads: int = 0  # key/value heads (grouped-query attention); 0 = as many as query heads
     qk_norm: bool = False  # RMSNorm over head_dim on q and k before the rotary embedding
 
@@ -39,7 +39,7 @@ class ModelShape:
         return q * h + 2 * kv * h + h * q + 3 * f * h
 
     def weight_bytes_per_layer(self) -> int:
-        return self.layer_param_count() * (2 if self.dtype == "bf16" else 4)
+        return self.layer_param_count() * (4 if self.dtype == "f32" else 2)
 
 
 SHAPES = {
@@ -56,6 +56,11 @@ SHAPES = {
     "llama3_8b": ModelShape("llama3_8b", 32, 4096, 32, 128, 14336, 128256, rope_base=500000.0, n_kv_heads=8),
     "qwen3_8b": ModelShape("qwen3_8b", 36, 4096, 32, 128, 12288, 151936, rope_base=1000000.0, rms_eps=1e-6,
                            n_kv_heads=8, qk_norm=True),
+    # fp16 storage, the precision the paper runs in (App. C): oracle-scale models and the 7B shape
+    "tiny_f16": ModelShape("tiny_f16", 2, 256, 4, 64, 688, 1024, dtype="f16"),
+    "small_gqa_qknorm_f16": ModelShape("small_gqa_qknorm_f16", 3, 1024, 8, 128, 2752, 4096, dtype="f16",
+                                       n_kv_heads=2, qk_norm=True, rms_eps=1e-6),
+    "7b_f16": ModelShape("7b_f16", 32, 4096, 32, 128, 11008, 32000, dtype="f16"),
     # oracle-scale models with the same structure
     "tiny_gqa_bf16": ModelShape("tiny_gqa_bf16", 2, 256, 4, 64, 688, 1024, dtype="bf16", n_kv_heads=2),
     "small_gqa_qknorm_bf16": ModelShape("small_gqa_qknorm_bf16", 3, 1024, 8, 128, 2752, 4096, dtype="bf16",

@@ -75,7 +75,7 @@ def gen_normal(seed: int, tensor_id: int, shape, std: float, dtype: torch.dtype,
 
 
 def _torch_dtype(shape_dtype: str) -> torch.dtype:
-    return torch.bfloat16 if shape_dtype == "bf16" else torch.float32
+    return {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[shape_dtype]
 
 
 def norm_gain(shape, seed: int, tensor_id: int, jitter: float, device="cpu", width: int = 0) -> torch.Tensor:

@@ -34,13 +34,14 @@
  * other model families of Sec. 5.1).  Raw weight matrices are row-major [out][in].
  *
  * Storage types.  desc.dtype selects the storage type T of weights, KV cache and gains:
- * GOOSE_DTYPE_BF16 (MFMA kernels, fp32 accumulation) or GOOSE_DTYPE_F32 (plain fp32
- * kernels for small models).  The residual stream x is always fp32 [B][hidden].
+ * GOOSE_DTYPE_BF16 or GOOSE_DTYPE_F16 (the precision the paper runs in, App. C; both: MFMA
+ * kernels on 16-bit operands, fp32 accumulation) or GOOSE_DTYPE_F32 (plain fp32 kernels for
+ * small models).  The residual stream x is always fp32 [B][hidden].
  *
  * KV cache: two allocations of n_layers * n_kv_heads * cap * head_dim elements each, one KV head's
  * cap * head_dim elements contiguous, cap a multiple of 64.  K is stored after the rotary embedding.
  *   GOOSE_DTYPE_F32:  K[layer][kv head][slot][d];  V TRANSPOSED, Vt[layer][kv head][d][slot].
- *   GOOSE_DTYPE_BF16: both in MFMA OPERAND ORDER, in blocks of 32 slots, so that the attention
+ *   GOOSE_DTYPE_BF16, GOOSE_DTYPE_F16: both in MFMA OPERAND ORDER, in blocks of 32 slots, so that the attention
  *   kernel streams them with one coalesced 16-byte load per lane and no re-arrangement.
  *   With g = slot, kk = g % 32, c = head-dim column, the element offset inside one head is
  *     K: (((g/32)*(d/16) + c/16)*64 + i + 32*((c/8)%2))*8 + c%8,
@@ -69,7 +70,7 @@ typedef enum {
   GOOSE_ERR_UNSUPPORTED = -6
 } goose_status;
 
-enum { GOOSE_DTYPE_BF16 = 0, GOOSE_DTYPE_F32 = 1 };
+enum { GOOSE_DTYPE_BF16 = 0, GOOSE_DTYPE_F32 = 1, GOOSE_DTYPE_F16 = 2 };
 enum { GOOSE_MAX_B = 128 };
 /* Most rows (nodes of all requests, each request rounded up to 32) one batched pass may stack. */
 enum { GOOSE_MAX_ROWS = 512 };
@@ -79,9 +80,9 @@ typedef struct {
   float rope_base, rms_eps;
   int32_t dtype;      /* GOOSE_DTYPE_* */
   int32_t n_kv_heads; /* key/value heads; 0 = n_heads.  Must divide n_heads: query head h reads KV head
-                         h / (n_heads / n_kv_heads) (grouped-query attention; bf16 models only) */
+                         h / (n_heads / n_kv_heads) (grouped-query attention; 16-bit models only) */
   int32_t qk_norm;    /* != 0: RMSNorm over head_dim (gains gq, gk, eps = rms_eps) on every head of q and k
-                         before the rotary embedding (bf16 models only) */
+                         before the rotary embedding (16-bit models only) */
 } goose_model_desc;
 
 /* Raw weights of one decoder layer as a checkpoint stores them: device pointers,
@@ -117,7 +118,7 @@ void goose_destroy(goose_ctx* ctx);
 int goose_check_parent(const int32_t* h_parent, int B);
 
 /* ---- weight packing (once, at load time) -------------------------------------------
- * The kernels stream weights from a packed copy: for bf16 each matrix is re-tiled so
+ * The kernels stream weights from a packed copy: for the 16-bit types each matrix is re-tiled so
  * that one wavefront load instruction reads 1 KiB of consecutive bytes that is exactly
  * one MFMA operand (32 output rows x 16 inputs); q,k,v rows are concatenated and
  * gate/up rows interleaved in blocks of 32.  For fp32 the blob holds plain row-major
@@ -214,7 +215,7 @@ int goose_verify_step(goose_ctx* ctx, const goose_model_ptrs* model, const goose
  * the rounded-up B must not exceed the context's max_rows (goose_create_batched), each B its max_B.
  * Projections, norms and the LM head run once over all rows (beyond 128 rows in chunks of 128 that
  * share the weight stream through the L2 cache); the attention runs on every request's own caches
- * as one launch per tree-size class; walk and compaction run per request.  bf16 models only.
+ * as one launch per tree-size class; walk and compaction run per request.  16-bit models only.
  * d_argmax_all: int32 [max_rows], receives every row's prediction (request r's rows start
  * at the sum of round_up(B, 32) of the requests before it).  All pointers DEVICE; P of a request is
  * read from *d_P (P_max: host upper bound, as in goose_verify_step) and updated in place. */
@@ -291,11 +292,11 @@ double goose_ema_update(double p_hat, int accepted_spine, int offered_spine, dou
  * array that is not topological.  Synchronises `stream`. */
 int goose_device_flags(goose_ctx* ctx, void* stream, int32_t* h_flags_out);
 
-/* ---- the projection kernel on its own (unit tests and tuning; bf16 only) ---------------------
+/* ---- the projection kernel on its own (unit tests and tuning; dtype = GOOSE_DTYPE_BF16 or _F16) ---
  * out[m][n] = sum_k A[m][k] * W[n][k] for the skinny-M shapes of the pass (M = B <= 128 tree nodes;
  * up to GOOSE_MAX_ROWS stacked rows of a batch, computed in chunks of 128 rows).
- * goose_pack_matrix re-tiles a row-major bf16 W[N][K] into goose_packed_matrix_bytes(N, K) bytes
- * (N padded to 32, K to 128, zero filled).  goose_gemm_packed multiplies: d_a is bf16 with
+ * goose_pack_matrix re-tiles a row-major 16-bit W[N][K] into goose_packed_matrix_bytes(N, K) bytes
+ * (N padded to 32, K to 128, zero filled).  goose_gemm_packed multiplies: d_a is 16-bit with
  * round_up(B,32) readable rows (round_up(B,128) when B > 128) of lda >= round_up(K,128) elements
  * (columns K.. and rows B.. must be finite),
  * nw = 2 or 4 column tiles per workgroup, ksplit = split-K factor (every split non-empty).
@@ -303,11 +304,11 @@ int goose_device_flags(goose_ctx* ctx, void* stream, int32_t* h_flags_out);
  * the first index, rows < B (other rows are not written). */
 size_t goose_packed_matrix_bytes(int N, int K);
 int goose_pack_matrix(const void* d_w, int N, int K, void* d_packed, void* stream);
-int goose_gemm_packed(const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, int ksplit,
+int goose_gemm_packed(int dtype, const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, int ksplit,
                       float* d_partials, void* stream);
 /* Same product with the fused SwiGLU epilogue: the N rows of W (N a multiple of 64) alternate in blocks
- * of 32 between gate rows and up rows; d_h bf16 [B][ldh] receives silu(gate) * up, N/2 columns. */
-int goose_gemm_swiglu_packed(const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, void* d_h,
+ * of 32 between gate rows and up rows; d_h 16-bit [B][ldh] receives silu(gate) * up, N/2 columns. */
+int goose_gemm_swiglu_packed(int dtype, const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, void* d_h,
                              int ldh, void* stream);
 
 /* ---- diagnostics: per-kernel timing --------------------------------------------------------

@@ -24,7 +24,8 @@ EXPORTS = [
     "goose_cycle_mode", "goose_verify_step_batched",
 ]
 
-GOOSE_DTYPE_BF16, GOOSE_DTYPE_F32 = 0, 1
+GOOSE_DTYPE_BF16, GOOSE_DTYPE_F32, GOOSE_DTYPE_F16 = 0, 1, 2
+DTYPE_CODES = {"bf16": GOOSE_DTYPE_BF16, "f32": GOOSE_DTYPE_F32, "f16": GOOSE_DTYPE_F16}
 
 
 class GooseError(RuntimeError):
@@ -87,7 +88,7 @@ class ModelDesc:
 
     def _c(self):
         return _Desc(self.n_layers, self.hidden, self.n_heads, self.head_dim, self.ffn, self.vocab,
-                     self.rope_base, self.rms_eps, GOOSE_DTYPE_BF16 if self.dtype == "bf16" else GOOSE_DTYPE_F32,
+                     self.rope_base, self.rms_eps, DTYPE_CODES[self.dtype],
                      self.n_kv_heads, int(self.qk_norm))
 
 
@@ -136,8 +137,8 @@ def load_library():
     lib.goose_packed_matrix_bytes.argtypes = [C.c_int, C.c_int]
     lib.goose_packed_matrix_bytes.restype = C.c_size_t
     lib.goose_pack_matrix.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
-    lib.goose_gemm_packed.argtypes = [C.c_void_p, C.c_int, C.c_void_p] + [C.c_int] * 5 + [C.c_void_p, C.c_void_p]
-    lib.goose_gemm_swiglu_packed.argtypes = [C.c_void_p, C.c_int, C.c_void_p] + [C.c_int] * 4 + [C.c_void_p, C.c_int,
+    lib.goose_gemm_packed.argtypes = [C.c_int, C.c_void_p, C.c_int, C.c_void_p] + [C.c_int] * 5 + [C.c_void_p, C.c_void_p]
+    lib.goose_gemm_swiglu_packed.argtypes = [C.c_int, C.c_void_p, C.c_int, C.c_void_p] + [C.c_int] * 4 + [C.c_void_p, C.c_int,
                                                                                                 C.c_void_p]
     lib.goose_profile_enable.argtypes = [C.c_void_p, C.c_int]
     lib.goose_profile_kinds.argtypes = []
@@ -248,14 +249,20 @@ def goose_pack_matrix(w, N, K, packed):
     _check(load_library().goose_pack_matrix(_ptr(w), N, K, _ptr(packed), _stream()), "goose_pack_matrix")
 
 
+def _dtype_code(t):
+    import torch
+    return {torch.bfloat16: GOOSE_DTYPE_BF16, torch.float16: GOOSE_DTYPE_F16}[t.dtype]
+
+
 def goose_gemm_packed(a, lda, packed, N, K, B, nw, ksplit, partials):
-    _check(load_library().goose_gemm_packed(_ptr(a), lda, _ptr(packed), N, K, B, nw, ksplit, _ptr(partials), _stream()),
-           "goose_gemm_packed")
+    """a: bf16 or fp16 tensor (its dtype selects the kernel); packed: goose_pack_matrix of weights of the same type."""
+    _check(load_library().goose_gemm_packed(_dtype_code(a), _ptr(a), lda, _ptr(packed), N, K, B, nw, ksplit,
+                                            _ptr(partials), _stream()), "goose_gemm_packed")
 
 
 def goose_gemm_swiglu_packed(a, lda, packed, N, K, B, nw, h, ldh):
-    _check(load_library().goose_gemm_swiglu_packed(_ptr(a), lda, _ptr(packed), N, K, B, nw, _ptr(h), ldh, _stream()),
-           "goose_gemm_swiglu_packed")
+    _check(load_library().goose_gemm_swiglu_packed(_dtype_code(a), _ptr(a), lda, _ptr(packed), N, K, B, nw, _ptr(h), ldh,
+                                                   _stream()), "goose_gemm_swiglu_packed")
 
 
 def goose_copy_probe(src, dst, nbytes):

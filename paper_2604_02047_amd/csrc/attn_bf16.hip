@@ -1,6 +1,6 @@
 // Tree-masked attention of the B draft-node queries over the cached prefix plus their own
 // ancestors (Sec. 4, tree attention mask), fused with the rotary embedding of q and k and the
-// write of the new K/V rows; bf16 operands, fp32 softmax, for gfx950.
+// write of the new K/V rows; bf16 or fp16 operands, fp32 softmax, for gfx950.
 //
 // All B queries of a head share the same keys, so the B nodes are the N dimension of an MFMA and
 // every K/V byte fetched from HBM is used B times.  The caches are stored in MFMA OPERAND ORDER
@@ -10,7 +10,7 @@
 // barriers.
 //
 // Per 32-key block and 32-query tile:
-//     S^T[key][query]  = K . Q^T          (v_mfma_f32_32x32x16_bf16, rows = keys)
+//     S^T[key][query]  = K . Q^T          (v_mfma_f32_32x32x16_{bf16,f16}, rows = keys)
 //     online softmax over keys: each lane owns ONE query (column l%32) and 16 keys, so the
 //     running max / sum / rescale are per-lane scalars plus one exchange with the twin lane l^32;
 //     O^T[d][query]   += V^T . P^T        (rows = head-dim, columns = the same queries).
@@ -24,14 +24,13 @@
 // cycles), and attends to them under the ancestor mask.  Every wavefront rotates its own q
 // operand from the projection slices (lane-local: the rotation pairs (j, j+d/2) live in the same
 // lane).  Groups are merged through LDS; splits write (max, sum, unnormalised O) partials that
-// k_attn_merge combines in fixed order (a single split writes the normalised bf16 rows itself).
+// k_attn_merge combines in fixed order (a single split writes the normalised 16-bit rows itself).
 
 #include "goose_internal.h"
+#include "mma16.h"
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -59,23 +58,28 @@ __device__ inline size_t v_elem_off(int g, int c) {
 // what the kernels need of one request (see AttnSeg); the table travels as a kernel argument
 struct SegDev {
   int32_t row0, B;
-  bf16_t* kc;
-  bf16_t* vc;
+  void* kc;
+  void* vc;
   const int32_t* dP;
   const uint64_t* mask;
 };
 struct SegTable { SegDev s[ATTN_MAX_SEGS]; };
 
-template <int D, int NG, int NQH>
+// F16: fp16 instead of bf16 storage (caches, operands, probabilities, output).
+template <int D, int NG, int NQH, bool F16>
 __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
     const float* part, int ks, size_t part_stride, size_t part_ld, int n_heads, int n_kv_heads, const float2* cs,
-    int cap, const bf16_t* __restrict__ gq, const bf16_t* __restrict__ gk, float eps, float* __restrict__ att_o,
-    float* __restrict__ att_ml, int Bpad, bf16_t* o_out, int ldo, const SegTable segs) {
+    int cap, const typename Mma16<F16>::T* __restrict__ gq, const typename Mma16<F16>::T* __restrict__ gk, float eps,
+    float* __restrict__ att_o, float* __restrict__ att_ml, int Bpad, typename Mma16<F16>::T* o_out, int ldo,
+    const SegTable segs) {
+  typedef typename Mma16<F16>::T T;
+  typedef typename Mma16<F16>::v8 op8;
+  typedef typename Mma16<F16>::v4 op4;
   // this workgroup's request: its rows of the stacked buffers, its caches, length and mask
   const SegDev& sg = segs.s[blockIdx.z];
   const int B = sg.B, row0 = sg.row0;
-  bf16_t* const kc = sg.kc;
-  bf16_t* const vc = sg.vc;
+  T* const kc = static_cast<T*>(sg.kc);
+  T* const vc = static_cast<T*>(sg.vc);
   const uint64_t* const mask = sg.mask;
   part += (size_t)row0 * part_ld;
   cs += (size_t)row0 * (D / 2);
@@ -134,8 +138,8 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   const int ntail = last ? (nbt - g + NG - 1) / NG : 0;
   const int total = nblk + (ntail > 0 ? ntail : 0);
 
-  const bf16_t* kh = kc + (size_t)kvh * cap * D;
-  const bf16_t* vh = vc + (size_t)kvh * cap * D;
+  const T* kh = kc + (size_t)kvh * cap * D;
+  const T* vh = vc + (size_t)kvh * cap * D;
   // One block of operands in registers.  The K pieces are free again after the first MFMA chain
   // and the V pieces after the second, so the next block's loads are issued right there: they fly
   // during the softmax and the second chain (the loop below exists once: code executed once per
@@ -233,7 +237,7 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
 #pragma unroll
           for (int off = 1; off < D / 8; off <<= 1) ss += __shfl_xor(ss, off, 64);
           const float rstd = 1.0f / sqrtf(ss / (float)D + eps);
-          const bf16_t* g = w == 0 ? gq : gk;
+          const T* g = w == 0 ? gq : gk;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             acc[u][2 * w][e] *= rstd * (float)g[j0 + e];
@@ -249,35 +253,35 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
       const f32x4 c01 = *reinterpret_cast<const f32x4*>(cs + (size_t)i * (D / 2) + j0);      // cos,sin of j0, j0+1
       const f32x4 c23 = *reinterpret_cast<const f32x4*>(cs + (size_t)i * (D / 2) + j0 + 2);  // ... j0+2, j0+3
       const float co[4] = {c01[0], c01[2], c23[0], c23[2]}, si[4] = {c01[1], c01[3], c23[1], c23[3]};
-      bf16x4 rl, rh;
+      op4 rl, rh;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        rl[e] = (__bf16)(acc[u][0][e] * co[e] - acc[u][1][e] * si[e]);
-        rh[e] = (__bf16)(acc[u][1][e] * co[e] + acc[u][0][e] * si[e]);
+        rl[e] = (T)(acc[u][0][e] * co[e] - acc[u][1][e] * si[e]);
+        rh[e] = (T)(acc[u][1][e] * co[e] + acc[u][0][e] * si[e]);
       }
-      *reinterpret_cast<bf16x4*>(Qs + i * KROW + j0 * 2) = rl;
-      *reinterpret_cast<bf16x4*>(Qs + i * KROW + (j0 + D / 2) * 2) = rh;
+      *reinterpret_cast<op4*>(Qs + i * KROW + j0 * 2) = rl;
+      *reinterpret_cast<op4*>(Qs + i * KROW + (j0 + D / 2) * 2) = rh;
       if (last && i < rows) {  // rows of the tree's blocks beyond B are zero (kv false)
-        bf16x4 kl, kh4, vl, vh4;
+        op4 kl, kh4, vl, vh4;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          kl[e] = (__bf16)(acc[u][2][e] * co[e] - acc[u][3][e] * si[e]);
-          kh4[e] = (__bf16)(acc[u][3][e] * co[e] + acc[u][2][e] * si[e]);
-          vl[e] = (__bf16)acc[u][4][e];
-          vh4[e] = (__bf16)acc[u][5][e];
+          kl[e] = (T)(acc[u][2][e] * co[e] - acc[u][3][e] * si[e]);
+          kh4[e] = (T)(acc[u][3][e] * co[e] + acc[u][2][e] * si[e]);
+          vl[e] = (T)acc[u][4][e];
+          vh4[e] = (T)acc[u][5][e];
         }
         if (kv[u] && tail_writer) {
           // key row of slot P+i into the cache: columns j0..j0+3 sit in chunk (j0/16, (j0/8)%2) at j0%8
-          bf16_t* kw = const_cast<bf16_t*>(kh);
-          *reinterpret_cast<bf16x4*>(kw + k_chunk_off<D>(P + i, j0 >> 4, (j0 >> 3) & 1) + (j0 & 7)) = kl;
-          *reinterpret_cast<bf16x4*>(kw + k_chunk_off<D>(P + i, (j0 + D / 2) >> 4, (j0 >> 3) & 1) + (j0 & 7)) = kh4;
+          T* kw = const_cast<T*>(kh);
+          *reinterpret_cast<op4*>(kw + k_chunk_off<D>(P + i, j0 >> 4, (j0 >> 3) & 1) + (j0 & 7)) = kl;
+          *reinterpret_cast<op4*>(kw + k_chunk_off<D>(P + i, (j0 + D / 2) >> 4, (j0 >> 3) & 1) + (j0 & 7)) = kh4;
         }
-        *reinterpret_cast<bf16x4*>(Kt + i * KROW + j0 * 2) = kl;
-        *reinterpret_cast<bf16x4*>(Kt + i * KROW + (j0 + D / 2) * 2) = kh4;
+        *reinterpret_cast<op4*>(Kt + i * KROW + j0 * 2) = kl;
+        *reinterpret_cast<op4*>(Kt + i * KROW + (j0 + D / 2) * 2) = kh4;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          *reinterpret_cast<__bf16*>(Vt + (j0 + e) * VROW + i * 2) = vl[e];
-          *reinterpret_cast<__bf16*>(Vt + (j0 + D / 2 + e) * VROW + i * 2) = vh4[e];
+          *reinterpret_cast<T*>(Vt + (j0 + e) * VROW + i * 2) = vl[e];
+          *reinterpret_cast<T*>(Vt + (j0 + D / 2 + e) * VROW + i * 2) = vh4[e];
         }
       }
     }
@@ -286,9 +290,9 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
 
   // ---- this wavefront's q operand and ancestor row
   const int qi = qh * 32 + l31;
-  bf16x8 qf[NS];
+  op8 qf[NS];
 #pragma unroll
-  for (int s = 0; s < NS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(Qs + qi * KROW + (16 * s + 8 * hh) * 2);
+  for (int s = 0; s < NS; ++s) qf[s] = *reinterpret_cast<const op8*>(Qs + qi * KROW + (16 * s + 8 * hh) * 2);
   uint64_t mw0 = 0, mw1 = 0;
   if (qi < B) {
     const int W = (B + 63) >> 6;
@@ -300,10 +304,10 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   // ---- the tree's values into the cache, node index fastest so that neighbouring lanes fill
   // neighbouring bytes (the keys went out above)
   if (last && tail_writer) {
-    bf16_t* vw = const_cast<bf16_t*>(vh);
+    T* vw = const_cast<T*>(vh);
     for (int it = tid; it < rows * D; it += NTHR) {
       const int i = it % rows, c = it / rows;
-      if (i < B) vw[v_elem_off<D>(P + i, c)] = *reinterpret_cast<const bf16_t*>(Vt + c * VROW + i * 2);
+      if (i < B) vw[v_elem_off<D>(P + i, c)] = *reinterpret_cast<const T*>(Vt + c * VROW + i * 2);
     }
   }
 
@@ -337,7 +341,7 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
     for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
     for (int s = 0; s < NS; ++s)
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[s]), qf[s], sacc, 0, 0, 0);
+      sacc = Mma16<F16>::mfma(__builtin_bit_cast(op8, kreg[s]), qf[s], sacc);
     if (idx + 1 < total) fetch_k(idx + 1);
     if (masked) {
 #pragma unroll
@@ -373,11 +377,11 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
       }
     }
     float psum = 0.f;
-    bf16x8 pf[2];
+    op8 pf[2];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       psum += p[r];
-      pf[r >> 3][r & 7] = (__bf16)p[r];
+      pf[r >> 3][r & 7] = (T)p[r];
     }
     l_run = l_run * alpha + psum;
     // the running maximum settles after a few blocks: skip the rescale of O when no lane's maximum grew
@@ -391,8 +395,7 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
     for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
-        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vreg[dt * 2 + j]), pf[j],
-                                                           oacc[dt], 0, 0, 0);
+        oacc[dt] = Mma16<F16>::mfma(__builtin_bit_cast(op8, vreg[dt * 2 + j]), pf[j], oacc[dt]);
     if (idx + 1 < total) fetch_v(idx + 1);
   }
 
@@ -435,14 +438,14 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   if (qi >= B) return;
   if (nsplit == 1) {
     const float inv = 1.0f / l_tot;
-    bf16_t* orow = o_out + (size_t)qi * ldo + h * D;
+    T* orow = o_out + (size_t)qi * ldo + h * D;
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
-        bf16x4 v = {(__bf16)(oacc[dt][a * 4] * inv), (__bf16)(oacc[dt][a * 4 + 1] * inv),
-                    (__bf16)(oacc[dt][a * 4 + 2] * inv), (__bf16)(oacc[dt][a * 4 + 3] * inv)};
-        *reinterpret_cast<bf16x4*>(orow + dt * 32 + a * 8 + hh * 4) = v;
+        op4 v = {(T)(oacc[dt][a * 4] * inv), (T)(oacc[dt][a * 4 + 1] * inv),
+                    (T)(oacc[dt][a * 4 + 2] * inv), (T)(oacc[dt][a * 4 + 3] * inv)};
+        *reinterpret_cast<op4*>(orow + dt * 32 + a * 8 + hh * 4) = v;
       }
   } else {
     const size_t base = ((size_t)h * nsplit + split) * Bpad + row0 + qi;
@@ -462,8 +465,9 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
 }
 
 // o[q][h*D + c] = sum_s 2^(m_s - m) O_s[c] / sum_s 2^(m_s - m) l_s, splits taken in index order.
+template <typename T>
 __global__ void k_attn_merge(const float* __restrict__ att_o, const float* __restrict__ att_ml, int nsplit, int Bpad,
-                             int D, bf16_t* __restrict__ o, int ldo, const SegTable segs) {
+                             int D, T* __restrict__ o, int ldo, const SegTable segs) {
   const SegDev& sg = segs.s[blockIdx.z];
   if ((int)blockIdx.x >= sg.B) return;
   const int qi = sg.row0 + blockIdx.x, h = blockIdx.y, c = threadIdx.x;
@@ -476,7 +480,7 @@ __global__ void k_attn_merge(const float* __restrict__ att_o, const float* __res
     den += w * att_ml[base * 2 + 1];
     num += w * att_o[base * D + c];
   }
-  o[(size_t)qi * ldo + h * D + c] = (bf16_t)(num / den);
+  o[(size_t)qi * ldo + h * D + c] = (T)(num / den);
 }
 
 // (cos, sin) of pos[m] * base^(-2j/d) for every node m and pair j: the angle is reduced in double,
@@ -494,16 +498,22 @@ __global__ void k_rope_table(const int32_t* __restrict__ pos, const double* __re
 
 struct AttnArgs {
   const float* part; int ks; size_t part_stride, part_ld; int n_heads, n_kv;
-  const float2* cs; int cap; const bf16_t* gq; const bf16_t* gk; float eps;
-  float* att_o; float* att_ml; int Bpad; bf16_t* o; int ldo;
+  const float2* cs; int cap; const void* gq; const void* gk; float eps;
+  float* att_o; float* att_ml; int Bpad; void* o; int ldo; bool f16;
 };
+
+template <int D, int NG, int NQH, bool F16>
+int launch_t(dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable& t) {
+  typedef typename Mma16<F16>::T T;
+  hipLaunchKernelGGL((k_attn_fused<D, NG, NQH, F16>), grid, dim3(64 * NG * NQH), 0, st, a.part, a.ks, a.part_stride,
+                     a.part_ld, a.n_heads, a.n_kv, a.cs, a.cap, (const T*)a.gq, (const T*)a.gk, a.eps, a.att_o,
+                     a.att_ml, a.Bpad, (T*)a.o, a.ldo, t);
+  return goose_launch_status();
+}
 
 template <int D, int NG, int NQH>
 int launch_cfg(dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable& t) {
-  hipLaunchKernelGGL((k_attn_fused<D, NG, NQH>), grid, dim3(64 * NG * NQH), 0, st, a.part, a.ks, a.part_stride,
-                     a.part_ld, a.n_heads, a.n_kv, a.cs, a.cap, a.gq, a.gk, a.eps, a.att_o, a.att_ml, a.Bpad, a.o,
-                     a.ldo, t);
-  return goose_launch_status();
+  return a.f16 ? launch_t<D, NG, NQH, true>(grid, st, a, t) : launch_t<D, NG, NQH, false>(grid, st, a, t);
 }
 
 template <int D>
@@ -536,16 +546,17 @@ int pick_attn_splits(int n_heads, int keys_max, int max_splits) {
   return s;
 }
 
-int launch_attn_bf16(const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs, int n_heads,
-                     int n_kv_heads, int head_dim, int cap, const AttnSeg* segs, int nseg, int splits_or_0,
-                     int max_splits, int key_groups, const void* gq, const void* gk, float eps, float* att_o,
-                     float* att_ml, int Bpad, void* o, int ldo, hipStream_t st) {
+int launch_attn_16(int dtype, const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs,
+                   int n_heads, int n_kv_heads, int head_dim, int cap, const AttnSeg* segs, int nseg, int splits_or_0,
+                   int max_splits, int key_groups, const void* gq, const void* gk, float eps, float* att_o,
+                   float* att_ml, int Bpad, void* o, int ldo, hipStream_t st) {
+  if (dtype != GOOSE_DTYPE_BF16 && dtype != GOOSE_DTYPE_F16) return GOOSE_ERR_ARG;
   if (n_kv_heads < 1 || n_heads % n_kv_heads != 0 || (gq == nullptr) != (gk == nullptr)) return GOOSE_ERR_ARG;
   if (nseg < 1 || nseg > ATTN_MAX_SEGS || max_splits < 1 || (key_groups != 2 && key_groups != 4) || (cap & 31))
     return GOOSE_ERR_ARG;
   if (head_dim != 128 && head_dim != 64) return GOOSE_ERR_SHAPE;
-  const AttnArgs a{part, ks, part_stride, part_ld, n_heads, n_kv_heads, (const float2*)cs, cap, (const bf16_t*)gq,
-                   (const bf16_t*)gk, eps, att_o, att_ml, Bpad, (bf16_t*)o, ldo};
+  const AttnArgs a{part, ks, part_stride, part_ld, n_heads, n_kv_heads, (const float2*)cs, cap, gq, gk, eps,
+                   att_o, att_ml, Bpad, o, ldo, dtype == GOOSE_DTYPE_F16};
   // a 3-tile tree runs the 4-tile kernel, which reads projection rows up to row0 + 128
   auto tiles_of = [](int B) { const int qt = (B + 31) / 32; return qt >= 3 ? 4 : qt; };
   for (int r = 0; r < nseg; ++r) {
@@ -561,7 +572,7 @@ int launch_attn_bf16(const float* part, int ks, size_t part_stride, size_t part_
     for (int r = 0; r < nseg; ++r) {
       const AttnSeg& g = segs[r];
       if (tiles_of(g.B) != cls) continue;
-      t.s[n++] = SegDev{g.row0, g.B, (bf16_t*)g.kc, (bf16_t*)g.vc, g.dP, g.mask};
+      t.s[n++] = SegDev{g.row0, g.B, g.kc, g.vc, g.dP, g.mask};
       keys_max = g.P_max + g.B > keys_max ? g.P_max + g.B : keys_max;
       b_max = g.B > b_max ? g.B : b_max;
     }
@@ -572,8 +583,12 @@ int launch_attn_bf16(const float* part, int ks, size_t part_stride, size_t part_
     int rc = head_dim == 128 ? launch_d<128>(cls, key_groups, grid, st, a, t) : launch_d<64>(cls, key_groups, grid, st, a, t);
     if (rc != GOOSE_OK) return rc;
     if (splits == 1) continue;
-    hipLaunchKernelGGL(k_attn_merge, dim3(b_max, n_heads, n), dim3(head_dim), 0, st, att_o, att_ml, splits, Bpad,
-                       head_dim, (bf16_t*)o, ldo, t);
+    if (a.f16)
+      hipLaunchKernelGGL(k_attn_merge<f16_t>, dim3(b_max, n_heads, n), dim3(head_dim), 0, st, att_o, att_ml, splits,
+                         Bpad, head_dim, (f16_t*)o, ldo, t);
+    else
+      hipLaunchKernelGGL(k_attn_merge<bf16_t>, dim3(b_max, n_heads, n), dim3(head_dim), 0, st, att_o, att_ml, splits,
+                         Bpad, head_dim, (bf16_t*)o, ldo, t);
     rc = goose_launch_status();
     if (rc != GOOSE_OK) return rc;
   }

@@ -1,10 +1,11 @@
-// Skinny-M bf16 GEMM for gfx950: out[m][n] = sum_k A[m][k] * W[n][k], M = tree nodes (<= 128).
+// Skinny-M GEMM of 16-bit operands (bf16 or fp16) for gfx950: out[m][n] = sum_k A[m][k] * W[n][k],
+// M = tree nodes (<= 128).
 //
 // The pass is weight-bandwidth bound (every weight byte is used for only M multiply-adds), so
 // the kernel is organised around streaming W once, with wide fully-coalesced loads:
-//   * W is pre-tiled (launch_pack_bf16) into MFMA-operand order: tile (nt, kt) = 32 output
+//   * W is pre-tiled (launch_pack_16) into MFMA-operand order: tile (nt, kt) = 32 output
 //     rows x 16 inputs = 1 KiB, lane l of a wavefront owning W[nt*32 + l%32][kt*16 + 8*(l/32) .. +7].
-//     One global_load_dwordx4 per lane fetches a whole operand of v_mfma_f32_32x32x16_bf16 and
+//     One global_load_dwordx4 per lane fetches a whole operand of v_mfma_f32_32x32x16_{bf16,f16} and
 //     consecutive kt are consecutive in memory, so each wavefront reads one long contiguous run.
 //   * The M x K activation block is small and shared: the workgroup stages 128-wide K slices of it
 //     in LDS (double buffered) and every wavefront reads its A operands from there.
@@ -15,6 +16,7 @@
 #include <type_traits>
 
 #include "goose_internal.h"
+#include "mma16.h"
 #include <climits>
 
 namespace {
@@ -26,7 +28,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int KGRAN = 128;  // granularity of K padding and of split-K ranges (inputs)
 
 // ------------------------------------------------------------------------------------------
-// Re-tile raw row-major bf16 matrices.  Packed row n comes from
+// Re-tile raw row-major matrices of 16-bit elements (moved as bit patterns: bf16 or fp16).  Packed row n comes from
 //   PACK_PLAIN   : s0 row n
 //   PACK_QKV     : q|k|v stacked: rows_each rows of s0, then rows_kv rows of s1, then rows_kv rows of s2
 //   PACK_GATE_UP : blocks of 32 rows alternate gate (s0) / up (s1): block b -> (b&1 ? up : gate) rows (b>>1)*32..
@@ -83,13 +85,16 @@ __global__ __launch_bounds__(256) void k_pack_bf16(int mode, const bf16_t* __res
 // (largest, second largest, index of largest) triple per row, for the greedy argmax.
 // STREAM: the weights are read once by the whole grid (non-temporal loads keep them from
 // displacing the L2's other lines); false when several row chunks read them (see below).
-template <int MT, int NW, int EPI, int KC, int RING, bool STREAM = true>
-__global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict__ A, int lda,
+// F16: fp16 instead of bf16 operands (and SwiGLU output).
+template <int MT, int NW, int EPI, int KC, int RING, bool STREAM = true, bool F16 = false>
+__global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>::T* __restrict__ A, int lda,
                                                        const u32x4* __restrict__ Wp, int ntiles, int ksteps_total,
                                                        int stages_per_split, int B, void* __restrict__ out,
                                                        size_t ldo, size_t split_stride,
                                                        float4* __restrict__ top2, int n_valid, int gx, int nsplit,
                                                        int nchunk) {
+  typedef typename Mma16<F16>::T T;
+  typedef typename Mma16<F16>::v8 op8;
   constexpr int LDS_ROW = KC * 2 + 16;  // bytes; the 16-byte pad staggers rows across banks
   constexpr int NTHR = 64 * NW;
   constexpr int STEPS = KC / 16;                    // MFMA k-steps per stage
@@ -146,7 +151,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict_
   // what was issued RING stages ago; RING * (8 + APT) loads per wavefront stay outstanding.
   static_assert(RING == 2 || RING == 4, "ring depth");
   u32x4 areg[RING][APT];
-  const bf16_t* a_src[APT];
+  const T* a_src[APT];
   int a_dst[APT];
 #pragma unroll
   for (int i = 0; i < APT; ++i) {
@@ -184,12 +189,11 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict_
     const u32x4* pn = wbase + (size_t)(st + RING) * STEPS * 64;
 #pragma unroll
     for (int s = 0; s < STEPS; ++s) {
-      const bf16x8 b = __builtin_bit_cast(bf16x8, wreg[slot][s]);
+      const op8 b = __builtin_bit_cast(op8, wreg[slot][s]);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(
-            &lds[buf * STAGE_BYTES + mt * 32 * LDS_ROW + a_frag + s * 32]);
-        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mt], 0, 0, 0);
+        const op8 a = *reinterpret_cast<const op8*>(&lds[buf * STAGE_BYTES + mt * 32 * LDS_ROW + a_frag + s * 32]);
+        acc[mt] = Mma16<F16>::mfma(a, b, acc[mt]);
       }
       if (refill) wreg[slot][s] = STREAM ? __builtin_nontemporal_load(pn + s * 64) : pn[s * 64];
       __builtin_amdgcn_sched_barrier(0);
@@ -313,7 +317,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict_
     }
     __syncthreads();
     if (active && !(wave & 1)) {
-      bf16_t* hq = reinterpret_cast<bf16_t*>(out);
+      T* hq = reinterpret_cast<T*>(out);
       const int col = (tile >> 1) * 32 + (lane & 31);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
@@ -321,51 +325,57 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const bf16_t* __restrict_
         for (int r = 0; r < 16; ++r) {
           const int row = row_base + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
           const float g = acc[mt][r], u = swap[(mt * 16 + r) * 64 + lane];
-          if (row < B) hq[(size_t)row * ldo + col] = (bf16_t)(g / (1.0f + __expf(-g)) * u);
+          if (row < B) hq[(size_t)row * ldo + col] = (T)(g / (1.0f + __expf(-g)) * u);
         }
     }
   }
 }
 
-template <int MT, int NW, int EPI>
-int launch_one(const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit, void* out, size_t ldo,
-               size_t split_stride, hipStream_t st, void* top2 = nullptr, int n_valid = 0) {
-  const int ntiles = Npad / 32, ksteps = Kpad / 16;
-  const int gx = (ntiles + NW - 1) / NW;
-  const int nchunk = (B + MT * 32 - 1) / (MT * 32);  // more than 128 rows: chunks of 4 row tiles
-  const dim3 grid(nchunk == 1 ? gx * ksplit : (gx * ksplit + 7) / 8 * 8 * nchunk);
-  const int granules = Kpad / KGRAN;                      // split-K ranges are multiples of 128 inputs
-  const int gps = (granules + ksplit - 1) / ksplit;       // granules (= stages) per split
-  // two stages of each stream in flight measured best (four: every projection 2-3 us slower)
-  if constexpr (MT == 4) {
-    if (nchunk > 1) {  // the chunks of a column group share their weights through the L2: ordinary loads
-      hipLaunchKernelGGL((k_gemm_bf16<MT, NW, EPI, 128, 2, false>), grid, dim3(64 * NW), 0, st, (const bf16_t*)A, lda,
-                         (const u32x4*)Wp, ntiles, ksteps, gps, B, out, ldo, split_stride, (float4*)top2, n_valid, gx,
-                         ksplit, nchunk);
-      return goose_launch_status();
-    }
-  }
-  hipLaunchKernelGGL((k_gemm_bf16<MT, NW, EPI, 128, 2>), grid, dim3(64 * NW), 0, st, (const bf16_t*)A, lda,
-                     (const u32x4*)Wp, ntiles, ksteps, gps, B, out, ldo, split_stride, (float4*)top2, n_valid, gx,
-                     ksplit, nchunk);
+struct GemmCall {
+  const void* A; int lda; const void* Wp; int Npad, Kpad, B, ksplit; void* out; size_t ldo, split_stride;
+  hipStream_t st; void* top2; int n_valid; bool f16;
+};
+
+template <int MT, int NW, int EPI, bool STREAM, bool F16>
+int launch_k(const GemmCall& g, dim3 grid, int gx, int gps, int nchunk) {
+  hipLaunchKernelGGL((k_gemm_bf16<MT, NW, EPI, 128, 2, STREAM, F16>), grid, dim3(64 * NW), 0, g.st,
+                     (const typename Mma16<F16>::T*)g.A, g.lda, (const u32x4*)g.Wp, g.Npad / 32, g.Kpad / 16, gps, g.B,
+                     g.out, g.ldo, g.split_stride, (float4*)g.top2, g.n_valid, gx, g.ksplit, nchunk);
   return goose_launch_status();
 }
 
+template <int MT, int NW, int EPI>
+int launch_one(const GemmCall& g) {
+  const int ntiles = g.Npad / 32;
+  const int gx = (ntiles + NW - 1) / NW;
+  const int nchunk = (g.B + MT * 32 - 1) / (MT * 32);  // more than 128 rows: chunks of 4 row tiles
+  const dim3 grid(nchunk == 1 ? gx * g.ksplit : (gx * g.ksplit + 7) / 8 * 8 * nchunk);
+  const int granules = g.Kpad / KGRAN;                      // split-K ranges are multiples of 128 inputs
+  const int gps = (granules + g.ksplit - 1) / g.ksplit;     // granules (= stages) per split
+  // two stages of each stream in flight measured best (four: every projection 2-3 us slower)
+  if constexpr (MT == 4) {
+    if (nchunk > 1)  // the chunks of a column group share their weights through the L2: ordinary loads
+      return g.f16 ? launch_k<MT, NW, EPI, false, true>(g, grid, gx, gps, nchunk)
+                   : launch_k<MT, NW, EPI, false, false>(g, grid, gx, gps, nchunk);
+  }
+  return g.f16 ? launch_k<MT, NW, EPI, true, true>(g, grid, gx, gps, nchunk)
+               : launch_k<MT, NW, EPI, true, false>(g, grid, gx, gps, nchunk);
+}
+
 template <int NW, int EPI>
-int launch_mt(int MT, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit, void* out,
-              size_t ldo, size_t split_stride, hipStream_t st, void* top2 = nullptr, int n_valid = 0) {
+int launch_mt(int MT, const GemmCall& g) {
   switch (MT) {
-    case 1: return launch_one<1, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st, top2, n_valid);
-    case 2: return launch_one<2, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st, top2, n_valid);
-    case 3: return launch_one<3, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st, top2, n_valid);
-    case 4: return launch_one<4, NW, EPI>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, st, top2, n_valid);
+    case 1: return launch_one<1, NW, EPI>(g);
+    case 2: return launch_one<2, NW, EPI>(g);
+    case 3: return launch_one<3, NW, EPI>(g);
+    case 4: return launch_one<4, NW, EPI>(g);
   }
   return GOOSE_ERR_ARG;
 }
 
 }  // namespace
 
-int launch_pack_bf16(int mode, const void* s0, const void* s1, const void* s2, int rows_each, int K, int Npad,
+int launch_pack_16(int mode, const void* s0, const void* s1, const void* s2, int rows_each, int K, int Npad,
                      int Kpad, void* dst, hipStream_t st, int rows_kv) {
   if (rows_kv <= 0) rows_kv = rows_each;
   const size_t total = (size_t)(Npad / 32) * (Kpad / 16) * 64;
@@ -391,31 +401,40 @@ void pick_gemm_config(int Npad, int Kpad, int max_ksplit, int* nw_out, int* kspl
   *ksplit_out = ks;
 }
 
-int launch_gemm_top2_bf16(const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw, float* out,
-                          size_t ldo, void* top2, int n_valid, hipStream_t st) {
+static bool dtype16(int dtype, bool* f16) {
+  *f16 = dtype == GOOSE_DTYPE_F16;
+  return dtype == GOOSE_DTYPE_BF16 || dtype == GOOSE_DTYPE_F16;
+}
+
+int launch_gemm_top2_16(int dtype, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw,
+                        float* out, size_t ldo, void* top2, int n_valid, hipStream_t st) {
+  bool f16;
+  if (!dtype16(dtype, &f16)) return GOOSE_ERR_ARG;
   if (B < 1 || B > GOOSE_MAX_ROWS || (Npad & 31) || (Kpad % KGRAN) || !top2 || n_valid < 1 || n_valid > Npad)
     return GOOSE_ERR_ARG;
   const int MT = B > 128 ? 4 : (B + 31) / 32;
-  if (nw == 4) return launch_mt<4, EPI_TOP2>(MT, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st, top2, n_valid);
-  return launch_mt<2, EPI_TOP2>(MT, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st, top2, n_valid);
+  const GemmCall g{A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st, top2, n_valid, f16};
+  return nw == 4 ? launch_mt<4, EPI_TOP2>(MT, g) : launch_mt<2, EPI_TOP2>(MT, g);
 }
 
-int launch_gemm_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw, int ksplit,
-                     void* out, size_t ldo, size_t out_split_stride, hipStream_t st) {
+int launch_gemm_16(int dtype, int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw,
+                   int ksplit, void* out, size_t ldo, size_t out_split_stride, hipStream_t st) {
+  bool f16;
+  if (!dtype16(dtype, &f16)) return GOOSE_ERR_ARG;
   if (B < 1 || B > GOOSE_MAX_ROWS || (Npad & 31) || (Kpad % KGRAN) || ksplit < 1) return GOOSE_ERR_ARG;
   if (epi != EPI_PARTIAL && epi != EPI_SWIGLU) return GOOSE_ERR_ARG;
+  if (epi == EPI_SWIGLU && (ksplit != 1 || (Npad & 63))) return GOOSE_ERR_ARG;
   if (B > 128) {
     // the kernel blocked for the matrix cores; GOOSE_ROWS_KERNEL=0 (tuning aid) keeps the skinny kernel in row chunks
     static const bool rows_kernel = !getenv("GOOSE_ROWS_KERNEL") || atoi(getenv("GOOSE_ROWS_KERNEL")) != 0;
     if (rows_kernel)
-      return launch_gemm_rows_bf16(epi, A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st);
+      return launch_gemm_rows_16(dtype, epi, A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st);
   }
   const int MT = B > 128 ? 4 : (B + 31) / 32;
   if (epi == EPI_SWIGLU) {
-    if (ksplit != 1 || (Npad & 63)) return GOOSE_ERR_ARG;
-    if (nw == 4) return launch_mt<4, EPI_SWIGLU>(MT, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st);
-    return launch_mt<2, EPI_SWIGLU>(MT, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st);
+    const GemmCall g{A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st, nullptr, 0, f16};
+    return nw == 4 ? launch_mt<4, EPI_SWIGLU>(MT, g) : launch_mt<2, EPI_SWIGLU>(MT, g);
   }
-  if (nw == 4) return launch_mt<4, EPI_PARTIAL>(MT, A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st);
-  return launch_mt<2, EPI_PARTIAL>(MT, A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st);
+  const GemmCall g{A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st, nullptr, 0, f16};
+  return nw == 4 ? launch_mt<4, EPI_PARTIAL>(MT, g) : launch_mt<2, EPI_PARTIAL>(MT, g);
 }

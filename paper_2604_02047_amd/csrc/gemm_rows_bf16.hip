@@ -1,4 +1,4 @@
-// Many-row bf16 GEMM for gfx950: out[m][n] = sum_k A[m][k] * W[n][k] for the stacked rows of a
+// Many-row GEMM of 16-bit operands (bf16 or fp16) for gfx950: out[m][n] = sum_k A[m][k] * W[n][k] for the stacked rows of a
 // batch of requests, 128 < M <= 512 (the batch sweep of App. D).  Same operands and the same
 // results, bit for bit, as the skinny kernel of gemm_bf16.hip (each accumulator takes its k-steps
 // in ascending order there and here), but organised for the matrix cores rather than for the
@@ -23,10 +23,10 @@
 #include <type_traits>
 
 #include "goose_internal.h"
+#include "mma16.h"
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
@@ -34,11 +34,13 @@ constexpr int NW = 4;   // wavefronts per workgroup
 constexpr int NT = 2;   // column tiles per wavefront
 
 // KC: inputs per stage
-template <int MT, int EPI, int KC>
-__global__ __launch_bounds__(64 * NW) void k_gemm_rows(const bf16_t* A, int lda, const u32x4* __restrict__ Wp,
+template <int MT, int EPI, int KC, bool F16>
+__global__ __launch_bounds__(64 * NW) void k_gemm_rows(const typename Mma16<F16>::T* A, int lda, const u32x4* __restrict__ Wp,
                                                        int ntiles, int ksteps_total, int stages_per_split, int B,
                                                        void* __restrict__ out, size_t ldo, size_t split_stride, int gx,
                                                        int nsplit, int nchunk) {
+  typedef typename Mma16<F16>::T T;
+  typedef typename Mma16<F16>::v8 op8;
   constexpr int LDS_ROW = KC * 2 + 16;  // bytes; 9 x 16: rows start in different banks
   constexpr int NTHR = 64 * NW;
   constexpr int STEPS = KC / 16;
@@ -74,7 +76,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const bf16_t* A, int lda,
 
   // both operand streams run two stages ahead in registers (slots st % 2, compile-time indices)
   u32x4 areg[2][APT];
-  const bf16_t* a_src[APT];
+  const T* a_src[APT];
   int a_dst[APT];
 #pragma unroll
   for (int i = 0; i < APT; ++i) {
@@ -115,24 +117,24 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const bf16_t* A, int lda,
     if (refill) load_a(st + 2, slot_c);  // this slot's previous content (stage st) is in LDS already
     __builtin_amdgcn_sched_barrier(0);
     // the A operands of step s+1 are read from LDS before the matrix instructions of step s issue
-    bf16x8 af[2][MT];
+    op8 af[2][MT];
     auto read_a = [&](int s, int which) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
-        af[which][mt] = *reinterpret_cast<const bf16x8*>(&lds[buf * STAGE_BYTES + mt * 32 * LDS_ROW + a_frag + s * 32]);
+        af[which][mt] = *reinterpret_cast<const op8*>(&lds[buf * STAGE_BYTES + mt * 32 * LDS_ROW + a_frag + s * 32]);
     };
     read_a(0, 0);
 #pragma unroll
     for (int s = 0; s < STEPS; ++s) {
       if (s + 1 < STEPS) read_a(s + 1, (s + 1) & 1);
-      bf16x8 b[NT];
+      op8 b[NT];
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) b[nt] = __builtin_bit_cast(bf16x8, wreg[slot][s][nt]);
+      for (int nt = 0; nt < NT; ++nt) b[nt] = __builtin_bit_cast(op8, wreg[slot][s][nt]);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s & 1][mt], b[nt], acc[mt][nt], 0, 0, 0);
+          acc[mt][nt] = Mma16<F16>::mfma(af[s & 1][mt], b[nt], acc[mt][nt]);
       if (refill) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) wreg[slot][s][nt] = wbase[nt][((size_t)(st + 2) * STEPS + s) * 64];
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const bf16_t* A, int lda,
   } else {  // EPI_SWIGLU: column tile 2c holds gate rows, 2c+1 the matching up rows
     static_assert(NT == 2, "gate and up tile of a column block sit in one wavefront");
     if (tile0 + 1 >= ntiles) return;
-    bf16_t* hq = reinterpret_cast<bf16_t*>(out);
+    T* hq = reinterpret_cast<T*>(out);
     const int col = (tile0 >> 1) * 32 + (lane & 31);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -200,18 +202,18 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const bf16_t* A, int lda,
       for (int r = 0; r < 16; ++r) {
         const int row = row_base + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         const float g = acc[mt][0][r], u = acc[mt][1][r];
-        if (row < B) hq[(size_t)row * ldo + col] = (bf16_t)(g / (1.0f + __expf(-g)) * u);
+        if (row < B) hq[(size_t)row * ldo + col] = (T)(g / (1.0f + __expf(-g)) * u);
       }
   }
 }
 
-template <int MT, int EPI, int KC>
+template <int MT, int EPI, int KC, bool F16>
 int launch_rows(const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit, void* out, size_t ldo,
                 size_t split_stride, hipStream_t st) {
   constexpr int LDS_BYTES = 2 * MT * 32 * (KC * 2 + 16);
   static bool configured = false;  // more LDS than a kernel gets by default: ask once
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_rows<MT, EPI, KC>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_rows<MT, EPI, KC, F16>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (e != hipSuccess) { goose_note_hip_error(e, "hipFuncSetAttribute(k_gemm_rows)", __LINE__); return GOOSE_ERR_HIP; }
     configured = true;
@@ -222,7 +224,8 @@ int launch_rows(const void* A, int lda, const void* Wp, int Npad, int Kpad, int 
   const int granules = Kpad / 128;                        // split-K ranges are multiples of 128 inputs,
   const int gps = (granules + ksplit - 1) / ksplit;       // the same ranges as the skinny kernel's
   const dim3 grid((gx * ksplit + 7) / 8 * 8 * nchunk);
-  hipLaunchKernelGGL((k_gemm_rows<MT, EPI, KC>), grid, dim3(64 * NW), LDS_BYTES, st, (const bf16_t*)A, lda,
+  hipLaunchKernelGGL((k_gemm_rows<MT, EPI, KC, F16>), grid, dim3(64 * NW), LDS_BYTES, st,
+                     (const typename Mma16<F16>::T*)A, lda,
                      (const u32x4*)Wp, ntiles, ksteps, gps * (128 / KC), B, out, ldo, split_stride, gx, ksplit, nchunk);
   return goose_launch_status();
 }
@@ -230,13 +233,17 @@ int launch_rows(const void* A, int lda, const void* Wp, int Npad, int Kpad, int 
 }  // namespace
 
 // A must hold whole chunks of 128 readable rows.
-int launch_gemm_rows_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit,
-                          void* out, size_t ldo, size_t out_split_stride, hipStream_t st) {
+int launch_gemm_rows_16(int dtype, int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B,
+                        int ksplit, void* out, size_t ldo, size_t out_split_stride, hipStream_t st) {
+  if (dtype != GOOSE_DTYPE_BF16 && dtype != GOOSE_DTYPE_F16) return GOOSE_ERR_ARG;
+  const bool f16 = dtype == GOOSE_DTYPE_F16;
   if (B < 1 || B > GOOSE_MAX_ROWS || (Npad & 31) || (Kpad % 128) || ksplit < 1) return GOOSE_ERR_ARG;
   if (epi == EPI_SWIGLU) {
     if (ksplit != 1 || (Npad & 63)) return GOOSE_ERR_ARG;
-    return launch_rows<4, EPI_SWIGLU, 64>(A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st);
+    return f16 ? launch_rows<4, EPI_SWIGLU, 64, true>(A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st)
+               : launch_rows<4, EPI_SWIGLU, 64, false>(A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st);
   }
   if (epi != EPI_PARTIAL) return GOOSE_ERR_ARG;
-  return launch_rows<4, EPI_PARTIAL, 64>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st);
+  return f16 ? launch_rows<4, EPI_PARTIAL, 64, true>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st)
+             : launch_rows<4, EPI_PARTIAL, 64, false>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st);
 }

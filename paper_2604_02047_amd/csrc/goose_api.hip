@@ -19,7 +19,8 @@ void goose_note_hip_error(hipError_t e, const char* what, int line) {
 namespace {
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
-inline size_t elem_size(int dtype) { return dtype == GOOSE_DTYPE_BF16 ? 2 : 4; }
+inline bool is16(int dtype) { return dtype == GOOSE_DTYPE_BF16 || dtype == GOOSE_DTYPE_F16; }  // the MFMA path
+inline size_t elem_size(int dtype) { return is16(dtype) ? 2 : 4; }
 
 int env_int(const char* name, int dflt) {
   const char* v = getenv(name);
@@ -73,7 +74,7 @@ void compute_layouts(goose_ctx* c) {
   p.g2 = off; off = round_up_sz(off + (size_t)d.hidden * es, A);
   p.gq = off; off = round_up_sz(off + (size_t)d.head_dim * es, A);
   p.gk = off; off = round_up_sz(off + (size_t)d.head_dim * es, A);
-  if (d.dtype == GOOSE_DTYPE_BF16) {
+  if (is16(d.dtype)) {
     const size_t f32r = (size_t)round_up(d.ffn, 32);
     p.wqkv = off; off = round_up_sz(off + (size_t)round_up(c->Hq + 2 * c->Hkv, 32) * c->Kh * 2, A);
     p.wo = off;   off = round_up_sz(off + (size_t)round_up(d.hidden, 32) * c->Kq * 2, A);
@@ -89,7 +90,7 @@ void compute_layouts(goose_ctx* c) {
   PackedHeadLayout& hl = c->ph;
   hl.gf = 0;
   hl.wlm = round_up_sz((size_t)d.hidden * es, A);
-  hl.total = round_up_sz(hl.wlm + (d.dtype == GOOSE_DTYPE_BF16 ? (size_t)c->Vpad * c->Kh * 2
+  hl.total = round_up_sz(hl.wlm + (is16(d.dtype) ? (size_t)c->Vpad * c->Kh * 2
                                                                : (size_t)d.vocab * d.hidden * 4), A);
 }
 
@@ -171,12 +172,12 @@ int goose_create_batched(const goose_model_desc* desc, int max_B, int max_rows, 
   const goose_model_desc& d = *desc;
   if (d.n_layers < 1 || d.hidden < 1 || d.n_heads < 1 || d.head_dim < 2 || d.ffn < 1 || d.vocab < 1)
     return GOOSE_ERR_ARG;
-  if (d.dtype != GOOSE_DTYPE_BF16 && d.dtype != GOOSE_DTYPE_F32) return GOOSE_ERR_ARG;
+  if (!is16(d.dtype) && d.dtype != GOOSE_DTYPE_F32) return GOOSE_ERR_ARG;
   if (!(d.rope_base > 1.0f) || !(d.rms_eps >= 0.0f)) return GOOSE_ERR_ARG;
   if (d.head_dim % 8 != 0 || d.head_dim > 256) return GOOSE_ERR_SHAPE;
   const int n_kv = d.n_kv_heads > 0 ? d.n_kv_heads : d.n_heads;
   if (n_kv > d.n_heads || d.n_heads % n_kv != 0) return GOOSE_ERR_SHAPE;
-  if (d.dtype == GOOSE_DTYPE_BF16) {
+  if (is16(d.dtype)) {
     // MFMA kernels: 16-byte vector access to rows, two head sizes
     if (d.head_dim != 64 && d.head_dim != 128) return GOOSE_ERR_SHAPE;
     if (d.hidden % 8 != 0 || d.ffn % 8 != 0) return GOOSE_ERR_SHAPE;
@@ -268,22 +269,22 @@ int goose_pack_layer(goose_ctx* c, const goose_layer_weights* w, void* d_packed,
   const hipMemcpyKind D2D = hipMemcpyDeviceToDevice;
   GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.g1, w->g1, d.hidden * es, D2D, st));
   GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.g2, w->g2, d.hidden * es, D2D, st));
-  if (d.dtype == GOOSE_DTYPE_BF16) {
+  if (is16(d.dtype)) {
     if (d.qk_norm) {
       if (!w->gq || !w->gk) return GOOSE_ERR_ARG;
       GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.gq, w->gq, d.head_dim * elem_size(d.dtype), hipMemcpyDeviceToDevice, st));
       GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.gk, w->gk, d.head_dim * elem_size(d.dtype), hipMemcpyDeviceToDevice, st));
     }
-    int rc = launch_pack_bf16(PACK_QKV, w->wq, w->wk, w->wv, c->Hq, d.hidden, round_up(c->Hq + 2 * c->Hkv, 32), c->Kh,
+    int rc = launch_pack_16(PACK_QKV, w->wq, w->wk, w->wv, c->Hq, d.hidden, round_up(c->Hq + 2 * c->Hkv, 32), c->Kh,
                               base + c->pl.wqkv, st, c->Hkv);
     if (rc) return rc;
-    rc = launch_pack_bf16(PACK_PLAIN, w->wo, nullptr, nullptr, d.hidden, c->Hq, round_up(d.hidden, 32), c->Kq,
+    rc = launch_pack_16(PACK_PLAIN, w->wo, nullptr, nullptr, d.hidden, c->Hq, round_up(d.hidden, 32), c->Kq,
                           base + c->pl.wo, st);
     if (rc) return rc;
-    rc = launch_pack_bf16(PACK_GATE_UP, w->wg, w->wu, nullptr, d.ffn, d.hidden, 2 * round_up(d.ffn, 32), c->Kh,
+    rc = launch_pack_16(PACK_GATE_UP, w->wg, w->wu, nullptr, d.ffn, d.hidden, 2 * round_up(d.ffn, 32), c->Kh,
                           base + c->pl.wgu, st);
     if (rc) return rc;
-    return launch_pack_bf16(PACK_PLAIN, w->wd, nullptr, nullptr, d.hidden, d.ffn, round_up(d.hidden, 32), c->Fpad,
+    return launch_pack_16(PACK_PLAIN, w->wd, nullptr, nullptr, d.hidden, d.ffn, round_up(d.hidden, 32), c->Fpad,
                             base + c->pl.wd, st);
   }
   const size_t qb = (size_t)c->Hq * d.hidden * 4, fb = (size_t)d.ffn * d.hidden * 4;
@@ -303,8 +304,8 @@ int goose_pack_lm_head(goose_ctx* c, const void* d_gf, const void* d_wlm, void* 
   const goose_model_desc& d = c->d;
   char* base = (char*)d_packed;
   GOOSE_HIP_TRY(hipMemcpyAsync(base + c->ph.gf, d_gf, d.hidden * elem_size(d.dtype), hipMemcpyDeviceToDevice, st));
-  if (d.dtype == GOOSE_DTYPE_BF16)
-    return launch_pack_bf16(PACK_PLAIN, d_wlm, nullptr, nullptr, d.vocab, d.hidden, c->Vpad, c->Kh,
+  if (is16(d.dtype))
+    return launch_pack_16(PACK_PLAIN, d_wlm, nullptr, nullptr, d.vocab, d.hidden, c->Vpad, c->Kh,
                             base + c->ph.wlm, st);
   GOOSE_HIP_TRY(hipMemcpyAsync(base + c->ph.wlm, d_wlm, (size_t)d.vocab * d.hidden * 4, hipMemcpyDeviceToDevice, st));
   return GOOSE_OK;
@@ -351,13 +352,13 @@ static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, v
   }
   if (rc) return rc;
 
-  if (d.dtype == GOOSE_DTYPE_BF16) {
+  if (is16(d.dtype)) {
     const int Nqkv = round_up(Hq + 2 * c->Hkv, 32), Nh = round_up(H, 32), Ngu = 2 * round_up(d.ffn, 32);
     static const int splits_env = env_int("GOOSE_ATTN_SPLITS", 0);
     const GemmCfg cq = gemm_cfg(c, "GOOSE_CFG_QKV", Nqkv, c->Kh);
     int ks = cq.ks;
     { PROF(PK_GEMM_QKV);
-      rc = launch_gemm_bf16(EPI_PARTIAL, c->xn, c->Kh, w + c->pl.wqkv, Nqkv, c->Kh, B, cq.nw, ks, c->part,
+      rc = launch_gemm_16(d.dtype, EPI_PARTIAL, c->xn, c->Kh, w + c->pl.wqkv, Nqkv, c->Kh, B, cq.nw, ks, c->part,
                             c->part_ld, pstride, st); }
     if (rc) return rc;
     // rotary embedding of q and k, KV rows of the tree into the cache, tree attention: one kernel
@@ -365,7 +366,7 @@ static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, v
     const AttnSeg whole{0, B, P, d_kcache, d_vcache, dP, d_mask};
     if (nseg == 0) { segs = &whole; nseg = 1; }
     { PROF(PK_ATTN);
-      rc = launch_attn_bf16(c->part, ks, pstride, c->part_ld, c->rope_cs, d.n_heads, c->n_kv, d.head_dim, c->cap, segs,
+      rc = launch_attn_16(d.dtype, c->part, ks, pstride, c->part_ld, c->rope_cs, d.n_heads, c->n_kv, d.head_dim, c->cap, segs,
                             nseg, splits_env, c->max_splits, ng_env, d.qk_norm ? w + c->pl.gq : nullptr,
                             d.qk_norm ? w + c->pl.gk : nullptr, d.rms_eps, c->att_o, c->att_ml, c->Bpad, c->o, c->Kq,
                             st); }
@@ -373,7 +374,7 @@ static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, v
     const GemmCfg co = gemm_cfg(c, "GOOSE_CFG_O", Nh, c->Kq);
     ks = co.ks;
     { PROF(PK_GEMM_O);
-      rc = launch_gemm_bf16(EPI_PARTIAL, c->o, c->Kq, w + c->pl.wo, Nh, c->Kq, B, co.nw, ks, c->part, c->part_ld,
+      rc = launch_gemm_16(d.dtype, EPI_PARTIAL, c->o, c->Kq, w + c->pl.wo, Nh, c->Kq, B, co.nw, ks, c->part, c->part_ld,
                             pstride, st); }
     if (rc) return rc;
     // x += attention projection; x_hat = RMSNorm(x) * g2
@@ -383,12 +384,12 @@ static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, v
     if (rc) return rc;
     static const int gu_nw = env_int("GOOSE_GU_NW", 4) == 2 ? 2 : 4;
     { PROF(PK_GEMM_GATE_UP);
-      rc = launch_gemm_bf16(EPI_SWIGLU, c->xn, c->Kh, w + c->pl.wgu, Ngu, c->Kh, B, gu_nw, 1, c->h, c->Fpad, 0, st); }
+      rc = launch_gemm_16(d.dtype, EPI_SWIGLU, c->xn, c->Kh, w + c->pl.wgu, Ngu, c->Kh, B, gu_nw, 1, c->h, c->Fpad, 0, st); }
     if (rc) return rc;
     const GemmCfg cd = gemm_cfg(c, "GOOSE_CFG_DOWN", Nh, c->Fpad);
     ks = cd.ks;
     { PROF(PK_GEMM_DOWN);
-      rc = launch_gemm_bf16(EPI_PARTIAL, c->h, c->Fpad, w + c->pl.wd, Nh, c->Fpad, B, cd.nw, ks, c->part, c->part_ld,
+      rc = launch_gemm_16(d.dtype, EPI_PARTIAL, c->h, c->Fpad, w + c->pl.wd, Nh, c->Fpad, B, cd.nw, ks, c->part, c->part_ld,
                             pstride, st); }
     if (rc) return rc;
     // x += MLP output (and the following normalisation when its gain is known)
@@ -433,7 +434,7 @@ int goose_verify_layer(goose_ctx* c, const void* d_packed_layer, float* d_x, voi
   const int32_t* dP;
   rc = resolve_P(c, P, d_P, st, &dP);
   if (rc) return rc;
-  if (c->d.dtype == GOOSE_DTYPE_BF16) {
+  if (is16(c->d.dtype)) {
     PROF(PK_ROPE);
     rc = launch_rope_table(d_pos, c->inv_freq, B, c->d.head_dim, c->rope_cs, st);
     if (rc) return rc;
@@ -472,7 +473,7 @@ static int lm_head_impl(goose_ctx* c, const void* d_packed_head, const float* d_
     rc = launch_resid_norm(d.dtype, const_cast<float*>(d_x), d.hidden, nullptr, 0, 0, 0, w + c->ph.gf, d.rms_eps,
                            c->xn, c->Kh, B, st);
   if (rc) return rc;
-  if (d.dtype == GOOSE_DTYPE_BF16) {
+  if (is16(d.dtype)) {
     // the projection kernel reduces its own columns to (max, second, index) per row; logits are
     // written only on request (through the padded workspace when rows are no multiple of a tile)
     static const int lm_nw = env_int("GOOSE_LM_NW", 4) == 2 ? 2 : 4;
@@ -482,7 +483,7 @@ static int lm_head_impl(goose_ctx* c, const void* d_packed_head, const float* d_
     const size_t ld = out == c->logits ? (size_t)c->Vpad : (size_t)d.vocab;
     const int groups = (c->Vpad / 32 + lm_nw - 1) / lm_nw;
     { PROF(PK_LM_HEAD);
-      rc = launch_gemm_top2_bf16(c->xn, c->Kh, w + c->ph.wlm, c->Vpad, c->Kh, B, lm_nw, out, ld, c->top2, d.vocab, st); }
+      rc = launch_gemm_top2_16(d.dtype, c->xn, c->Kh, w + c->ph.wlm, c->Vpad, c->Kh, B, lm_nw, out, ld, c->top2, d.vocab, st); }
     if (rc) return rc;
     if (bounce)
       GOOSE_HIP_TRY(hipMemcpy2DAsync(d_logits_or_null, (size_t)d.vocab * 4, c->logits, (size_t)c->Vpad * 4,
@@ -549,7 +550,7 @@ int goose_verify_step(goose_ctx* c, const goose_model_ptrs* m, const goose_step_
   if (rc) return rc;
   rc = launch_embed(d.dtype, m->d_embed, io->d_tokens, B, d.hidden, d.vocab, c->s_x, st);
   if (rc) return rc;
-  if (d.dtype == GOOSE_DTYPE_BF16) {  // the tree's rotary angles, once for all layers
+  if (is16(d.dtype)) {  // the tree's rotary angles, once for all layers
     PROF(PK_ROPE);
     rc = launch_rope_table(c->s_pos, c->inv_freq, B, d.head_dim, c->rope_cs, st);
     if (rc) return rc;
@@ -587,7 +588,7 @@ int goose_verify_step_batched(goose_ctx* c, const goose_model_ptrs* m, const goo
   if (!c || !m || !reqs || !d_argmax_all || n_req < 1 || n_req > GOOSE_MAX_REQUESTS) return GOOSE_ERR_ARG;
   if (!m->d_embed || !m->d_packed_layers || !m->d_packed_head) return GOOSE_ERR_ARG;
   const goose_model_desc& d = c->d;
-  if (d.dtype != GOOSE_DTYPE_BF16) return GOOSE_ERR_SHAPE;
+  if (!is16(d.dtype)) return GOOSE_ERR_SHAPE;
   hipStream_t st = as_stream(stream);
   AttnSeg segs[GOOSE_MAX_REQUESTS];
   int rows = 0;
@@ -658,30 +659,30 @@ size_t goose_packed_matrix_bytes(int N, int K) {
 
 int goose_pack_matrix(const void* d_w, int N, int K, void* d_packed, void* stream) {
   if (!d_w || !d_packed || N < 1 || K < 1) return GOOSE_ERR_ARG;
-  return launch_pack_bf16(PACK_PLAIN, d_w, nullptr, nullptr, N, K, round_up(N, 32), round_up(K, 128), d_packed,
-                          as_stream(stream));
+  return launch_pack_16(PACK_PLAIN, d_w, nullptr, nullptr, N, K, round_up(N, 32), round_up(K, 128), d_packed,
+                        as_stream(stream));
 }
 
-int goose_gemm_swiglu_packed(const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, void* d_h,
+int goose_gemm_swiglu_packed(int dtype, const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, void* d_h,
                              int ldh, void* stream) {
   if (!d_a || !d_packed || !d_h || N < 64 || (N % 64) != 0 || K < 1) return GOOSE_ERR_ARG;
-  if (B < 1 || B > GOOSE_MAX_ROWS || (nw != 2 && nw != 4)) return GOOSE_ERR_ARG;
+  if (!is16(dtype) || B < 1 || B > GOOSE_MAX_ROWS || (nw != 2 && nw != 4)) return GOOSE_ERR_ARG;
   const int Kpad = round_up(K, 128);
   if (lda < Kpad || (lda % 8) != 0 || ldh < N / 2) return GOOSE_ERR_ARG;
-  return launch_gemm_bf16(EPI_SWIGLU, d_a, lda, d_packed, N, Kpad, B, nw, 1, d_h, (size_t)ldh, 0, as_stream(stream));
+  return launch_gemm_16(dtype, EPI_SWIGLU, d_a, lda, d_packed, N, Kpad, B, nw, 1, d_h, (size_t)ldh, 0, as_stream(stream));
 }
 
-int goose_gemm_packed(const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, int ksplit,
+int goose_gemm_packed(int dtype, const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, int ksplit,
                       float* d_partials, void* stream) {
   if (!d_a || !d_packed || !d_partials || N < 1 || K < 1) return GOOSE_ERR_ARG;
-  if (B < 1 || B > GOOSE_MAX_ROWS || (nw != 2 && nw != 4) || ksplit < 1) return GOOSE_ERR_ARG;
+  if (!is16(dtype) || B < 1 || B > GOOSE_MAX_ROWS || (nw != 2 && nw != 4) || ksplit < 1) return GOOSE_ERR_ARG;
   const int Npad = round_up(N, 32), Kpad = round_up(K, 128);
   if (lda < Kpad || (lda % 8) != 0) return GOOSE_ERR_ARG;
   const int nstages = Kpad / 128;
   if (ksplit > nstages || ((nstages + ksplit - 1) / ksplit) * (ksplit - 1) >= nstages) return GOOSE_ERR_ARG;
   const int rows = round_up(B, 32);
-  return launch_gemm_bf16(EPI_PARTIAL, d_a, lda, d_packed, Npad, Kpad, B, nw, ksplit, d_partials, (size_t)Npad,
-                          (size_t)rows * Npad, as_stream(stream));
+  return launch_gemm_16(dtype, EPI_PARTIAL, d_a, lda, d_packed, Npad, Kpad, B, nw, ksplit, d_partials, (size_t)Npad,
+                        (size_t)rows * Npad, as_stream(stream));
 }
 
 int goose_copy_probe(const void* d_src, void* d_dst, size_t bytes, void* stream) {

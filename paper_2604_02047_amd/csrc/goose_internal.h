@@ -106,25 +106,26 @@ int launch_gemm_f32(const float* A, int lda, const float* W, int N, int K, int M
 int launch_attn_f32(const float* q, int ldq, const float* kc, const float* vc, int n_heads, int head_dim, int cap,
                     const int32_t* dP, int B, const uint64_t* mask, float* o, int ldo, int P_max, hipStream_t st);
 
-// ---- bf16 path (gemm_bf16.hip, attn_bf16.hip)
+// ---- the MFMA path: 16-bit storage, dtype = GOOSE_DTYPE_BF16 or GOOSE_DTYPE_F16
+// (gemm_bf16.hip, gemm_rows_bf16.hip, attn_bf16.hip: the files are named for the first type built)
 enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
-// Re-tiles raw [rows][K] bf16 matrices into MFMA-operand order; Npad x Kpad zero padded.
+// Re-tiles raw [rows][K] matrices of 16-bit elements into MFMA-operand order; Npad x Kpad zero padded.
 // rows_each: rows of s0 (and of s1, s2 unless rows_kv > 0: then s1 and s2 have rows_kv rows each)
-int launch_pack_bf16(int mode, const void* s0, const void* s1, const void* s2, int rows_each, int K, int Npad,
-                     int Kpad, void* dst, hipStream_t st, int rows_kv = 0);
+int launch_pack_16(int mode, const void* s0, const void* s1, const void* s2, int rows_each, int K, int Npad,
+                   int Kpad, void* dst, hipStream_t st, int rows_kv = 0);
 enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_TOP2 = 2 };
-// out partials f32 [ksplit][Bpad][ldo] (EPI_PARTIAL) or bf16 h [Bpad][ldo] (EPI_SWIGLU, ksplit must be 1)
-int launch_gemm_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw, int ksplit,
-                     void* out, size_t ldo, size_t out_split_stride, hipStream_t st);
+// out partials f32 [ksplit][Bpad][ldo] (EPI_PARTIAL) or 16-bit h [Bpad][ldo] (EPI_SWIGLU, ksplit must be 1)
+int launch_gemm_16(int dtype, int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw,
+                   int ksplit, void* out, size_t ldo, size_t out_split_stride, hipStream_t st);
 // The same products for 128 < B <= GOOSE_MAX_ROWS stacked rows, blocked for the matrix cores
 // (gemm_rows_bf16.hip); A must hold whole chunks of 128 readable rows.
-int launch_gemm_rows_bf16(int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit,
-                          void* out, size_t ldo, size_t out_split_stride, hipStream_t st);
+int launch_gemm_rows_16(int dtype, int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B,
+                        int ksplit, void* out, size_t ldo, size_t out_split_stride, hipStream_t st);
 // Projection whose workgroups (nw column tiles each) also emit per-row (max, second max, index of
 // max) over their valid columns (< n_valid): top2 is float4 [B][ceil(Npad/32/nw)], index bits in .z.
 // `out` (f32 [B][ldo]) may be null when only the reduction is wanted.
-int launch_gemm_top2_bf16(const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw, float* out,
-                          size_t ldo, void* top2, int n_valid, hipStream_t st);
+int launch_gemm_top2_16(int dtype, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw,
+                        float* out, size_t ldo, void* top2, int n_valid, hipStream_t st);
 int launch_harvest_topk(const float* logits, size_t ld, int V, const int32_t* tokens, int B, int K, int table_rows,
                         int32_t* succ_ids, float* succ_scores, hipStream_t st);
 int launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
@@ -145,10 +146,10 @@ struct AttnSeg {
 enum { ATTN_MAX_SEGS = 16 };
 // Fused rotary embedding + KV-tail write + tree attention of `nseg` requests.  part: the q|k|v
 // projection as `ks` split-K slices of f32 [Bpad][part_ld]; cs: rotary table of all rows;
-// o: bf16 [Bpad][ldo].  Requests with the same number of 32-row query tiles share one launch
+// o: 16-bit [Bpad][ldo].  Requests with the same number of 32-row query tiles share one launch
 // (grid z = request).  splits_or_0: key splits per head, 0 = chosen here (at most max_splits).
-int launch_attn_bf16(const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs, int n_heads,
-                     int n_kv_heads, int head_dim, int cap, const AttnSeg* segs, int nseg, int splits_or_0,
-                     int max_splits, int key_groups, const void* gq, const void* gk, float eps, float* att_o,
-                     float* att_ml, int Bpad, void* o, int ldo, hipStream_t st);
+int launch_attn_16(int dtype, const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs,
+                   int n_heads, int n_kv_heads, int head_dim, int cap, const AttnSeg* segs, int nseg, int splits_or_0,
+                   int max_splits, int key_groups, const void* gq, const void* gk, float eps, float* att_o,
+                   float* att_ml, int Bpad, void* o, int ldo, hipStream_t st);
 int pick_attn_splits(int n_heads, int keys_max, int max_splits);

@@ -75,6 +75,12 @@ __device__ inline void store4<bf16_t>(bf16_t* p, float a, float b, float c, floa
   bf16x4 v = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
   *reinterpret_cast<bf16x4*>(p) = v;
 }
+template <>
+__device__ inline void store4<_Float16>(_Float16* p, float a, float b, float c, float d) {
+  typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+  f16x4 v = {(_Float16)a, (_Float16)b, (_Float16)c, (_Float16)d};
+  *reinterpret_cast<f16x4*>(p) = v;
+}
 
 template <typename T, int NTHR>
 __global__ __launch_bounds__(NTHR) void k_resid_norm(float* __restrict__ x, int H, const float* __restrict__ part,
@@ -546,6 +552,8 @@ int launch_build_mask(const int32_t* parent, int B, const int32_t* dP, uint64_t*
 int launch_embed(int dtype, const void* E, const int32_t* tokens, int B, int H, int V, float* x, hipStream_t st) {
   if (dtype == GOOSE_DTYPE_BF16)
     hipLaunchKernelGGL(k_embed<bf16_t>, dim3(B), dim3(256), 0, st, (const bf16_t*)E, tokens, H, V, x);
+  else if (dtype == GOOSE_DTYPE_F16)
+    hipLaunchKernelGGL(k_embed<_Float16>, dim3(B), dim3(256), 0, st, (const _Float16*)E, tokens, H, V, x);
   else
     hipLaunchKernelGGL(k_embed<float>, dim3(B), dim3(256), 0, st, (const float*)E, tokens, H, V, x);
   return goose_launch_status();
@@ -562,6 +570,13 @@ int launch_resid_norm(int dtype, float* x, int H, const float* part, int S, size
     else
       hipLaunchKernelGGL((k_resid_norm<bf16_t, 256>), dim3(B), dim3(256), 0, st, x, H, part, S, part_stride, part_ld,
                          (const bf16_t*)g, eps, (bf16_t*)xn, ldxn);
+  } else if (dtype == GOOSE_DTYPE_F16) {
+    if (big)
+      hipLaunchKernelGGL((k_resid_norm<_Float16, 1024>), dim3(B), dim3(1024), 0, st, x, H, part, S, part_stride,
+                         part_ld, (const _Float16*)g, eps, (_Float16*)xn, ldxn);
+    else
+      hipLaunchKernelGGL((k_resid_norm<_Float16, 256>), dim3(B), dim3(256), 0, st, x, H, part, S, part_stride, part_ld,
+                         (const _Float16*)g, eps, (_Float16*)xn, ldxn);
   } else {
     if (big)
       hipLaunchKernelGGL((k_resid_norm<float, 1024>), dim3(B), dim3(1024), 0, st, x, H, part, S, part_stride, part_ld,
@@ -630,7 +645,7 @@ int launch_compact(int elem_bytes, void* kall, void* vall, int n_layers, int n_h
                    const int32_t* dP, const int32_t* path, const int32_t* accept_len, int32_t* new_P,
                    hipStream_t st) {
   int rc;
-  if (elem_bytes == 2) {  // bf16: operand-ordered blocks
+  if (elem_bytes == 2) {  // bf16 / fp16 (moved as bit patterns): operand-ordered blocks
     if (head_dim == 128)
       hipLaunchKernelGGL(k_compact_tiled<128>, dim3(n_layers * n_heads), dim3(128), 0, st, (bf16_t*)kall, (bf16_t*)vall,
                          cap, dP, path, accept_len);

@@ -12,7 +12,7 @@ from .binding import GooseContext, ModelDesc
 
 
 def _torch_dtype(name):
-    return torch.bfloat16 if name == "bf16" else torch.float32
+    return {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[name]
 
 
 class GooseModel:
@@ -40,8 +40,8 @@ class GooseModel:
         del wl, gf
         assert cap % 64 == 0, "cap must be a multiple of 64"
         # One head's cache is cap * head_dim elements.  fp32 models: K[slot][d] and V transposed, Vt[d][slot];
-        # bf16 models: 32-key blocks in MFMA operand order (layout.py), kept here as flat vectors.
-        self.tiled = desc.dtype == "bf16"
+        # bf16 / fp16 models: 32-key blocks in MFMA operand order (layout.py), kept here as flat vectors.
+        self.tiled = desc.dtype in ("bf16", "f16")
         kvh = desc.kv_heads  # caches hold key/value heads (fewer than query heads under grouped queries)
         if self.tiled:
             self.kcache = torch.zeros((desc.n_layers, kvh, cap * desc.head_dim), dtype=self.dt, device=self.device)

@@ -205,6 +205,7 @@ def test_7b_hundred_cycles_walk_and_compaction_bit_exact():
     ("7b", 128, 450, gi.tree_spine_stress),
     ("llama3_8b", 64, 333, lambda: gi.tree_spine_7b(1)),
     ("qwen3_8b", 80, 250, gi.tree_spine_13b),
+    ("7b_f16", 64, 333, lambda: gi.tree_spine_7b(2)),
 ])
 def test_single_layer_of_the_larger_shapes(name, B, P0, tree_fn):
     """One decoder layer with the projection sizes of the larger models (and a small vocabulary),
@@ -224,5 +225,5 @@ def test_single_layer_of_the_larger_shapes(name, B, P0, tree_fn):
     assert tree.B == B
     tokens = gi.draft_tokens_uniform(12, tree.parent, shape.vocab, int(prefix[-1]))
     print(f"{name}: step", flush=True)
-    _compare_step(shape, gm, om, cache, tokens, tree, TOL_BF16)
+    _compare_step(shape, gm, om, cache, tokens, tree, TOL[shape.dtype])
     gm.ctx.close()

@@ -104,7 +104,8 @@ def _rows_of(sizes):
 @pytest.mark.parametrize("shape_name,sizes", [("small_bf16", [64, 30, 20]), ("small_gqa_qknorm_bf16", [33, 64]),
                                               ("tiny_bf16", [16, 9, 1, 32]), ("tiny_gqa_bf16", [128]),
                                               ("small_bf16", [32] * 8), ("tiny_bf16", [16, 9, 1, 32, 64, 100, 3]),
-                                              ("small_gqa_qknorm_bf16", [32] * 16)])
+                                              ("small_gqa_qknorm_bf16", [32] * 16),
+                                              ("small_gqa_qknorm_f16", [64, 20, 32, 100, 7])])
 def test_batched_step_equals_the_requests_alone(shape_name, sizes):
     """Short prefixes: one key split alone and batched, hence identical arithmetic per request
     (also beyond 128 stacked rows, where the projections run in chunks of 128 rows)."""

@@ -13,13 +13,13 @@ def _a_rows(B):
     return (B + 31) // 32 * 32 if B <= 128 else (B + 127) // 128 * 128
 
 
-def _run(B, N, K, nw, ks, seed=0):
+def _run(B, N, K, nw, ks, seed=0, dt=torch.bfloat16):
     dev = "cuda:0"
     gen = torch.Generator(device="cpu").manual_seed(seed)
     Kp, Np, rows = (K + 127) // 128 * 128, (N + 31) // 32 * 32, (B + 31) // 32 * 32
-    a = torch.zeros((_a_rows(B), Kp), dtype=torch.bfloat16)
-    a[:B, :K] = (torch.randn((B, K), generator=gen)).to(torch.bfloat16)
-    w = (torch.randn((N, K), generator=gen) * 0.05).to(torch.bfloat16)
+    a = torch.zeros((_a_rows(B), Kp), dtype=dt)
+    a[:B, :K] = (torch.randn((B, K), generator=gen)).to(dt)
+    w = (torch.randn((N, K), generator=gen) * 0.05).to(dt)
     ref = a[:B, :K].double().numpy() @ w.double().numpy().T
     packed = torch.zeros(g.goose_packed_matrix_bytes(N, K), dtype=torch.uint8, device=dev)
     g.goose_pack_matrix(w.to(dev), N, K, packed)
@@ -57,6 +57,13 @@ def test_gemm_stage_counts_and_splits(stages, ks):
             _run(B, 160, stages * 128, nw, ks, seed=stages)
 
 
+@pytest.mark.parametrize("B", [16, 80, 128, 300])
+def test_gemm_fp16_operands(B):
+    """The same kernels on fp16 operands (exact products, fp32 accumulation: the same bound)."""
+    _run(B, 288, 1024, 4, 2, dt=torch.float16)
+    _run(B, 1000, 1000, 2, 1, dt=torch.float16)
+
+
 def test_gemm_ragged_shapes():
     _run(50, 1000, 1000, 4, 2)   # N not a multiple of the 4-tile group, K padded to 1024
     _run(7, 40, 200, 2, 1)
@@ -66,25 +73,27 @@ def test_gemm_ragged_shapes():
 @pytest.mark.parametrize("B,F,K,nw", [(16, 96, 256, 2), (16, 2752, 1024, 2), (64, 2752, 1024, 4), (80, 352, 640, 2),
                                        (128, 704, 256, 4), (33, 64, 4096, 2), (300, 704, 256, 4), (512, 352, 640, 2),
                                        (160, 2752, 1024, 4)])
-def test_gemm_swiglu_epilogue(B, F, K, nw):
+@pytest.mark.parametrize("dt", [torch.bfloat16, torch.float16])
+def test_gemm_swiglu_epilogue(B, F, K, nw, dt):
     dev = "cuda:0"
     gen = torch.Generator(device="cpu").manual_seed(F)
     Kp, rows = (K + 127) // 128 * 128, (B + 31) // 32 * 32
-    a = torch.zeros((_a_rows(B), Kp), dtype=torch.bfloat16)
-    a[:B, :K] = torch.randn((B, K), generator=gen).to(torch.bfloat16)
-    wg = (torch.randn((F, K), generator=gen) * 0.05).to(torch.bfloat16)
-    wu = (torch.randn((F, K), generator=gen) * 0.05).to(torch.bfloat16)
+    a = torch.zeros((_a_rows(B), Kp), dtype=dt)
+    a[:B, :K] = torch.randn((B, K), generator=gen).to(dt)
+    wg = (torch.randn((F, K), generator=gen) * 0.05).to(dt)
+    wu = (torch.randn((F, K), generator=gen) * 0.05).to(dt)
     assert F % 32 == 0
     inter = torch.stack([wg.view(F // 32, 32, K), wu.view(F // 32, 32, K)], dim=1).reshape(2 * F, K).contiguous()
     gd, ud = a[:B, :K].double() @ wg.double().T, a[:B, :K].double() @ wu.double().T
     ref = (gd / (1 + torch.exp(-gd)) * ud).numpy()
     packed = torch.zeros(g.goose_packed_matrix_bytes(2 * F, K), dtype=torch.uint8, device=dev)
     g.goose_pack_matrix(inter.to(dev), 2 * F, K, packed)
-    h = torch.full((rows, F), float("nan"), dtype=torch.bfloat16, device=dev)
+    h = torch.full((rows, F), float("nan"), dtype=dt, device=dev)
     g.goose_gemm_swiglu_packed(a.to(dev), Kp, packed, 2 * F, K, B, nw, h, F)
     torch.cuda.synchronize()
     out = h[:B].double().cpu().numpy()
-    assert np.abs(out - ref).max() <= 6e-3 * np.abs(ref).max()  # one bf16 rounding of the result
+    # one rounding of the result to the storage type (relative to the element, hence to the largest)
+    assert np.abs(out - ref).max() <= (6e-3 if dt == torch.bfloat16 else 8e-4) * np.abs(ref).max()
 
 
 def test_gemm_repeated_large_launches_are_stable():

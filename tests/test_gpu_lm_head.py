@@ -16,8 +16,8 @@ pytestmark = pytest.mark.gpu
 TOL_BF16 = 2e-2
 
 
-def _model(vocab, hidden=256, seed=5):
-    shape = gi.ModelShape(f"head_v{vocab}", 1, hidden, 4, hidden // 4, 688, vocab, dtype="bf16")
+def _model(vocab, hidden=256, seed=5, dtype="bf16"):
+    shape = gi.ModelShape(f"head_v{vocab}", 1, hidden, 4, hidden // 4, 688, vocab, dtype=dtype)
     tm = torch_model(shape, seed=seed, gain_jitter=0.1)
     return shape, tm
 
@@ -32,10 +32,11 @@ def _run(gm, x, B, want_logits):
     return am[:B].cpu().numpy(), mg[:B].cpu().numpy(), None if logits is None else logits.cpu().numpy()
 
 
-@pytest.mark.parametrize("vocab", [1000, 1024, 4093, 33])
+@pytest.mark.parametrize("vocab,dtype", [(1000, "bf16"), (1024, "bf16"), (4093, "bf16"), (33, "bf16"), (4093, "f16")])
 @pytest.mark.parametrize("B", [1, 33, 64, 100])
-def test_top2_matches_the_logits_and_the_oracle(vocab, B):
-    shape, tm = _model(vocab)
+def test_top2_matches_the_logits_and_the_oracle(vocab, dtype, B):
+    shape, tm = _model(vocab, dtype=dtype)
+    TOL_BF16 = 2e-2 if dtype == "bf16" else 2.5e-3
     om = oracle_model(shape, tm)
     gm = gpu_model(shape, tm, max_B=128, cap=128)
     x = gi.gen_normal(77, 900 + B, (B, shape.hidden), 1.0, torch.float32, "cpu")

@@ -1,7 +1,7 @@
 """Parity of the HIP verification path with the CPU oracle, element by element.
 
 Tolerances (max abs error relative to the logit scale max|logit_oracle| of the step):
-fp32 storage 1e-4, bf16 storage 2e-2.  Integer results are bit-exact; an accept decision is only
+fp32 storage 1e-4, bf16 storage 2e-2, fp16 storage 2.5e-3 (three more mantissa bits than bf16).  Integer results are bit-exact; an accept decision is only
 compared where the oracle's top-2 logit margin at the deciding node exceeds the tolerance.
 """
 import numpy as np
@@ -14,7 +14,7 @@ from util import device_cache_as_oracle, gpu_model, load_prefix_cache, oracle_mo
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-4, "bf16": 2e-2}
+TOL = {"f32": 1e-4, "bf16": 2e-2, "f16": 2.5e-3}
 
 
 def tol_for(shape):
@@ -161,15 +161,16 @@ def test_tiny_fp32_empty_prefix_and_big_trees():
 
 
 @pytest.mark.parametrize("shape_name,P0,chunk", [("tiny_bf16", 128, 16), ("small_bf16", 200, 50),
-                                                 ("tiny_gqa_bf16", 100, 32), ("small_gqa_qknorm_bf16", 210, 70)])
+                                                 ("tiny_gqa_bf16", 100, 32), ("small_gqa_qknorm_bf16", 210, 70),
+                                                 ("tiny_f16", 128, 16), ("small_gqa_qknorm_f16", 210, 70)])
 def test_bf16_cycles_match_the_oracle(shape_name, P0, chunk):
-    """bf16 MFMA path; the oracle starts every cycle from the device's own stored cache bytes."""
+    """MFMA path (bf16 and fp16 storage); the oracle starts every cycle from the device's own stored cache bytes."""
     trees = [gi.tree_tiny_spine(), gi.tree_spine_7b(0), gi.tree_random(33, 4, spine_len=8), gi.tree_spine_13b(),
              gi.tree_spine_stress(), gi.tree_single(), gi.tree_balanced()]
     _run_cycles(shape_name, 7, P0, trees, seed=2, oracle_prefill=False, chunk=chunk)
 
 
-@pytest.mark.parametrize("shape_name", ["small_bf16", "small_gqa_qknorm_bf16"])
+@pytest.mark.parametrize("shape_name", ["small_bf16", "small_gqa_qknorm_bf16", "small_gqa_qknorm_f16"])
 def test_bf16_independent_prefill_stays_within_tolerance(shape_name):
     trees = [gi.tree_spine_7b(3), gi.tree_tiny_spine()]
     _run_cycles(shape_name, 2, 96, trees, seed=5, oracle_prefill=True, chunk=32)
