@@ -63,20 +63,22 @@ struct SegDev {
   const int32_t* dP;
   const uint64_t* mask;
 };
-struct SegTable { SegDev s[ATTN_MAX_SEGS]; };
+// TS = 1 for a single request (short kernel argument block, no indexing), else ATTN_MAX_SEGS
+template <int TS>
+struct SegTable { SegDev s[TS]; };
 
 // F16: fp16 instead of bf16 storage (caches, operands, probabilities, output).
-template <int D, int NG, int NQH, bool F16>
+template <int D, int NG, int NQH, bool F16, int TS>
 __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
     const float* part, int ks, size_t part_stride, size_t part_ld, int n_heads, int n_kv_heads, const float2* cs,
     int cap, const typename Mma16<F16>::T* __restrict__ gq, const typename Mma16<F16>::T* __restrict__ gk, float eps,
     float* __restrict__ att_o, float* __restrict__ att_ml, int Bpad, typename Mma16<F16>::T* o_out, int ldo,
-    const SegTable segs) {
+    const SegTable<TS> segs) {
   typedef typename Mma16<F16>::T T;
   typedef typename Mma16<F16>::v8 op8;
   typedef typename Mma16<F16>::v4 op4;
   // this workgroup's request: its rows of the stacked buffers, its caches, length and mask
-  const SegDev& sg = segs.s[blockIdx.z];
+  const SegDev& sg = segs.s[TS == 1 ? 0 : blockIdx.z];
   const int B = sg.B, row0 = sg.row0;
   T* const kc = static_cast<T*>(sg.kc);
   T* const vc = static_cast<T*>(sg.vc);
@@ -465,10 +467,10 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
 }
 
 // o[q][h*D + c] = sum_s 2^(m_s - m) O_s[c] / sum_s 2^(m_s - m) l_s, splits taken in index order.
-template <typename T>
+template <typename T, int TS>
 __global__ void k_attn_merge(const float* __restrict__ att_o, const float* __restrict__ att_ml, int nsplit, int Bpad,
-                             int D, T* __restrict__ o, int ldo, const SegTable segs) {
-  const SegDev& sg = segs.s[blockIdx.z];
+                             int D, T* __restrict__ o, int ldo, const SegTable<TS> segs) {
+  const SegDev& sg = segs.s[TS == 1 ? 0 : blockIdx.z];
   if ((int)blockIdx.x >= sg.B) return;
   const int qi = sg.row0 + blockIdx.x, h = blockIdx.y, c = threadIdx.x;
   float mmax = NEG_BIG;
@@ -503,25 +505,46 @@ struct AttnArgs {
 };
 
 template <int D, int NG, int NQH, bool F16>
-int launch_t(dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable& t) {
+int launch_t(dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable<ATTN_MAX_SEGS>& t) {
   typedef typename Mma16<F16>::T T;
-  hipLaunchKernelGGL((k_attn_fused<D, NG, NQH, F16>), grid, dim3(64 * NG * NQH), 0, st, a.part, a.ks, a.part_stride,
-                     a.part_ld, a.n_heads, a.n_kv, a.cs, a.cap, (const T*)a.gq, (const T*)a.gk, a.eps, a.att_o,
-                     a.att_ml, a.Bpad, (T*)a.o, a.ldo, t);
+  if (grid.z == 1) {
+    const SegTable<1> t1{{t.s[0]}};
+    hipLaunchKernelGGL((k_attn_fused<D, NG, NQH, F16, 1>), grid, dim3(64 * NG * NQH), 0, st, a.part, a.ks,
+                       a.part_stride, a.part_ld, a.n_heads, a.n_kv, a.cs, a.cap, (const T*)a.gq, (const T*)a.gk, a.eps,
+                       a.att_o, a.att_ml, a.Bpad, (T*)a.o, a.ldo, t1);
+  } else {
+    hipLaunchKernelGGL((k_attn_fused<D, NG, NQH, F16, ATTN_MAX_SEGS>), grid, dim3(64 * NG * NQH), 0, st, a.part, a.ks,
+                       a.part_stride, a.part_ld, a.n_heads, a.n_kv, a.cs, a.cap, (const T*)a.gq, (const T*)a.gk, a.eps,
+                       a.att_o, a.att_ml, a.Bpad, (T*)a.o, a.ldo, t);
+  }
   return goose_launch_status();
 }
 
 template <int D, int NG, int NQH>
-int launch_cfg(dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable& t) {
+int launch_cfg(dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable<ATTN_MAX_SEGS>& t) {
   return a.f16 ? launch_t<D, NG, NQH, true>(grid, st, a, t) : launch_t<D, NG, NQH, false>(grid, st, a, t);
 }
 
 template <int D>
-int launch_d(int QT, int ng, dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable& t) {
+int launch_d(int QT, int ng, dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable<ATTN_MAX_SEGS>& t) {
   // one wavefront per (query tile, key group); at most 8 wavefronts per workgroup
   if (QT == 1) return ng == 4 ? launch_cfg<D, 4, 1>(grid, st, a, t) : launch_cfg<D, 2, 1>(grid, st, a, t);
   if (QT == 2) return ng == 4 ? launch_cfg<D, 4, 2>(grid, st, a, t) : launch_cfg<D, 2, 2>(grid, st, a, t);
   return launch_cfg<D, 2, 4>(grid, st, a, t);
+}
+
+template <typename T>
+int launch_merge(dim3 grid, int head_dim, hipStream_t st, const AttnArgs& a, int splits,
+                 const SegTable<ATTN_MAX_SEGS>& t) {
+  if (grid.z == 1) {
+    const SegTable<1> t1{{t.s[0]}};
+    hipLaunchKernelGGL((k_attn_merge<T, 1>), grid, dim3(head_dim), 0, st, a.att_o, a.att_ml, splits, a.Bpad, head_dim,
+                       (T*)a.o, a.ldo, t1);
+  } else {
+    hipLaunchKernelGGL((k_attn_merge<T, ATTN_MAX_SEGS>), grid, dim3(head_dim), 0, st, a.att_o, a.att_ml, splits, a.Bpad,
+                       head_dim, (T*)a.o, a.ldo, t);
+  }
+  return goose_launch_status();
 }
 
 }  // namespace
@@ -567,7 +590,7 @@ int launch_attn_16(int dtype, const float* part, int ks, size_t part_stride, siz
   }
   // one launch per class of tree size (1, 2, or 3-4 query tiles): the class fixes the workgroup shape
   for (int cls : {1, 2, 4}) {
-    SegTable t{};
+    SegTable<ATTN_MAX_SEGS> t{};
     int n = 0, keys_max = 0, b_max = 0;
     for (int r = 0; r < nseg; ++r) {
       const AttnSeg& g = segs[r];
@@ -583,13 +606,9 @@ int launch_attn_16(int dtype, const float* part, int ks, size_t part_stride, siz
     int rc = head_dim == 128 ? launch_d<128>(cls, key_groups, grid, st, a, t) : launch_d<64>(cls, key_groups, grid, st, a, t);
     if (rc != GOOSE_OK) return rc;
     if (splits == 1) continue;
-    if (a.f16)
-      hipLaunchKernelGGL(k_attn_merge<f16_t>, dim3(b_max, n_heads, n), dim3(head_dim), 0, st, att_o, att_ml, splits,
-                         Bpad, head_dim, (f16_t*)o, ldo, t);
-    else
-      hipLaunchKernelGGL(k_attn_merge<bf16_t>, dim3(b_max, n_heads, n), dim3(head_dim), 0, st, att_o, att_ml, splits,
-                         Bpad, head_dim, (bf16_t*)o, ldo, t);
-    rc = goose_launch_status();
+    const dim3 mgrid(b_max, n_heads, n);
+    rc = a.f16 ? launch_merge<f16_t>(mgrid, head_dim, st, a, splits, t)
+               : launch_merge<bf16_t>(mgrid, head_dim, st, a, splits, t);
     if (rc != GOOSE_OK) return rc;
   }
   return GOOSE_OK;

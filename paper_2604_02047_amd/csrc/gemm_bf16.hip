@@ -83,10 +83,11 @@ __global__ __launch_bounds__(256) void k_pack_bf16(int mode, const bf16_t* __res
 // is handed over through LDS and the even wavefront writes h = silu(gate) * up.
 // EPI_TOP2: besides the optional plain output, every workgroup reduces its columns to one
 // (largest, second largest, index of largest) triple per row, for the greedy argmax.
-// STREAM: the weights are read once by the whole grid (non-temporal loads keep them from
-// displacing the L2's other lines); false when several row chunks read them (see below).
-// F16: fp16 instead of bf16 operands (and SwiGLU output).
-template <int MT, int NW, int EPI, int KC, int RING, bool STREAM = true, bool F16 = false>
+// CHUNKED: more than MT*32 rows, computed as several row chunks that read the same weights (1-D
+// grid in an XCD-aware order, ordinary loads so that the chunks share the L2); otherwise the
+// weights are read once by the whole grid, with non-temporal loads that keep them from displacing
+// the L2's other lines.  F16: fp16 instead of bf16 operands (and SwiGLU output).
+template <int MT, int NW, int EPI, int KC, int RING, bool CHUNKED = false, bool F16 = false>
 __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>::T* __restrict__ A, int lda,
                                                        const u32x4* __restrict__ Wp, int ntiles, int ksteps_total,
                                                        int stages_per_split, int B, void* __restrict__ out,
@@ -109,24 +110,23 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
   constexpr int LDS_BYTES = 2 * STAGE_BYTES > EPI_BYTES ? 2 * STAGE_BYTES : EPI_BYTES;
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // Work item = (column-tile group bx, split-K range by, row chunk of MT*32 rows).  Workgroups are
-  // dealt to the 8 XCDs round-robin in launch order; the chunks of one (bx, by) read the same
-  // weights, so they take consecutive slots of ONE XCD: its L2 then serves all but the first.
-  int bx, by, chunk = 0;
-  if (nchunk == 1) {
-    by = blockIdx.x / gx;
-    bx = blockIdx.x - by * gx;
-  } else {
+  // Work item = (column-tile group bx, split-K range by, row chunk of MT*32 rows).  One chunk: the
+  // plain 2-D grid.  Several chunks: a 1-D grid; workgroups are dealt to the 8 XCDs round-robin in
+  // launch order and the chunks of one (bx, by) read the same weights, so they take consecutive
+  // slots of ONE XCD: its L2 then serves all but the first.
+  constexpr bool STREAM = !CHUNKED;
+  int bx = blockIdx.x, by = blockIdx.y, row_base = 0, ngroups = gridDim.x;
+  if (CHUNKED) {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int j = slot / nchunk;
-    chunk = slot - j * nchunk;
+    const int j = slot / nchunk, chunk = slot - j * nchunk;
     const int t = j * 8 + xcd;
     if (t >= gx * nsplit) return;  // the grid is rounded up to whole groups of 8
     by = t / gx;
     bx = t - by * gx;
+    row_base = chunk * MT * 32;
+    A += (size_t)row_base * lda;
+    ngroups = gx;
   }
-  const int row_base = chunk * MT * 32;
-  A += (size_t)row_base * lda;
   const int tile = bx * NW + wave;
   const bool active = tile < ntiles;
   // a wavefront past the last tile redoes the last tile (no divergent control flow in the
@@ -304,7 +304,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
           if (e.x > t.x) { t.y = fmaxf(t.x, e.y); t.x = e.x; t.z = e.z; }
           else t.y = fmaxf(t.y, e.x);
         }
-        if (row_base + row < B) top2[(size_t)(row_base + row) * gx + bx] = t;
+        if (row_base + row < B) top2[(size_t)(row_base + row) * ngroups + bx] = t;
       }
     }
   } else {  // EPI_SWIGLU (the last loop barrier already separates the A stages from this reuse of LDS)
@@ -336,9 +336,9 @@ struct GemmCall {
   hipStream_t st; void* top2; int n_valid; bool f16;
 };
 
-template <int MT, int NW, int EPI, bool STREAM, bool F16>
+template <int MT, int NW, int EPI, bool CHUNKED, bool F16>
 int launch_k(const GemmCall& g, dim3 grid, int gx, int gps, int nchunk) {
-  hipLaunchKernelGGL((k_gemm_bf16<MT, NW, EPI, 128, 2, STREAM, F16>), grid, dim3(64 * NW), 0, g.st,
+  hipLaunchKernelGGL((k_gemm_bf16<MT, NW, EPI, 128, 2, CHUNKED, F16>), grid, dim3(64 * NW), 0, g.st,
                      (const typename Mma16<F16>::T*)g.A, g.lda, (const u32x4*)g.Wp, g.Npad / 32, g.Kpad / 16, gps, g.B,
                      g.out, g.ldo, g.split_stride, (float4*)g.top2, g.n_valid, gx, g.ksplit, nchunk);
   return goose_launch_status();
@@ -349,17 +349,17 @@ int launch_one(const GemmCall& g) {
   const int ntiles = g.Npad / 32;
   const int gx = (ntiles + NW - 1) / NW;
   const int nchunk = (g.B + MT * 32 - 1) / (MT * 32);  // more than 128 rows: chunks of 4 row tiles
-  const dim3 grid(nchunk == 1 ? gx * g.ksplit : (gx * g.ksplit + 7) / 8 * 8 * nchunk);
+  const dim3 grid = nchunk == 1 ? dim3(gx, g.ksplit) : dim3((gx * g.ksplit + 7) / 8 * 8 * nchunk);
   const int granules = g.Kpad / KGRAN;                      // split-K ranges are multiples of 128 inputs
   const int gps = (granules + g.ksplit - 1) / g.ksplit;     // granules (= stages) per split
   // two stages of each stream in flight measured best (four: every projection 2-3 us slower)
   if constexpr (MT == 4) {
-    if (nchunk > 1)  // the chunks of a column group share their weights through the L2: ordinary loads
-      return g.f16 ? launch_k<MT, NW, EPI, false, true>(g, grid, gx, gps, nchunk)
-                   : launch_k<MT, NW, EPI, false, false>(g, grid, gx, gps, nchunk);
+    if (nchunk > 1)
+      return g.f16 ? launch_k<MT, NW, EPI, true, true>(g, grid, gx, gps, nchunk)
+                   : launch_k<MT, NW, EPI, true, false>(g, grid, gx, gps, nchunk);
   }
-  return g.f16 ? launch_k<MT, NW, EPI, true, true>(g, grid, gx, gps, nchunk)
-               : launch_k<MT, NW, EPI, true, false>(g, grid, gx, gps, nchunk);
+  return g.f16 ? launch_k<MT, NW, EPI, false, true>(g, grid, gx, gps, nchunk)
+               : launch_k<MT, NW, EPI, false, false>(g, grid, gx, gps, nchunk);
 }
 
 template <int NW, int EPI>
