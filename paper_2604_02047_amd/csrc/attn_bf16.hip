@@ -70,10 +70,11 @@ struct SegTable { SegDev s[TS]; };
 // F16: fp16 instead of bf16 storage (caches, operands, probabilities, output).
 template <int D, int NG, int NQH, bool F16, int TS>
 __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
-    const float* part, int ks, size_t part_stride, size_t part_ld, int n_heads, int n_kv_heads, const float2* cs,
-    int cap, const typename Mma16<F16>::T* __restrict__ gq, const typename Mma16<F16>::T* __restrict__ gk, float eps,
-    float* __restrict__ att_o, float* __restrict__ att_ml, int Bpad, typename Mma16<F16>::T* o_out, int ldo,
-    const SegTable<TS> segs) {
+    // (what the first cache loads depend on comes first: the leading kernel arguments are preloaded)
+    const SegTable<TS> segs, int n_heads, int n_kv_heads, int cap, const float* part, int ks, size_t part_stride,
+    size_t part_ld, const float2* cs, const typename Mma16<F16>::T* __restrict__ gq,
+    const typename Mma16<F16>::T* __restrict__ gk, float eps, float* __restrict__ att_o, float* __restrict__ att_ml,
+    int Bpad, typename Mma16<F16>::T* o_out, int ldo) {
   typedef typename Mma16<F16>::T T;
   typedef typename Mma16<F16>::v8 op8;
   typedef typename Mma16<F16>::v4 op4;
@@ -509,13 +510,13 @@ int launch_t(dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable<ATTN_M
   typedef typename Mma16<F16>::T T;
   if (grid.z == 1) {
     const SegTable<1> t1{{t.s[0]}};
-    hipLaunchKernelGGL((k_attn_fused<D, NG, NQH, F16, 1>), grid, dim3(64 * NG * NQH), 0, st, a.part, a.ks,
-                       a.part_stride, a.part_ld, a.n_heads, a.n_kv, a.cs, a.cap, (const T*)a.gq, (const T*)a.gk, a.eps,
-                       a.att_o, a.att_ml, a.Bpad, (T*)a.o, a.ldo, t1);
+    hipLaunchKernelGGL((k_attn_fused<D, NG, NQH, F16, 1>), grid, dim3(64 * NG * NQH), 0, st, t1, a.n_heads, a.n_kv,
+                       a.cap, a.part, a.ks, a.part_stride, a.part_ld, a.cs, (const T*)a.gq, (const T*)a.gk, a.eps,
+                       a.att_o, a.att_ml, a.Bpad, (T*)a.o, a.ldo);
   } else {
-    hipLaunchKernelGGL((k_attn_fused<D, NG, NQH, F16, ATTN_MAX_SEGS>), grid, dim3(64 * NG * NQH), 0, st, a.part, a.ks,
-                       a.part_stride, a.part_ld, a.n_heads, a.n_kv, a.cs, a.cap, (const T*)a.gq, (const T*)a.gk, a.eps,
-                       a.att_o, a.att_ml, a.Bpad, (T*)a.o, a.ldo, t);
+    hipLaunchKernelGGL((k_attn_fused<D, NG, NQH, F16, ATTN_MAX_SEGS>), grid, dim3(64 * NG * NQH), 0, st, t, a.n_heads,
+                       a.n_kv, a.cap, a.part, a.ks, a.part_stride, a.part_ld, a.cs, (const T*)a.gq, (const T*)a.gk,
+                       a.eps, a.att_o, a.att_ml, a.Bpad, (T*)a.o, a.ldo);
   }
   return goose_launch_status();
 }
