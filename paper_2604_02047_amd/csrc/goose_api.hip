@@ -603,16 +603,17 @@ int goose_verify_step_batched(goose_ctx* c, const goose_model_ptrs* m, const goo
     rows += round_up(q.B, 32);
   }
   if (rows > c->max_rows) return GOOSE_ERR_CAPACITY;
-  int rc;
+  BatchReq br[GOOSE_MAX_REQUESTS];
+  int b_max = 0;
   for (int r = 0; r < n_req; ++r) {
     const goose_request& q = reqs[r];
-    const int row0 = segs[r].row0;
-    rc = launch_build_mask(q.d_parent, q.B, q.d_P, c->s_mask + (size_t)row0 * 2, c->s_depth + row0, c->s_pos + row0,
-                           c->flags, st);
-    if (rc) return rc;
-    rc = launch_embed(d.dtype, m->d_embed, q.d_tokens, q.B, d.hidden, d.vocab, c->s_x + (size_t)row0 * d.hidden, st);
-    if (rc) return rc;
+    br[r] = BatchReq{q.d_tokens, q.d_parent, q.d_is_spine, q.B, segs[r].row0, q.d_kcache_all, q.d_vcache_all, q.d_P,
+                     q.d_accept_len, q.d_path, q.d_bonus, q.d_next_root_or_null};
+    b_max = q.B > b_max ? q.B : b_max;
   }
+  int rc = launch_batch_begin(d.dtype, br, n_req, b_max, m->d_embed, d.hidden, d.vocab, c->s_mask, c->s_depth, c->s_pos,
+                              c->s_x, c->flags, st);
+  if (rc) return rc;
   // rows between requests keep stale (finite) values: they ride through the projections unused
   rc = launch_rope_table(c->s_pos, c->inv_freq, rows, d.head_dim, c->rope_cs, st);
   if (rc) return rc;
@@ -630,16 +631,7 @@ int goose_verify_step_batched(goose_ctx* c, const goose_model_ptrs* m, const goo
   }
   rc = lm_head_impl(c, m->d_packed_head, c->s_x, rows, d_argmax_all, nullptr, nullptr, st, true, HarvestArgs());
   if (rc) return rc;
-  for (int r = 0; r < n_req; ++r) {
-    const goose_request& q = reqs[r];
-    rc = launch_accept(q.d_parent, q.d_tokens, q.d_is_spine, d_argmax_all + segs[r].row0, q.B, q.d_accept_len, q.d_path,
-                       q.d_bonus, q.d_next_root_or_null, st);
-    if (rc) return rc;
-    rc = launch_compact((int)elem_size(d.dtype), q.d_kcache_all, q.d_vcache_all, d.n_layers, c->n_kv, c->cap,
-                        d.head_dim, q.d_P, q.d_path, q.d_accept_len, q.d_P, st);
-    if (rc) return rc;
-  }
-  return GOOSE_OK;
+  return launch_batch_end(br, n_req, d_argmax_all, d.n_layers, c->n_kv, c->cap, d.head_dim, st);
 }
 
 int goose_device_flags(goose_ctx* c, void* stream, int32_t* h_flags_out) {

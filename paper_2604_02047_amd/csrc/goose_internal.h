@@ -96,6 +96,26 @@ int launch_swiglu_f32(const float* gu, size_t ld, int F, float* h, int ldh, int 
 int launch_argmax(const float* logits, size_t ld, int V, int B, int32_t* argmax, float* margin, hipStream_t st);
 int launch_accept(const int32_t* parent, const int32_t* tokens, const uint8_t* is_spine, const int32_t* argmax, int B,
                   int32_t* accept_len, int32_t* path, int32_t* bonus, int32_t* next_root, hipStream_t st);
+// One request of a batched pass as the per-request kernels see it (16-bit storage only).
+struct BatchReq {
+  const int32_t* tokens;
+  const int32_t* parent;
+  const uint8_t* is_spine;  // or null
+  int32_t B, row0;          // its rows [row0, row0 + B) of the stacked buffers
+  void* kall;               // its caches, all layers
+  void* vall;
+  int32_t* dP;              // cache length, in/out
+  int32_t* accept_len;
+  int32_t* path;
+  int32_t* bonus;
+  int32_t* next_root;       // or null
+};
+// mask/depth/positions and embedding rows of all requests (2 launches); E: embedding table.
+int launch_batch_begin(int dtype, const BatchReq* reqs, int n, int max_B, const void* E, int H, int V,
+                       uint64_t* mask, int32_t* depth, int32_t* pos, float* x, int32_t* flags, hipStream_t st);
+// walk, compaction and new cache length of all requests (3 launches)
+int launch_batch_end(const BatchReq* reqs, int n, const int32_t* argmax_all, int n_layers, int n_kv_heads, int cap,
+                     int head_dim, hipStream_t st);
 int launch_compact(int elem_bytes, void* kall, void* vall, int n_layers, int n_heads, int cap, int head_dim,
                    const int32_t* dP, const int32_t* path, const int32_t* accept_len, int32_t* new_P, hipStream_t st);
 

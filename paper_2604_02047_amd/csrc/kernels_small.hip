@@ -22,10 +22,9 @@ __global__ void k_set_int(int32_t* dst, int v) {
 
 // Ancestor-or-self bit rows, depth and position of every node (Sec. 4, tree attention mask).
 // One thread per node climbs its own root path; parent[v] < v makes every climb finite.
-__global__ __launch_bounds__(128) void k_build_mask(const int32_t* __restrict__ parent, int B,
-                                                    const int32_t* __restrict__ dP, uint64_t* __restrict__ mask,
-                                                    int32_t* __restrict__ depth, int32_t* __restrict__ pos,
-                                                    int32_t* __restrict__ flags) {
+__device__ inline void build_mask_body(const int32_t* __restrict__ parent, int B, const int32_t* __restrict__ dP,
+                                       uint64_t* __restrict__ mask, int32_t* __restrict__ depth,
+                                       int32_t* __restrict__ pos, int32_t* __restrict__ flags) {
   const int i = threadIdx.x;
   if (i >= B) return;
   const int W = (B + 63) >> 6;
@@ -48,6 +47,24 @@ __global__ __launch_bounds__(128) void k_build_mask(const int32_t* __restrict__ 
   if (bad) atomicOr(flags, 1);
 }
 
+__global__ __launch_bounds__(128) void k_build_mask(const int32_t* __restrict__ parent, int B,
+                                                    const int32_t* __restrict__ dP, uint64_t* __restrict__ mask,
+                                                    int32_t* __restrict__ depth, int32_t* __restrict__ pos,
+                                                    int32_t* __restrict__ flags) {
+  build_mask_body(parent, B, dP, mask, depth, pos, flags);
+}
+
+// The per-request steps of a batch as single launches: block index = request, taken from a table
+// that travels as a kernel argument (rows of request r start at row0 in the stacked buffers).
+struct ReqTable { BatchReq r[GOOSE_MAX_REQUESTS]; };
+
+__global__ __launch_bounds__(128) void k_build_mask_batch(const ReqTable t, uint64_t* __restrict__ mask,
+                                                          int32_t* __restrict__ depth, int32_t* __restrict__ pos,
+                                                          int32_t* __restrict__ flags) {
+  const BatchReq& q = t.r[blockIdx.x];
+  build_mask_body(q.parent, q.B, q.dP, mask + (size_t)q.row0 * 2, depth + q.row0, pos + q.row0, flags);
+}
+
 // ------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void k_embed(const T* __restrict__ E, const int32_t* __restrict__ tokens, int H,
@@ -57,6 +74,19 @@ __global__ __launch_bounds__(256) void k_embed(const T* __restrict__ E, const in
   t = t < 0 ? 0 : (t >= V ? V - 1 : t);
   const T* row = E + (size_t)t * H;
   for (int c = threadIdx.x; c < H; c += 256) x[(size_t)m * H + c] = to_f32(row[c]);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_embed_batch(const T* __restrict__ E, const ReqTable t, int H, int V,
+                                                     float* __restrict__ x) {
+  const BatchReq& q = t.r[blockIdx.y];
+  const int i = blockIdx.x;
+  if (i >= q.B) return;
+  int tok = q.tokens[i];
+  tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+  const T* row = E + (size_t)tok * H;
+  float* xr = x + (size_t)(q.row0 + i) * H;
+  for (int c = threadIdx.x; c < H; c += 256) xr[c] = to_f32(row[c]);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -422,11 +452,10 @@ __global__ __launch_bounds__(256) void k_harvest_topk(const float* __restrict__ 
 // at its parent) bids for its parent with the key (branch?1:0, node index); the lowest key
 // wins, i.e. spine children before branch children, lower index first.  Thread 0 then follows
 // the winners from the root; node indices grow along any path, so the walk is finite.
-__global__ __launch_bounds__(128) void k_accept(const int32_t* __restrict__ parent, const int32_t* __restrict__ tokens,
-                                                const uint8_t* __restrict__ is_spine,
-                                                const int32_t* __restrict__ argmax, int B,
-                                                int32_t* __restrict__ accept_len, int32_t* __restrict__ path,
-                                                int32_t* __restrict__ bonus, int32_t* __restrict__ next_root) {
+__device__ inline void accept_body(const int32_t* __restrict__ parent, const int32_t* __restrict__ tokens,
+                                   const uint8_t* __restrict__ is_spine, const int32_t* __restrict__ argmax, int B,
+                                   int32_t* __restrict__ accept_len, int32_t* __restrict__ path,
+                                   int32_t* __restrict__ bonus, int32_t* __restrict__ next_root) {
   __shared__ int nxt[GOOSE_MAX_B];
   __shared__ int xh[GOOSE_MAX_B];
   __shared__ int L_sh;
@@ -460,6 +489,19 @@ __global__ __launch_bounds__(128) void k_accept(const int32_t* __restrict__ pare
   if (i > L_sh && i < B) path[i] = -1;
 }
 
+__global__ __launch_bounds__(128) void k_accept(const int32_t* __restrict__ parent, const int32_t* __restrict__ tokens,
+                                                const uint8_t* __restrict__ is_spine,
+                                                const int32_t* __restrict__ argmax, int B,
+                                                int32_t* __restrict__ accept_len, int32_t* __restrict__ path,
+                                                int32_t* __restrict__ bonus, int32_t* __restrict__ next_root) {
+  accept_body(parent, tokens, is_spine, argmax, B, accept_len, path, bonus, next_root);
+}
+
+__global__ __launch_bounds__(128) void k_accept_batch(const ReqTable t, const int32_t* __restrict__ argmax_all) {
+  const BatchReq& q = t.r[blockIdx.x];
+  accept_body(q.parent, q.tokens, q.is_spine, argmax_all + q.row0, q.B, q.accept_len, q.path, q.bonus, q.next_root);
+}
+
 // ------------------------------------------------------------------------------------------
 // Commit of the accepted path: cache slot P + path[j] -> slot P + j, j = 1..L, in every layer and head.
 // K[head][slot][d]: one thread owns one 16-byte column chunk of all rows.  Vt[head][d][slot]: one thread
@@ -484,10 +526,9 @@ __global__ __launch_bounds__(64) void k_compact_k(uint4* __restrict__ kall, int 
 // The same for bf16 caches in MFMA operand order (32-key blocks; the layouts are spelled out in
 // goose.h): thread c moves chunk c of the K row (16 bytes) and column c of the V row (2 bytes).
 template <int D>
-__global__ __launch_bounds__(D) void k_compact_tiled(bf16_t* __restrict__ kall, bf16_t* __restrict__ vall, int cap,
-                                                     const int32_t* __restrict__ dP,
-                                                     const int32_t* __restrict__ path,
-                                                     const int32_t* __restrict__ accept_len) {
+__device__ inline void compact_tiled_body(bf16_t* __restrict__ kall, bf16_t* __restrict__ vall, int cap,
+                                          const int32_t* __restrict__ dP, const int32_t* __restrict__ path,
+                                          const int32_t* __restrict__ accept_len) {
   const int c = threadIdx.x;
   bf16_t* kb = kall + (size_t)blockIdx.x * cap * D;  // blockIdx.x = layer * n_heads + head
   bf16_t* vb = vall + (size_t)blockIdx.x * cap * D;
@@ -513,6 +554,20 @@ __global__ __launch_bounds__(D) void k_compact_tiled(bf16_t* __restrict__ kall, 
   }
 }
 
+template <int D>
+__global__ __launch_bounds__(D) void k_compact_tiled(bf16_t* __restrict__ kall, bf16_t* __restrict__ vall, int cap,
+                                                     const int32_t* __restrict__ dP,
+                                                     const int32_t* __restrict__ path,
+                                                     const int32_t* __restrict__ accept_len) {
+  compact_tiled_body<D>(kall, vall, cap, dP, path, accept_len);
+}
+
+template <int D>
+__global__ __launch_bounds__(D) void k_compact_tiled_batch(const ReqTable t, int cap) {
+  const BatchReq& q = t.r[blockIdx.y];
+  compact_tiled_body<D>((bf16_t*)q.kall, (bf16_t*)q.vall, cap, q.dP, q.path, q.accept_len);
+}
+
 template <typename T>
 __global__ void k_compact_vt(T* __restrict__ vall, int cap, int head_dim, const int32_t* __restrict__ dP,
                              const int32_t* __restrict__ path, const int32_t* __restrict__ accept_len) {
@@ -532,6 +587,13 @@ __global__ void k_new_P(const int32_t* dP, const int32_t* accept_len, int32_t* n
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     const int p = *dP, l = *accept_len;
     *new_P = p + l + 1;
+  }
+}
+
+__global__ void k_new_P_batch(const ReqTable t) {  // in place: after the compaction has read the old lengths
+  if (threadIdx.x == 0) {
+    const BatchReq& q = t.r[blockIdx.x];
+    *q.dP = *q.dP + *q.accept_len + 1;
   }
 }
 
@@ -631,6 +693,47 @@ int launch_harvest_topk(const float* logits, size_t ld, int V, const int32_t* to
   if (K < 1 || K > 16) return GOOSE_ERR_ARG;
   hipLaunchKernelGGL(k_harvest_topk<16>, dim3(B), dim3(256), 0, st, logits, ld, V, tokens, B, K, table_rows, succ_ids,
                      succ_scores);
+  return goose_launch_status();
+}
+
+static ReqTable req_table(const BatchReq* reqs, int n) {
+  ReqTable t{};
+  for (int r = 0; r < n; ++r) t.r[r] = reqs[r];
+  return t;
+}
+
+int launch_batch_begin(int dtype, const BatchReq* reqs, int n, int max_B, const void* E, int H, int V,
+                       uint64_t* mask, int32_t* depth, int32_t* pos, float* x, int32_t* flags, hipStream_t st) {
+  if (n < 1 || n > GOOSE_MAX_REQUESTS) return GOOSE_ERR_ARG;
+  const ReqTable t = req_table(reqs, n);
+  hipLaunchKernelGGL(k_build_mask_batch, dim3(n), dim3(128), 0, st, t, mask, depth, pos, flags);
+  int rc = goose_launch_status();
+  if (rc != GOOSE_OK) return rc;
+  if (dtype == GOOSE_DTYPE_BF16)
+    hipLaunchKernelGGL(k_embed_batch<bf16_t>, dim3(max_B, n), dim3(256), 0, st, (const bf16_t*)E, t, H, V, x);
+  else if (dtype == GOOSE_DTYPE_F16)
+    hipLaunchKernelGGL(k_embed_batch<_Float16>, dim3(max_B, n), dim3(256), 0, st, (const _Float16*)E, t, H, V, x);
+  else
+    return GOOSE_ERR_SHAPE;
+  return goose_launch_status();
+}
+
+int launch_batch_end(const BatchReq* reqs, int n, const int32_t* argmax_all, int n_layers, int n_kv_heads, int cap,
+                     int head_dim, hipStream_t st) {
+  if (n < 1 || n > GOOSE_MAX_REQUESTS) return GOOSE_ERR_ARG;
+  const ReqTable t = req_table(reqs, n);
+  hipLaunchKernelGGL(k_accept_batch, dim3(n), dim3(128), 0, st, t, argmax_all);
+  int rc = goose_launch_status();
+  if (rc != GOOSE_OK) return rc;
+  if (head_dim == 128)
+    hipLaunchKernelGGL(k_compact_tiled_batch<128>, dim3(n_layers * n_kv_heads, n), dim3(128), 0, st, t, cap);
+  else if (head_dim == 64)
+    hipLaunchKernelGGL(k_compact_tiled_batch<64>, dim3(n_layers * n_kv_heads, n), dim3(64), 0, st, t, cap);
+  else
+    return GOOSE_ERR_SHAPE;
+  rc = goose_launch_status();
+  if (rc != GOOSE_OK) return rc;
+  hipLaunchKernelGGL(k_new_P_batch, dim3(n), dim3(64), 0, st, t);
   return goose_launch_status();
 }
 
