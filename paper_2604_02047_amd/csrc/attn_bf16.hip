@@ -468,9 +468,10 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
 }
 
 // o[q][h*D + c] = sum_s 2^(m_s - m) O_s[c] / sum_s 2^(m_s - m) l_s, splits taken in index order.
-template <typename T, int TS>
+template <bool F16, int TS>
 __global__ void k_attn_merge(const float* __restrict__ att_o, const float* __restrict__ att_ml, int nsplit, int Bpad,
-                             int D, T* __restrict__ o, int ldo, const SegTable<TS> segs) {
+                             int D, typename Mma16<F16>::T* __restrict__ o, int ldo, const SegTable<TS> segs) {
+  typedef typename Mma16<F16>::T T;
   const SegDev& sg = segs.s[TS == 1 ? 0 : blockIdx.z];
   if ((int)blockIdx.x >= sg.B) return;
   const int qi = sg.row0 + blockIdx.x, h = blockIdx.y, c = threadIdx.x;
@@ -534,15 +535,16 @@ int launch_d(int QT, int ng, dim3 grid, hipStream_t st, const AttnArgs& a, const
   return launch_cfg<D, 2, 4>(grid, st, a, t);
 }
 
-template <typename T>
+template <bool F16>
 int launch_merge(dim3 grid, int head_dim, hipStream_t st, const AttnArgs& a, int splits,
                  const SegTable<ATTN_MAX_SEGS>& t) {
+  typedef typename Mma16<F16>::T T;
   if (grid.z == 1) {
     const SegTable<1> t1{{t.s[0]}};
-    hipLaunchKernelGGL((k_attn_merge<T, 1>), grid, dim3(head_dim), 0, st, a.att_o, a.att_ml, splits, a.Bpad, head_dim,
+    hipLaunchKernelGGL((k_attn_merge<F16, 1>), grid, dim3(head_dim), 0, st, a.att_o, a.att_ml, splits, a.Bpad, head_dim,
                        (T*)a.o, a.ldo, t1);
   } else {
-    hipLaunchKernelGGL((k_attn_merge<T, ATTN_MAX_SEGS>), grid, dim3(head_dim), 0, st, a.att_o, a.att_ml, splits, a.Bpad,
+    hipLaunchKernelGGL((k_attn_merge<F16, ATTN_MAX_SEGS>), grid, dim3(head_dim), 0, st, a.att_o, a.att_ml, splits, a.Bpad,
                        head_dim, (T*)a.o, a.ldo, t);
   }
   return goose_launch_status();
@@ -608,8 +610,8 @@ int launch_attn_16(int dtype, const float* part, int ks, size_t part_stride, siz
     if (rc != GOOSE_OK) return rc;
     if (splits == 1) continue;
     const dim3 mgrid(b_max, n_heads, n);
-    rc = a.f16 ? launch_merge<f16_t>(mgrid, head_dim, st, a, splits, t)
-               : launch_merge<bf16_t>(mgrid, head_dim, st, a, splits, t);
+    rc = a.f16 ? launch_merge<true>(mgrid, head_dim, st, a, splits, t)
+               : launch_merge<false>(mgrid, head_dim, st, a, splits, t);
     if (rc != GOOSE_OK) return rc;
   }
   return GOOSE_OK;

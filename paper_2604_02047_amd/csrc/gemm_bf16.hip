@@ -217,7 +217,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
       load_w(s_begin, c0);
       load_a(s_begin + 1, c1);
       load_w(s_begin + 1, c1);
-      if (RING == 4) {
+      if constexpr (RING == 4) {
         load_a(s_begin + 2, c2);
         load_w(s_begin + 2, c2);
         load_a(s_begin + 3, c3);
@@ -228,7 +228,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
       for (; i + 2 * RING - 1 < nst; i += RING) {  // steady state: no conditionals inside
         stage(c0, s_begin + i, yes, yes);
         stage(c1, s_begin + i + 1, yes, yes);
-        if (RING == 4) {
+        if constexpr (RING == 4) {
           stage(c2, s_begin + i + 2, yes, yes);
           stage(c3, s_begin + i + 3, yes, yes);
         }
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
       load_a(s_begin, c0);
       load_w(s_begin, c0);
       if (nst > 1) { load_a(s_begin + 1, c1); load_w(s_begin + 1, c1); }
-      if (RING == 4) {
+      if constexpr (RING == 4) {
         if (nst > 2) { load_a(s_begin + 2, c2); load_w(s_begin + 2, c2); }
         if (nst > 3) { load_a(s_begin + 3, c3); load_w(s_begin + 3, c3); }
       }
@@ -249,8 +249,8 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
       switch (i % RING) {
         case 0: stage(c0, s_begin + i, na, rf); break;
         case 1: stage(c1, s_begin + i, na, rf); break;
-        case 2: if (RING == 4) stage(c2, s_begin + i, na, rf); break;
-        default: if (RING == 4) stage(c3, s_begin + i, na, rf); break;
+        case 2: if constexpr (RING == 4) stage(c2, s_begin + i, na, rf); break;
+        default: if constexpr (RING == 4) stage(c3, s_begin + i, na, rf); break;
       }
     }
   }
