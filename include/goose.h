@@ -215,7 +215,8 @@ int goose_verify_step(goose_ctx* ctx, const goose_model_ptrs* model, const goose
  * the rounded-up B must not exceed the context's max_rows (goose_create_batched), each B its max_B.
  * Projections, norms and the LM head run once over all rows (beyond 128 rows in chunks of 128 that
  * share the weight stream through the L2 cache); the attention runs on every request's own caches
- * as one launch per tree-size class; walk and compaction run per request.  16-bit models only.
+ * as one launch per tree-size class; walk, compaction and the optional harvest (into the request's own
+ * successor tables) run per request.  16-bit models only.
  * d_argmax_all: int32 [max_rows], receives every row's prediction (request r's rows start
  * at the sum of round_up(B, 32) of the requests before it).  All pointers DEVICE; P of a request is
  * read from *d_P (P_max: host upper bound, as in goose_verify_step) and updated in place. */
@@ -233,6 +234,9 @@ typedef struct {
   int32_t* d_path;           /* [B] out */
   int32_t* d_bonus;          /* [1] out */
   int32_t* d_next_root_or_null;
+  int32_t* d_succ_ids_or_null;    /* this request's successor tables [vocab][harvest_k]: harvest the logits */
+  float* d_succ_scores_or_null;   /* of its nodes as goose_harvest_topk does; both or neither */
+  int32_t harvest_k;              /* 1..16 when harvesting */
 } goose_request;
 int goose_verify_step_batched(goose_ctx* ctx, const goose_model_ptrs* model, const goose_request* reqs, int n_req,
                               int32_t* d_argmax_all, void* stream);

@@ -60,7 +60,8 @@ class _Request(C.Structure):
     _fields_ = [("d_tokens", C.c_void_p), ("d_parent", C.c_void_p), ("d_is_spine", C.c_void_p), ("B", C.c_int32),
                 ("P_max", C.c_int32), ("d_kcache_all", C.c_void_p), ("d_vcache_all", C.c_void_p), ("d_P", C.c_void_p),
                 ("d_accept_len", C.c_void_p), ("d_path", C.c_void_p), ("d_bonus", C.c_void_p),
-                ("d_next_root_or_null", C.c_void_p)]
+                ("d_next_root_or_null", C.c_void_p), ("d_succ_ids_or_null", C.c_void_p),
+                ("d_succ_scores_or_null", C.c_void_p), ("harvest_k", C.c_int32)]
 
 
 @dataclass
@@ -360,7 +361,7 @@ class GooseContext:
 
     def goose_verify_step_batched(self, model: dict, requests: list, argmax_all):
         """requests: dicts with tokens, parent, is_spine (or None), B, P_max, kcache, vcache, P, accept_len, path,
-        bonus, next_root (or None) -- device tensors / ints."""
+        bonus, next_root (or None), succ_ids / succ_scores (or None: no harvest) -- device tensors / ints."""
         m = _ModelPtrs(model["embed"].data_ptr(), model["packed_layers"].data_ptr(), model["packed_head"].data_ptr(),
                        None, None)
         arr = (_Request * len(requests))()
@@ -369,7 +370,9 @@ class GooseContext:
                 t = q.get(name)
                 return None if t is None else t.data_ptr()
             arr[i] = _Request(p("tokens"), p("parent"), p("is_spine"), int(q["B"]), int(q["P_max"]), p("kcache"),
-                              p("vcache"), p("P"), p("accept_len"), p("path"), p("bonus"), p("next_root"))
+                              p("vcache"), p("P"), p("accept_len"), p("path"), p("bonus"), p("next_root"),
+                              p("succ_ids"), p("succ_scores"),
+                              0 if q.get("succ_ids") is None else int(q["succ_ids"].shape[1]))
         _check(self.lib.goose_verify_step_batched(self._h, C.byref(m), arr, len(requests), _ptr(argmax_all),
                                                   _stream()), "goose_verify_step_batched")
 

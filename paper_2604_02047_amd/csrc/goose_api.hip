@@ -448,6 +448,7 @@ struct HarvestArgs {  // optional harvest of the logits into the successor table
   int K = 0;
   int32_t* ids = nullptr;
   float* scores = nullptr;
+  bool keep_logits = false;  // write the logits to the workspace even though nothing is harvested here
 };
 static int lm_head_impl(goose_ctx* c, const void* d_packed_head, const float* d_x, int B, int32_t* d_argmax,
                         float* d_logits_or_null, float* d_margin_or_null, hipStream_t st, bool xhat_ready,
@@ -479,7 +480,7 @@ static int lm_head_impl(goose_ctx* c, const void* d_packed_head, const float* d_
     static const int lm_nw = env_int("GOOSE_LM_NW", 4) == 2 ? 2 : 4;
     // (the harvest needs them too: into the workspace then)
     const bool bounce = d_logits_or_null && (d.vocab % 32) != 0;
-    float* out = (bounce || (!d_logits_or_null && hv.ids)) ? c->logits : d_logits_or_null;
+    float* out = (bounce || (!d_logits_or_null && (hv.ids || hv.keep_logits))) ? c->logits : d_logits_or_null;
     const size_t ld = out == c->logits ? (size_t)c->Vpad : (size_t)d.vocab;
     const int groups = (c->Vpad / 32 + lm_nw - 1) / lm_nw;
     { PROF(PK_LM_HEAD);
@@ -592,6 +593,7 @@ int goose_verify_step_batched(goose_ctx* c, const goose_model_ptrs* m, const goo
   hipStream_t st = as_stream(stream);
   AttnSeg segs[GOOSE_MAX_REQUESTS];
   int rows = 0;
+  bool any_harvest = false;
   for (int r = 0; r < n_req; ++r) {
     const goose_request& q = reqs[r];
     int rc = check_tree_args(c, q.B, q.P_max);
@@ -599,6 +601,9 @@ int goose_verify_step_batched(goose_ctx* c, const goose_model_ptrs* m, const goo
     if (!q.d_tokens || !q.d_parent || !q.d_P || !q.d_kcache_all || !q.d_vcache_all || !q.d_accept_len || !q.d_path ||
         !q.d_bonus)
       return GOOSE_ERR_ARG;
+    if ((q.d_succ_ids_or_null == nullptr) != (q.d_succ_scores_or_null == nullptr)) return GOOSE_ERR_ARG;
+    if (q.d_succ_ids_or_null && (q.harvest_k < 1 || q.harvest_k > 16)) return GOOSE_ERR_ARG;
+    any_harvest = any_harvest || q.d_succ_ids_or_null != nullptr;
     segs[r] = AttnSeg{rows, q.B, q.P_max, nullptr, nullptr, q.d_P, c->s_mask + (size_t)rows * 2};
     rows += round_up(q.B, 32);
   }
@@ -629,8 +634,17 @@ int goose_verify_step_batched(goose_ctx* c, const goose_model_ptrs* m, const goo
     rc = layer_impl(c, w, c->s_x, nullptr, nullptr, 0, nullptr, rows, nullptr, c->s_pos, st, l > 0, g_next, segs, n_req);
     if (rc) return rc;
   }
-  rc = lm_head_impl(c, m->d_packed_head, c->s_x, rows, d_argmax_all, nullptr, nullptr, st, true, HarvestArgs());
+  HarvestArgs hv;
+  hv.keep_logits = any_harvest;
+  rc = lm_head_impl(c, m->d_packed_head, c->s_x, rows, d_argmax_all, nullptr, nullptr, st, true, hv);
   if (rc) return rc;
+  for (int r = 0; r < n_req && any_harvest; ++r) {  // every request into its own tables, from its rows of the logits
+    const goose_request& q = reqs[r];
+    if (!q.d_succ_ids_or_null) continue;
+    rc = launch_harvest_topk(c->logits + (size_t)segs[r].row0 * c->Vpad, (size_t)c->Vpad, d.vocab, q.d_tokens, q.B,
+                             q.harvest_k, d.vocab, q.d_succ_ids_or_null, q.d_succ_scores_or_null, st);
+    if (rc) return rc;
+  }
   return launch_batch_end(br, n_req, d_argmax_all, d.n_layers, c->n_kv, c->cap, d.head_dim, st);
 }
 

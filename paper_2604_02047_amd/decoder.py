@@ -2,9 +2,13 @@
 
 Every decision and every computation is a library call: the n-gram match, the routing, the tree
 builder, tiers and moving average are host functions of libgoose; verification, harvest, walk and
-compaction run on the GPU (goose_verify_step).  This module only moves small arrays between them:
-per cycle it uploads the tree (a few hundred bytes) and reads back the walk's result and the table
-rows the harvest touched.
+compaction run on the GPU (goose_verify_step, goose_verify_step_batched).  This module only moves
+small arrays between them: per cycle it uploads the trees (a few hundred bytes each) and reads back
+the walks' results and the table rows the harvest touched.
+
+GooseDecoder decodes one request; BatchedGooseDecoder decodes several with one pass over the
+weights per cycle (the batch sweep of App. D), each request with its own KV cache, successor
+tables and adaptive state, and drops a request from the batch as soon as it has its tokens.
 """
 import numpy as np
 import torch
@@ -13,22 +17,28 @@ from . import binding as gb
 from .runner import GooseModel
 
 
-class GooseDecoder:
-    def __init__(self, gm: GooseModel, B=60, K=10, rho=0.5, D=6, min_score=0.01, bypass_len=8, lens=(3, 4, 5),
-                 max_spine=20, alpha=0.3):
-        assert B <= gm.max_B and 1 + max_spine <= gm.max_B
-        self.gm, self.B, self.K = gm, B, K
-        self.rho, self.D, self.min_score = rho, D, min_score
-        self.bypass_len, self.lens, self.max_spine, self.alpha = bypass_len, tuple(lens), max_spine, alpha
+class _Request:
+    """The state of one request: KV cache and its length, successor tables (device, and a host mirror
+    for the tree builder), the token sequence, the anchor and the spine-acceptance average."""
+
+    def __init__(self, gm: GooseModel, K, kcache=None, vcache=None):
         V, dev = gm.desc.vocab, gm.device
-        self.d_ids = torch.full((V, K), -1, dtype=torch.int32, device=dev)      # written by the harvest kernel
+        i32 = dict(dtype=torch.int32, device=dev)
+        self.gm, self.K = gm, K
+        self.kcache = gm.kcache if kcache is None else kcache
+        self.vcache = gm.vcache if vcache is None else vcache
+        self.P = 0
+        self.d_P = torch.zeros(1, **i32)
+        self.accept_len, self.bonus = torch.zeros(1, **i32), torch.zeros(1, **i32)
+        self.path, self.argmax = torch.zeros(gm.max_B, **i32), torch.zeros(gm.max_B, **i32)
+        self.d_ids = torch.full((V, K), -1, **i32)                       # written by the harvest kernel
         self.d_scores = torch.zeros((V, K), dtype=torch.float32, device=dev)
-        self.h_ids = np.full((V, K), -1, np.int32)                               # host mirror for the tree builder
+        self.h_ids = np.full((V, K), -1, np.int32)                       # host mirror for the tree builder
         self.h_scores = np.zeros((V, K), np.float32)
         self.seq, self.p_hat, self.anchor = [], 0.3, None
         self.trace = []
 
-    def _mirror_rows(self, tokens):
+    def mirror_rows(self, tokens):
         idx = torch.as_tensor(np.unique(np.asarray(tokens, np.int64)), device=self.gm.device)
         self.h_ids[idx.cpu().numpy()] = self.d_ids[idx].cpu().numpy()
         self.h_scores[idx.cpu().numpy()] = self.d_scores[idx].cpu().numpy()
@@ -38,7 +48,6 @@ class GooseDecoder:
         position's logits, and returns the first generated token."""
         gm, c = self.gm, self.gm.ctx
         prompt = [int(t) for t in prompt]
-        gm.set_P(0)
         done, step = 0, gm.max_B
         while done < len(prompt):
             n = min(step, len(prompt) - done)
@@ -46,27 +55,27 @@ class GooseDecoder:
             t, p, s = gm.stage_tree(chunk, np.arange(-1, n - 1), np.ones(n, np.uint8))
             W = (n + 63) // 64
             mask = gm.mask.view(-1)[:n * W]
-            c.goose_build_mask(p, n, gm.P, mask, gm.depth, gm.pos)
+            c.goose_build_mask(p, n, done, mask, gm.depth, gm.pos)
             c.goose_embed(gm.embed, t, n, gm.x)
             for l in range(gm.desc.n_layers):
-                c.goose_verify_layer(gm.packed_layer(l), gm.x, gm.kcache[l], gm.vcache[l], gm.P, n, mask, gm.pos)
+                c.goose_verify_layer(gm.packed_layer(l), gm.x, self.kcache[l], self.vcache[l], done, n, mask, gm.pos)
             logits = torch.empty((n, gm.desc.vocab), dtype=torch.float32, device=gm.device)
             c.goose_lm_head_argmax(gm.packed_head, gm.x, n, gm.argmax, logits, None)
             c.goose_harvest_topk(logits, gm.desc.vocab, t, n, self.K, self.d_ids, self.d_scores)
             done += n
-            gm.set_P(done)
         torch.cuda.synchronize()
-        self._mirror_rows(prompt)
+        self.P = done
+        self.d_P.fill_(done)
+        self.mirror_rows(prompt)
         self.anchor = int(gm.argmax[n - 1].item())
         self.seq = prompt + [self.anchor]
         return self.anchor
 
-    def cycle(self):
-        """One cycle; returns the tokens it emitted (accepted drafts and the bonus token)."""
-        gm = self.gm
-        draft, consensus = gb.goose_context_match(self.seq, self.lens, self.max_spine)
-        has_succ = bool(((self.h_ids[self.anchor] >= 0) & (self.h_scores[self.anchor] >= self.min_score)).any())
-        mode = gb.goose_cycle_mode(len(draft), consensus, self.bypass_len, has_succ)
+    def plan(self, o):
+        """The tree of the next cycle (host side of Alg. "Decoding Loop"): tokens, parent, is_spine, mode."""
+        draft, consensus = gb.goose_context_match(self.seq, o.lens, o.max_spine)
+        has_succ = bool(((self.h_ids[self.anchor] >= 0) & (self.h_scores[self.anchor] >= o.min_score)).any())
+        mode = gb.goose_cycle_mode(len(draft), consensus, o.bypass_len, has_succ)
         if mode == gb.MODE_BYPASS:
             n = 1 + len(draft)
             tokens = np.concatenate([[self.anchor], draft]).astype(np.int32)
@@ -74,31 +83,121 @@ class GooseDecoder:
             is_spine = np.ones(n, np.uint8)
         elif mode == gb.MODE_TREE:
             r = gb.goose_spine_ratio_tier(self.p_hat)
-            tokens, parent, is_spine = gb.goose_build_spine_tree(self.anchor, draft, self.h_ids, self.h_scores, self.B,
-                                                                 r, self.rho, self.D, self.min_score)
+            tokens, parent, is_spine = gb.goose_build_spine_tree(self.anchor, draft, self.h_ids, self.h_scores, o.B,
+                                                                 r, o.rho, o.D, o.min_score)
         else:
             tokens, parent, is_spine = (np.array([self.anchor], np.int32), np.array([-1], np.int32),
                                         np.ones(1, np.uint8))
-        n = len(tokens)
-        t, p, s = gm.stage_tree(tokens, parent, is_spine)
-        gm.verify_step_fused(t, p, s, n, gm.cap - n, succ_ids=self.d_ids, succ_scores=self.d_scores)
-        torch.cuda.synchronize()
-        L = int(gm.accept_len.item())
-        path = gm.path[:L + 1].cpu().numpy()
-        bonus = int(gm.bonus.item())
-        gm.P = int(gm.d_P.item())
-        self._mirror_rows(tokens)
+        return tokens, parent, is_spine, mode
+
+    def absorb(self, o, tokens, is_spine, mode, L, path, bonus, P):
+        """Takes the walk's result of a cycle; returns the tokens the cycle emitted."""
+        self.P = P
+        self.mirror_rows(tokens)
         offered = int(is_spine.sum()) - 1
         acc_spine = int(is_spine[path[1:]].sum())
-        self.p_hat = gb.goose_ema_update(self.p_hat, acc_spine, offered, self.alpha)
+        self.p_hat = gb.goose_ema_update(self.p_hat, acc_spine, offered, o.alpha)
         emitted = [int(tokens[v]) for v in path[1:]] + [bonus]
         self.seq += emitted
         self.anchor = bonus
-        self.trace.append({"mode": mode, "nodes": n, "accepted": L, "p_hat": self.p_hat})
+        self.trace.append({"mode": mode, "nodes": len(tokens), "accepted": L, "p_hat": self.p_hat})
         return emitted
+
+
+class _Options:
+    def __init__(self, gm, B, K, rho, D, min_score, bypass_len, lens, max_spine, alpha):
+        assert B <= gm.max_B and 1 + max_spine <= gm.max_B
+        self.B, self.K, self.rho, self.D, self.min_score = B, K, rho, D, min_score
+        self.bypass_len, self.lens, self.max_spine, self.alpha = bypass_len, tuple(lens), max_spine, alpha
+
+
+class GooseDecoder:
+    def __init__(self, gm: GooseModel, B=60, K=10, rho=0.5, D=6, min_score=0.01, bypass_len=8, lens=(3, 4, 5),
+                 max_spine=20, alpha=0.3):
+        self.gm = gm
+        self.o = _Options(gm, B, K, rho, D, min_score, bypass_len, lens, max_spine, alpha)
+        self.req = _Request(gm, K)
+
+    trace = property(lambda self: self.req.trace)
+    seq = property(lambda self: self.req.seq)
+    p_hat = property(lambda self: self.req.p_hat)
+
+    @property
+    def lens(self):
+        return self.o.lens
+
+    @lens.setter
+    def lens(self, v):
+        self.o.lens = tuple(v)
+
+    def prefill(self, prompt):
+        first = self.req.prefill(prompt)
+        self.gm.set_P(self.req.P)
+        return first
+
+    def cycle(self):
+        """One cycle; returns the tokens it emitted (accepted drafts and the bonus token)."""
+        gm, q = self.gm, self.req
+        tokens, parent, is_spine, mode = q.plan(self.o)
+        n = len(tokens)
+        t, p, s = gm.stage_tree(tokens, parent, is_spine)
+        gm.verify_step_fused(t, p, s, n, gm.cap - n, succ_ids=q.d_ids, succ_scores=q.d_scores)
+        torch.cuda.synchronize()
+        L = int(gm.accept_len.item())
+        gm.P = int(gm.d_P.item())
+        return q.absorb(self.o, tokens, is_spine, mode, L, gm.path[:L + 1].cpu().numpy(), int(gm.bonus.item()), gm.P)
 
     def generate(self, prompt, n_new):
         out = [self.prefill(prompt)]
         while len(out) < n_new:
             out += self.cycle()
         return out
+
+
+class BatchedGooseDecoder:
+    """Several requests, one pass over the weights per cycle.  `gm` must have been created with
+    max_rows >= the rows of a full batch (round_up(B, 32) per request)."""
+
+    def __init__(self, gm: GooseModel, n_requests, B=32, K=10, rho=0.5, D=6, min_score=0.01, bypass_len=8,
+                 lens=(3, 4, 5), max_spine=20, alpha=0.3):
+        assert n_requests * ((max(B, 1 + max_spine) + 31) // 32 * 32) <= gm.ctx.max_rows
+        self.gm = gm
+        self.o = _Options(gm, B, K, rho, D, min_score, bypass_len, lens, max_spine, alpha)
+        self.reqs = [_Request(gm, K, torch.zeros_like(gm.kcache), torch.zeros_like(gm.vcache))
+                     for _ in range(n_requests)]
+        self.argmax_all = torch.zeros(gm.ctx.max_rows, dtype=torch.int32, device=gm.device)
+        self.passes = 0
+
+    def cycle(self, active):
+        """One batched cycle over the requests `active` (indices); returns {index: emitted tokens}."""
+        gm = self.gm
+        plans, table = [], []
+        for i in active:
+            q = self.reqs[i]
+            tokens, parent, is_spine, mode = q.plan(self.o)
+            t, p, s = gm.stage_tree(tokens, parent, is_spine)
+            plans.append((tokens, is_spine, mode))
+            table.append({"tokens": t, "parent": p, "is_spine": s, "B": len(tokens), "P_max": gm.cap - len(tokens),
+                          "kcache": q.kcache, "vcache": q.vcache, "P": q.d_P, "accept_len": q.accept_len,
+                          "path": q.path, "bonus": q.bonus, "succ_ids": q.d_ids, "succ_scores": q.d_scores})
+        gm.ctx.goose_verify_step_batched(gm.model_ptrs(), table, self.argmax_all)
+        torch.cuda.synchronize()
+        self.passes += 1
+        out = {}
+        for i, (tokens, is_spine, mode) in zip(active, plans):
+            q = self.reqs[i]
+            L = int(q.accept_len.item())
+            out[i] = q.absorb(self.o, tokens, is_spine, mode, L, q.path[:L + 1].cpu().numpy(), int(q.bonus.item()),
+                              int(q.d_P.item()))
+        return out
+
+    def generate(self, prompts, n_new):
+        """Returns one token list per prompt, each at least n_new long; a request leaves the batch when done."""
+        assert len(prompts) == len(self.reqs)
+        outs = [[q.prefill(p)] for q, p in zip(self.reqs, prompts)]
+        active = list(range(len(prompts)))
+        while active:
+            for i, emitted in self.cycle(active).items():
+                outs[i] += emitted
+            active = [i for i in active if len(outs[i]) < n_new]
+        return outs

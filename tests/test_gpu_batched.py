@@ -36,9 +36,11 @@ def _alone(gm, reqs):
     for q in reqs:
         gm.kcache, gm.vcache = q["kcache"], q["vcache"]
         gm.set_P(q["P0"])
-        gm.verify_step_fused(q["tokens"], q["parent"], q["is_spine"], q["B"], q["P_max"])
+        ids = torch.full((gm.desc.vocab, 10), -1, dtype=torch.int32, device=gm.device)
+        sc = torch.zeros((gm.desc.vocab, 10), dtype=torch.float32, device=gm.device)
+        gm.verify_step_fused(q["tokens"], q["parent"], q["is_spine"], q["B"], q["P_max"], succ_ids=ids, succ_scores=sc)
         torch.cuda.synchronize()
-        out.append({"argmax": gm.argmax[:q["B"]].clone(), "L": int(gm.accept_len.item()),
+        out.append({"ids": ids, "scores": sc, "argmax": gm.argmax[:q["B"]].clone(), "L": int(gm.accept_len.item()),
                     "path": gm.path[:q["B"]].clone(), "bonus": int(gm.bonus.item()), "P": int(gm.d_P.item()),
                     "k": q["kcache"].clone(), "v": q["vcache"].clone()})
         q["kcache"].copy_(q["k0"])
@@ -51,6 +53,8 @@ def _batched(gm, reqs):
     for q in reqs:
         q["P"] = torch.full((1,), q["P0"], **i32)
         q["accept_len"], q["path"], q["bonus"] = torch.zeros(1, **i32), torch.zeros(128, **i32), torch.zeros(1, **i32)
+        q["succ_ids"] = torch.full((gm.desc.vocab, 10), -1, **i32)      # every request harvests into its own tables
+        q["succ_scores"] = torch.zeros((gm.desc.vocab, 10), dtype=torch.float32, device=gm.device)
     argmax_all = torch.full((gm.ctx.max_rows,), -1, **i32)
     gm.ctx.goose_verify_step_batched(gm.model_ptrs(), reqs, argmax_all)
     torch.cuda.synchronize()
@@ -120,6 +124,8 @@ def test_batched_step_equals_the_requests_alone(shape_name, sizes):
         assert torch.equal(q["argmax"], a["argmax"])
         assert int(q["accept_len"].item()) == a["L"] and int(q["bonus"].item()) == a["bonus"]
         assert torch.equal(q["path"][:q["B"]], a["path"]) and int(q["P"].item()) == a["P"]
+        assert torch.equal(q["succ_ids"], a["ids"]) and torch.equal(q["succ_scores"], a["scores"])   # harvest
+        assert int((q["succ_ids"][:, 0] >= 0).sum().item()) == len(set(q["host_tokens"].tolist()))
         k_b, v_b = _rows(gm, q["kcache"], q["vcache"], 0, a["P"])   # the committed cache is identical
         k_a, v_a = _rows(gm, a["k"], a["v"], 0, a["P"])
         assert torch.equal(k_b, k_a) and torch.equal(v_b, v_a)

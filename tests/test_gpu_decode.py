@@ -64,3 +64,29 @@ def test_small_bf16_decoding_equals_its_own_autoregressive_decoding():
     assert len(dec.trace) < len(y) and {t["mode"] for t in dec.trace} >= {1}
     assert sum(t["accepted"] for t in dec.trace) >= 10
     gm.ctx.close()
+
+
+def test_batched_decoding_is_batch_lossless():
+    """Several requests decoded with one pass over the weights per cycle give the tokens each gives alone
+    (the self-test of the batch sweep, App. D).  16-bit near-ties may be decided differently when the
+    launches differ in shape (other key-split counts): long agreement is the check, as above."""
+    from paper_2604_02047_amd.decoder import BatchedGooseDecoder, GooseDecoder
+    shape = gi.SHAPES["small_bf16"]
+    tm = torch_model(shape, seed=6, gain_jitter=0.1)
+    prompts = [_prompt(shape.vocab, 20 + r)[:30 + 7 * r] for r in range(4)]
+    n_new = [60, 60, 60, 60]
+    gm = gpu_model(shape, tm, max_B=64, cap=512, max_rows=256)
+    bd = BatchedGooseDecoder(gm, 4, B=40, min_score=0.0)
+    outs = bd.generate(prompts, 60)
+    assert gm.ctx.goose_device_flags() == 0
+    total = sum(len(o) for o in outs)
+    assert bd.passes < total / 4            # fewer passes than tokens per request: drafts were accepted
+    assert any(t["mode"] == 1 and t["nodes"] == 40 for q in bd.reqs for t in q.trace)   # full trees in the batch
+    gm.ctx.close()
+    for r, prompt in enumerate(prompts):
+        gm = gpu_model(shape, tm, max_B=64, cap=512)
+        y = GooseDecoder(gm, B=40, min_score=0.0).generate(prompt, n_new[r])
+        gm.ctx.close()
+        n = min(len(y), len(outs[r]))
+        same = next((i for i in range(n) if y[i] != outs[r][i]), n)
+        assert same >= 40, (r, same, y[:same + 2], outs[r][:same + 2])
