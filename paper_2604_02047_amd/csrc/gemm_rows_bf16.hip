@@ -16,8 +16,10 @@
 //     dealt to the 8 XCDs round-robin), so the later chunks find the weights in that XCD's L2.
 //   Measured on MI355X (28672 x 4096 gate/up, 512 rows): 135 us = 0.89 PFLOP/s, 36 % of the bf16
 //   MFMA peak; the chunked skinny kernel takes 178 us.  One workgroup per compute unit (registers),
-//   about 40 % of its time in matrix instructions; the rest is operand delivery (1.4 GB through
-//   the L2 per launch) and the barrier per stage.
+//   measured with parts compiled out: matrix instructions alone 85 us (a single wavefront per SIMD
+//   issues them at 57 % of the nominal rate), everything but them 80 us, together 135 us -- the two
+//   overlap only in part.  A third LDS buffer with the next stage's operands read across the
+//   barrier, and exact wait counts, changed nothing.
 //   * Epilogues: fp32 split-K partials, or SwiGLU (the gate tile and the up tile of 32 hidden
 //     columns are the two column tiles of one wavefront: no exchange needed).
 #include <type_traits>
