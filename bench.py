@@ -444,9 +444,11 @@ def bench_batched(args, shape, P0, K, W, log):
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(shape, gm, seed, B, P0, tree_kind, log):
-    """Times the NumPy fp64 oracle on a few decoder layers and the LM head of one step at this workload's
-    shape (same weights, the device's own prefix KV as input) and scales to the full layer count."""
+def cpu_baseline(shape, gm, seed, B, P0, tree_kind, log, n_steps=14):
+    """Times the NumPy fp64 oracle on a bounded sample of this workload: `n_steps` verification steps
+    (different trees and draft tokens, the device's own prefix KV as input, the same weights) through
+    half of the decoder layers, plus LM head, argmax and walk; the layer time is scaled to the full
+    layer count.  About 10 s of oracle arithmetic at the 7B shape."""
     import torch
     import goose_inputs as gi
     from oracle import goose_oracle as orc
@@ -460,34 +462,41 @@ def cpu_baseline(shape, gm, seed, B, P0, tree_kind, log):
         return t.detach().to("cpu").to(torch.float64).numpy()
 
     n_s = min(16, shape.n_layers)
-    log(f"cpu baseline: building the {n_s}-layer oracle sample")
+    log(f"cpu baseline: {n_steps} steps through a {n_s}-layer oracle sample")
     om = orc.OracleModel(shape.n_heads, shape.head_dim, shape.rope_base, shape.rms_eps, [None] * n_s,
                          f64(gm.embed), f64(gi.lm_head(shape, seed, gm.device)),
                          f64(gi.final_norm(shape, seed, gm.device)), n_kv_heads=shape.kv_heads, qk_norm=shape.qk_norm)
     kr, vr = gm.k_rows(0, P0), gm.v_rows(0, P0)
-    tree = make_tree(tree_kind, 0)
-    toks = gi.draft_tokens_uniform(seed, tree.parent, shape.vocab, 1)
-    anc, depth = orc.ancestor_mask(tree.parent)
-    allow = np.concatenate([np.ones((B, P0), dtype=bool), anc], axis=1)
-    x = om.embed[toks.astype(np.int64)]
+    steps = []
+    for t in range(n_steps):
+        tree = make_tree(tree_kind, t)
+        toks = gi.draft_tokens_uniform(seed + t, tree.parent, shape.vocab, 1 + t)
+        anc, depth = orc.ancestor_mask(tree.parent)
+        steps.append({"tree": tree, "toks": toks, "pos": P0 + depth,
+                      "allow": np.concatenate([np.ones((B, P0), dtype=bool), anc], axis=1),
+                      "x": om.embed[toks.astype(np.int64)]})
     t_layers = 0.0
     for l in range(n_s):  # one layer's fp64 weights at a time; only the oracle's arithmetic is timed
         w = {k: f64(v) for k, v in gi.layer_weights(shape, seed, l, gm.device).items()}
         Kc, Vc = f64(kr[l]), f64(vr[l])
         ta = time.perf_counter()
-        x, _, _ = orc.decoder_layer(om, w, x, Kc, Vc, P0 + depth, allow)
+        for st in steps:
+            st["x"], _, _ = orc.decoder_layer(om, w, st["x"], Kc, Vc, st["pos"], st["allow"])
         t_layers += time.perf_counter() - ta
         del w, Kc, Vc
     tb = time.perf_counter()
-    logits = orc.final_logits(om, x)
-    x_hat = orc.argmax_lowest(logits)
-    orc.greedy_walk(tree.parent, toks, tree.is_spine, x_hat)
+    for st in steps:
+        logits = orc.final_logits(om, st["x"])
+        x_hat = orc.argmax_lowest(logits)
+        orc.greedy_walk(st["tree"].parent, st["toks"], st["tree"].is_spine, x_hat)
     tc = time.perf_counter()
-    t_step = t_layers / n_s * shape.n_layers + (tc - tb)
-    log(f"cpu baseline: {n_s} layers {t_layers:.2f}s, head {tc - tb:.2f}s -> {t_step:.1f}s/step on {threads} threads")
+    t_step = (t_layers / n_s * shape.n_layers + (tc - tb)) / n_steps
+    log(f"cpu baseline: {n_steps} x {n_s} layers {t_layers:.2f}s, heads {tc - tb:.2f}s -> {t_step:.2f}s/step "
+        f"on {threads} threads")
     return {"value": round(1.0 / t_step, 5), "unit": "steps/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{n_s} of {shape.n_layers} decoder layers + LM head + walk of one step "
-                      f"(B={B}, P={P0}), layer time scaled linearly to {shape.n_layers} layers",
+            "sample": f"{n_steps} steps (B={B}, P={P0}, different trees and tokens) through {n_s} of "
+                      f"{shape.n_layers} decoder layers + LM head + walk; layer time scaled linearly to "
+                      f"{shape.n_layers} layers",
             "seconds_measured": round(t_layers + tc - tb, 2)}
 
 
