@@ -94,7 +94,7 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   constexpr int VROW = TROWS * 2 + 16;     // bytes per V^T row in LDS (padded)
   constexpr int TAIL_BYTES = 2 * TROWS * KROW + D * VROW;  // tree keys, tree values, rotated queries
   constexpr int OREGS = (D / 32) * 16;                     // accumulator floats per lane
-  constexpr int MERGE_BYTES = (NG / 2) * NQH * (OREGS + 2) * 64 * 4;
+  constexpr int MERGE_BYTES = (NG / 2) * NQH * (OREGS + 4) * 64 * 4;
   constexpr int LDS_BYTES = TAIL_BYTES > MERGE_BYTES ? TAIL_BYTES : MERGE_BYTES;
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
   unsigned char* Kt = lds;                  // tree keys   [i][c]  (rotated)
@@ -306,11 +306,26 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
 
   // ---- the tree's values into the cache, node index fastest so that neighbouring lanes fill
   // neighbouring bytes (the keys went out above)
+  // (eight consecutive slots of one column are 16 contiguous bytes of the cache: one store per
+  // (column, 8-slot group) where the group lies inside the tree, single elements at its two ends)
   if (last && tail_writer) {
     T* vw = const_cast<T*>(vh);
-    for (int it = tid; it < rows * D; it += NTHR) {
-      const int i = it % rows, c = it / rows;
-      if (i < B) vw[v_elem_off<D>(P + i, c)] = *reinterpret_cast<const T*>(Vt + c * VROW + i * 2);
+    const int g_lo = P >> 3, ngrp = ((P + B - 1) >> 3) - g_lo + 1;
+    for (int it = tid; it < ngrp * D; it += NTHR) {
+      const int c = it % D, G = g_lo + it / D;
+      const int i0 = (G << 3) - P;  // tree node of the group's first slot (may be negative)
+      const unsigned char* src = Vt + c * VROW;
+      T* dst = vw + v_elem_off<D>(G << 3, c);
+      if (i0 >= 0 && i0 + 8 <= B) {
+        op8 v;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = *reinterpret_cast<const T*>(src + (i0 + e) * 2);
+        *reinterpret_cast<op8*>(dst) = v;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (i0 + e >= 0 && i0 + e < B) dst[e] = *reinterpret_cast<const T*>(src + (i0 + e) * 2);
+      }
     }
   }
 
@@ -406,22 +421,26 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   if (NG > 1) {
     __syncthreads();  // every wavefront is done with the tree and query buffers
     float* mbuf = reinterpret_cast<float*>(lds);
-    constexpr int WFLOATS = (OREGS + 2) * 64;
+    // a wavefront's state as 16-byte pieces, piece q of lane l at float 256*q + 4*l: (m, l, -, -), then
+    // the accumulator four registers at a time
+    constexpr int WFLOATS = (OREGS + 4) * 64;
 #pragma unroll
     for (int half = NG / 2; half >= 1; half >>= 1) {
       if (g >= half && g < 2 * half) {
-        float* dst = mbuf + (size_t)(qh * (NG / 2) + (g - half)) * WFLOATS + lane;
-        dst[0] = m_run;
-        dst[64] = l_run;
+        float* dst = mbuf + (size_t)(qh * (NG / 2) + (g - half)) * WFLOATS + lane * 4;
+        *reinterpret_cast<f32x4*>(dst) = f32x4{m_run, l_run, 0.f, 0.f};
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) dst[64 * (2 + dt * 16 + r)] = oacc[dt][r];
+          for (int a = 0; a < 4; ++a)
+            *reinterpret_cast<f32x4*>(dst + 256 * (1 + dt * 4 + a)) =
+                f32x4{oacc[dt][a * 4], oacc[dt][a * 4 + 1], oacc[dt][a * 4 + 2], oacc[dt][a * 4 + 3]};
       }
       __syncthreads();
       if (g < half) {
-        const float* src = mbuf + (size_t)(qh * (NG / 2) + g) * WFLOATS + lane;
-        const float mo = src[0], lo = src[64];
+        const float* src = mbuf + (size_t)(qh * (NG / 2) + g) * WFLOATS + lane * 4;
+        const f32x4 ml = *reinterpret_cast<const f32x4*>(src);
+        const float mo = ml[0], lo = ml[1];
         const float m_new = fmaxf(m_run, mo);
         const float a = __builtin_amdgcn_exp2f(m_run - m_new), b = __builtin_amdgcn_exp2f(mo - m_new);
         m_run = m_new;
@@ -429,7 +448,11 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[dt][r] = oacc[dt][r] * a + src[64 * (2 + dt * 16 + r)] * b;
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const f32x4 o4 = *reinterpret_cast<const f32x4*>(src + 256 * (1 + dt * 4 + q4));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) oacc[dt][q4 * 4 + e] = oacc[dt][q4 * 4 + e] * a + o4[e] * b;
+          }
       }
       if (half > 1) __syncthreads();
     }
