@@ -330,6 +330,11 @@ def main():
         "tokens_emitted_per_s": round(float(np.sum(np.asarray(acc_hist[W:]) + 1)) / elapsed, 1),
         "achieved_GBps": round(achieved, 1), "hbm_frac": round(achieved / HBM_PEAK_GBPS, 4),
         "algorithmic_GB_per_step": round(bytes_timed / K / 1e9, 3),
+        # evidence that the matrix cores keep up with the stream (not the bound): 2 flops per weight per node
+        # for the projections and the LM head, 4 * B * (P + B) * hidden per layer for the attention
+        "achieved_TFLOPs": round(sum(2.0 * B * (shape.n_layers * shape.layer_param_count() + shape.vocab * shape.hidden)
+                                     + 4.0 * B * (P_hist[t] + B) * shape.n_heads * shape.head_dim * shape.n_layers
+                                     for t in range(W, total)) / elapsed / 1e12, 1),
         "roofline": roofline, "cpu_baseline": cpu, "kernels_avg_us": kernels,
     }
     print(json.dumps(out), flush=True)
