@@ -133,12 +133,15 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
       b_hi = (int)(((long)rest * (split + 1)) / (nsplit - 1));
     }
   }
-  const int nb_split = b_hi - b_lo;
+  // a wavefront whose query tile lies wholly beyond the tree (a 3-tile tree in the 4-tile kernel)
+  // walks no blocks; it still takes part in the prologue and in the barriers
+  const bool idle = qh * 32 >= B;
+  const int nb_split = idle ? 0 : b_hi - b_lo;
   const int blk0 = b_lo + (nb_split * g) / NG;
   const int nblk = b_lo + (nb_split * (g + 1)) / NG - blk0;
   // This wavefront's block sequence: its prefix blocks (operands from the cache), then, in the
   // last split, the tree blocks t = g, g+NG, .. (operands from LDS).
-  const int ntail = last ? (nbt - g + NG - 1) / NG : 0;
+  const int ntail = (last && !idle) ? (nbt - g + NG - 1) / NG : 0;
   const int total = nblk + (ntail > 0 ? ntail : 0);
 
   const T* kh = kc + (size_t)kvh * cap * D;
