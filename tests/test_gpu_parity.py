@@ -160,6 +160,24 @@ def test_tiny_fp32_empty_prefix_and_big_trees():
     gm.ctx.close()
 
 
+@pytest.mark.parametrize("shape_name", ["tiny_bf16", "small_gqa_qknorm_f16"])
+def test_16bit_empty_prefix_and_big_trees(shape_name):
+    """MFMA path from an empty cache (no prefix blocks at all, then a ragged first block): every tree shape."""
+    trees = [gi.tree_spine_7b(1), gi.tree_single(), gi.tree_spine_stress(), gi.tree_random(65, 2), gi.tree_balanced()]
+    shape = gi.SHAPES[shape_name]
+    tm = torch_model(shape, seed=1, gain_jitter=0.1)
+    om = oracle_model(shape, tm)
+    gm = gpu_model(shape, tm, max_B=128, cap=1024)
+    gm.set_P(0)
+    root = 17
+    for n, tree in enumerate(trees):
+        cache = device_cache_as_oracle(gm, gm.P) if gm.P else orc.empty_cache(om)
+        tokens = gi.draft_tokens_uniform(n, tree.parent, shape.vocab, root)
+        g, o, decisive = _compare_step(shape, gm, om, cache, tokens, tree, tol_for(shape))
+        root = g["bonus"]
+    gm.ctx.close()
+
+
 @pytest.mark.parametrize("shape_name,P0,chunk", [("tiny_bf16", 128, 16), ("small_bf16", 200, 50),
                                                  ("tiny_gqa_bf16", 100, 32), ("small_gqa_qknorm_bf16", 210, 70),
                                                  ("tiny_f16", 128, 16), ("small_gqa_qknorm_f16", 210, 70)])
