@@ -192,3 +192,21 @@ def test_bf16_cycles_match_the_oracle(shape_name, P0, chunk):
 def test_bf16_independent_prefill_stays_within_tolerance(shape_name):
     trees = [gi.tree_spine_7b(3), gi.tree_tiny_spine()]
     _run_cycles(shape_name, 2, 96, trees, seed=5, oracle_prefill=True, chunk=32)
+
+
+def test_16bit_tree_that_fills_the_cache_to_its_last_slot():
+    """P + B == cap exactly (the largest tree in the last free slots), and one slot more is refused."""
+    from paper_2604_02047_amd.binding import GooseError
+    shape = gi.SHAPES["tiny_bf16"]
+    tm = torch_model(shape, seed=3, gain_jitter=0.1)
+    om = oracle_model(shape, tm)
+    gm = gpu_model(shape, tm, max_B=128, cap=192)
+    _gpu_prefill(gm, gi.prefix_tokens(9, 64, shape.vocab), 64)
+    assert gm.P == 64
+    tree = gi.tree_spine_stress()
+    tokens = gi.draft_tokens_uniform(4, tree.parent, shape.vocab, 5)
+    _compare_step(shape, gm, om, device_cache_as_oracle(gm, 64), tokens, tree, tol_for(shape))
+    gm.set_P(65)
+    with pytest.raises(GooseError):
+        gm.verify_step_calls(tokens, tree.parent, tree.is_spine, commit=False)
+    gm.ctx.close()
