@@ -40,3 +40,20 @@ def test_every_generated_tree_passes_the_host_check():
     for t in [gi.tree_tiny_spine(), gi.tree_spine_7b(0), gi.tree_spine_13b(), gi.tree_spine_33b(),
               gi.tree_spine_stress(), gi.tree_balanced(), gi.tree_random(128, 0)]:
         assert g.goose_check_parent(t.parent) == 0
+
+
+def test_the_public_header_is_plain_c(tmp_path):
+    """include/goose.h is the boundary: it must compile as C99 (no C++ or torch types in the signatures)."""
+    import os
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        import pytest
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "h.c"
+    src.write_text('#include "goose.h"\nint main(void) { return GOOSE_OK; }\n')
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                        "-I", os.path.join(root, "include"), str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
