@@ -103,7 +103,10 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = wave % NG, qh = wave / NG;  // key group, query tile
-  const int split = blockIdx.x, nsplit = gridDim.x, h = blockIdx.y;
+  // head = the fast grid index: workgroups are dealt to the 8 XCDs round-robin, so head h runs on
+  // XCD h % 8, where the projection kernel's workgroup of the same 128 columns ran (q, k and v
+  // of head h sit 32 and 64 column groups apart): its partial sums are still in that XCD's L2
+  const int h = blockIdx.x, split = blockIdx.y, nsplit = gridDim.y;
   const int l31 = lane & 31, hh = lane >> 5;
   // grouped queries: `group` query heads share KV head kvh; their projections sit at columns
   // [0,Hq) q, [Hq, Hq+Hkv) k, [Hq+Hkv, Hq+2Hkv) v of the fused projection
@@ -499,8 +502,9 @@ __global__ void k_attn_merge(const float* __restrict__ att_o, const float* __res
                              int D, typename Mma16<F16>::T* __restrict__ o, int ldo, const SegTable<TS> segs) {
   typedef typename Mma16<F16>::T T;
   const SegDev& sg = segs.s[TS == 1 ? 0 : blockIdx.z];
-  if ((int)blockIdx.x >= sg.B) return;
-  const int qi = sg.row0 + blockIdx.x, h = blockIdx.y, c = threadIdx.x;
+  if ((int)blockIdx.y >= sg.B) return;
+  // head = the fast grid index: the workgroup runs on the XCD whose L2 holds that head's partials
+  const int qi = sg.row0 + blockIdx.y, h = blockIdx.x, c = threadIdx.x;
   float mmax = NEG_BIG;
   for (int s = 0; s < nsplit; ++s) mmax = fmaxf(mmax, att_ml[(((size_t)h * nsplit + s) * Bpad + qi) * 2]);
   float num = 0.f, den = 0.f;
@@ -631,11 +635,11 @@ int launch_attn_16(int dtype, const float* part, int ks, size_t part_stride, siz
     if (n == 0) continue;
     int splits = splits_or_0 > 0 ? splits_or_0 : pick_attn_splits(n_heads * n, keys_max, max_splits);
     if (splits > max_splits) splits = max_splits;
-    const dim3 grid(splits, n_heads, n);
+    const dim3 grid(n_heads, splits, n);
     int rc = head_dim == 128 ? launch_d<128>(cls, key_groups, grid, st, a, t) : launch_d<64>(cls, key_groups, grid, st, a, t);
     if (rc != GOOSE_OK) return rc;
     if (splits == 1) continue;
-    const dim3 mgrid(b_max, n_heads, n);
+    const dim3 mgrid(n_heads, b_max, n);
     rc = a.f16 ? launch_merge<true>(mgrid, head_dim, st, a, splits, t)
                : launch_merge<false>(mgrid, head_dim, st, a, splits, t);
     if (rc != GOOSE_OK) return rc;
