@@ -106,7 +106,16 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   // head = the fast grid index: workgroups are dealt to the 8 XCDs round-robin, so head h runs on
   // XCD h % 8, where the projection kernel's workgroup of the same 128 columns ran (q, k and v
   // of head h sit 32 and 64 column groups apart): its partial sums are still in that XCD's L2
-  const int h = blockIdx.x, split = blockIdx.y, nsplit = gridDim.y;
+  const int split = blockIdx.y, nsplit = gridDim.y;
+  int h = blockIdx.x;
+  if (n_kv_heads != n_heads && (n_kv_heads & 7) == 0) {
+    // grouped queries: the heads of one KV head stream the same cache blocks, so they share an XCD
+    // (KV head j on XCD j % 8) and all but the first find the blocks in its L2; 8 | n_kv_heads
+    // makes this a permutation of the heads
+    const int grp = n_heads / n_kv_heads, xcd = h & 7, s = h >> 3;
+    const int t = s / grp;
+    h = (xcd + 8 * t) * grp + (s - t * grp);
+  }
   const int l31 = lane & 31, hh = lane >> 5;
   // grouped queries: `group` query heads share KV head kvh; their projections sit at columns
   // [0,Hq) q, [Hq, Hq+Hkv) k, [Hq+Hkv, Hq+2Hkv) v of the fused projection
