@@ -158,9 +158,11 @@ def main():
     log(f"prefill done, P={gm.P}")
 
     # ---- staging buffers of a step (device resident)
-    cur_tok = torch.zeros(B, dtype=torch.int32, device=dev)
-    cur_par = torch.zeros(B, dtype=torch.int32, device=dev)
-    cur_spn = torch.zeros(B, dtype=torch.uint8, device=dev)
+    # tokens | parents | spine tags of the current step in one record: staged with one small copy
+    cur_rec = torch.zeros(9 * B, dtype=torch.uint8, device=dev)
+    cur_tok = cur_rec[0:4 * B].view(torch.int32)
+    cur_par = cur_rec[4 * B:8 * B].view(torch.int32)
+    cur_spn = cur_rec[8 * B:9 * B]
     next_root = torch.zeros(1, dtype=torch.int32, device=dev)
 
     bound = {"P_max": P_max}  # upper bound of the device-resident P that sizes the launches
@@ -214,14 +216,13 @@ def main():
         f"(launch bound {bound['P_max']})")
 
     # ---- device-resident inputs of the timed run
-    tok_all = torch.as_tensor(np.stack(toks).astype(np.int32), device=dev)
-    par_all = torch.as_tensor(np.stack([t.parent for t in trees]).astype(np.int32), device=dev)
-    spn_all = torch.as_tensor(np.stack([t.is_spine for t in trees]).astype(np.uint8), device=dev)
+    rec_all = torch.as_tensor(np.stack([np.concatenate([tk.astype(np.int32).view(np.uint8),
+                                                        tr.parent.astype(np.int32).view(np.uint8),
+                                                        tr.is_spine.astype(np.uint8)])
+                                        for tk, tr in zip(toks, trees)]), device=dev)
 
     def stage(t):  # tiny device-to-device copies; the root is the previous step's bonus token
-        cur_tok.copy_(tok_all[t])
-        cur_par.copy_(par_all[t])
-        cur_spn.copy_(spn_all[t])
+        cur_rec.copy_(rec_all[t])
         if t > 0:
             cur_tok[0:1].copy_(next_root)
 
