@@ -292,8 +292,16 @@ int goose_cycle_mode(int m, int consensus, int bypass_len, int anchor_has_succes
 double goose_spine_ratio_tier(double p_hat);
 double goose_ema_update(double p_hat, int accepted_spine, int offered_spine, double alpha);
 
-/* Device-side diagnostics: bit 0 set if any kernel since the last call saw a parent
- * array that is not topological.  Synchronises `stream`. */
+/* Device-side diagnostics of the calls queued on this context since the last read (the word is then
+ * cleared).  Kernels that take the cache length from device memory (d_P) cannot return a status, so
+ * they record here what the host checks catch for a host-known P:
+ *   GOOSE_FLAG_BAD_PARENT  a parent array that is not a rooted tree in topological order;
+ *   GOOSE_FLAG_CAPACITY    *d_P < 0, *d_P > P_max (the bound the launches were sized for), *d_P + B > cap,
+ *                          or a commit whose new length would exceed cap.
+ * With either bit set the results of that step are meaningless (indices were clamped to stay inside
+ * the buffers) and the caches of the offending request must be treated as corrupt.
+ * This is the one call that synchronises `stream`. */
+enum { GOOSE_FLAG_BAD_PARENT = 1, GOOSE_FLAG_CAPACITY = 2 };
 int goose_device_flags(goose_ctx* ctx, void* stream, int32_t* h_flags_out);
 
 /* ---- the projection kernel on its own (unit tests and tuning; dtype = GOOSE_DTYPE_BF16 or _F16) ---

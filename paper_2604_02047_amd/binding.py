@@ -227,6 +227,8 @@ def goose_build_spine_tree(anchor, draft, succ_ids, succ_scores, B, r, rho=0.5, 
 
 
 MODE_AR, MODE_TREE, MODE_BYPASS = 0, 1, 2
+GOOSE_FLAG_BAD_PARENT, GOOSE_FLAG_CAPACITY = 1, 2   # bits of goose_device_flags
+GOOSE_ERR_CAPACITY, GOOSE_ERR_NOT_TOPOLOGICAL = -3, -4
 
 
 def goose_cycle_mode(m, consensus, bypass_len, anchor_has_successors) -> int:

@@ -57,7 +57,7 @@ __device__ inline size_t v_elem_off(int g, int c) {
 
 // what the kernels need of one request (see AttnSeg); the table travels as a kernel argument
 struct SegDev {
-  int32_t row0, B;
+  int32_t row0, B, P_max;
   void* kc;
   void* vc;
   const int32_t* dP;
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
     const SegTable<TS> segs, int n_heads, int n_kv_heads, int cap, const float* part, int ks, size_t part_stride,
     size_t part_ld, const float2* cs, const typename Mma16<F16>::T* __restrict__ gq,
     const typename Mma16<F16>::T* __restrict__ gk, float eps, float* __restrict__ att_o, float* __restrict__ att_ml,
-    int Bpad, typename Mma16<F16>::T* o_out, int ldo) {
+    int Bpad, typename Mma16<F16>::T* o_out, int ldo, int32_t* __restrict__ flags) {
   typedef typename Mma16<F16>::T T;
   typedef typename Mma16<F16>::v8 op8;
   typedef typename Mma16<F16>::v4 op4;
@@ -124,7 +124,11 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   const int kcol = Hq + kvh * D - h * D, vcol = kcol + Hkv;  // relative to this head's q columns
   const bool tail_writer = (h % group) == 0;                  // one head of the group stores the tree's K/V
   int P = *sg.dP;
-  if (P > cap - B) P = cap - B;  // callers guarantee P + B <= cap; never index outside the cache
+  // a cache length the launch was not sized for, or one that leaves no room for the tree: flagged
+  // (GOOSE_FLAG_CAPACITY), and clamped so that nothing is indexed outside the cache
+  if ((P < 0 || P > sg.P_max || P > cap - B) && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+    atomicOr(flags, GOOSE_FLAG_CAPACITY);
+  if (P > cap - B) P = cap - B;
   if (P < 0) P = 0;
   const bool last = split == nsplit - 1;
 
@@ -542,7 +546,7 @@ __global__ void k_rope_table(const int32_t* __restrict__ pos, const double* __re
 struct AttnArgs {
   const float* part; int ks; size_t part_stride, part_ld; int n_heads, n_kv;
   const float2* cs; int cap; const void* gq; const void* gk; float eps;
-  float* att_o; float* att_ml; int Bpad; void* o; int ldo; bool f16;
+  float* att_o; float* att_ml; int Bpad; void* o; int ldo; bool f16; int32_t* flags;
 };
 
 template <int D, int NG, int NQH, bool F16>
@@ -552,11 +556,11 @@ int launch_t(dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable<ATTN_M
     const SegTable<1> t1{{t.s[0]}};
     hipLaunchKernelGGL((k_attn_fused<D, NG, NQH, F16, 1>), grid, dim3(64 * NG * NQH), 0, st, t1, a.n_heads, a.n_kv,
                        a.cap, a.part, a.ks, a.part_stride, a.part_ld, a.cs, (const T*)a.gq, (const T*)a.gk, a.eps,
-                       a.att_o, a.att_ml, a.Bpad, (T*)a.o, a.ldo);
+                       a.att_o, a.att_ml, a.Bpad, (T*)a.o, a.ldo, a.flags);
   } else {
     hipLaunchKernelGGL((k_attn_fused<D, NG, NQH, F16, ATTN_MAX_SEGS>), grid, dim3(64 * NG * NQH), 0, st, t, a.n_heads,
                        a.n_kv, a.cap, a.part, a.ks, a.part_stride, a.part_ld, a.cs, (const T*)a.gq, (const T*)a.gk,
-                       a.eps, a.att_o, a.att_ml, a.Bpad, (T*)a.o, a.ldo);
+                       a.eps, a.att_o, a.att_ml, a.Bpad, (T*)a.o, a.ldo, a.flags);
   }
   return goose_launch_status();
 }
@@ -614,14 +618,14 @@ int pick_attn_splits(int n_heads, int keys_max, int max_splits) {
 int launch_attn_16(int dtype, const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs,
                    int n_heads, int n_kv_heads, int head_dim, int cap, const AttnSeg* segs, int nseg, int splits_or_0,
                    int max_splits, int key_groups, const void* gq, const void* gk, float eps, float* att_o,
-                   float* att_ml, int Bpad, void* o, int ldo, hipStream_t st) {
+                   float* att_ml, int Bpad, void* o, int ldo, int32_t* flags, hipStream_t st) {
   if (dtype != GOOSE_DTYPE_BF16 && dtype != GOOSE_DTYPE_F16) return GOOSE_ERR_ARG;
   if (n_kv_heads < 1 || n_heads % n_kv_heads != 0 || (gq == nullptr) != (gk == nullptr)) return GOOSE_ERR_ARG;
   if (nseg < 1 || nseg > ATTN_MAX_SEGS || max_splits < 1 || (key_groups != 2 && key_groups != 4) || (cap & 31))
     return GOOSE_ERR_ARG;
   if (head_dim != 128 && head_dim != 64) return GOOSE_ERR_SHAPE;
   const AttnArgs a{part, ks, part_stride, part_ld, n_heads, n_kv_heads, (const float2*)cs, cap, gq, gk, eps,
-                   att_o, att_ml, Bpad, o, ldo, dtype == GOOSE_DTYPE_F16};
+                   att_o, att_ml, Bpad, o, ldo, dtype == GOOSE_DTYPE_F16, flags};
   // a 3-tile tree runs the 4-tile kernel, which reads projection rows up to row0 + 128
   auto tiles_of = [](int B) { const int qt = (B + 31) / 32; return qt >= 3 ? 4 : qt; };
   for (int r = 0; r < nseg; ++r) {
@@ -637,7 +641,7 @@ int launch_attn_16(int dtype, const float* part, int ks, size_t part_stride, siz
     for (int r = 0; r < nseg; ++r) {
       const AttnSeg& g = segs[r];
       if (tiles_of(g.B) != cls) continue;
-      t.s[n++] = SegDev{g.row0, g.B, g.kc, g.vc, g.dP, g.mask};
+      t.s[n++] = SegDev{g.row0, g.B, g.P_max, g.kc, g.vc, g.dP, g.mask};
       keys_max = g.P_max + g.B > keys_max ? g.P_max + g.B : keys_max;
       b_max = g.B > b_max ? g.B : b_max;
     }

@@ -40,7 +40,7 @@ __global__ __launch_bounds__(64) void k_attn_f32(const float* __restrict__ q, in
                                                  const float* __restrict__ vc, int head_dim, int cap,
                                                  const int32_t* __restrict__ dP, int B,
                                                  const uint64_t* __restrict__ mask, float* __restrict__ o, int ldo,
-                                                 int lds_keys) {
+                                                 int lds_keys, int32_t* __restrict__ flags) {
   extern __shared__ float sm[];
   float* sq = sm;             // [head_dim]
   float* sc = sm + head_dim;  // [lds_keys]
@@ -48,8 +48,12 @@ __global__ __launch_bounds__(64) void k_attn_f32(const float* __restrict__ q, in
   const int W = (B + 63) >> 6;
   const int P = *dP;
   int nk = P + B;
-  if (nk > lds_keys) nk = lds_keys;  // launch sized from the host's upper bound of P
+  // the launch is sized from the host's upper bound of P: a longer cache is flagged
+  // (GOOSE_FLAG_CAPACITY) and the keys beyond the bound are dropped so that nothing is indexed outside LDS
+  if ((P < 0 || nk > lds_keys || nk > cap) && i == 0 && h == 0 && lane == 0) atomicOr(flags, GOOSE_FLAG_CAPACITY);
+  if (nk > lds_keys) nk = lds_keys;
   if (nk > cap) nk = cap;
+  if (nk < 0) nk = 0;
   for (int c = lane; c < head_dim; c += 64) sq[c] = q[(size_t)i * ldq + h * head_dim + c];
   __syncthreads();
   const float scale = 1.0f / sqrtf((float)head_dim);
@@ -101,11 +105,12 @@ int launch_gemm_f32(const float* A, int lda, const float* W, int N, int K, int M
 }
 
 int launch_attn_f32(const float* q, int ldq, const float* kc, const float* vc, int n_heads, int head_dim, int cap,
-                    const int32_t* dP, int B, const uint64_t* mask, float* o, int ldo, int P_max, hipStream_t st) {
+                    const int32_t* dP, int B, const uint64_t* mask, float* o, int ldo, int P_max, int32_t* flags,
+                    hipStream_t st) {
   const int lds_keys = P_max + B;
   const size_t smem = (size_t)(head_dim + lds_keys) * sizeof(float);
   if (smem > 64 * 1024) return GOOSE_ERR_CAPACITY;  // the fp32 path keeps all scores of a row in LDS
   hipLaunchKernelGGL(k_attn_f32, dim3(B, n_heads), dim3(64), smem, st, q, ldq, kc, vc, head_dim, cap, dP, B, mask, o,
-                     ldo, lds_keys);
+                     ldo, lds_keys, flags);
   return goose_launch_status();
 }

@@ -320,7 +320,7 @@ int goose_build_mask(goose_ctx* c, const int32_t* d_parent, int B, int P, const 
   const int32_t* dP;
   rc = resolve_P(c, P, d_P, st, &dP);
   if (rc) return rc;
-  return launch_build_mask(d_parent, B, dP, d_mask, d_depth, d_pos, c->flags, st);
+  return launch_build_mask(d_parent, B, dP, d_mask, d_depth, d_pos, c->flags, c->cap, d_P ? c->cap - B : P, st);
 }
 
 int goose_embed(goose_ctx* c, const void* d_embed, const int32_t* d_tokens, int B, float* d_x, void* stream) {
@@ -369,7 +369,7 @@ static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, v
       rc = launch_attn_16(d.dtype, c->part, ks, pstride, c->part_ld, c->rope_cs, d.n_heads, c->n_kv, d.head_dim, c->cap, segs,
                             nseg, splits_env, c->max_splits, ng_env, d.qk_norm ? w + c->pl.gq : nullptr,
                             d.qk_norm ? w + c->pl.gk : nullptr, d.rms_eps, c->att_o, c->att_ml, c->Bpad, c->o, c->Kq,
-                            st); }
+                            c->flags, st); }
     if (rc) return rc;
     const GemmCfg co = gemm_cfg(c, "GOOSE_CFG_O", Nh, c->Kq);
     ks = co.ks;
@@ -404,10 +404,10 @@ static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, v
   rc = launch_gemm_f32(xn, c->Kh, (const float*)(w + c->pl.wqkv), 3 * Hq, H, B, c->part, c->part_ld, st);
   if (rc) return rc;
   rc = launch_rope_kv(d.dtype, c->part, 1, pstride, c->part_ld, B, d.n_heads, d.head_dim, d_pos, c->inv_freq, dP,
-                      c->cap, c->q, c->Kq, d_kcache, d_vcache, st);
+                      c->cap, c->q, c->Kq, d_kcache, d_vcache, c->flags, st);
   if (rc) return rc;
   rc = launch_attn_f32((const float*)c->q, c->Kq, (const float*)d_kcache, (const float*)d_vcache, d.n_heads,
-                       d.head_dim, c->cap, dP, B, d_mask, (float*)c->o, c->Kq, P, st);
+                       d.head_dim, c->cap, dP, B, d_mask, (float*)c->o, c->Kq, P, c->flags, st);
   if (rc) return rc;
   rc = launch_gemm_f32((const float*)c->o, c->Kq, (const float*)(w + c->pl.wo), H, Hq, B, c->part, c->part_ld, st);
   if (rc) return rc;
@@ -533,7 +533,7 @@ int goose_compact_kv(goose_ctx* c, void* d_kcache_all, void* d_vcache_all, int P
   if (rc) return rc;
   const goose_model_desc& d = c->d;
   return launch_compact((int)elem_size(d.dtype), d_kcache_all, d_vcache_all, d.n_layers, c->n_kv, c->cap,
-                        d.head_dim, dP, d_path, d_accept_len, d_new_P_or_null, st);
+                        d.head_dim, dP, d_path, d_accept_len, d_new_P_or_null, c->flags, st);
 }
 
 int goose_verify_step(goose_ctx* c, const goose_model_ptrs* m, const goose_step_io* io, int B, int P_max,
@@ -547,7 +547,7 @@ int goose_verify_step(goose_ctx* c, const goose_model_ptrs* m, const goose_step_
     return GOOSE_ERR_ARG;
   hipStream_t st = as_stream(stream);
   const goose_model_desc& d = c->d;
-  rc = launch_build_mask(io->d_parent, B, io->d_P, c->s_mask, c->s_depth, c->s_pos, c->flags, st);
+  rc = launch_build_mask(io->d_parent, B, io->d_P, c->s_mask, c->s_depth, c->s_pos, c->flags, c->cap, P_max, st);
   if (rc) return rc;
   rc = launch_embed(d.dtype, m->d_embed, io->d_tokens, B, d.hidden, d.vocab, c->s_x, st);
   if (rc) return rc;
@@ -581,7 +581,7 @@ int goose_verify_step(goose_ctx* c, const goose_model_ptrs* m, const goose_step_
                      io->d_bonus, io->d_next_root_or_null, st);
   if (rc) return rc;
   return launch_compact((int)elem_size(d.dtype), m->d_kcache_all, m->d_vcache_all, d.n_layers, c->n_kv, c->cap,
-                        d.head_dim, io->d_P, io->d_path, io->d_accept_len, io->d_P, st);
+                        d.head_dim, io->d_P, io->d_path, io->d_accept_len, io->d_P, c->flags, st);
 }
 
 int goose_verify_step_batched(goose_ctx* c, const goose_model_ptrs* m, const goose_request* reqs, int n_req,
@@ -612,12 +612,12 @@ int goose_verify_step_batched(goose_ctx* c, const goose_model_ptrs* m, const goo
   int b_max = 0;
   for (int r = 0; r < n_req; ++r) {
     const goose_request& q = reqs[r];
-    br[r] = BatchReq{q.d_tokens, q.d_parent, q.d_is_spine, q.B, segs[r].row0, q.d_kcache_all, q.d_vcache_all, q.d_P,
+    br[r] = BatchReq{q.d_tokens, q.d_parent, q.d_is_spine, q.B, segs[r].row0, q.P_max, q.d_kcache_all, q.d_vcache_all, q.d_P,
                      q.d_accept_len, q.d_path, q.d_bonus, q.d_next_root_or_null};
     b_max = q.B > b_max ? q.B : b_max;
   }
   int rc = launch_batch_begin(d.dtype, br, n_req, b_max, m->d_embed, d.hidden, d.vocab, c->s_mask, c->s_depth, c->s_pos,
-                              c->s_x, c->flags, st);
+                              c->s_x, c->flags, c->cap, st);
   if (rc) return rc;
   // rows between requests keep stale (finite) values: they ride through the projections unused
   rc = launch_rope_table(c->s_pos, c->inv_freq, rows, d.head_dim, c->rope_cs, st);
@@ -645,7 +645,7 @@ int goose_verify_step_batched(goose_ctx* c, const goose_model_ptrs* m, const goo
                              q.harvest_k, d.vocab, q.d_succ_ids_or_null, q.d_succ_scores_or_null, st);
     if (rc) return rc;
   }
-  return launch_batch_end(br, n_req, d_argmax_all, d.n_layers, c->n_kv, c->cap, d.head_dim, st);
+  return launch_batch_end(br, n_req, d_argmax_all, d.n_layers, c->n_kv, c->cap, d.head_dim, c->flags, st);
 }
 
 int goose_device_flags(goose_ctx* c, void* stream, int32_t* h_flags_out) {

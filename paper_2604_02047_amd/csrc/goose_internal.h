@@ -82,8 +82,10 @@ struct goose_ctx {
 
 // ---- small kernels (kernels_small.hip)
 int launch_set_int(int32_t* dst, int v, hipStream_t st);
+// flags: GOOSE_FLAG_BAD_PARENT for a parent array that is no topological tree, GOOSE_FLAG_CAPACITY
+// for a cache length *dP outside [0, P_max] or with *dP + B > cap
 int launch_build_mask(const int32_t* parent, int B, const int32_t* dP, uint64_t* mask, int32_t* depth, int32_t* pos,
-                      int32_t* flags, hipStream_t st);
+                      int32_t* flags, int cap, int P_max, hipStream_t st);
 int launch_embed(int dtype, const void* E, const int32_t* tokens, int B, int H, int V, float* x, hipStream_t st);
 // x[m][:] += sum_s part[s][m][:H] (S may be 0); xn[m][:] = T(rmsnorm(x[m]) * g) if xn != NULL
 int launch_resid_norm(int dtype, float* x, int H, const float* part, int S, size_t part_stride, size_t part_ld,
@@ -91,7 +93,7 @@ int launch_resid_norm(int dtype, float* x, int H, const float* part, int S, size
 // qkv = sum_s part[s][m][0:3Hq]; rotary on q,k; q -> qout, k/v -> cache slots P+m
 int launch_rope_kv(int dtype, const float* part, int S, size_t part_stride, size_t part_ld, int B, int n_heads,
                    int head_dim, const int32_t* pos, const double* inv_freq, const int32_t* dP, int cap, void* qout,
-                   int ldq, void* kcache, void* vcache, hipStream_t st);
+                   int ldq, void* kcache, void* vcache, int32_t* flags, hipStream_t st);
 int launch_swiglu_f32(const float* gu, size_t ld, int F, float* h, int ldh, int B, hipStream_t st);
 int launch_argmax(const float* logits, size_t ld, int V, int B, int32_t* argmax, float* margin, hipStream_t st);
 int launch_accept(const int32_t* parent, const int32_t* tokens, const uint8_t* is_spine, const int32_t* argmax, int B,
@@ -102,6 +104,7 @@ struct BatchReq {
   const int32_t* parent;
   const uint8_t* is_spine;  // or null
   int32_t B, row0;          // its rows [row0, row0 + B) of the stacked buffers
+  int32_t P_max;            // host upper bound of *dP the launches are sized for
   void* kall;               // its caches, all layers
   void* vall;
   int32_t* dP;              // cache length, in/out
@@ -112,19 +115,21 @@ struct BatchReq {
 };
 // mask/depth/positions and embedding rows of all requests (2 launches); E: embedding table.
 int launch_batch_begin(int dtype, const BatchReq* reqs, int n, int max_B, const void* E, int H, int V,
-                       uint64_t* mask, int32_t* depth, int32_t* pos, float* x, int32_t* flags, hipStream_t st);
+                       uint64_t* mask, int32_t* depth, int32_t* pos, float* x, int32_t* flags, int cap, hipStream_t st);
 // walk, compaction and new cache length of all requests (3 launches)
 int launch_batch_end(const BatchReq* reqs, int n, const int32_t* argmax_all, int n_layers, int n_kv_heads, int cap,
-                     int head_dim, hipStream_t st);
+                     int head_dim, int32_t* flags, hipStream_t st);
 int launch_compact(int elem_bytes, void* kall, void* vall, int n_layers, int n_heads, int cap, int head_dim,
-                   const int32_t* dP, const int32_t* path, const int32_t* accept_len, int32_t* new_P, hipStream_t st);
+                   const int32_t* dP, const int32_t* path, const int32_t* accept_len, int32_t* new_P, int32_t* flags,
+                   hipStream_t st);
 
 // ---- fp32 path (f32_path.hip)
 // out[m][n] = sum_k A[m][k] * W[n][k]
 int launch_gemm_f32(const float* A, int lda, const float* W, int N, int K, int M, float* out, size_t ldo,
                     hipStream_t st);
 int launch_attn_f32(const float* q, int ldq, const float* kc, const float* vc, int n_heads, int head_dim, int cap,
-                    const int32_t* dP, int B, const uint64_t* mask, float* o, int ldo, int P_max, hipStream_t st);
+                    const int32_t* dP, int B, const uint64_t* mask, float* o, int ldo, int P_max, int32_t* flags,
+                    hipStream_t st);
 
 // ---- the MFMA path: 16-bit storage, dtype = GOOSE_DTYPE_BF16 or GOOSE_DTYPE_F16
 // (gemm_bf16.hip, gemm_rows_bf16.hip, attn_bf16.hip: the files are named for the first type built)
@@ -171,5 +176,5 @@ enum { ATTN_MAX_SEGS = 16 };
 int launch_attn_16(int dtype, const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs,
                    int n_heads, int n_kv_heads, int head_dim, int cap, const AttnSeg* segs, int nseg, int splits_or_0,
                    int max_splits, int key_groups, const void* gq, const void* gk, float eps, float* att_o,
-                   float* att_ml, int Bpad, void* o, int ldo, hipStream_t st);
+                   float* att_ml, int Bpad, void* o, int ldo, int32_t* flags, hipStream_t st);
 int pick_attn_splits(int n_heads, int keys_max, int max_splits);

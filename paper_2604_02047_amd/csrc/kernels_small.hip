@@ -22,10 +22,17 @@ __global__ void k_set_int(int32_t* dst, int v) {
 
 // Ancestor-or-self bit rows, depth and position of every node (Sec. 4, tree attention mask).
 // One thread per node climbs its own root path; parent[v] < v makes every climb finite.
+// A cache length outside what the launch was sized for (P > P_max) or that leaves no room for the
+// tree (P + B > cap) raises GOOSE_FLAG_CAPACITY: the later kernels then clamp their indices and the
+// step's results are meaningless.
 __device__ inline void build_mask_body(const int32_t* __restrict__ parent, int B, const int32_t* __restrict__ dP,
                                        uint64_t* __restrict__ mask, int32_t* __restrict__ depth,
-                                       int32_t* __restrict__ pos, int32_t* __restrict__ flags) {
+                                       int32_t* __restrict__ pos, int32_t* __restrict__ flags, int cap, int P_max) {
   const int i = threadIdx.x;
+  if (i == 0) {
+    const int P = *dP;
+    if (P < 0 || P > P_max || P + B > cap) atomicOr(flags, GOOSE_FLAG_CAPACITY);
+  }
   if (i >= B) return;
   const int W = (B + 63) >> 6;
   uint64_t w0 = 0, w1 = 0;
@@ -44,14 +51,14 @@ __device__ inline void build_mask_body(const int32_t* __restrict__ parent, int B
   if (W > 1) mask[(size_t)i * W + 1] = w1;
   depth[i] = dep;
   pos[i] = *dP + dep;
-  if (bad) atomicOr(flags, 1);
+  if (bad) atomicOr(flags, GOOSE_FLAG_BAD_PARENT);
 }
 
 __global__ __launch_bounds__(128) void k_build_mask(const int32_t* __restrict__ parent, int B,
                                                     const int32_t* __restrict__ dP, uint64_t* __restrict__ mask,
                                                     int32_t* __restrict__ depth, int32_t* __restrict__ pos,
-                                                    int32_t* __restrict__ flags) {
-  build_mask_body(parent, B, dP, mask, depth, pos, flags);
+                                                    int32_t* __restrict__ flags, int cap, int P_max) {
+  build_mask_body(parent, B, dP, mask, depth, pos, flags, cap, P_max);
 }
 
 // The per-request steps of a batch as single launches: block index = request, taken from a table
@@ -60,9 +67,9 @@ struct ReqTable { BatchReq r[GOOSE_MAX_REQUESTS]; };
 
 __global__ __launch_bounds__(128) void k_build_mask_batch(const ReqTable t, uint64_t* __restrict__ mask,
                                                           int32_t* __restrict__ depth, int32_t* __restrict__ pos,
-                                                          int32_t* __restrict__ flags) {
+                                                          int32_t* __restrict__ flags, int cap) {
   const BatchReq& q = t.r[blockIdx.x];
-  build_mask_body(q.parent, q.B, q.dP, mask + (size_t)q.row0 * 2, depth + q.row0, pos + q.row0, flags);
+  build_mask_body(q.parent, q.B, q.dP, mask + (size_t)q.row0 * 2, depth + q.row0, pos + q.row0, flags, cap, q.P_max);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -166,12 +173,15 @@ template <typename T>
 __global__ void k_rope_kv(const float* __restrict__ part, int S, size_t part_stride, size_t part_ld, int n_heads,
                           int head_dim, const int32_t* __restrict__ pos, const double* __restrict__ inv_freq,
                           const int32_t* __restrict__ dP, int cap, T* __restrict__ qout, int ldq,
-                          T* __restrict__ kcache, T* __restrict__ vtcache) {
+                          T* __restrict__ kcache, T* __restrict__ vtcache, int32_t* __restrict__ flags) {
   const int m = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
   const int half = head_dim >> 1;
   const int Hq = n_heads * head_dim;
   const int slot = *dP + m;
-  if (slot >= cap) return;
+  if (slot < 0 || slot >= cap) {  // no room for this node: say so instead of writing outside the cache
+    if (j == 0 && h == 0) atomicOr(flags, GOOSE_FLAG_CAPACITY);
+    return;
+  }
   float v6[6] = {0, 0, 0, 0, 0, 0};
   for (int s = 0; s < S; ++s) {
     const float* r = part + s * part_stride + (size_t)m * part_ld + h * head_dim + j;
@@ -583,17 +593,20 @@ __global__ void k_compact_vt(T* __restrict__ vall, int cap, int head_dim, const 
   }
 }
 
-__global__ void k_new_P(const int32_t* dP, const int32_t* accept_len, int32_t* new_P) {
+__global__ void k_new_P(const int32_t* dP, const int32_t* accept_len, int32_t* new_P, int cap, int32_t* flags) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     const int p = *dP, l = *accept_len;
+    if (p < 0 || l < 0 || p + l + 1 > cap) atomicOr(flags, GOOSE_FLAG_CAPACITY);
     *new_P = p + l + 1;
   }
 }
 
-__global__ void k_new_P_batch(const ReqTable t) {  // in place: after the compaction has read the old lengths
+__global__ void k_new_P_batch(const ReqTable t, int cap, int32_t* flags) {  // in place: after the compaction has read the old lengths
   if (threadIdx.x == 0) {
     const BatchReq& q = t.r[blockIdx.x];
-    *q.dP = *q.dP + *q.accept_len + 1;
+    const int p = *q.dP, l = *q.accept_len;
+    if (p < 0 || l < 0 || p + l + 1 > cap) atomicOr(flags, GOOSE_FLAG_CAPACITY);
+    *q.dP = p + l + 1;
   }
 }
 
@@ -606,8 +619,8 @@ int launch_set_int(int32_t* dst, int v, hipStream_t st) {
 }
 
 int launch_build_mask(const int32_t* parent, int B, const int32_t* dP, uint64_t* mask, int32_t* depth, int32_t* pos,
-                      int32_t* flags, hipStream_t st) {
-  hipLaunchKernelGGL(k_build_mask, dim3(1), dim3(128), 0, st, parent, B, dP, mask, depth, pos, flags);
+                      int32_t* flags, int cap, int P_max, hipStream_t st) {
+  hipLaunchKernelGGL(k_build_mask, dim3(1), dim3(128), 0, st, parent, B, dP, mask, depth, pos, flags, cap, P_max);
   return goose_launch_status();
 }
 
@@ -652,14 +665,14 @@ int launch_resid_norm(int dtype, float* x, int H, const float* part, int S, size
 
 int launch_rope_kv(int dtype, const float* part, int S, size_t part_stride, size_t part_ld, int B, int n_heads,
                    int head_dim, const int32_t* pos, const double* inv_freq, const int32_t* dP, int cap, void* qout,
-                   int ldq, void* kcache, void* vcache, hipStream_t st) {
+                   int ldq, void* kcache, void* vcache, int32_t* flags, hipStream_t st) {
   dim3 grid(B, n_heads), block(head_dim / 2);
   if (dtype == GOOSE_DTYPE_BF16)
     hipLaunchKernelGGL(k_rope_kv<bf16_t>, grid, block, 0, st, part, S, part_stride, part_ld, n_heads, head_dim, pos,
-                       inv_freq, dP, cap, (bf16_t*)qout, ldq, (bf16_t*)kcache, (bf16_t*)vcache);
+                       inv_freq, dP, cap, (bf16_t*)qout, ldq, (bf16_t*)kcache, (bf16_t*)vcache, flags);
   else
     hipLaunchKernelGGL(k_rope_kv<float>, grid, block, 0, st, part, S, part_stride, part_ld, n_heads, head_dim, pos,
-                       inv_freq, dP, cap, (float*)qout, ldq, (float*)kcache, (float*)vcache);
+                       inv_freq, dP, cap, (float*)qout, ldq, (float*)kcache, (float*)vcache, flags);
   return goose_launch_status();
 }
 
@@ -703,10 +716,10 @@ static ReqTable req_table(const BatchReq* reqs, int n) {
 }
 
 int launch_batch_begin(int dtype, const BatchReq* reqs, int n, int max_B, const void* E, int H, int V,
-                       uint64_t* mask, int32_t* depth, int32_t* pos, float* x, int32_t* flags, hipStream_t st) {
+                       uint64_t* mask, int32_t* depth, int32_t* pos, float* x, int32_t* flags, int cap, hipStream_t st) {
   if (n < 1 || n > GOOSE_MAX_REQUESTS) return GOOSE_ERR_ARG;
   const ReqTable t = req_table(reqs, n);
-  hipLaunchKernelGGL(k_build_mask_batch, dim3(n), dim3(128), 0, st, t, mask, depth, pos, flags);
+  hipLaunchKernelGGL(k_build_mask_batch, dim3(n), dim3(128), 0, st, t, mask, depth, pos, flags, cap);
   int rc = goose_launch_status();
   if (rc != GOOSE_OK) return rc;
   if (dtype == GOOSE_DTYPE_BF16)
@@ -719,7 +732,7 @@ int launch_batch_begin(int dtype, const BatchReq* reqs, int n, int max_B, const 
 }
 
 int launch_batch_end(const BatchReq* reqs, int n, const int32_t* argmax_all, int n_layers, int n_kv_heads, int cap,
-                     int head_dim, hipStream_t st) {
+                     int head_dim, int32_t* flags, hipStream_t st) {
   if (n < 1 || n > GOOSE_MAX_REQUESTS) return GOOSE_ERR_ARG;
   const ReqTable t = req_table(reqs, n);
   hipLaunchKernelGGL(k_accept_batch, dim3(n), dim3(128), 0, st, t, argmax_all);
@@ -733,7 +746,7 @@ int launch_batch_end(const BatchReq* reqs, int n, const int32_t* argmax_all, int
     return GOOSE_ERR_SHAPE;
   rc = goose_launch_status();
   if (rc != GOOSE_OK) return rc;
-  hipLaunchKernelGGL(k_new_P_batch, dim3(n), dim3(64), 0, st, t);
+  hipLaunchKernelGGL(k_new_P_batch, dim3(n), dim3(64), 0, st, t, cap, flags);
   return goose_launch_status();
 }
 
@@ -746,7 +759,7 @@ int launch_accept(const int32_t* parent, const int32_t* tokens, const uint8_t* i
 
 int launch_compact(int elem_bytes, void* kall, void* vall, int n_layers, int n_heads, int cap, int head_dim,
                    const int32_t* dP, const int32_t* path, const int32_t* accept_len, int32_t* new_P,
-                   hipStream_t st) {
+                   int32_t* flags, hipStream_t st) {
   int rc;
   if (elem_bytes == 2) {  // bf16 / fp16 (moved as bit patterns): operand-ordered blocks
     if (head_dim == 128)
@@ -770,7 +783,7 @@ int launch_compact(int elem_bytes, void* kall, void* vall, int n_layers, int n_h
   }
   if (rc != GOOSE_OK) return rc;
   if (new_P) {
-    hipLaunchKernelGGL(k_new_P, dim3(1), dim3(1), 0, st, dP, accept_len, new_P);
+    hipLaunchKernelGGL(k_new_P, dim3(1), dim3(1), 0, st, dP, accept_len, new_P, cap, flags);
     rc = goose_launch_status();
   }
   return rc;

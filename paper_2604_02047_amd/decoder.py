@@ -104,6 +104,19 @@ class _Request:
         return emitted
 
 
+def _require_room(P, n, cap):
+    """A cycle writes cache slots [P, P + n): refuse it before anything is overwritten."""
+    if P + n > cap:
+        raise gb.GooseError(gb.GOOSE_ERR_CAPACITY, f"cycle of {n} nodes on {P} committed slots, capacity {cap}")
+
+
+def _require_clean(flags):
+    """The device-side checks of the cycle just run (bad parent array, cache length out of range)."""
+    if flags:
+        raise gb.GooseError(gb.GOOSE_ERR_CAPACITY if flags & gb.GOOSE_FLAG_CAPACITY else gb.GOOSE_ERR_NOT_TOPOLOGICAL,
+                            f"the verification kernels flagged the cycle (goose_device_flags = {flags})")
+
+
 class _Options:
     def __init__(self, gm, B, K, rho, D, min_score, bypass_len, lens, max_spine, alpha):
         assert B <= gm.max_B and 1 + max_spine <= gm.max_B
@@ -140,9 +153,10 @@ class GooseDecoder:
         gm, q = self.gm, self.req
         tokens, parent, is_spine, mode = q.plan(self.o)
         n = len(tokens)
+        _require_room(gm.P, n, gm.cap)
         t, p, s = gm.stage_tree(tokens, parent, is_spine)
         gm.verify_step_fused(t, p, s, n, gm.cap - n, succ_ids=q.d_ids, succ_scores=q.d_scores)
-        torch.cuda.synchronize()
+        _require_clean(gm.ctx.goose_device_flags())   # (synchronises the stream)
         L = int(gm.accept_len.item())
         gm.P = int(gm.d_P.item())
         return q.absorb(self.o, tokens, is_spine, mode, L, gm.path[:L + 1].cpu().numpy(), int(gm.bonus.item()), gm.P)
@@ -175,13 +189,14 @@ class BatchedGooseDecoder:
         for i in active:
             q = self.reqs[i]
             tokens, parent, is_spine, mode = q.plan(self.o)
+            _require_room(q.P, len(tokens), gm.cap)
             t, p, s = gm.stage_tree(tokens, parent, is_spine)
             plans.append((tokens, is_spine, mode))
             table.append({"tokens": t, "parent": p, "is_spine": s, "B": len(tokens), "P_max": gm.cap - len(tokens),
                           "kcache": q.kcache, "vcache": q.vcache, "P": q.d_P, "accept_len": q.accept_len,
                           "path": q.path, "bonus": q.bonus, "succ_ids": q.d_ids, "succ_scores": q.d_scores})
         gm.ctx.goose_verify_step_batched(gm.model_ptrs(), table, self.argmax_all)
-        torch.cuda.synchronize()
+        _require_clean(gm.ctx.goose_device_flags())   # (synchronises the stream)
         self.passes += 1
         out = {}
         for i, (tokens, is_spine, mode) in zip(active, plans):

@@ -90,3 +90,27 @@ def test_batched_decoding_is_batch_lossless():
         n = min(len(y), len(outs[r]))
         same = next((i for i in range(n) if y[i] != outs[r][i]), n)
         assert same >= 40, (r, same, y[:same + 2], outs[r][:same + 2])
+
+
+def test_decoding_stops_with_an_error_when_the_cache_is_full():
+    """A cycle that would write past the cache is refused on the host before anything is overwritten;
+    a step whose device-resident cache length does not fit is flagged by the kernels."""
+    from paper_2604_02047_amd.binding import GooseError, GOOSE_ERR_CAPACITY, GOOSE_FLAG_CAPACITY
+    from paper_2604_02047_amd.decoder import GooseDecoder
+    shape = gi.SHAPES["tiny_bf16"]
+    tm = torch_model(shape, seed=4, gain_jitter=0.1)
+    gm = gpu_model(shape, tm, max_B=64, cap=128)
+    prompt = _prompt(shape.vocab, 3)                      # 41 tokens
+    dec = GooseDecoder(gm, B=24, min_score=0.0)
+    with pytest.raises(GooseError) as e:
+        dec.generate(prompt, 400)
+    assert e.value.status == GOOSE_ERR_CAPACITY
+    assert gm.P <= 128 and len(dec.seq) > len(prompt)     # it decoded until the cache was full, not beyond
+    assert gm.ctx.goose_device_flags() == 0               # the host check came first: no kernel saw a bad length
+    # the device-resident length one slot too far, through the whole-step entry point
+    tree = gi.tree_chain(8)
+    t, p, s = gm.stage_tree(np.arange(8), tree.parent, tree.is_spine)
+    gm.set_P(128 - 7)
+    gm.verify_step_fused(t, p, s, 8, 128 - 8)
+    assert gm.ctx.goose_device_flags() & GOOSE_FLAG_CAPACITY
+    gm.ctx.close()

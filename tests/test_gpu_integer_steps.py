@@ -146,3 +146,34 @@ def test_compact_kv_bit_exact(dtype):
             assert np.array_equal(k[l, :, :P + L + 1].double().cpu().numpy(), ref[l][0])
             assert np.array_equal(v[l, :, :P + L + 1].double().cpu().numpy(), ref[l][1])
     c.close()
+
+
+def test_cache_length_from_device_memory_out_of_range_sets_the_capacity_flag(ctx):
+    """A device-resident cache length cannot be refused by the host: one slot past what fits (P + B > cap),
+    past the bound the launch was sized for, or negative, the kernels must say so."""
+    from paper_2604_02047_amd.binding import GOOSE_FLAG_CAPACITY
+    dev = "cuda:0"
+    tree = gi.tree_chain(16)
+    parent = torch.as_tensor(tree.parent, device=dev)
+    mask = torch.zeros(16, dtype=torch.int64, device=dev)
+    depth = torch.zeros(16, dtype=torch.int32, device=dev)
+    pos = torch.zeros(16, dtype=torch.int32, device=dev)
+    cap = 4096
+    assert ctx.goose_device_flags() == 0
+    for P, bad in ((cap - 16, False), (cap - 15, True), (-1, True), (0, False)):
+        dP = torch.tensor([P], dtype=torch.int32, device=dev)
+        ctx.goose_build_mask(parent, 16, 0, mask, depth, pos, d_P=dP)
+        assert bool(ctx.goose_device_flags() & GOOSE_FLAG_CAPACITY) == bad, P
+    # a commit that would run past the cache
+    from paper_2604_02047_amd import GooseContext, ModelDesc
+    shape = gi.SHAPES["tiny_bf16"]
+    c = GooseContext(ModelDesc.from_shape(shape), 64, 128)
+    k = torch.zeros((shape.n_layers, shape.n_heads, 128 * shape.head_dim), dtype=torch.bfloat16, device=dev)
+    v = torch.zeros_like(k)
+    path = torch.tensor([0, 1, 2] + [-1] * 61, dtype=torch.int32, device=dev)
+    L = torch.tensor([2], dtype=torch.int32, device=dev)
+    for P, bad in ((125, False), (126, True)):
+        dP = torch.tensor([P], dtype=torch.int32, device=dev)
+        c.goose_compact_kv(k, v, 0, path, L, dP, d_P=dP)
+        assert bool(c.goose_device_flags() & GOOSE_FLAG_CAPACITY) == bad, P
+    c.close()
