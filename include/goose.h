@@ -83,7 +83,23 @@ typedef struct {
                          h / (n_heads / n_kv_heads) (grouped-query attention; 16-bit models only) */
   int32_t qk_norm;    /* != 0: RMSNorm over head_dim (gains gq, gk, eps = rms_eps) on every head of q and k
                          before the rotary embedding (16-bit models only) */
+  int32_t act_mode;   /* GOOSE_ACT_* below: how the projections carry their activation operands (16-bit models) */
 } goose_model_desc;
+
+/* Activation operands of the projections (the normalised rows, the attention output, the SwiGLU output).
+ * Rounding them to bf16 (8 significant bits) is what dominates the logit error of a deep bf16 model; the
+ * cached K/V rows, which the storage type does force to 16 bits, contribute ten times less.  Two remedies:
+ *   GOOSE_ACT_F16       the operands are fp16 (11 significant bits; the precision the paper runs in, App. C).
+ *                       Under bf16 storage the packed copy of every weight matrix then holds each weight w as
+ *                       the fp16 value 256 w -- the same number for 2^-32 <= |w| < 256, anything else raises
+ *                       GOOSE_FLAG_WEIGHT_RANGE -- the projections run the fp16 matrix instruction and scale
+ *                       their fp32 sums by 1/256; KV cache, gains and embedding stay bf16.  An operand beyond
+ *                       the fp16 range (65504) is clamped and raises GOOSE_FLAG_RANGE.  Costs nothing.
+ *   GOOSE_ACT_TWO_TERM  the operands keep the storage type and carry every value as hi + lo (two 16-bit
+ *                       values, 2^-17 relative): bf16's range is kept, each weight piece meets two matrix
+ *                       instructions and the small operand doubles in size (about 15 % per step at 64 rows).
+ * In both modes the rotated query of the attention keeps two terms as well. */
+enum { GOOSE_ACT_F16 = 0, GOOSE_ACT_TWO_TERM = 1 };
 
 /* Raw weights of one decoder layer as a checkpoint stores them: device pointers,
  * row-major [out][in] of the model's storage type. */
@@ -107,7 +123,10 @@ const char* goose_last_hip_error(void);
  * slots per head (a multiple of 64).  Allocates device memory on the current device. */
 int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** out);
 /* The same, with workspace for passes of up to max_rows stacked rows (goose_verify_step_batched):
- * max_B <= max_rows <= GOOSE_MAX_ROWS, a multiple of 32.  goose_create is max_rows = round_up(max_B, 32). */
+ * max_B <= max_rows <= GOOSE_MAX_ROWS, a multiple of 32.  A context made here gives a request the same
+ * bits alone and inside any batch (equal attention split counts assumed); one made by goose_create
+ * (max_rows = round_up(max_B, 32)) may run its projections on trees of up to 64 nodes with two
+ * wavefronts per column tile, which orders their sums differently from the wider kernels. */
 int goose_create_batched(const goose_model_desc* desc, int max_B, int max_rows, int cap, goose_ctx** out);
 void goose_destroy(goose_ctx* ctx);
 
@@ -301,7 +320,9 @@ double goose_ema_update(double p_hat, int accepted_spine, int offered_spine, dou
  * With either bit set the results of that step are meaningless (indices were clamped to stay inside
  * the buffers) and the caches of the offending request must be treated as corrupt.
  * This is the one call that synchronises `stream`. */
-enum { GOOSE_FLAG_BAD_PARENT = 1, GOOSE_FLAG_CAPACITY = 2 };
+/*   GOOSE_FLAG_RANGE        an fp16 activation operand overflowed and was clamped (GOOSE_ACT_F16);
+ *   GOOSE_FLAG_WEIGHT_RANGE a weight could not be re-encoded exactly while packing (GOOSE_ACT_F16, bf16 storage). */
+enum { GOOSE_FLAG_BAD_PARENT = 1, GOOSE_FLAG_CAPACITY = 2, GOOSE_FLAG_RANGE = 4, GOOSE_FLAG_WEIGHT_RANGE = 8 };
 int goose_device_flags(goose_ctx* ctx, void* stream, int32_t* h_flags_out);
 
 /* ---- the projection kernel on its own (unit tests and tuning; dtype = GOOSE_DTYPE_BF16 or _F16) ---
@@ -322,6 +343,20 @@ int goose_gemm_packed(int dtype, const void* d_a, int lda, const void* d_packed,
  * of 32 between gate rows and up rows; d_h 16-bit [B][ldh] receives silu(gate) * up, N/2 columns. */
 int goose_gemm_swiglu_packed(int dtype, const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, void* d_h,
                              int ldh, void* stream);
+/* The same two products as the decoder layers run them.
+ * terms = 2: the activation operand carries every value as the sum of two 16-bit values, hi + lo with
+ * lo = T(a - hi) (rounding 2^-17 instead of 2^-9 relative; the kernel feeds both to the matrix cores),
+ * stored in groups of eight inputs: inputs 8j..8j+7 occupy elements [16j, 16j+8) (hi) and [16j+8, 16j+16)
+ * (lo) of the row; lda >= 2*round_up(K,128).  goose_split_operand writes that layout from fp32 rows
+ * (d_src f32 [rows][ld_src], d_dst T [rows][ld_dst], ld_dst a multiple of 16, >= 2*round_up(cols,8);
+ * padding columns are zeroed).  With terms = 2 the SwiGLU result is written in the same two-term layout
+ * (ldh >= N: two elements per column).  out_scale multiplies every sum before it is used (1 normally). */
+int goose_split_operand(int dtype, const float* d_src, int rows, int cols, int ld_src, void* d_dst, int ld_dst,
+                        void* stream);
+int goose_gemm_packed_ex(int dtype, const void* d_a, int lda, int terms, const void* d_packed, int N, int K, int B,
+                         int nw, int ksplit, float out_scale, float* d_partials, void* stream);
+int goose_gemm_swiglu_packed_ex(int dtype, const void* d_a, int lda, int terms, const void* d_packed, int N, int K,
+                                int B, int nw, float out_scale, void* d_h, int ldh, void* stream);
 
 /* ---- diagnostics: per-kernel timing --------------------------------------------------------
  * While enabled, every kernel launch of verify_layer / lm_head_argmax is bracketed by two

@@ -13,6 +13,9 @@ from .binding import (  # noqa: F401
     goose_pack_matrix,
     goose_gemm_packed,
     goose_gemm_swiglu_packed,
+    goose_gemm_packed_ex,
+    goose_gemm_swiglu_packed_ex,
+    goose_split_operand,
     lib_path,
     load_library,
     EXPORTS,

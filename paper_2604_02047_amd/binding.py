@@ -22,6 +22,7 @@ EXPORTS = [
     "goose_copy_probe", "goose_harvest_topk",
     "goose_context_match", "goose_spine_budget", "goose_build_spine_tree", "goose_spine_ratio_tier", "goose_ema_update",
     "goose_cycle_mode", "goose_verify_step_batched",
+    "goose_split_operand", "goose_gemm_packed_ex", "goose_gemm_swiglu_packed_ex",
 ]
 
 GOOSE_DTYPE_BF16, GOOSE_DTYPE_F32, GOOSE_DTYPE_F16 = 0, 1, 2
@@ -37,7 +38,7 @@ class GooseError(RuntimeError):
 class _Desc(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("ffn", C.c_int32), ("vocab", C.c_int32), ("rope_base", C.c_float), ("rms_eps", C.c_float),
-                ("dtype", C.c_int32), ("n_kv_heads", C.c_int32), ("qk_norm", C.c_int32)]
+                ("dtype", C.c_int32), ("n_kv_heads", C.c_int32), ("qk_norm", C.c_int32), ("act_mode", C.c_int32)]
 
 
 class _LayerWeights(C.Structure):
@@ -77,6 +78,7 @@ class ModelDesc:
     dtype: str = "bf16"
     n_kv_heads: int = 0
     qk_norm: bool = False
+    act_mode: int = 0      # GOOSE_ACT_F16 (0) or GOOSE_ACT_TWO_TERM (1): see goose.h
 
     @property
     def kv_heads(self):
@@ -85,12 +87,12 @@ class ModelDesc:
     @classmethod
     def from_shape(cls, s):
         return cls(s.n_layers, s.hidden, s.n_heads, s.head_dim, s.ffn, s.vocab, s.rope_base, s.rms_eps, s.dtype,
-                   getattr(s, "n_kv_heads", 0), getattr(s, "qk_norm", False))
+                   getattr(s, "n_kv_heads", 0), getattr(s, "qk_norm", False), getattr(s, "act_mode", 0))
 
     def _c(self):
         return _Desc(self.n_layers, self.hidden, self.n_heads, self.head_dim, self.ffn, self.vocab,
                      self.rope_base, self.rms_eps, DTYPE_CODES[self.dtype],
-                     self.n_kv_heads, int(self.qk_norm))
+                     self.n_kv_heads, int(self.qk_norm), int(self.act_mode))
 
 
 _lib = None
@@ -141,6 +143,11 @@ def load_library():
     lib.goose_gemm_packed.argtypes = [C.c_int, C.c_void_p, C.c_int, C.c_void_p] + [C.c_int] * 5 + [C.c_void_p, C.c_void_p]
     lib.goose_gemm_swiglu_packed.argtypes = [C.c_int, C.c_void_p, C.c_int, C.c_void_p] + [C.c_int] * 4 + [C.c_void_p, C.c_int,
                                                                                                 C.c_void_p]
+    lib.goose_split_operand.argtypes = [C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_void_p]
+    lib.goose_gemm_packed_ex.argtypes = ([C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p] + [C.c_int] * 5 +
+                                         [C.c_float, C.c_void_p, C.c_void_p])
+    lib.goose_gemm_swiglu_packed_ex.argtypes = ([C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p] + [C.c_int] * 4 +
+                                                [C.c_float, C.c_void_p, C.c_int, C.c_void_p])
     lib.goose_profile_enable.argtypes = [C.c_void_p, C.c_int]
     lib.goose_profile_kinds.argtypes = []
     lib.goose_profile_kind_name.argtypes = [C.c_int]
@@ -227,7 +234,8 @@ def goose_build_spine_tree(anchor, draft, succ_ids, succ_scores, B, r, rho=0.5, 
 
 
 MODE_AR, MODE_TREE, MODE_BYPASS = 0, 1, 2
-GOOSE_FLAG_BAD_PARENT, GOOSE_FLAG_CAPACITY = 1, 2   # bits of goose_device_flags
+GOOSE_FLAG_BAD_PARENT, GOOSE_FLAG_CAPACITY, GOOSE_FLAG_RANGE, GOOSE_FLAG_WEIGHT_RANGE = 1, 2, 4, 8   # goose_device_flags
+GOOSE_ACT_F16, GOOSE_ACT_TWO_TERM = 0, 1
 GOOSE_ERR_CAPACITY, GOOSE_ERR_NOT_TOPOLOGICAL = -3, -4
 
 
@@ -266,6 +274,22 @@ def goose_gemm_packed(a, lda, packed, N, K, B, nw, ksplit, partials):
 def goose_gemm_swiglu_packed(a, lda, packed, N, K, B, nw, h, ldh):
     _check(load_library().goose_gemm_swiglu_packed(_dtype_code(a), _ptr(a), lda, _ptr(packed), N, K, B, nw, _ptr(h), ldh,
                                                    _stream()), "goose_gemm_swiglu_packed")
+
+
+def goose_split_operand(src, rows, cols, ld_src, dst, ld_dst):
+    """fp32 rows -> the two-term operand layout (dst's dtype selects bf16 or fp16)."""
+    _check(load_library().goose_split_operand(_dtype_code(dst), _ptr(src), rows, cols, ld_src, _ptr(dst), ld_dst,
+                                              _stream()), "goose_split_operand")
+
+
+def goose_gemm_packed_ex(a, lda, terms, packed, N, K, B, nw, ksplit, partials, out_scale=1.0):
+    _check(load_library().goose_gemm_packed_ex(_dtype_code(a), _ptr(a), lda, terms, _ptr(packed), N, K, B, nw, ksplit,
+                                               out_scale, _ptr(partials), _stream()), "goose_gemm_packed_ex")
+
+
+def goose_gemm_swiglu_packed_ex(a, lda, terms, packed, N, K, B, nw, h, ldh, out_scale=1.0):
+    _check(load_library().goose_gemm_swiglu_packed_ex(_dtype_code(a), _ptr(a), lda, terms, _ptr(packed), N, K, B, nw,
+                                                      out_scale, _ptr(h), ldh, _stream()), "goose_gemm_swiglu_packed_ex")
 
 
 def goose_copy_probe(src, dst, nbytes):

@@ -55,6 +55,16 @@ __device__ inline size_t v_elem_off(int g, int c) {
          (kk & 7);
 }
 
+// The attention output feeds the O projection, whose activation type may differ from the caches'
+// (fp16 operands over a bf16 cache): a float as the 16 bits of that type.
+__device__ inline unsigned short out_bits16(float f, bool f16) {
+  return f16 ? __builtin_bit_cast(unsigned short, (_Float16)f) : __builtin_bit_cast(unsigned short, (__bf16)f);
+}
+__device__ inline float out_back16(unsigned short b, bool f16) {
+  return f16 ? (float)__builtin_bit_cast(_Float16, b) : (float)__builtin_bit_cast(__bf16, b);
+}
+typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+
 // what the kernels need of one request (see AttnSeg); the table travels as a kernel argument
 struct SegDev {
   int32_t row0, B, P_max;
@@ -74,7 +84,7 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
     const SegTable<TS> segs, int n_heads, int n_kv_heads, int cap, const float* part, int ks, size_t part_stride,
     size_t part_ld, const float2* cs, const typename Mma16<F16>::T* __restrict__ gq,
     const typename Mma16<F16>::T* __restrict__ gk, float eps, float* __restrict__ att_o, float* __restrict__ att_ml,
-    int Bpad, typename Mma16<F16>::T* o_out, int ldo, int32_t* __restrict__ flags) {
+    int Bpad, unsigned short* o_out, int ldo, int oterms, int o_f16, int32_t* __restrict__ flags) {
   typedef typename Mma16<F16>::T T;
   typedef typename Mma16<F16>::v8 op8;
   typedef typename Mma16<F16>::v4 op4;
@@ -92,14 +102,15 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   constexpr int TROWS = NQH * 32;          // tree rows the LDS buffers hold (>= B for this instantiation)
   constexpr int KROW = D * 2 + 16;         // bytes per K / Q row in LDS (padded)
   constexpr int VROW = TROWS * 2 + 16;     // bytes per V^T row in LDS (padded)
-  constexpr int TAIL_BYTES = 2 * TROWS * KROW + D * VROW;  // tree keys, tree values, rotated queries
+  constexpr int TAIL_BYTES = 3 * TROWS * KROW + D * VROW;  // tree keys, tree values, rotated queries (two terms)
   constexpr int OREGS = (D / 32) * 16;                     // accumulator floats per lane
   constexpr int MERGE_BYTES = (NG / 2) * NQH * (OREGS + 4) * 64 * 4;
   constexpr int LDS_BYTES = TAIL_BYTES > MERGE_BYTES ? TAIL_BYTES : MERGE_BYTES;
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
   unsigned char* Kt = lds;                  // tree keys   [i][c]  (rotated)
   unsigned char* Vt = lds + TROWS * KROW;   // tree values [c][i]  (transposed)
-  unsigned char* Qs = Vt + D * VROW;        // rotated queries [i][c]
+  unsigned char* Qs = Vt + D * VROW;        // rotated queries [i][c]: the 16-bit value ...
+  unsigned char* Ql = Qs + TROWS * KROW;    // ... and the 16-bit remainder of the fp32 query (q = Qs + Ql to 2^-17)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = wave % NG, qh = wave / NG;  // key group, query tile
@@ -275,14 +286,22 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
       const f32x4 c01 = *reinterpret_cast<const f32x4*>(cs + (size_t)i * (D / 2) + j0);      // cos,sin of j0, j0+1
       const f32x4 c23 = *reinterpret_cast<const f32x4*>(cs + (size_t)i * (D / 2) + j0 + 2);  // ... j0+2, j0+3
       const float co[4] = {c01[0], c01[2], c23[0], c23[2]}, si[4] = {c01[1], c01[3], c23[1], c23[3]};
-      op4 rl, rh;
+      // the query keeps two terms (the scores of a row share the query's rounding error, which
+      // therefore does not average out over the keys as the keys' own rounding does)
+      op4 rl, rh, rl2, rh2;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        rl[e] = (T)(acc[u][0][e] * co[e] - acc[u][1][e] * si[e]);
-        rh[e] = (T)(acc[u][1][e] * co[e] + acc[u][0][e] * si[e]);
+        const float ql = acc[u][0][e] * co[e] - acc[u][1][e] * si[e];
+        const float qh = acc[u][1][e] * co[e] + acc[u][0][e] * si[e];
+        rl[e] = (T)ql;
+        rh[e] = (T)qh;
+        rl2[e] = (T)(ql - (float)rl[e]);
+        rh2[e] = (T)(qh - (float)rh[e]);
       }
       *reinterpret_cast<op4*>(Qs + i * KROW + j0 * 2) = rl;
       *reinterpret_cast<op4*>(Qs + i * KROW + (j0 + D / 2) * 2) = rh;
+      *reinterpret_cast<op4*>(Ql + i * KROW + j0 * 2) = rl2;
+      *reinterpret_cast<op4*>(Ql + i * KROW + (j0 + D / 2) * 2) = rh2;
       if (last && i < rows) {  // rows of the tree's blocks beyond B are zero (kv false)
         op4 kl, kh4, vl, vh4;
 #pragma unroll
@@ -379,6 +398,11 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
 #pragma unroll
     for (int s = 0; s < NS; ++s)
       sacc = Mma16<F16>::mfma(__builtin_bit_cast(op8, kreg[s]), qf[s], sacc);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {  // the query's second term, read from LDS as it is used
+      const op8 ql = *reinterpret_cast<const op8*>(Ql + qi * KROW + (16 * s + 8 * hh) * 2);
+      sacc = Mma16<F16>::mfma(__builtin_bit_cast(op8, kreg[s]), ql, sacc);
+    }
     if (idx + 1 < total) fetch_k(idx + 1);
     if (masked) {
 #pragma unroll
@@ -483,14 +507,21 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   if (qi >= B) return;
   if (nsplit == 1) {
     const float inv = 1.0f / l_tot;
-    T* orow = o_out + (size_t)qi * ldo + h * D;
+    unsigned short* orow = o_out + (size_t)qi * ldo;
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
-        op4 v = {(T)(oacc[dt][a * 4] * inv), (T)(oacc[dt][a * 4 + 1] * inv),
-                    (T)(oacc[dt][a * 4 + 2] * inv), (T)(oacc[dt][a * 4 + 3] * inv)};
-        *reinterpret_cast<op4*>(orow + dt * 32 + a * 8 + hh * 4) = v;
+        u16x4 v, v2;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float f = oacc[dt][a * 4 + e] * inv;
+          v[e] = out_bits16(f, o_f16);
+          v2[e] = out_bits16(f - out_back16(v[e], o_f16), o_f16);
+        }
+        unsigned short* dst = orow + term_pos(oterms, h * D + dt * 32 + a * 8 + hh * 4);  // four columns inside one group of eight
+        *reinterpret_cast<u16x4*>(dst) = v;
+        if (oterms == 2) *reinterpret_cast<u16x4*>(dst + 8) = v2;
       }
   } else {
     const size_t base = ((size_t)h * nsplit + split) * Bpad + row0 + qi;
@@ -512,7 +543,8 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
 // o[q][h*D + c] = sum_s 2^(m_s - m) O_s[c] / sum_s 2^(m_s - m) l_s, splits taken in index order.
 template <bool F16, int TS>
 __global__ void k_attn_merge(const float* __restrict__ att_o, const float* __restrict__ att_ml, int nsplit, int Bpad,
-                             int D, typename Mma16<F16>::T* __restrict__ o, int ldo, const SegTable<TS> segs) {
+                             int D, unsigned short* __restrict__ o, int ldo, int oterms, int o_f16,
+                             const SegTable<TS> segs) {
   typedef typename Mma16<F16>::T T;
   const SegDev& sg = segs.s[TS == 1 ? 0 : blockIdx.z];
   if ((int)blockIdx.y >= sg.B) return;
@@ -527,7 +559,11 @@ __global__ void k_attn_merge(const float* __restrict__ att_o, const float* __res
     den += w * att_ml[base * 2 + 1];
     num += w * att_o[base * D + c];
   }
-  o[(size_t)qi * ldo + h * D + c] = (T)(num / den);
+  const float f = num / den;
+  const unsigned short hi = out_bits16(f, o_f16);
+  unsigned short* dst = o + (size_t)qi * ldo + term_pos(oterms, h * D + c);
+  dst[0] = hi;
+  if (oterms == 2) dst[8] = out_bits16(f - out_back16(hi, o_f16), o_f16);
 }
 
 // (cos, sin) of pos[m] * base^(-2j/d) for every node m and pair j: the angle is reduced in double,
@@ -546,7 +582,7 @@ __global__ void k_rope_table(const int32_t* __restrict__ pos, const double* __re
 struct AttnArgs {
   const float* part; int ks; size_t part_stride, part_ld; int n_heads, n_kv;
   const float2* cs; int cap; const void* gq; const void* gk; float eps;
-  float* att_o; float* att_ml; int Bpad; void* o; int ldo; bool f16; int32_t* flags;
+  float* att_o; float* att_ml; int Bpad; void* o; int ldo; int oterms; int o_f16; bool f16; int32_t* flags;
 };
 
 template <int D, int NG, int NQH, bool F16>
@@ -556,11 +592,11 @@ int launch_t(dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable<ATTN_M
     const SegTable<1> t1{{t.s[0]}};
     hipLaunchKernelGGL((k_attn_fused<D, NG, NQH, F16, 1>), grid, dim3(64 * NG * NQH), 0, st, t1, a.n_heads, a.n_kv,
                        a.cap, a.part, a.ks, a.part_stride, a.part_ld, a.cs, (const T*)a.gq, (const T*)a.gk, a.eps,
-                       a.att_o, a.att_ml, a.Bpad, (T*)a.o, a.ldo, a.flags);
+                       a.att_o, a.att_ml, a.Bpad, (unsigned short*)a.o, a.ldo, a.oterms, a.o_f16, a.flags);
   } else {
     hipLaunchKernelGGL((k_attn_fused<D, NG, NQH, F16, ATTN_MAX_SEGS>), grid, dim3(64 * NG * NQH), 0, st, t, a.n_heads,
                        a.n_kv, a.cap, a.part, a.ks, a.part_stride, a.part_ld, a.cs, (const T*)a.gq, (const T*)a.gk,
-                       a.eps, a.att_o, a.att_ml, a.Bpad, (T*)a.o, a.ldo, a.flags);
+                       a.eps, a.att_o, a.att_ml, a.Bpad, (unsigned short*)a.o, a.ldo, a.oterms, a.o_f16, a.flags);
   }
   return goose_launch_status();
 }
@@ -585,10 +621,10 @@ int launch_merge(dim3 grid, int head_dim, hipStream_t st, const AttnArgs& a, int
   if (grid.z == 1) {
     const SegTable<1> t1{{t.s[0]}};
     hipLaunchKernelGGL((k_attn_merge<F16, 1>), grid, dim3(head_dim), 0, st, a.att_o, a.att_ml, splits, a.Bpad, head_dim,
-                       (T*)a.o, a.ldo, t1);
+                       (unsigned short*)a.o, a.ldo, a.oterms, a.o_f16, t1);
   } else {
     hipLaunchKernelGGL((k_attn_merge<F16, ATTN_MAX_SEGS>), grid, dim3(head_dim), 0, st, a.att_o, a.att_ml, splits, a.Bpad,
-                       head_dim, (T*)a.o, a.ldo, t);
+                       head_dim, (unsigned short*)a.o, a.ldo, a.oterms, a.o_f16, t);
   }
   return goose_launch_status();
 }
@@ -618,14 +654,15 @@ int pick_attn_splits(int n_heads, int keys_max, int max_splits) {
 int launch_attn_16(int dtype, const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs,
                    int n_heads, int n_kv_heads, int head_dim, int cap, const AttnSeg* segs, int nseg, int splits_or_0,
                    int max_splits, int key_groups, const void* gq, const void* gk, float eps, float* att_o,
-                   float* att_ml, int Bpad, void* o, int ldo, int32_t* flags, hipStream_t st) {
+                   float* att_ml, int Bpad, void* o, int ldo, int oterms, int o_dtype, int32_t* flags, hipStream_t st) {
   if (dtype != GOOSE_DTYPE_BF16 && dtype != GOOSE_DTYPE_F16) return GOOSE_ERR_ARG;
   if (n_kv_heads < 1 || n_heads % n_kv_heads != 0 || (gq == nullptr) != (gk == nullptr)) return GOOSE_ERR_ARG;
   if (nseg < 1 || nseg > ATTN_MAX_SEGS || max_splits < 1 || (key_groups != 2 && key_groups != 4) || (cap & 31))
     return GOOSE_ERR_ARG;
   if (head_dim != 128 && head_dim != 64) return GOOSE_ERR_SHAPE;
+  if ((oterms != 1 && oterms != 2) || (o_dtype != GOOSE_DTYPE_BF16 && o_dtype != GOOSE_DTYPE_F16)) return GOOSE_ERR_ARG;
   const AttnArgs a{part, ks, part_stride, part_ld, n_heads, n_kv_heads, (const float2*)cs, cap, gq, gk, eps,
-                   att_o, att_ml, Bpad, o, ldo, dtype == GOOSE_DTYPE_F16, flags};
+                   att_o, att_ml, Bpad, o, ldo, oterms, o_dtype == GOOSE_DTYPE_F16 ? 1 : 0, dtype == GOOSE_DTYPE_F16, flags};
   // a 3-tile tree runs the 4-tile kernel, which reads projection rows up to row0 + 128
   auto tiles_of = [](int B) { const int qt = (B + 31) / 32; return qt >= 3 ? 4 : qt; };
   for (int r = 0; r < nseg; ++r) {

@@ -35,18 +35,20 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int NW = 4;   // wavefronts per workgroup
 constexpr int NT = 2;   // column tiles per wavefront
 
-// KC: inputs per stage
-template <int MT, int EPI, int KC, bool F16>
+// KC: inputs per stage; TERMS: terms of the activation operand (gemm_bf16.hip): with two, every weight
+// operand meets the hi and then the lo operand of its rows, as in the skinny kernel
+template <int MT, int EPI, int KC, bool F16, int TERMS>
 __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const typename Mma16<F16>::T* A, int lda, const u32x4* __restrict__ Wp,
                                                        int ntiles, int ksteps_total, int stages_per_split, int B,
                                                        void* __restrict__ out, size_t ldo, size_t split_stride, int gx,
-                                                       int nsplit, int nchunk) {
+                                                       int nsplit, int nchunk, float out_scale,
+                                                       int32_t* __restrict__ flags) {
   typedef typename Mma16<F16>::T T;
   typedef typename Mma16<F16>::v8 op8;
-  constexpr int LDS_ROW = KC * 2 + 16;  // bytes; 9 x 16: rows start in different banks
+  constexpr int LDS_ROW = KC * 2 * TERMS + 16;  // bytes; an odd number of 16-byte units: rows start in different banks
   constexpr int NTHR = 64 * NW;
   constexpr int STEPS = KC / 16;
-  constexpr int ASEG = MT * 32 * (KC / 8);  // 16-byte segments of one A stage
+  constexpr int ASEG = MT * 32 * (KC / 8) * TERMS;  // 16-byte segments of one A stage
   constexpr int APT = ASEG / NTHR;
   static_assert(ASEG % NTHR == 0, "A stage must divide evenly over the workgroup");
   constexpr int STAGE_BYTES = MT * 32 * LDS_ROW;
@@ -83,7 +85,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const typename Mma16<F16>
 #pragma unroll
   for (int i = 0; i < APT; ++i) {
     const int seg = tid + NTHR * i;
-    const int row = seg / (KC / 8), c16 = seg % (KC / 8);
+    const int row = seg / (KC / 8 * TERMS), c16 = seg % (KC / 8 * TERMS);
     a_src[i] = A + (size_t)row * lda + c16 * 8;
     a_dst[i] = row * LDS_ROW + c16 * 16;
   }
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const typename Mma16<F16>
   auto load_a = [&](int st, auto slot_c) {
     constexpr int slot = decltype(slot_c)::value;
 #pragma unroll
-    for (int i = 0; i < APT; ++i) areg[slot][i] = *reinterpret_cast<const u32x4*>(a_src[i] + (size_t)st * KC);
+    for (int i = 0; i < APT; ++i) areg[slot][i] = *reinterpret_cast<const u32x4*>(a_src[i] + (size_t)st * KC * TERMS);
   };
   auto store_a = [&](int buf, auto slot_c) {
     constexpr int slot = decltype(slot_c)::value;
@@ -112,18 +114,21 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const typename Mma16<F16>
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) wreg[slot][s][nt] = wbase[nt][((size_t)st * STEPS + s) * 64];
   };
-  const int a_frag = (lane & 31) * LDS_ROW + (lane >> 5) * 16;
+  const int a_frag = (lane & 31) * LDS_ROW + (lane >> 5) * 16 * TERMS;
   auto stage = [&](auto slot_c, int st, auto next_a, auto refill) {
     constexpr int slot = decltype(slot_c)::value, buf = slot;
     const std::integral_constant<int, slot ^ 1> nslot;
     if (refill) load_a(st + 2, slot_c);  // this slot's previous content (stage st) is in LDS already
     __builtin_amdgcn_sched_barrier(0);
     // the A operands of step s+1 are read from LDS before the matrix instructions of step s issue
-    op8 af[2][MT];
+    op8 af[2][MT][TERMS];
     auto read_a = [&](int s, int which) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
-        af[which][mt] = *reinterpret_cast<const op8*>(&lds[buf * STAGE_BYTES + mt * 32 * LDS_ROW + a_frag + s * 32]);
+#pragma unroll
+        for (int t = 0; t < TERMS; ++t)
+          af[which][mt][t] = *reinterpret_cast<const op8*>(
+              &lds[buf * STAGE_BYTES + mt * 32 * LDS_ROW + a_frag + s * 32 * TERMS + t * 16]);
     };
     read_a(0, 0);
 #pragma unroll
@@ -136,7 +141,8 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const typename Mma16<F16>
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
-          acc[mt][nt] = Mma16<F16>::mfma(af[s & 1][mt], b[nt], acc[mt][nt]);
+#pragma unroll
+          for (int t = 0; t < TERMS; ++t) acc[mt][nt] = Mma16<F16>::mfma(af[s & 1][mt][t], b[nt], acc[mt][nt]);
       if (refill) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) wreg[slot][s][nt] = wbase[nt][((size_t)(st + 2) * STEPS + s) * 64];
@@ -190,7 +196,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const typename Mma16<F16>
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int row = row_base + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          if (row < B) o[(size_t)row * ldo + col] = acc[mt][nt][r];
+          if (row < B) o[(size_t)row * ldo + col] = acc[mt][nt][r] * out_scale;
         }
     }
   } else {  // EPI_SWIGLU: column tile 2c holds gate rows, 2c+1 the matching up rows
@@ -198,24 +204,34 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const typename Mma16<F16>
     if (tile0 + 1 >= ntiles) return;
     T* hq = reinterpret_cast<T*>(out);
     const int col = (tile0 >> 1) * 32 + (lane & 31);
+    const size_t cpos = term_pos(TERMS, col);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = row_base + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const float g = acc[mt][0][r], u = acc[mt][1][r];
-        if (row < B) hq[(size_t)row * ldo + col] = (T)(g / (1.0f + __expf(-g)) * u);
+        const float g = acc[mt][0][r] * out_scale, u = acc[mt][1][r] * out_scale;
+        float hval = g / (1.0f + __expf(-g)) * u;
+        if (F16 && fabsf(hval) > 65504.0f) {  // beyond fp16: clamp, and say so (GOOSE_FLAG_RANGE)
+          hval = copysignf(65504.0f, hval);
+          if (flags != nullptr && row < B) atomicOr(flags, GOOSE_FLAG_RANGE);
+        }
+        if (row < B) {
+          const T hi = (T)hval;
+          hq[(size_t)row * ldo + cpos] = hi;
+          if (TERMS == 2) hq[(size_t)row * ldo + cpos + 8] = (T)(hval - (float)hi);
+        }
       }
   }
 }
 
-template <int MT, int EPI, int KC, bool F16>
+template <int MT, int EPI, int KC, bool F16, int TERMS>
 int launch_rows(const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit, void* out, size_t ldo,
-                size_t split_stride, hipStream_t st) {
-  constexpr int LDS_BYTES = 2 * MT * 32 * (KC * 2 + 16);
+                size_t split_stride, float out_scale, int32_t* flags, hipStream_t st) {
+  constexpr int LDS_BYTES = 2 * MT * 32 * (KC * 2 * TERMS + 16);
   static bool configured = false;  // more LDS than a kernel gets by default: ask once
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_rows<MT, EPI, KC, F16>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_rows<MT, EPI, KC, F16, TERMS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (e != hipSuccess) { goose_note_hip_error(e, "hipFuncSetAttribute(k_gemm_rows)", __LINE__); return GOOSE_ERR_HIP; }
     configured = true;
@@ -226,26 +242,38 @@ int launch_rows(const void* A, int lda, const void* Wp, int Npad, int Kpad, int 
   const int granules = Kpad / 128;                        // split-K ranges are multiples of 128 inputs,
   const int gps = (granules + ksplit - 1) / ksplit;       // the same ranges as the skinny kernel's
   const dim3 grid((gx * ksplit + 7) / 8 * 8 * nchunk);
-  hipLaunchKernelGGL((k_gemm_rows<MT, EPI, KC, F16>), grid, dim3(64 * NW), LDS_BYTES, st,
+  hipLaunchKernelGGL((k_gemm_rows<MT, EPI, KC, F16, TERMS>), grid, dim3(64 * NW), LDS_BYTES, st,
                      (const typename Mma16<F16>::T*)A, lda,
-                     (const u32x4*)Wp, ntiles, ksteps, gps * (128 / KC), B, out, ldo, split_stride, gx, ksplit, nchunk);
+                     (const u32x4*)Wp, ntiles, ksteps, gps * (128 / KC), B, out, ldo, split_stride, gx, ksplit, nchunk, out_scale,
+                     flags);
   return goose_launch_status();
+}
+
+template <int EPI>
+int launch_rows_any(bool f16, int terms, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int ksplit,
+                    void* out, size_t ldo, size_t split_stride, float out_scale, int32_t* flags, hipStream_t st) {
+  if (terms == 2)
+    return f16 ? launch_rows<4, EPI, 64, true, 2>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, out_scale, flags, st)
+               : launch_rows<4, EPI, 64, false, 2>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, out_scale, flags, st);
+  return f16 ? launch_rows<4, EPI, 64, true, 1>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, out_scale, flags, st)
+             : launch_rows<4, EPI, 64, false, 1>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, split_stride, out_scale, flags, st);
 }
 
 }  // namespace
 
 // A must hold whole chunks of 128 readable rows.
-int launch_gemm_rows_16(int dtype, int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B,
-                        int ksplit, void* out, size_t ldo, size_t out_split_stride, hipStream_t st) {
+int launch_gemm_rows_16(int dtype, int epi, const void* A, int lda, int terms, const void* Wp, int Npad, int Kpad, int B,
+                        int ksplit, void* out, size_t ldo, size_t out_split_stride, float out_scale, int32_t* flags,
+                        hipStream_t st) {
   if (dtype != GOOSE_DTYPE_BF16 && dtype != GOOSE_DTYPE_F16) return GOOSE_ERR_ARG;
   const bool f16 = dtype == GOOSE_DTYPE_F16;
-  if (B < 1 || B > GOOSE_MAX_ROWS || (Npad & 31) || (Kpad % 128) || ksplit < 1) return GOOSE_ERR_ARG;
+  if (B < 1 || B > GOOSE_MAX_ROWS || (Npad & 31) || (Kpad % 128) || ksplit < 1 || (terms != 1 && terms != 2))
+    return GOOSE_ERR_ARG;
   if (epi == EPI_SWIGLU) {
     if (ksplit != 1 || (Npad & 63)) return GOOSE_ERR_ARG;
-    return f16 ? launch_rows<4, EPI_SWIGLU, 64, true>(A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st)
-               : launch_rows<4, EPI_SWIGLU, 64, false>(A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st);
+    return launch_rows_any<EPI_SWIGLU>(f16, terms, A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, out_scale, flags, st);
   }
   if (epi != EPI_PARTIAL) return GOOSE_ERR_ARG;
-  return f16 ? launch_rows<4, EPI_PARTIAL, 64, true>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st)
-             : launch_rows<4, EPI_PARTIAL, 64, false>(A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st);
+  return launch_rows_any<EPI_PARTIAL>(f16, terms, A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, out_scale,
+                                      flags, st);
 }

@@ -22,9 +22,16 @@ inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s);
 inline bool is16(int dtype) { return dtype == GOOSE_DTYPE_BF16 || dtype == GOOSE_DTYPE_F16; }  // the MFMA path
 inline size_t elem_size(int dtype) { return is16(dtype) ? 2 : 4; }
 
+// Launch-shape overrides from the environment exist only in builds made with -DGOOSE_TUNING (a
+// development aid: they change split counts, hence summation orders); the library proper reads none.
 int env_int(const char* name, int dflt) {
+#ifdef GOOSE_TUNING
   const char* v = getenv(name);
   return (v && *v) ? atoi(v) : dflt;
+#else
+  (void)name;
+  return dflt;
+#endif
 }
 
 // ---- optional per-kernel timing with HIP events on the caller's stream -----------------------
@@ -113,15 +120,20 @@ struct GemmCfg { int nw, ks; };
 GemmCfg gemm_cfg(const goose_ctx* c, const char* env_name, int Npad, int Kpad) {
   GemmCfg g;
   pick_gemm_config(Npad, Kpad, c->max_ksplit, &g.nw, &g.ks);
+#ifdef GOOSE_TUNING
   const char* v = getenv(env_name);
   if (v && *v) {
     int nw = 0, ks = 0;
+    const int nstages = Kpad / 128;
     if (sscanf(v, "%d,%d", &nw, &ks) == 2 && (nw == 2 || nw == 4) && ks >= 1 && ks <= c->max_ksplit &&
-        ks <= Kpad / 128) {
+        ks <= nstages && ((nstages + ks - 1) / ks) * (ks - 1) < nstages) {  // no empty split
       g.nw = nw;
       g.ks = ks;
     }
   }
+#else
+  (void)env_name;
+#endif
   return g;
 }
 
@@ -173,6 +185,7 @@ int goose_create_batched(const goose_model_desc* desc, int max_B, int max_rows, 
   if (d.n_layers < 1 || d.hidden < 1 || d.n_heads < 1 || d.head_dim < 2 || d.ffn < 1 || d.vocab < 1)
     return GOOSE_ERR_ARG;
   if (!is16(d.dtype) && d.dtype != GOOSE_DTYPE_F32) return GOOSE_ERR_ARG;
+  if (d.act_mode != GOOSE_ACT_F16 && d.act_mode != GOOSE_ACT_TWO_TERM) return GOOSE_ERR_ARG;
   if (!(d.rope_base > 1.0f) || !(d.rms_eps >= 0.0f)) return GOOSE_ERR_ARG;
   if (d.head_dim % 8 != 0 || d.head_dim > 256) return GOOSE_ERR_SHAPE;
   const int n_kv = d.n_kv_heads > 0 ? d.n_kv_heads : d.n_heads;
@@ -201,6 +214,19 @@ int goose_create_batched(const goose_model_desc* desc, int max_B, int max_rows, 
   c->Vpad = round_up(d.vocab, 32);
   c->max_splits = 32;
   c->max_ksplit = 16;
+  // 16-bit storage: how the projections carry their activation operands (goose.h, GOOSE_ACT_*)
+  c->act_dtype = d.dtype;
+  c->terms = 1;
+  c->w_exp = 0;
+  c->out_scale = 1.0f;
+  if (is16(d.dtype)) {
+    if (d.act_mode == GOOSE_ACT_TWO_TERM) {
+      c->terms = 2;
+    } else {
+      c->act_dtype = GOOSE_DTYPE_F16;
+      if (d.dtype == GOOSE_DTYPE_BF16) { c->w_exp = 8; c->out_scale = 1.0f / 256.0f; }
+    }
+  }
   compute_layouts(c);
 
   const size_t es = elem_size(d.dtype);
@@ -210,11 +236,11 @@ int goose_create_batched(const goose_model_desc* desc, int max_B, int max_rows, 
   c->part_ld = widest;
   int rc = GOOSE_OK;
   auto A = [&](void** p, size_t bytes) { if (rc == GOOSE_OK) rc = dev_alloc(p, bytes); };
-  A(&c->xn, (size_t)c->Bpad * c->Kh * es);
+  A(&c->xn, (size_t)c->Bpad * c->Kh * es * c->terms);
   A((void**)&c->part, (size_t)c->max_ksplit * c->Bpad * c->part_ld * sizeof(float));
   A(&c->q, (size_t)c->Bpad * c->Kq * es);
-  A(&c->o, (size_t)c->Bpad * c->Kq * es);
-  A(&c->h, (size_t)c->Bpad * c->Fpad * es);
+  A(&c->o, (size_t)c->Bpad * c->Kq * es * c->terms);
+  A(&c->h, (size_t)c->Bpad * c->Fpad * es * c->terms);
   A((void**)&c->att_o, (size_t)d.n_heads * c->max_splits * c->Bpad * d.head_dim * sizeof(float));
   A((void**)&c->att_ml, (size_t)d.n_heads * c->max_splits * c->Bpad * 2 * sizeof(float));
   A((void**)&c->logits, (size_t)c->Bpad * c->Vpad * sizeof(float));
@@ -276,16 +302,16 @@ int goose_pack_layer(goose_ctx* c, const goose_layer_weights* w, void* d_packed,
       GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.gk, w->gk, d.head_dim * elem_size(d.dtype), hipMemcpyDeviceToDevice, st));
     }
     int rc = launch_pack_16(PACK_QKV, w->wq, w->wk, w->wv, c->Hq, d.hidden, round_up(c->Hq + 2 * c->Hkv, 32), c->Kh,
-                              base + c->pl.wqkv, st, c->Hkv);
+                            base + c->pl.wqkv, st, c->Hkv, c->w_exp, c->flags);
     if (rc) return rc;
     rc = launch_pack_16(PACK_PLAIN, w->wo, nullptr, nullptr, d.hidden, c->Hq, round_up(d.hidden, 32), c->Kq,
-                          base + c->pl.wo, st);
+                        base + c->pl.wo, st, 0, c->w_exp, c->flags);
     if (rc) return rc;
     rc = launch_pack_16(PACK_GATE_UP, w->wg, w->wu, nullptr, d.ffn, d.hidden, 2 * round_up(d.ffn, 32), c->Kh,
-                          base + c->pl.wgu, st);
+                        base + c->pl.wgu, st, 0, c->w_exp, c->flags);
     if (rc) return rc;
     return launch_pack_16(PACK_PLAIN, w->wd, nullptr, nullptr, d.hidden, d.ffn, round_up(d.hidden, 32), c->Fpad,
-                            base + c->pl.wd, st);
+                          base + c->pl.wd, st, 0, c->w_exp, c->flags);
   }
   const size_t qb = (size_t)c->Hq * d.hidden * 4, fb = (size_t)d.ffn * d.hidden * 4;
   GOOSE_HIP_TRY(hipMemcpyAsync(base + c->pl.wqkv, w->wq, qb, D2D, st));
@@ -306,7 +332,7 @@ int goose_pack_lm_head(goose_ctx* c, const void* d_gf, const void* d_wlm, void* 
   GOOSE_HIP_TRY(hipMemcpyAsync(base + c->ph.gf, d_gf, d.hidden * elem_size(d.dtype), hipMemcpyDeviceToDevice, st));
   if (is16(d.dtype))
     return launch_pack_16(PACK_PLAIN, d_wlm, nullptr, nullptr, d.vocab, d.hidden, c->Vpad, c->Kh,
-                            base + c->ph.wlm, st);
+                          base + c->ph.wlm, st, 0, c->w_exp, c->flags);
   GOOSE_HIP_TRY(hipMemcpyAsync(base + c->ph.wlm, d_wlm, (size_t)d.vocab * d.hidden * 4, hipMemcpyDeviceToDevice, st));
   return GOOSE_OK;
 }
@@ -348,18 +374,20 @@ static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, v
   // x_hat = RMSNorm(x) * g1
   if (!xhat_ready) {
     PROF(PK_NORM);
-    rc = launch_resid_norm(d.dtype, d_x, H, nullptr, 0, 0, 0, w + c->pl.g1, d.rms_eps, c->xn, c->Kh, B, st);
+    rc = launch_resid_norm(d.dtype, c->act_dtype, d_x, H, nullptr, 0, 0, 0, w + c->pl.g1, d.rms_eps, c->xn,
+                           c->Kh * c->terms, c->terms, B, st);
   }
   if (rc) return rc;
 
   if (is16(d.dtype)) {
+    const int T = c->terms;
     const int Nqkv = round_up(Hq + 2 * c->Hkv, 32), Nh = round_up(H, 32), Ngu = 2 * round_up(d.ffn, 32);
     static const int splits_env = env_int("GOOSE_ATTN_SPLITS", 0);
     const GemmCfg cq = gemm_cfg(c, "GOOSE_CFG_QKV", Nqkv, c->Kh);
     int ks = cq.ks;
     { PROF(PK_GEMM_QKV);
-      rc = launch_gemm_16(d.dtype, EPI_PARTIAL, c->xn, c->Kh, w + c->pl.wqkv, Nqkv, c->Kh, B, cq.nw, ks, c->part,
-                            c->part_ld, pstride, st); }
+      rc = launch_gemm_16(c->act_dtype, EPI_PARTIAL, c->xn, c->Kh * T, T, w + c->pl.wqkv, Nqkv, c->Kh, B, cq.nw, ks,
+                          c->part, c->part_ld, pstride, c->out_scale, c->flags, st); }
     if (rc) return rc;
     // rotary embedding of q and k, KV rows of the tree into the cache, tree attention: one kernel
     static const int ng_env = env_int("GOOSE_ATTN_NG", 4) == 2 ? 2 : 4;
@@ -368,34 +396,35 @@ static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, v
     { PROF(PK_ATTN);
       rc = launch_attn_16(d.dtype, c->part, ks, pstride, c->part_ld, c->rope_cs, d.n_heads, c->n_kv, d.head_dim, c->cap, segs,
                             nseg, splits_env, c->max_splits, ng_env, d.qk_norm ? w + c->pl.gq : nullptr,
-                            d.qk_norm ? w + c->pl.gk : nullptr, d.rms_eps, c->att_o, c->att_ml, c->Bpad, c->o, c->Kq,
-                            c->flags, st); }
+                            d.qk_norm ? w + c->pl.gk : nullptr, d.rms_eps, c->att_o, c->att_ml, c->Bpad, c->o, c->Kq * T,
+                            T, c->act_dtype, c->flags, st); }
     if (rc) return rc;
     const GemmCfg co = gemm_cfg(c, "GOOSE_CFG_O", Nh, c->Kq);
     ks = co.ks;
     { PROF(PK_GEMM_O);
-      rc = launch_gemm_16(d.dtype, EPI_PARTIAL, c->o, c->Kq, w + c->pl.wo, Nh, c->Kq, B, co.nw, ks, c->part, c->part_ld,
-                            pstride, st); }
+      rc = launch_gemm_16(c->act_dtype, EPI_PARTIAL, c->o, c->Kq * T, T, w + c->pl.wo, Nh, c->Kq, B, co.nw, ks, c->part,
+                          c->part_ld, pstride, c->out_scale, c->flags, st); }
     if (rc) return rc;
     // x += attention projection; x_hat = RMSNorm(x) * g2
     { PROF(PK_NORM);
-      rc = launch_resid_norm(d.dtype, d_x, H, c->part, ks, pstride, c->part_ld, w + c->pl.g2, d.rms_eps, c->xn,
-                             c->Kh, B, st); }
+      rc = launch_resid_norm(d.dtype, c->act_dtype, d_x, H, c->part, ks, pstride, c->part_ld, w + c->pl.g2, d.rms_eps,
+                             c->xn, c->Kh * T, T, B, st); }
     if (rc) return rc;
     static const int gu_nw = env_int("GOOSE_GU_NW", 4) == 2 ? 2 : 4;
     { PROF(PK_GEMM_GATE_UP);
-      rc = launch_gemm_16(d.dtype, EPI_SWIGLU, c->xn, c->Kh, w + c->pl.wgu, Ngu, c->Kh, B, gu_nw, 1, c->h, c->Fpad, 0, st); }
+      rc = launch_gemm_16(c->act_dtype, EPI_SWIGLU, c->xn, c->Kh * T, T, w + c->pl.wgu, Ngu, c->Kh, B, gu_nw, 1, c->h,
+                          (size_t)c->Fpad * T, 0, c->out_scale, c->flags, st); }
     if (rc) return rc;
     const GemmCfg cd = gemm_cfg(c, "GOOSE_CFG_DOWN", Nh, c->Fpad);
     ks = cd.ks;
     { PROF(PK_GEMM_DOWN);
-      rc = launch_gemm_16(d.dtype, EPI_PARTIAL, c->h, c->Fpad, w + c->pl.wd, Nh, c->Fpad, B, cd.nw, ks, c->part, c->part_ld,
-                            pstride, st); }
+      rc = launch_gemm_16(c->act_dtype, EPI_PARTIAL, c->h, c->Fpad * T, T, w + c->pl.wd, Nh, c->Fpad, B, cd.nw, ks,
+                          c->part, c->part_ld, pstride, c->out_scale, c->flags, st); }
     if (rc) return rc;
     // x += MLP output (and the following normalisation when its gain is known)
     PROF(PK_NORM);
-    return launch_resid_norm(d.dtype, d_x, H, c->part, ks, pstride, c->part_ld, g_next, d.rms_eps,
-                             g_next ? c->xn : nullptr, g_next ? c->Kh : 0, B, st);
+    return launch_resid_norm(d.dtype, c->act_dtype, d_x, H, c->part, ks, pstride, c->part_ld, g_next, d.rms_eps,
+                             g_next ? c->xn : nullptr, g_next ? c->Kh * T : 0, T, B, st);
   }
 
   // fp32 storage: plain kernels (one request)
@@ -411,8 +440,8 @@ static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, v
   if (rc) return rc;
   rc = launch_gemm_f32((const float*)c->o, c->Kq, (const float*)(w + c->pl.wo), H, Hq, B, c->part, c->part_ld, st);
   if (rc) return rc;
-  rc = launch_resid_norm(d.dtype, d_x, H, c->part, 1, pstride, c->part_ld, w + c->pl.g2, d.rms_eps, c->xn, c->Kh, B,
-                         st);
+  rc = launch_resid_norm(d.dtype, d.dtype, d_x, H, c->part, 1, pstride, c->part_ld, w + c->pl.g2, d.rms_eps, c->xn, c->Kh,
+                         1, B, st);
   if (rc) return rc;
   rc = launch_gemm_f32(xn, c->Kh, (const float*)(w + c->pl.wgu), 2 * d.ffn, H, B, c->part, c->part_ld, st);
   if (rc) return rc;
@@ -421,8 +450,8 @@ static int layer_impl(goose_ctx* c, const char* w, float* d_x, void* d_kcache, v
   rc = launch_gemm_f32((const float*)c->h, c->Fpad, (const float*)(w + c->pl.wd), H, d.ffn, B, c->part, c->part_ld,
                        st);
   if (rc) return rc;
-  return launch_resid_norm(d.dtype, d_x, H, c->part, 1, pstride, c->part_ld, g_next, d.rms_eps,
-                           g_next ? c->xn : nullptr, g_next ? c->Kh : 0, B, st);
+  return launch_resid_norm(d.dtype, d.dtype, d_x, H, c->part, 1, pstride, c->part_ld, g_next, d.rms_eps,
+                           g_next ? c->xn : nullptr, g_next ? c->Kh : 0, 1, B, st);
 }
 
 int goose_verify_layer(goose_ctx* c, const void* d_packed_layer, float* d_x, void* d_kcache, void* d_vcache, int P,
@@ -471,8 +500,8 @@ static int lm_head_impl(goose_ctx* c, const void* d_packed_head, const float* d_
   // the residual stream is left untouched: normalise into the operand buffer only
   int rc = GOOSE_OK;
   if (!xhat_ready)
-    rc = launch_resid_norm(d.dtype, const_cast<float*>(d_x), d.hidden, nullptr, 0, 0, 0, w + c->ph.gf, d.rms_eps,
-                           c->xn, c->Kh, B, st);
+    rc = launch_resid_norm(d.dtype, c->act_dtype, const_cast<float*>(d_x), d.hidden, nullptr, 0, 0, 0, w + c->ph.gf,
+                           d.rms_eps, c->xn, c->Kh * c->terms, c->terms, B, st);
   if (rc) return rc;
   if (is16(d.dtype)) {
     // the projection kernel reduces its own columns to (max, second, index) per row; logits are
@@ -484,7 +513,8 @@ static int lm_head_impl(goose_ctx* c, const void* d_packed_head, const float* d_
     const size_t ld = out == c->logits ? (size_t)c->Vpad : (size_t)d.vocab;
     const int groups = (c->Vpad / 32 + lm_nw - 1) / lm_nw;
     { PROF(PK_LM_HEAD);
-      rc = launch_gemm_top2_16(d.dtype, c->xn, c->Kh, w + c->ph.wlm, c->Vpad, c->Kh, B, lm_nw, out, ld, c->top2, d.vocab, st); }
+      rc = launch_gemm_top2_16(c->act_dtype, c->xn, c->Kh * c->terms, c->terms, w + c->ph.wlm, c->Vpad, c->Kh, B, lm_nw, out,
+                               ld, c->top2, d.vocab, c->out_scale, st); }
     if (rc) return rc;
     if (bounce)
       GOOSE_HIP_TRY(hipMemcpy2DAsync(d_logits_or_null, (size_t)d.vocab * 4, c->logits, (size_t)c->Vpad * 4,
@@ -669,26 +699,46 @@ int goose_pack_matrix(const void* d_w, int N, int K, void* d_packed, void* strea
                         as_stream(stream));
 }
 
-int goose_gemm_swiglu_packed(int dtype, const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, void* d_h,
-                             int ldh, void* stream) {
+int goose_split_operand(int dtype, const float* d_src, int rows, int cols, int ld_src, void* d_dst, int ld_dst,
+                        void* stream) {
+  if (!d_src || !d_dst || rows < 1 || cols < 1 || ld_src < cols || !is16(dtype)) return GOOSE_ERR_ARG;
+  if (ld_dst < 2 * round_up(cols, 8) || (ld_dst % 16) != 0) return GOOSE_ERR_ARG;
+  return launch_split_operand(dtype, d_src, rows, cols, ld_src, d_dst, ld_dst, as_stream(stream));
+}
+
+int goose_gemm_swiglu_packed_ex(int dtype, const void* d_a, int lda, int terms, const void* d_packed, int N, int K,
+                                int B, int nw, float out_scale, void* d_h, int ldh, void* stream) {
   if (!d_a || !d_packed || !d_h || N < 64 || (N % 64) != 0 || K < 1) return GOOSE_ERR_ARG;
   if (!is16(dtype) || B < 1 || B > GOOSE_MAX_ROWS || (nw != 2 && nw != 4)) return GOOSE_ERR_ARG;
+  if (terms != 1 && terms != 2) return GOOSE_ERR_ARG;
   const int Kpad = round_up(K, 128);
-  if (lda < Kpad || (lda % 8) != 0 || ldh < N / 2) return GOOSE_ERR_ARG;
-  return launch_gemm_16(dtype, EPI_SWIGLU, d_a, lda, d_packed, N, Kpad, B, nw, 1, d_h, (size_t)ldh, 0, as_stream(stream));
+  if (lda < Kpad * terms || (lda % 8) != 0 || ldh < N / 2 * terms) return GOOSE_ERR_ARG;
+  return launch_gemm_16(dtype, EPI_SWIGLU, d_a, lda, terms, d_packed, N, Kpad, B, nw, 1, d_h, (size_t)ldh, 0, out_scale,
+                        nullptr, as_stream(stream));
+}
+
+int goose_gemm_swiglu_packed(int dtype, const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw,
+                             void* d_h, int ldh, void* stream) {
+  return goose_gemm_swiglu_packed_ex(dtype, d_a, lda, 1, d_packed, N, K, B, nw, 1.0f, d_h, ldh, stream);
+}
+
+int goose_gemm_packed_ex(int dtype, const void* d_a, int lda, int terms, const void* d_packed, int N, int K, int B,
+                         int nw, int ksplit, float out_scale, float* d_partials, void* stream) {
+  if (!d_a || !d_packed || !d_partials || N < 1 || K < 1) return GOOSE_ERR_ARG;
+  if (!is16(dtype) || B < 1 || B > GOOSE_MAX_ROWS || (nw != 2 && nw != 4) || ksplit < 1) return GOOSE_ERR_ARG;
+  if (terms != 1 && terms != 2) return GOOSE_ERR_ARG;
+  const int Npad = round_up(N, 32), Kpad = round_up(K, 128);
+  if (lda < Kpad * terms || (lda % 8) != 0) return GOOSE_ERR_ARG;
+  const int nstages = Kpad / 128;
+  if (ksplit > nstages || ((nstages + ksplit - 1) / ksplit) * (ksplit - 1) >= nstages) return GOOSE_ERR_ARG;
+  const int rows = round_up(B, 32);
+  return launch_gemm_16(dtype, EPI_PARTIAL, d_a, lda, terms, d_packed, Npad, Kpad, B, nw, ksplit, d_partials,
+                        (size_t)Npad, (size_t)rows * Npad, out_scale, nullptr, as_stream(stream));
 }
 
 int goose_gemm_packed(int dtype, const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, int ksplit,
                       float* d_partials, void* stream) {
-  if (!d_a || !d_packed || !d_partials || N < 1 || K < 1) return GOOSE_ERR_ARG;
-  if (!is16(dtype) || B < 1 || B > GOOSE_MAX_ROWS || (nw != 2 && nw != 4) || ksplit < 1) return GOOSE_ERR_ARG;
-  const int Npad = round_up(N, 32), Kpad = round_up(K, 128);
-  if (lda < Kpad || (lda % 8) != 0) return GOOSE_ERR_ARG;
-  const int nstages = Kpad / 128;
-  if (ksplit > nstages || ((nstages + ksplit - 1) / ksplit) * (ksplit - 1) >= nstages) return GOOSE_ERR_ARG;
-  const int rows = round_up(B, 32);
-  return launch_gemm_16(dtype, EPI_PARTIAL, d_a, lda, d_packed, Npad, Kpad, B, nw, ksplit, d_partials, (size_t)Npad,
-                        (size_t)rows * Npad, as_stream(stream));
+  return goose_gemm_packed_ex(dtype, d_a, lda, 1, d_packed, N, K, B, nw, ksplit, 1.0f, d_partials, stream);
 }
 
 int goose_copy_probe(const void* d_src, void* d_dst, size_t bytes, void* stream) {

@@ -54,6 +54,10 @@ struct goose_ctx {
   int Vpad;    // vocab rounded up to 32
   int max_splits;  // attention key splits the workspace is sized for
   int max_ksplit;  // split-K factor the partial buffer is sized for
+  int act_dtype;   // type of the projections' activation operands (xn, o, h): fp16 unless two-term bf16 / fp32
+  int terms;       // terms of those operands: 2 in GOOSE_ACT_TWO_TERM mode (hi + lo), else 1
+  int w_exp;       // 16-bit weights were packed as fp16 values w * 2^w_exp (0: packed as stored)
+  float out_scale; // 2^-w_exp
   PackedLayout pl;
   PackedHeadLayout ph;
 
@@ -87,9 +91,11 @@ int launch_set_int(int32_t* dst, int v, hipStream_t st);
 int launch_build_mask(const int32_t* parent, int B, const int32_t* dP, uint64_t* mask, int32_t* depth, int32_t* pos,
                       int32_t* flags, int cap, int P_max, hipStream_t st);
 int launch_embed(int dtype, const void* E, const int32_t* tokens, int B, int H, int V, float* x, hipStream_t st);
-// x[m][:] += sum_s part[s][m][:H] (S may be 0); xn[m][:] = T(rmsnorm(x[m]) * g) if xn != NULL
-int launch_resid_norm(int dtype, float* x, int H, const float* part, int S, size_t part_stride, size_t part_ld,
-                      const void* g, float eps, void* xn, int ldxn, int B, hipStream_t st);
+// x[m][:] += sum_s part[s][m][:H] (S may be 0); xn[m][:] = Ta(rmsnorm(x[m]) * g) if xn != NULL, in `terms`
+// terms (two: hi + lo in groups of eight columns, the operand layout of the projections; 16-bit types only).
+// gain_dtype: type of g; act_dtype: type Ta of xn (equal, or fp16 activations under bf16 gains).
+int launch_resid_norm(int gain_dtype, int act_dtype, float* x, int H, const float* part, int S, size_t part_stride,
+                      size_t part_ld, const void* g, float eps, void* xn, int ldxn, int terms, int B, hipStream_t st);
 // qkv = sum_s part[s][m][0:3Hq]; rotary on q,k; q -> qout, k/v -> cache slots P+m
 int launch_rope_kv(int dtype, const float* part, int S, size_t part_stride, size_t part_ld, int B, int n_heads,
                    int head_dim, const int32_t* pos, const double* inv_freq, const int32_t* dP, int cap, void* qout,
@@ -136,23 +142,36 @@ int launch_attn_f32(const float* q, int ldq, const float* kc, const float* vc, i
 enum { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATE_UP = 2 };
 // Re-tiles raw [rows][K] matrices of 16-bit elements into MFMA-operand order; Npad x Kpad zero padded.
 // rows_each: rows of s0 (and of s1, s2 unless rows_kv > 0: then s1 and s2 have rows_kv rows each)
+// cvt_exp > 0 (bf16 sources only): re-encode every weight as the fp16 value w * 2^cvt_exp (exact for
+// 2^(-24-cvt_exp) <= |w| < 65504 / 2^cvt_exp; anything else raises GOOSE_FLAG_WEIGHT_RANGE in *flags)
 int launch_pack_16(int mode, const void* s0, const void* s1, const void* s2, int rows_each, int K, int Npad,
-                   int Kpad, void* dst, hipStream_t st, int rows_kv = 0);
+                   int Kpad, void* dst, hipStream_t st, int rows_kv = 0, int cvt_exp = 0, int32_t* flags = nullptr);
 enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_TOP2 = 2 };
-// out partials f32 [ksplit][Bpad][ldo] (EPI_PARTIAL) or 16-bit h [Bpad][ldo] (EPI_SWIGLU, ksplit must be 1)
-int launch_gemm_16(int dtype, int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw,
-                   int ksplit, void* out, size_t ldo, size_t out_split_stride, hipStream_t st);
+// Activation operands come in `terms` = 1 or 2 terms (gemm_bf16.hip): two terms carry a value as hi + lo,
+// stored in groups of eight inputs, 8 hi values then their 8 lo values; lda = elements per row = terms * K at least.
+// Element offset of input column c in such a row:
+static inline __host__ __device__ size_t term_pos(int terms, int c) { return terms == 1 ? (size_t)c : (size_t)(c >> 3) * 16 + (c & 7); }
+// out partials f32 [ksplit][Bpad][ldo] (EPI_PARTIAL) or 16-bit h [Bpad][ldo] in `terms` terms (EPI_SWIGLU, ksplit must be 1).
+// out_scale: an exact power of two applied to every sum before the epilogue uses it (1, or the inverse of
+// the scale of weights re-encoded by launch_pack_16).  flags (or null): GOOSE_FLAG_RANGE is raised when
+// an fp16 SwiGLU result had to be clamped.
+int launch_gemm_16(int dtype, int epi, const void* A, int lda, int terms, const void* Wp, int Npad, int Kpad, int B,
+                   int nw, int ksplit, void* out, size_t ldo, size_t out_split_stride, float out_scale, int32_t* flags,
+                   hipStream_t st);
 // The same products for 128 < B <= GOOSE_MAX_ROWS stacked rows, blocked for the matrix cores
 // (gemm_rows_bf16.hip); A must hold whole chunks of 128 readable rows.
-int launch_gemm_rows_16(int dtype, int epi, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B,
-                        int ksplit, void* out, size_t ldo, size_t out_split_stride, hipStream_t st);
+int launch_gemm_rows_16(int dtype, int epi, const void* A, int lda, int terms, const void* Wp, int Npad, int Kpad, int B,
+                        int ksplit, void* out, size_t ldo, size_t out_split_stride, float out_scale, int32_t* flags,
+                        hipStream_t st);
 // Projection whose workgroups (nw column tiles each) also emit per-row (max, second max, index of
 // max) over their valid columns (< n_valid): top2 is float4 [B][ceil(Npad/32/nw)], index bits in .z.
 // `out` (f32 [B][ldo]) may be null when only the reduction is wanted.
-int launch_gemm_top2_16(int dtype, const void* A, int lda, const void* Wp, int Npad, int Kpad, int B, int nw,
-                        float* out, size_t ldo, void* top2, int n_valid, hipStream_t st);
+int launch_gemm_top2_16(int dtype, const void* A, int lda, int terms, const void* Wp, int Npad, int Kpad, int B, int nw,
+                        float* out, size_t ldo, void* top2, int n_valid, float out_scale, hipStream_t st);
 int launch_harvest_topk(const float* logits, size_t ld, int V, const int32_t* tokens, int B, int K, int table_rows,
                         int32_t* succ_ids, float* succ_scores, hipStream_t st);
+int launch_split_operand(int dtype, const float* src, int rows, int cols, int ld_src, void* dst, int ld_dst,
+                         hipStream_t st);
 int launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
 int launch_argmax_top2(const void* top2, int n_groups, int B, int32_t* argmax, float* margin, hipStream_t st);
 void pick_gemm_config(int Npad, int Kpad, int max_ksplit, int* nw_out, int* ksplit_out);
@@ -171,10 +190,12 @@ struct AttnSeg {
 enum { ATTN_MAX_SEGS = 16 };
 // Fused rotary embedding + KV-tail write + tree attention of `nseg` requests.  part: the q|k|v
 // projection as `ks` split-K slices of f32 [Bpad][part_ld]; cs: rotary table of all rows;
-// o: 16-bit [Bpad][ldo].  Requests with the same number of 32-row query tiles share one launch
+// o: 16-bit [Bpad][ldo] of type o_dtype (which may differ from the caches' type `dtype`) in `oterms` terms
+// (the operand layout of the O projection, see launch_gemm_16).
+// Requests with the same number of 32-row query tiles share one launch
 // (grid z = request).  splits_or_0: key splits per head, 0 = chosen here (at most max_splits).
 int launch_attn_16(int dtype, const float* part, int ks, size_t part_stride, size_t part_ld, const void* cs,
                    int n_heads, int n_kv_heads, int head_dim, int cap, const AttnSeg* segs, int nseg, int splits_or_0,
                    int max_splits, int key_groups, const void* gq, const void* gk, float eps, float* att_o,
-                   float* att_ml, int Bpad, void* o, int ldo, int32_t* flags, hipStream_t st);
+                   float* att_ml, int Bpad, void* o, int ldo, int oterms, int o_dtype, int32_t* flags, hipStream_t st);
 int pick_attn_splits(int n_heads, int keys_max, int max_splits);

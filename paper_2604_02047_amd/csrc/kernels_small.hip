@@ -119,10 +119,13 @@ __device__ inline void store4<_Float16>(_Float16* p, float a, float b, float c, 
   *reinterpret_cast<f16x4*>(p) = v;
 }
 
-template <typename T, int NTHR>
+// TERMS = 2 (16-bit types): xn is written as hi + lo, lo = T(v - hi), in groups of eight columns
+// (8 hi values, then their 8 lo values; row length 2 * columns): the operand layout of the projections.
+// Tg: type of the gains; T: type of xn (fp16 activations may meet bf16 gains).
+template <typename Tg, typename T, int NTHR, int TERMS>
 __global__ __launch_bounds__(NTHR) void k_resid_norm(float* __restrict__ x, int H, const float* __restrict__ part,
                                                      int S, size_t part_stride, size_t part_ld,
-                                                     const T* __restrict__ g, float eps, T* __restrict__ xn,
+                                                     const Tg* __restrict__ g, float eps, T* __restrict__ xn,
                                                      int ldxn) {
   constexpr int MAXV = 4;  // float4 slots per thread kept in registers (H <= 16 * NTHR)
   const int m = blockIdx.x;
@@ -157,9 +160,17 @@ __global__ __launch_bounds__(NTHR) void k_resid_norm(float* __restrict__ x, int 
   for (int i = 0; i < MAXV; ++i) {
     const int c4 = threadIdx.x + i * NTHR;
     if (c4 < nvec) {
-      const T* gp = g + c4 * 4;
-      store4<T>(xn + (size_t)m * ldxn + c4 * 4, (v[i].x * rstd) * to_f32(gp[0]), (v[i].y * rstd) * to_f32(gp[1]),
-                (v[i].z * rstd) * to_f32(gp[2]), (v[i].w * rstd) * to_f32(gp[3]));
+      const Tg* gp = g + c4 * 4;
+      const float o0 = (v[i].x * rstd) * to_f32(gp[0]), o1 = (v[i].y * rstd) * to_f32(gp[1]);
+      const float o2 = (v[i].z * rstd) * to_f32(gp[2]), o3 = (v[i].w * rstd) * to_f32(gp[3]);
+      if (TERMS == 1) {
+        store4<T>(xn + (size_t)m * ldxn + c4 * 4, o0, o1, o2, o3);
+      } else {  // columns 4 c4 .. 4 c4 + 3 lie inside one group of eight
+        T* dst = xn + (size_t)m * ldxn + (size_t)(c4 >> 1) * 16 + (c4 & 1) * 4;
+        const T h0 = (T)o0, h1 = (T)o1, h2 = (T)o2, h3 = (T)o3;
+        store4<T>(dst, to_f32(h0), to_f32(h1), to_f32(h2), to_f32(h3));
+        store4<T>(dst + 8, o0 - to_f32(h0), o1 - to_f32(h1), o2 - to_f32(h2), o3 - to_f32(h3));
+      }
     }
   }
 }
@@ -634,32 +645,39 @@ int launch_embed(int dtype, const void* E, const int32_t* tokens, int B, int H, 
   return goose_launch_status();
 }
 
-int launch_resid_norm(int dtype, float* x, int H, const float* part, int S, size_t part_stride, size_t part_ld,
-                      const void* g, float eps, void* xn, int ldxn, int B, hipStream_t st) {
-  if ((H & 3) || H > 16 * 1024) return GOOSE_ERR_SHAPE;
-  const bool big = H > 4 * 256;  // 1024 threads once a row has more than 1024 columns
-  if (dtype == GOOSE_DTYPE_BF16) {
-    if (big)
-      hipLaunchKernelGGL((k_resid_norm<bf16_t, 1024>), dim3(B), dim3(1024), 0, st, x, H, part, S, part_stride,
-                         part_ld, (const bf16_t*)g, eps, (bf16_t*)xn, ldxn);
-    else
-      hipLaunchKernelGGL((k_resid_norm<bf16_t, 256>), dim3(B), dim3(256), 0, st, x, H, part, S, part_stride, part_ld,
-                         (const bf16_t*)g, eps, (bf16_t*)xn, ldxn);
-  } else if (dtype == GOOSE_DTYPE_F16) {
-    if (big)
-      hipLaunchKernelGGL((k_resid_norm<_Float16, 1024>), dim3(B), dim3(1024), 0, st, x, H, part, S, part_stride,
-                         part_ld, (const _Float16*)g, eps, (_Float16*)xn, ldxn);
-    else
-      hipLaunchKernelGGL((k_resid_norm<_Float16, 256>), dim3(B), dim3(256), 0, st, x, H, part, S, part_stride, part_ld,
-                         (const _Float16*)g, eps, (_Float16*)xn, ldxn);
-  } else {
-    if (big)
-      hipLaunchKernelGGL((k_resid_norm<float, 1024>), dim3(B), dim3(1024), 0, st, x, H, part, S, part_stride, part_ld,
-                         (const float*)g, eps, (float*)xn, ldxn);
-    else
-      hipLaunchKernelGGL((k_resid_norm<float, 256>), dim3(B), dim3(256), 0, st, x, H, part, S, part_stride, part_ld,
-                         (const float*)g, eps, (float*)xn, ldxn);
-  }
+template <typename Tg, typename T, int TERMS>
+static void launch_resid_norm_t(float* x, int H, const float* part, int S, size_t part_stride, size_t part_ld,
+                                const void* g, float eps, void* xn, int ldxn, int B, hipStream_t st) {
+  if (H > 4 * 256)  // 1024 threads once a row has more than 1024 columns
+    hipLaunchKernelGGL((k_resid_norm<Tg, T, 1024, TERMS>), dim3(B), dim3(1024), 0, st, x, H, part, S, part_stride,
+                       part_ld, (const Tg*)g, eps, (T*)xn, ldxn);
+  else
+    hipLaunchKernelGGL((k_resid_norm<Tg, T, 256, TERMS>), dim3(B), dim3(256), 0, st, x, H, part, S, part_stride, part_ld,
+                       (const Tg*)g, eps, (T*)xn, ldxn);
+}
+
+template <typename Tg, typename T>
+static void launch_resid_norm_terms(int terms, float* x, int H, const float* part, int S, size_t part_stride,
+                                    size_t part_ld, const void* g, float eps, void* xn, int ldxn, int B,
+                                    hipStream_t st) {
+  if (terms == 2) launch_resid_norm_t<Tg, T, 2>(x, H, part, S, part_stride, part_ld, g, eps, xn, ldxn, B, st);
+  else launch_resid_norm_t<Tg, T, 1>(x, H, part, S, part_stride, part_ld, g, eps, xn, ldxn, B, st);
+}
+
+int launch_resid_norm(int gain_dtype, int act_dtype, float* x, int H, const float* part, int S, size_t part_stride,
+                      size_t part_ld, const void* g, float eps, void* xn, int ldxn, int terms, int B, hipStream_t st) {
+  if ((H & 3) || H > 16 * 1024 || (terms == 2 && (H & 7))) return GOOSE_ERR_SHAPE;
+  if (terms != 1 && !(terms == 2 && act_dtype != GOOSE_DTYPE_F32)) return GOOSE_ERR_ARG;
+  if (gain_dtype == GOOSE_DTYPE_BF16 && act_dtype == GOOSE_DTYPE_BF16)
+    launch_resid_norm_terms<bf16_t, bf16_t>(terms, x, H, part, S, part_stride, part_ld, g, eps, xn, ldxn, B, st);
+  else if (gain_dtype == GOOSE_DTYPE_BF16 && act_dtype == GOOSE_DTYPE_F16)
+    launch_resid_norm_terms<bf16_t, _Float16>(terms, x, H, part, S, part_stride, part_ld, g, eps, xn, ldxn, B, st);
+  else if (gain_dtype == GOOSE_DTYPE_F16 && act_dtype == GOOSE_DTYPE_F16)
+    launch_resid_norm_terms<_Float16, _Float16>(terms, x, H, part, S, part_stride, part_ld, g, eps, xn, ldxn, B, st);
+  else if (gain_dtype == GOOSE_DTYPE_F32 && act_dtype == GOOSE_DTYPE_F32)
+    launch_resid_norm_t<float, float, 1>(x, H, part, S, part_stride, part_ld, g, eps, xn, ldxn, B, st);
+  else
+    return GOOSE_ERR_ARG;
   return goose_launch_status();
 }
 
@@ -683,6 +701,32 @@ int launch_swiglu_f32(const float* gu, size_t ld, int F, float* h, int ldh, int 
 
 int launch_argmax(const float* logits, size_t ld, int V, int B, int32_t* argmax, float* margin, hipStream_t st) {
   hipLaunchKernelGGL(k_argmax, dim3(B), dim3(256), 0, st, logits, ld, V, argmax, margin);
+  return goose_launch_status();
+}
+
+// fp32 rows -> the two-term 16-bit operand layout of the projections (groups of eight columns:
+// 8 hi values T(v), then their 8 lo values T(v - hi)); columns beyond `cols` up to ld_dst/2 are zero.
+template <typename T>
+__global__ __launch_bounds__(256) void k_split_operand(const float* __restrict__ src, int cols, int ld_src,
+                                                       T* __restrict__ dst, int ld_dst) {
+  const int m = blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= ld_dst / 2) return;
+  const float v = c < cols ? src[(size_t)m * ld_src + c] : 0.f;
+  const T hi = (T)v;
+  T* d = dst + (size_t)m * ld_dst + (size_t)(c >> 3) * 16 + (c & 7);
+  d[0] = hi;
+  d[8] = (T)(v - to_f32(hi));
+}
+
+int launch_split_operand(int dtype, const float* src, int rows, int cols, int ld_src, void* dst, int ld_dst,
+                         hipStream_t st) {
+  const dim3 grid((ld_dst / 2 + 255) / 256, rows);
+  if (dtype == GOOSE_DTYPE_BF16)
+    hipLaunchKernelGGL(k_split_operand<bf16_t>, grid, dim3(256), 0, st, src, cols, ld_src, (bf16_t*)dst, ld_dst);
+  else if (dtype == GOOSE_DTYPE_F16)
+    hipLaunchKernelGGL(k_split_operand<_Float16>, grid, dim3(256), 0, st, src, cols, ld_src, (_Float16*)dst, ld_dst);
+  else
+    return GOOSE_ERR_ARG;
   return goose_launch_status();
 }
 

@@ -6,7 +6,8 @@ device's own input to that layer (input rows and the layer's stored KV prefix ar
 oracle; output rows, the update on its own scale and the new KV rows are compared), the LM head on
 the final hidden rows, the walk (Alg. UnifiedGreedyWalk) and the compaction bit-exactly; the device-resident entry
 point the benchmark replays is then required to reproduce the same step bit for bit.  And as a
-whole, all 32 layers on both sides from the same stored prefix, at the depth-scaled tolerance.
+whole, all 32 layers on both sides from the same stored prefix, at the same tolerance (2e-2 of the logit
+scale), in both activation modes of the library (fp16 operands, two-term bf16 operands).
 """
 import numpy as np
 import pytest
@@ -128,14 +129,17 @@ def test_7b_step_in_the_benchmark_configuration():
 
 
 @pytest.mark.timeout(900)
-def test_7b_whole_step_against_the_oracle():
+@pytest.mark.parametrize("act_mode", [0, 1], ids=["fp16_operands", "two_term_operands"])
+def test_7b_whole_step_against_the_oracle(act_mode):
     """All 32 layers on both sides from the same stored KV prefix: hidden rows after every layer,
     logits, new KV rows, predictions, walk and compaction (the oracle streams its weights layer by layer)."""
+    import dataclasses
     from paper_2604_02047_amd import ModelDesc
     from paper_2604_02047_amd.runner import GooseModel
     shape, seed, B, P0 = gi.SHAPES["7b"], 0, 64, 1024
     dev = torch.device("cuda:0")
-    gm = GooseModel(ModelDesc.from_shape(shape), B, 1024 + 256, lambda l: gi.layer_weights(shape, seed, l, dev),
+    desc = dataclasses.replace(ModelDesc.from_shape(shape), act_mode=act_mode)
+    gm = GooseModel(desc, B, 1024 + 256, lambda l: gi.layer_weights(shape, seed, l, dev),
                     gi.embedding(shape, seed, dev), gi.lm_head(shape, seed, dev), gi.final_norm(shape, seed, dev))
     prefix = gi.prefix_tokens(seed, P0, shape.vocab)
     last = _gpu_prefill(gm, prefix, B)
@@ -155,6 +159,7 @@ def test_7b_whole_step_against_the_oracle():
     g, o, decisive = _compare_step(shape, gm, om, cache, tokens, tree, tol_for(shape))
     print(f"accepted {g['accept_len']} nodes, decisive={decisive}", flush=True)
     assert g["accept_len"] >= 1
+    assert gm.ctx.goose_device_flags() == 0    # every weight re-encoded exactly, no operand out of range
     gm.ctx.close()
 
 

@@ -13,18 +13,40 @@ def _a_rows(B):
     return (B + 31) // 32 * 32 if B <= 128 else (B + 127) // 128 * 128
 
 
-def _run(B, N, K, nw, ks, seed=0, dt=torch.bfloat16):
+def _operand(a32, rows, Kp, dt, terms, dev):
+    """fp32 rows [B][K] -> (device operand in `terms` terms with `rows` rows, the exact values it carries as fp64)."""
+    B, K = a32.shape
+    if terms == 1:
+        a = torch.zeros((rows, Kp), dtype=dt)
+        a[:B, :K] = a32.to(dt)
+        return a.to(dev), a[:B, :K].double().numpy()
+    src = torch.zeros((rows, Kp), dtype=torch.float32, device=dev)
+    src[:B, :K] = a32.to(dev)
+    a2 = torch.full((rows, 2 * Kp), float("nan"), dtype=dt, device=dev)
+    g.goose_split_operand(src, rows, Kp, Kp, a2, 2 * Kp)
+    torch.cuda.synchronize()
+    groups = a2.view(rows, Kp // 8, 2, 8).double().cpu()      # [row][group][hi|lo][8]
+    carried = (groups[:, :, 0] + groups[:, :, 1]).reshape(rows, Kp)
+    hi = groups[:, :, 0].reshape(rows, Kp)
+    assert torch.equal(hi[:B, :K].to(dt), a32.to(dt))                       # hi is the plain rounding
+    assert (carried[:B, :K] - a32.double()).abs().max() <= 2.0 ** -15 * a32.abs().max()   # hi + lo: 16 more bits
+    return a2, carried[:B, :K].numpy()
+
+
+def _run(B, N, K, nw, ks, seed=0, dt=torch.bfloat16, terms=1):
     dev = "cuda:0"
     gen = torch.Generator(device="cpu").manual_seed(seed)
     Kp, Np, rows = (K + 127) // 128 * 128, (N + 31) // 32 * 32, (B + 31) // 32 * 32
-    a = torch.zeros((_a_rows(B), Kp), dtype=dt)
-    a[:B, :K] = (torch.randn((B, K), generator=gen)).to(dt)
+    a, a_exact = _operand(torch.randn((B, K), generator=gen), _a_rows(B), Kp, dt, terms, dev)
     w = (torch.randn((N, K), generator=gen) * 0.05).to(dt)
-    ref = a[:B, :K].double().numpy() @ w.double().numpy().T
+    ref = a_exact @ w.double().numpy().T
     packed = torch.zeros(g.goose_packed_matrix_bytes(N, K), dtype=torch.uint8, device=dev)
     g.goose_pack_matrix(w.to(dev), N, K, packed)
     part = torch.full((ks, rows, Np), float("nan"), dtype=torch.float32, device=dev)
-    g.goose_gemm_packed(a.to(dev), Kp, packed, N, K, B, nw, ks, part)
+    if terms == 1:
+        g.goose_gemm_packed(a, Kp, packed, N, K, B, nw, ks, part)
+    else:
+        g.goose_gemm_packed_ex(a, Kp * terms, terms, packed, N, K, B, nw, ks, part)
     torch.cuda.synchronize()
     out = part[:, :B, :N].double().sum(0).cpu().numpy()
     scale = np.abs(ref).max()
@@ -64,6 +86,16 @@ def test_gemm_fp16_operands(B):
     _run(B, 1000, 1000, 2, 1, dt=torch.float16)
 
 
+@pytest.mark.parametrize("B", [1, 16, 33, 64, 80, 128, 200, 512])
+@pytest.mark.parametrize("dt", [torch.bfloat16, torch.float16])
+def test_gemm_two_term_operand(B, dt):
+    """The activation operand as hi + lo (the layout the decoder layers use): the product must be that of
+    the sum of both terms, i.e. of the fp32 activations to 2^-17."""
+    _run(B, 288, 1024, 4, 2, dt=dt, terms=2)
+    _run(B, 256, 512, 2, 1, dt=dt, terms=2)
+    _run(B, 1000, 1000, 4, 3, dt=dt, terms=2)
+
+
 def test_gemm_ragged_shapes():
     _run(50, 1000, 1000, 4, 2)   # N not a multiple of the 4-tile group, K padded to 1024
     _run(7, 40, 200, 2, 1)
@@ -74,26 +106,35 @@ def test_gemm_ragged_shapes():
                                        (128, 704, 256, 4), (33, 64, 4096, 2), (300, 704, 256, 4), (512, 352, 640, 2),
                                        (160, 2752, 1024, 4)])
 @pytest.mark.parametrize("dt", [torch.bfloat16, torch.float16])
-def test_gemm_swiglu_epilogue(B, F, K, nw, dt):
+@pytest.mark.parametrize("terms", [1, 2])
+def test_gemm_swiglu_epilogue(B, F, K, nw, dt, terms):
     dev = "cuda:0"
     gen = torch.Generator(device="cpu").manual_seed(F)
     Kp, rows = (K + 127) // 128 * 128, (B + 31) // 32 * 32
-    a = torch.zeros((_a_rows(B), Kp), dtype=dt)
-    a[:B, :K] = torch.randn((B, K), generator=gen).to(dt)
+    a, a_exact = _operand(torch.randn((B, K), generator=gen), _a_rows(B), Kp, dt, terms, dev)
     wg = (torch.randn((F, K), generator=gen) * 0.05).to(dt)
     wu = (torch.randn((F, K), generator=gen) * 0.05).to(dt)
     assert F % 32 == 0
     inter = torch.stack([wg.view(F // 32, 32, K), wu.view(F // 32, 32, K)], dim=1).reshape(2 * F, K).contiguous()
-    gd, ud = a[:B, :K].double() @ wg.double().T, a[:B, :K].double() @ wu.double().T
+    gd, ud = torch.from_numpy(a_exact) @ wg.double().T, torch.from_numpy(a_exact) @ wu.double().T
     ref = (gd / (1 + torch.exp(-gd)) * ud).numpy()
     packed = torch.zeros(g.goose_packed_matrix_bytes(2 * F, K), dtype=torch.uint8, device=dev)
     g.goose_pack_matrix(inter.to(dev), 2 * F, K, packed)
-    h = torch.full((rows, F), float("nan"), dtype=dt, device=dev)
-    g.goose_gemm_swiglu_packed(a.to(dev), Kp, packed, 2 * F, K, B, nw, h, F)
+    h = torch.full((rows, F * terms), float("nan"), dtype=dt, device=dev)
+    if terms == 1:
+        g.goose_gemm_swiglu_packed(a, Kp, packed, 2 * F, K, B, nw, h, F)
+    else:
+        g.goose_gemm_swiglu_packed_ex(a, Kp * terms, terms, packed, 2 * F, K, B, nw, h, F * terms)
     torch.cuda.synchronize()
-    out = h[:B].double().cpu().numpy()
-    # one rounding of the result to the storage type (relative to the element, hence to the largest)
-    assert np.abs(out - ref).max() <= (6e-3 if dt == torch.bfloat16 else 8e-4) * np.abs(ref).max()
+    if terms == 1:
+        out = h[:B].double().cpu().numpy()
+        # one rounding of the result to the storage type (relative to the element, hence to the largest)
+        tol = 6e-3 if dt == torch.bfloat16 else 8e-4
+    else:   # the result keeps two terms as well: hi + lo carries it to 2^-17 (the silu itself is fp32)
+        pair = h[:B].view(B, F // 8, 2, 8).double().cpu()
+        out = (pair[:, :, 0] + pair[:, :, 1]).reshape(B, F).numpy()
+        tol = 2e-5
+    assert np.abs(out - ref).max() <= tol * np.abs(ref).max()
 
 
 def test_gemm_repeated_large_launches_are_stable():

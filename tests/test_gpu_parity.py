@@ -1,7 +1,7 @@
 """Parity of the HIP verification path with the CPU oracle, element by element.
 
 Tolerances (max abs error relative to the logit scale max|logit_oracle| of the step):
-fp32 storage 1e-4, bf16 storage 2e-2, fp16 storage 2.5e-3 (three more mantissa bits than bf16).  Integer results are bit-exact; an accept decision is only
+fp32 storage 1e-4, bf16 storage 2e-2, fp16 storage 2.5e-3 (three more mantissa bits than bf16), at any depth.  Integer results are bit-exact; an accept decision is only
 compared where the oracle's top-2 logit margin at the deciding node exceeds the tolerance.
 """
 import numpy as np
@@ -18,12 +18,10 @@ TOL = {"f32": 1e-4, "bf16": 2e-2, "f16": 2.5e-3}
 
 
 def tol_for(shape):
-    """Tolerance of a whole pass through `shape`.  The base figure bounds one layer fed exact inputs
-    (and models up to 8 layers deep).  Rounding noise enters afresh in every layer (bf16 operands:
-    about 0.3 % of the layer's update) and is carried, and amplified, by all later layers; against
-    the fp64 oracle it grows linearly with depth (measured on the 32-layer 7B shape: 3.8e-2 of the
-    logit scale), so deeper models get the base figure per 8 layers."""
-    return TOL[shape.dtype] * max(1.0, shape.n_layers / 8.0)
+    """Tolerance of a whole pass through `shape`: the same flat figure at any depth (2e-2 of the logit scale
+    for the 16-bit types).  It holds for the 32-layer models because the projections' activation operands
+    are not rounded to 8 bits (fp16 operands or two bf16 terms, see goose.h GOOSE_ACT_*)."""
+    return TOL[shape.dtype]
 
 
 def _gpu_prefill(gm, prefix, chunk):
@@ -58,6 +56,7 @@ def _compare_step(shape, gm, om, cache, tokens, tree, tol, check_hidden=True):
     scale = np.abs(o["logits"]).max()
     gl = g["logits"].double().cpu().numpy()
     err = np.abs(gl - o["logits"]).max()
+    print(f"{shape.name}: max logit error {err / scale:.2e} of the logit scale {scale:.3f} (tolerance {tol:.0e})", flush=True)
     assert err <= tol * scale, (err, scale)
     # KV rows written for the tree nodes
     for l, (k_new, v_new) in enumerate(o["new_kv"]):
