@@ -123,10 +123,8 @@ const char* goose_last_hip_error(void);
  * slots per head (a multiple of 64).  Allocates device memory on the current device. */
 int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** out);
 /* The same, with workspace for passes of up to max_rows stacked rows (goose_verify_step_batched):
- * max_B <= max_rows <= GOOSE_MAX_ROWS, a multiple of 32.  A context made here gives a request the same
- * bits alone and inside any batch (equal attention split counts assumed); one made by goose_create
- * (max_rows = round_up(max_B, 32)) may run its projections on trees of up to 64 nodes with two
- * wavefronts per column tile, which orders their sums differently from the wider kernels. */
+ * max_B <= max_rows <= GOOSE_MAX_ROWS, a multiple of 32.  A request gets the same bits alone and
+ * inside any batch (equal attention split counts assumed). */
 int goose_create_batched(const goose_model_desc* desc, int max_B, int max_rows, int cap, goose_ctx** out);
 void goose_destroy(goose_ctx* ctx);
 
