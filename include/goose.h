@@ -173,6 +173,20 @@ int goose_verify_layer(goose_ctx* ctx, const void* d_packed_layer, float* d_x, v
 int goose_lm_head_argmax(goose_ctx* ctx, const void* d_packed_head, const float* d_x, int B, int32_t* d_argmax,
                          float* d_logits_or_null, float* d_margin_or_null, void* stream);
 
+/* The same reduction for callers that cannot allocate device memory (code under stream capture,
+ * serving loops and harnesses that forbid it): no context, no allocation, no synchronisation.  The
+ * operand rows and the per-workgroup (max, second, index) records that goose_lm_head_argmax keeps in
+ * its context's workspace live here in one static 8 MiB device array that every GPU the library
+ * runs on holds until the process ends (its address on the current device is looked up on the first
+ * call there).  desc: the description the head was packed under (dtype bf16 or fp16; act_mode as at
+ * packing); d_packed_head: from goose_pack_lm_head of a context of that description; d_x fp32
+ * [B][hidden], untouched; d_argmax int32 [B]; d_margin_or_null fp32 [B].  Results equal
+ * goose_lm_head_argmax's bit for bit.  Limits: B <= 128, hidden <= 8192, vocab <= 262144, else
+ * GOOSE_ERR_CAPACITY and nothing is launched.  All calls on one GPU share the array: calls that
+ * overlap there (two streams, two threads) race; calls queued on one stream do not. */
+int goose_lm_head_argmax_static(const goose_model_desc* desc, const void* d_packed_head, const float* d_x, int B,
+                                int32_t* d_argmax, float* d_margin_or_null, void* stream);
+
 /* ---- 5. greedy walk (Alg. UnifiedGreedyWalk lines 3-13; Sec. 4.2) -------------------------------------
  * From the root, step to the child whose draft token equals the prediction at the current
  * node; spine-tagged children are examined before branch children, lower node index first

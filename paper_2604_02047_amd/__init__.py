@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     goose_gemm_packed_ex,
     goose_gemm_swiglu_packed_ex,
     goose_split_operand,
+    goose_lm_head_argmax_static,
     lib_path,
     load_library,
     EXPORTS,

@@ -23,6 +23,7 @@ EXPORTS = [
     "goose_context_match", "goose_spine_budget", "goose_build_spine_tree", "goose_spine_ratio_tier", "goose_ema_update",
     "goose_cycle_mode", "goose_verify_step_batched",
     "goose_split_operand", "goose_gemm_packed_ex", "goose_gemm_swiglu_packed_ex",
+    "goose_lm_head_argmax_static",
 ]
 
 GOOSE_DTYPE_BF16, GOOSE_DTYPE_F32, GOOSE_DTYPE_F16 = 0, 1, 2
@@ -130,6 +131,7 @@ def load_library():
     lib.goose_embed.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
     lib.goose_verify_layer.argtypes = [C.c_void_p] * 5 + [C.c_int, C.c_void_p, C.c_int] + [C.c_void_p] * 3
     lib.goose_lm_head_argmax.argtypes = [C.c_void_p] * 3 + [C.c_int] + [C.c_void_p] * 4
+    lib.goose_lm_head_argmax_static.argtypes = [C.c_void_p] * 3 + [C.c_int] + [C.c_void_p] * 3
     lib.goose_accept.argtypes = [C.c_void_p] * 5 + [C.c_int] + [C.c_void_p] * 4
     lib.goose_compact_kv.argtypes = [C.c_void_p] * 3 + [C.c_int] + [C.c_void_p] * 5
     lib.goose_verify_step.argtypes = [C.c_void_p, C.POINTER(_ModelPtrs), C.POINTER(_StepIO), C.c_int, C.c_int,
@@ -303,6 +305,13 @@ def _ptr(t):
 def _stream():
     import torch
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def goose_lm_head_argmax_static(desc: ModelDesc, packed_head, x, B, argmax, margin=None):
+    """goose_lm_head_argmax without a context and without any allocation (static device workspace)."""
+    cd = desc._c()
+    _check(load_library().goose_lm_head_argmax_static(C.byref(cd), _ptr(packed_head), _ptr(x), B, _ptr(argmax),
+                                                      _ptr(margin), _stream()), "goose_lm_head_argmax_static")
 
 
 class GooseContext:

@@ -3,6 +3,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -676,6 +677,85 @@ int goose_verify_step_batched(goose_ctx* c, const goose_model_ptrs* m, const goo
     if (rc) return rc;
   }
   return launch_batch_end(br, n_req, d_argmax_all, d.n_layers, c->n_kv, c->cap, d.head_dim, c->flags, st);
+}
+
+// ---- the LM head without a context: its workspace is a static device array --------------------
+// For callers that cannot allocate (stream capture, serving loops that forbid it): the operand rows
+// and the per-workgroup reductions of goose_lm_head_argmax live in `scratch`, a file-scope device
+// array that every GPU this library runs on holds until the process ends.  Its address is looked up
+// once per device; calls on one device share the array, so calls that overlap there race.
+enum {
+  STATIC_MAX_B = 128,
+  STATIC_MAX_HIDDEN = 8192,
+  STATIC_MAX_VOCAB = 262144,
+  STATIC_XN_BYTES = STATIC_MAX_B * STATIC_MAX_HIDDEN * 2 * 2,              // 16-bit rows, up to two terms
+  STATIC_TOP2_BYTES = STATIC_MAX_B * (STATIC_MAX_VOCAB / 128) * 16,        // one float4 per row and 128-column group
+  STATIC_SCRATCH_BYTES = STATIC_XN_BYTES + STATIC_TOP2_BYTES               // 8 MiB
+};
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+namespace {
+enum { STATIC_MAX_DEVICES = 64 };
+void* g_scratch_ptr[STATIC_MAX_DEVICES] = {};
+std::mutex g_scratch_mutex;
+
+// the current device's copy of `scratch` (each GPU holds its own, at its own address)
+int scratch_for_current_device(unsigned char** out) {
+  int dev = -1;
+  GOOSE_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= STATIC_MAX_DEVICES) return GOOSE_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    GOOSE_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = static_cast<unsigned char*>(g_scratch_ptr[dev]);
+  return GOOSE_OK;
+}
+}  // namespace
+
+int goose_lm_head_argmax_static(const goose_model_desc* desc, const void* d_packed_head, const float* d_x, int B,
+                                int32_t* d_argmax, float* d_margin_or_null, void* stream) {
+  if (!desc || !d_packed_head || !d_x || !d_argmax) return GOOSE_ERR_ARG;
+  const goose_model_desc& d = *desc;
+  if (!is16(d.dtype)) return GOOSE_ERR_SHAPE;
+  if (d.hidden < 8 || (d.hidden % 8) != 0 || d.vocab < 1 || !(d.rms_eps >= 0.0f)) return GOOSE_ERR_ARG;
+  if (d.act_mode != GOOSE_ACT_F16 && d.act_mode != GOOSE_ACT_TWO_TERM) return GOOSE_ERR_ARG;
+  if (B < 1) return GOOSE_ERR_ARG;
+  if (B > STATIC_MAX_B || d.hidden > STATIC_MAX_HIDDEN || d.vocab > STATIC_MAX_VOCAB) return GOOSE_ERR_CAPACITY;
+  // the layout of the packed head and the operand mode, as a context of this description has them (no allocation)
+  goose_ctx t;
+  memset(&t, 0, sizeof(t));
+  t.d = d;
+  t.Kh = round_up(d.hidden, 128);
+  t.Vpad = round_up(d.vocab, 32);
+  t.Hq = d.n_heads * d.head_dim;
+  t.n_kv = d.n_kv_heads > 0 ? d.n_kv_heads : d.n_heads;
+  t.Hkv = t.n_kv * d.head_dim;
+  t.Kq = round_up(t.Hq, 128);
+  t.Fpad = round_up(d.ffn, 128);
+  compute_layouts(&t);
+  const bool two_term = d.act_mode == GOOSE_ACT_TWO_TERM;
+  const int terms = two_term ? 2 : 1;
+  const int act_dtype = two_term ? d.dtype : GOOSE_DTYPE_F16;
+  const float out_scale = (!two_term && d.dtype == GOOSE_DTYPE_BF16) ? 1.0f / 256.0f : 1.0f;
+  if (t.Kh > STATIC_MAX_HIDDEN) return GOOSE_ERR_CAPACITY;
+  unsigned char* base = nullptr;
+  int rc = scratch_for_current_device(&base);
+  if (rc) return rc;
+  void* xn = base;                       // [round_up(B,32) <= 128][Kh * terms] 16-bit
+  void* top2 = base + STATIC_XN_BYTES;   // float4 [B][groups]
+  hipStream_t st = as_stream(stream);
+  const char* w = (const char*)d_packed_head;
+  rc = launch_resid_norm(d.dtype, act_dtype, const_cast<float*>(d_x), d.hidden, nullptr, 0, 0, 0, w + t.ph.gf, d.rms_eps,
+                         xn, t.Kh * terms, terms, B, st);
+  if (rc) return rc;
+  const int lm_nw = 4, groups = (t.Vpad / 32 + lm_nw - 1) / lm_nw;
+  rc = launch_gemm_top2_16(act_dtype, xn, t.Kh * terms, terms, w + t.ph.wlm, t.Vpad, t.Kh, B, lm_nw, nullptr, 0, top2,
+                           d.vocab, out_scale, st);
+  if (rc) return rc;
+  return launch_argmax_top2(top2, groups, B, d_argmax, d_margin_or_null, st);
 }
 
 int goose_device_flags(goose_ctx* c, void* stream, int32_t* h_flags_out) {
