@@ -57,6 +57,12 @@ def recorded_traffic(workload):
     return None
 
 
+def cap_for(P0, B, total_steps):
+    """Slots per head of the KV cache for a run of `total_steps` steps from a prefix of P0 (a step commits
+    at most about 20 slots); the launches of a step are sized for cache lengths up to cap - B."""
+    return (P0 + total_steps * 20 + 2 * B + 63) // 64 * 64
+
+
 def make_tree(kind, seed):
     import goose_inputs as gi
     return {"spine_7b": lambda: gi.tree_spine_7b(seed), "spine_13b": gi.tree_spine_13b,
@@ -128,7 +134,7 @@ def main():
     K = args.steps if args.steps is not None else dflt_steps
     W = args.warmup
     total = K + W
-    cap = (P0 + total * 20 + 2 * B + 63) // 64 * 64
+    cap = cap_for(P0, B, total)
     P_max = cap - B
 
     def log(msg):

@@ -232,3 +232,71 @@ def test_single_layer_of_the_larger_shapes(name, B, P0, tree_fn):
     print(f"{name}: step", flush=True)
     _compare_step(shape, gm, om, cache, tokens, tree, TOL[shape.dtype])
     gm.ctx.close()
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("workload,vocab", [
+    ("13b_B80_P2048", 32000),              # 40 heads; also the LM head at the models' real vocabulary
+    ("33b_B80_P4096", 4096),               # 52 heads
+    ("7b_stress_B128_P16384", 4096),       # spine tree of 128 nodes over the longest prefix
+    ("7b_balanced_B128_P16384", 4096),     # balanced control tree, same sizes
+])
+def test_one_layer_at_the_launch_shapes_of_the_larger_workloads(workload, vocab):
+    """The attention and projection launch shapes the other benchmark workloads really take (full B, full
+    prefix length, the benchmark's cache capacity), on a one-layer model of the same widths: every output
+    element by element against the oracle, through the individual entry points (launches sized by the
+    host's cache length) and through goose_verify_step as the benchmark replays it (sized by cap - B)."""
+    import dataclasses
+    import bench
+    shape_name, B, P0, tree_kind, steps = bench.WORKLOADS[workload]
+    shape = dataclasses.replace(gi.SHAPES[shape_name], name=f"{workload}_1layer", n_layers=1, vocab=vocab)
+    tol = TOL[shape.dtype]
+    cap = bench.cap_for(P0, B, steps + 5)
+    dev = torch.device("cuda:0")
+    tm = torch_model(shape, seed=4, gain_jitter=0.1, device="cuda:0")
+    tm = {k: ([{n: t.cpu() for n, t in lw.items()} for lw in v] if k == "layers" else v.cpu()) for k, v in tm.items()}
+    om = oracle_model(shape, tm)
+    gm = gpu_model(shape, tm, max_B=B, cap=cap)
+    prefix = gi.prefix_tokens(21, P0, shape.vocab)
+    print(f"{workload}: prefill of {P0} tokens on the device", flush=True)
+    last = _gpu_prefill(gm, prefix, B)
+    root = int(last["argmax"][-1].item())
+    tree = bench.make_tree(tree_kind, 0)
+    assert tree.B == B
+    cont = _lookahead(gm, root, 8)
+    tokens = gi.draft_tokens_uniform(22, tree.parent, shape.vocab, root)
+    tokens = gi.plant_drafts(23, tree.parent, tree.is_spine, tokens, cont, shape.vocab,
+                             p_spine=0.9, p_branch=0.8, p_grand=0.8)
+    cache = device_cache_as_oracle(gm, P0)          # the stored prefix is an input of both sides
+    print(f"{workload}: step through the individual entry points", flush=True)
+    g, o, decisive = _compare_step(shape, gm, om, cache, tokens, tree, tol)
+
+    print(f"{workload}: the same step through goose_verify_step, launches sized for P <= {cap - B}", flush=True)
+    gm.set_P(P0)
+    t, p, s = gm.stage_tree(tokens, tree.parent, tree.is_spine)
+    logits = torch.empty((B, shape.vocab), dtype=torch.float32, device=dev)
+    margin = torch.empty(128, dtype=torch.float32, device=dev)
+    gm.verify_step_fused(t, p, s, B, cap - B, logits=logits, margin=margin)
+    torch.cuda.synchronize()
+    gl = logits.double().cpu().numpy()
+    scale = np.abs(o["logits"]).max()
+    err = np.abs(gl - o["logits"]).max()
+    print(f"{workload}: max logit error {err / scale:.2e} of the logit scale", flush=True)
+    assert err <= tol * scale
+    am = gm.argmax[:B].cpu().numpy()
+    assert np.array_equal(am, np.argmax(gl, axis=-1))
+    safe = o["margin"] > 2 * tol * scale
+    assert np.array_equal(am[safe], o["x_hat"][safe])
+    acc, bonus = orc.greedy_walk(tree.parent, tokens, tree.is_spine, am)
+    L = len(acc)
+    assert int(gm.accept_len.item()) == L and int(gm.bonus.item()) == bonus
+    assert int(gm.d_P.item()) == P0 + L + 1
+    # the committed rows are the new K/V rows of the accepted path
+    idx = np.asarray([0] + acc)
+    k_new, v_new = o["new_kv"][0]
+    gk = gm.k_rows(P0, P0 + L + 1)[0].double().cpu().numpy()
+    gv = gm.v_rows(P0, P0 + L + 1)[0].double().cpu().numpy()
+    assert np.abs(gk - k_new[:, idx]).max() <= tol * np.abs(k_new).max()
+    assert np.abs(gv - v_new[:, idx]).max() <= tol * np.abs(v_new).max()
+    assert gm.ctx.goose_device_flags() == 0
+    gm.ctx.close()
