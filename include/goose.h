@@ -352,7 +352,8 @@ int goose_pack_matrix(const void* d_w, int N, int K, void* d_packed, void* strea
 int goose_gemm_packed(int dtype, const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, int ksplit,
                       float* d_partials, void* stream);
 /* Same product with the fused SwiGLU epilogue: the N rows of W (N a multiple of 64) alternate in blocks
- * of 32 between gate rows and up rows; d_h 16-bit [B][ldh] receives silu(gate) * up, N/2 columns. */
+ * of 32 between gate rows and up rows; d_h 16-bit [B][ldh] (ldh even, d_h 4-byte aligned) receives
+ * silu(gate) * up, N/2 columns. */
 int goose_gemm_swiglu_packed(int dtype, const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, void* d_h,
                              int ldh, void* stream);
 /* The same two products as the decoder layers run them.

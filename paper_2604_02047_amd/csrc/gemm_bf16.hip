@@ -118,6 +118,8 @@ __global__ __launch_bounds__(256) void k_pack_bf16(int mode, const bf16_t* __res
 // grid in an XCD-aware order, ordinary loads so that the chunks share the L2); otherwise the
 // weights are read once by the whole grid, with non-temporal loads that keep them from displacing
 // the L2's other lines.  F16: fp16 instead of bf16 operands (and SwiGLU output).
+// word 3 of a raw buffer descriptor on this target (32-bit untyped data, range checking on the byte offset)
+#define GOOSE_BUFFER_WORD3 0x00020000
 #define GOOSE_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }  // s_waitcnt vmcnt(n) only
 
@@ -139,19 +141,36 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
   constexpr int COPIES = MT * 32 / ROWS_PER_COPY;
   constexpr int CPW = COPIES / NWAVES;                 // copy instructions per wavefront per stage
   static_assert(COPIES % NWAVES == 0, "the A copy must divide evenly over the wavefronts");
-  constexpr int SWAP_BYTES = (EPI == EPI_SWIGLU) ? (NW / 2) * MT * 16 * 64 * 4 : 0;
+  // SwiGLU: a gate tile and its up tile meet in LDS as fp32 (two wavefronts' accumulators each)
+  constexpr int SWAP_BYTES = (EPI == EPI_SWIGLU) ? NW * MT * 16 * 64 * 4 : 0;
   constexpr int CT_ROW = 33;  // floats per row of a transposed-read C tile (odd: conflict-free row scans)
   constexpr int TOP2_BYTES = (EPI == EPI_TOP2) ? NW * MT * 32 * (CT_ROW * 4 + 16) : 0;
   constexpr int EPI_BYTES = SWAP_BYTES > TOP2_BYTES ? SWAP_BYTES : TOP2_BYTES;
   constexpr int TAIL_BYTES = EPI_BYTES;
-  // Two buffers as two separate arrays: the compiler then knows that the copy into one does not
-  // touch what is read from the other (with one array it makes every operand read wait for the copy
-  // just issued, i.e. for all loads in flight).  The epilogues reuse the first.
+  // Ring depth D: every wavefront keeps D stages of its weight pieces in flight in registers and the
+  // workgroup D stages of A in LDS.
+#ifndef GOOSE_RING_MAX
+#define GOOSE_RING_MAX 2
+#endif
+  constexpr int LDS_BUDGET = 144 * 1024;
+  constexpr int D_FIT = (LDS_BUDGET - (TAIL_BYTES > STAGE_BYTES ? TAIL_BYTES - STAGE_BYTES : 0)) / STAGE_BYTES;
+  constexpr int D = D_FIT >= GOOSE_RING_MAX ? GOOSE_RING_MAX : (D_FIT < 2 ? 2 : D_FIT);
+  static_assert(D >= 2 && D <= 4, "ring depth");
+  // The buffers are separate arrays: the compiler then knows that the copy into one does not touch
+  // what is read from another (with one array it makes every operand read wait for the copy just
+  // issued, i.e. for all loads in flight).  The epilogues reuse the first.
   constexpr int LDS0_BYTES = STAGE_BYTES > TAIL_BYTES ? STAGE_BYTES : TAIL_BYTES;
-  static_assert(LDS0_BYTES + STAGE_BYTES <= 160 * 1024, "LDS of one compute unit");
+  static_assert(LDS0_BYTES + (D - 1) * STAGE_BYTES <= 160 * 1024, "LDS of one compute unit");
   __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS0_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char lds1[STAGE_BYTES];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __shared__ __attribute__((aligned(1024))) unsigned char lds2[D > 2 ? STAGE_BYTES : 16];
+  __shared__ __attribute__((aligned(1024))) unsigned char lds3[D > 3 ? STAGE_BYTES : 16];
+  auto lds_buf = [&](auto buf_c) -> unsigned char* {
+    constexpr int b = decltype(buf_c)::value;
+    return b == 0 ? lds : (b == 1 ? lds1 : (b == 2 ? lds2 : lds3));
+  };
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // (in a scalar register: it selects buffer descriptors)
   const int wt = wave;  // this wavefront's column tile
   // Work item = (column-tile group bx, split-K range by, row chunk of MT*32 rows).  One chunk: the
   // plain 2-D grid.  Several chunks: a 1-D grid; workgroups are dealt to the 8 XCDs round-robin in
@@ -178,7 +197,6 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
   const int s_begin = by * stages_per_split;
   const int s_end = min(s_begin + stages_per_split, nstages_total);
   const int nst = s_end - s_begin;
-  const int s0 = s_begin;
 
   f32x16 acc[MT];
 #pragma unroll
@@ -186,6 +204,14 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
 
+  // Code that runs once per workgroup is fetched from memory at a few tens of nanoseconds per 64
+  // bytes (the instruction cache starts every launch cold), which at these launch lengths costs as
+  // much as the data.  So there is ONE loop body for every stage -- no separate prologue, tail or
+  // short-range variants: loads that fall outside the K range are issued all the same and made
+  // harmless.  The weights are read through a buffer descriptor that covers exactly this
+  // wavefront's pieces of its K range: a load beyond it returns zeros without touching memory; the A
+  // copy of a stage beyond the range re-reads the last stage (it meets zero weights).  The stages
+  // computed are rounded up to a multiple of D.
   // ---- this wavefront's share of the A copy: copy instruction c of the stage fills rows
   // c*ROWS_PER_COPY ..; lane i fetches the unit that belongs at position i % SU of row i / SU
   // (swizzled, see above)
@@ -200,25 +226,32 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
                (size_t)s_begin * SU + unit;
   }
   auto copy_a = [&](int i, auto buf_c) {  // stage i -> LDS buffer buf
-    constexpr int buf = decltype(buf_c)::value;
+    const int ic = min(i, nst - 1);
 #pragma unroll
     for (int q = 0; q < CPW; ++q) {
       const int c = wave * CPW + q;  // (wavefront-uniform)
-      unsigned char* dst = (buf ? lds1 : lds) + c * 1024;
+      unsigned char* dst = lds_buf(buf_c) + c * 1024;
 #if defined(__HIP_DEVICE_COMPILE__)  // (the host pass knows no such builtin and would silently drop the kernel's stub)
-      __builtin_amdgcn_global_load_lds(a_src[q] + (size_t)i * SU, GOOSE_LDS_PTR(dst), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(a_src[q] + (size_t)ic * SU, GOOSE_LDS_PTR(dst), 16, 0, 0);
 #else
       (void)dst;
 #endif
     }
   };
-  u32x4 wreg[2][STEPS];
-  const u32x4* wbase = Wp + (size_t)tile_ld * ksteps_total * 64 + (size_t)s0 * STEPS * 64 + lane;
-  auto load_w = [&](int i, auto slot_c) {
+  u32x4 wreg[D][STEPS];
+#if defined(__HIP_DEVICE_COMPILE__)
+  const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<u32x4*>(Wp + ((size_t)tile_ld * ksteps_total + (size_t)s_begin * STEPS) * 64), 0,
+      (nst > 0 ? nst : 0) * STEPS * 1024, GOOSE_BUFFER_WORD3);
+#endif
+  const int w_lane = lane * 16;
+  auto load_w = [&](int i, auto slot_c) {  // (beyond the range: zeros, no memory traffic)
     constexpr int slot = decltype(slot_c)::value;
-    const u32x4* p = wbase + (size_t)i * STEPS * 64;
+#if defined(__HIP_DEVICE_COMPILE__)
 #pragma unroll
-    for (int s = 0; s < STEPS; ++s) wreg[slot][s] = STREAM ? __builtin_nontemporal_load(p + s * 64) : p[s * 64];
+    for (int s = 0; s < STEPS; ++s)
+      wreg[slot][s] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, w_lane, (i * STEPS + s) * 1024, STREAM ? 2 : 0);
+#endif
   };
   // operand reads: lane l holds row l % 32 (of row tile mt) and the eight inputs 8*(l/32).. of a k-step
   const int a_row = (lane & 31) * ROW_BYTES, a_x = lane & 15, a_hh = lane >> 5;
@@ -227,91 +260,105 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
   };
-  // one stage (slot = i % 2, compile-time so that no register array is indexed dynamically; the
-  // LDS buffer alternates with it)
-  auto stage = [&](auto slot_c, int i, auto next_a, auto refill) {
-    constexpr int slot = decltype(slot_c)::value, buf = slot;
-    const unsigned char* abuf = buf ? lds1 : lds;
-    if (next_a) copy_a(i + 1, std::integral_constant<int, buf ^ 1>());  // (its readers passed the barrier that ended stage i-1)
+  // Loads complete in order as far as the wait counter goes.  Stage j issues, in this order, the A copy
+  // of stage j+D-1 (into the buffer whose readers passed the barrier that ended stage j-1) and, one
+  // after each k-step's matrix instructions, the refills of its own register slot with the weights
+  // of stage j+D.  Before the barrier that ends stage j the A copy of stage j+1 must have landed; the
+  // STEADY_WAIT loads issued after that copy may stay in flight.
+  constexpr int STEADY_WAIT = (D - 2) * (STEPS + CPW) + STEPS;
+  static_assert(STEADY_WAIT <= 63, "wait counter");
+  // The operand reads of a k-step are issued PD k-steps ahead of the matrix instructions that use
+  // them (a compute unit runs one wavefront per SIMD here, so nothing else hides the LDS latency).
+  constexpr int MPS = MT * TERMS;                                   // matrix instructions per k-step
+  constexpr int PD = MPS >= 4 ? 1 : (MPS >= 2 ? 2 : 4), NB = PD + 1;
+  // one stage (slot = i % D, compile-time so that no register array is indexed dynamically; the
+  // LDS buffer goes with it)
+  auto stage = [&](auto slot_c, int i) {
+    constexpr int slot = decltype(slot_c)::value;
+    const unsigned char* abuf = lds_buf(slot_c);
+    copy_a(i + D - 1, std::integral_constant<int, (slot + D - 1) % D>());
     __builtin_amdgcn_sched_barrier(0);   // keep the issue order: the scheduler would sink these loads
-    const u32x4* pn = wbase + (size_t)(i + 2) * STEPS * 64;
-#pragma unroll
-    for (int s = 0; s < STEPS; ++s) {
-      const op8 b = __builtin_bit_cast(op8, wreg[slot][s]);
-      // (terms outside, row tiles inside: consecutive matrix instructions then go to different
-      // accumulators instead of waiting for each other; every accumulator still takes hi before lo)
+    op8 af[NB][TERMS][MT];
+    auto read_a = [&](int s, op8 (&dst)[TERMS][MT]) {
 #pragma unroll
       for (int t = 0; t < TERMS; ++t) {
         const int unit = (2 * s + a_hh) * TERMS + t;
         const int pos = (unit & ~15) | ((unit ^ a_x) & 15);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          const op8 a = *reinterpret_cast<const op8*>(&abuf[mt * 32 * ROW_BYTES + a_row + pos * 16]);
-          acc[mt] = Mma16<F16>::mfma(a, b, acc[mt]);
-        }
+        for (int mt = 0; mt < MT; ++mt)
+          dst[t][mt] = *reinterpret_cast<const op8*>(&abuf[mt * 32 * ROW_BYTES + a_row + pos * 16]);
       }
-      if (refill) wreg[slot][s] = STREAM ? __builtin_nontemporal_load(pn + s * 64) : pn[s * 64];
+    };
+#pragma unroll
+    for (int s = 0; s < PD; ++s) read_a(s, af[s % NB]);
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+      if (s + PD < STEPS) read_a(s + PD, af[(s + PD) % NB]);
+      const op8 b = __builtin_bit_cast(op8, wreg[slot][s]);
+      // (terms outside, row tiles inside: consecutive matrix instructions then go to different
+      // accumulators instead of waiting for each other; every accumulator still takes hi before lo)
+#pragma unroll
+      for (int t = 0; t < TERMS; ++t)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt] = Mma16<F16>::mfma(af[s % NB][t][mt], b, acc[mt]);
+#if defined(__HIP_DEVICE_COMPILE__)
+      wreg[slot][s] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, w_lane, ((i + D) * STEPS + s) * 1024, STREAM ? 2 : 0);
+#endif
       __builtin_amdgcn_sched_barrier(0);
     }
-    // the next stage's A (issued above, before this stage's weight refills) must have landed in
-    // LDS before anyone reads it; the STEPS refills issued after it may stay in flight
-    if (next_a) {
-      if (refill) __builtin_amdgcn_s_waitcnt(vmcnt_imm(STEPS));
-      else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(STEADY_WAIT));
     barrier();
   };
-  const std::true_type yes;
   const std::integral_constant<int, 0> c0;
   const std::integral_constant<int, 1> c1;
+  const std::integral_constant<int, 2> c2;
+  const std::integral_constant<int, 3> c3;
 
   if (nst > 0) {
-    int i = 0;
-    copy_a(0, std::integral_constant<int, 0>());
-    if (nst >= 4) {
-      // long range: both slots are filled unconditionally, so that the compiler's wait counts at
-      // the loop head are exact (it merges all paths into the loop, and a path with fewer loads
-      // in flight would make every iteration drain the ring)
-      load_w(0, c0);
-      load_w(1, c1);
-      // stage 0 of both streams has arrived, stage 1 of the weights is in flight: the state every
-      // stage below starts from.  (The compiler counts the copies to LDS and the register loads as
-      // two kinds that may overtake each other, and falls back to waiting for ALL loads wherever it
-      // has to wait for one with both kinds pending; so the waits are placed here and before each
-      // barrier by hand, and inside a stage everything it consumes is known to be there.)
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(STEPS));
-      barrier();
-      for (; i + 3 < nst; i += 2) {  // steady state: no conditionals inside
-        stage(c0, i, yes, yes);
-        stage(c1, i + 1, yes, yes);
-      }
-    } else {
-      load_w(0, c0);
-      if (nst > 1) load_w(1, c1);
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-      barrier();
+    // the ring is filled in the order the stages themselves would have issued these loads, so that
+    // one wait count fits the whole loop
+    load_w(0, c0);
+    copy_a(0, c0);
+    load_w(1, c1);
+    if constexpr (D > 2) { copy_a(1, c1); load_w(2, c2); }
+    if constexpr (D > 3) { copy_a(2, c2); load_w(3, c3); }
+    // stage 0 of both streams has arrived, later stages are in flight: the state every stage
+    // starts from.  (The compiler counts the copies to LDS and the register loads as two kinds that
+    // may overtake each other, and falls back to waiting for ALL loads wherever it has to wait for
+    // one with both kinds pending; so the waits are placed here and before each barrier by hand, and
+    // inside a stage everything it consumes is known to be there.)
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(STEADY_WAIT));
+    barrier();
+    for (int i = 0; i < nst; i += D) {
+      stage(c0, i);
+      stage(c1, i + 1);
+      if constexpr (D > 2) stage(c2, i + 2);
+      if constexpr (D > 3) stage(c3, i + 3);
     }
-    for (; i < nst; ++i) {  // the last stages (i is even on entry)
-      const bool na = (i + 1) < nst, rf = (i + 2) < nst;
-      if ((i & 1) == 0) stage(c0, i, na, rf);
-      else stage(c1, i, na, rf);
-    }
+    // the copies issued by the last stages still target the LDS buffers that the epilogues reuse
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    barrier();
   }
-
   const bool writer = active;
 
   // C layout of the 32x32 MFMA: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
   if (EPI == EPI_PARTIAL) {
     if (!writer) return;
-    float* o = reinterpret_cast<float*>(out) + by * split_stride;
+    // through a buffer descriptor over rows [0, B) of this split's slab: stores to rows >= B fall
+    // outside it and are dropped, so no store needs a branch or an address computation of its own
     const int col = tile * 32 + (lane & 31);
+#if defined(__HIP_DEVICE_COMPILE__)
+    const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<float*>(out) + by * split_stride, 0, (int)((size_t)B * ldo * 4), GOOSE_BUFFER_WORD3);
+    const int ldo4 = (int)ldo * 4;
+    const int voff = (row_base + 4 * (lane >> 5)) * ldo4 + col * 4;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = row_base + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row < B) o[(size_t)row * ldo + col] = acc[mt][r] * out_scale;
-      }
+      for (int r = 0; r < 16; ++r)
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, acc[mt][r] * out_scale), orsrc, voff,
+                                              (mt * 32 + 8 * (r >> 2) + (r & 3)) * ldo4, 0);
+#endif
   } else if (EPI == EPI_TOP2) {
     constexpr int ROWS = MT * 32;
     float* o = reinterpret_cast<float*>(out);
@@ -356,36 +403,49 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
       }
     }
   } else {  // EPI_SWIGLU
-    float* swap = reinterpret_cast<float*>(lds) + (size_t)(wt >> 1) * MT * 16 * 64;
-    if (writer && (wt & 1)) {
+    // Every wavefront leaves its accumulators in LDS (register r of lane l at [r][l]); then the two
+    // wavefronts of a gate/up pair share the pair's elements, two neighbouring columns per lane, in
+    // a short loop (compact code; the 16-bit results leave as 4-byte stores).
+    constexpr int TILE_F = MT * 16 * 64;  // floats of one wavefront's accumulators
+    float* mine = reinterpret_cast<float*>(lds) + (size_t)wt * TILE_F;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) swap[(mt * 16 + r) * 64 + lane] = acc[mt][r] * out_scale;
-    }
+      for (int r = 0; r < 16; ++r) mine[(mt * 16 + r) * 64 + lane] = acc[mt][r] * out_scale;
     __syncthreads();
-    if (writer && !(wt & 1)) {
+    const int gate_tile = tile & ~1;  // (a pair never straddles the last tile: the tile count is even)
+    if (gate_tile + 1 < ntiles) {
+      const float* gt = reinterpret_cast<const float*>(lds) + (size_t)(wt & ~1) * TILE_F;
+      const float* ut = gt + TILE_F;
       T* hq = reinterpret_cast<T*>(out);
-      const int col = (tile >> 1) * 32 + (lane & 31);
-      // position of column `col` in a row of TERMS terms (two terms: groups of eight hi values, then their lo values)
-      const size_t cpos = TERMS == 1 ? (size_t)col : (size_t)(col >> 3) * 16 + (col & 7);
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = row_base + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          const float g = acc[mt][r] * out_scale, u = swap[(mt * 16 + r) * 64 + lane];
-          float hval = g / (1.0f + __expf(-g)) * u;
-          if (F16 && fabsf(hval) > 65504.0f) {  // beyond fp16: clamp, and say so (GOOSE_FLAG_RANGE)
-            hval = copysignf(65504.0f, hval);
-            if (flags != nullptr && row < B) atomicOr(flags, GOOSE_FLAG_RANGE);
-          }
-          if (row < B) {
-            const T hi = (T)hval;
-            hq[(size_t)row * ldo + cpos] = hi;
-            if (TERMS == 2) hq[(size_t)row * ldo + cpos + 8] = (T)(hval - (float)hi);
+      const int half = (wt & 1) * 64 + lane;  // 0..127 within the pair
+      bool clamped = false;
+      for (int e = half; e < MT * 16 * 32; e += 128) {
+        const int l2 = (e & 31) * 2, rr = (e >> 5) & 15, mt = e >> 9;  // lane pair, register, row tile
+        const int row = row_base + mt * 32 + 8 * (rr >> 2) + 4 * (l2 >> 5) + (rr & 3);
+        const int col = (gate_tile >> 1) * 32 + (l2 & 31);
+        const float2 g = *reinterpret_cast<const float2*>(&gt[(mt * 16 + rr) * 64 + l2]);
+        const float2 u = *reinterpret_cast<const float2*>(&ut[(mt * 16 + rr) * 64 + l2]);
+        float h0 = swiglu_f32(g.x, u.x), h1 = swiglu_f32(g.y, u.y);
+        if (F16) {  // beyond fp16: clamp, and say so (GOOSE_FLAG_RANGE)
+          if (fabsf(h0) > 65504.0f) { h0 = copysignf(65504.0f, h0); clamped = clamped || row < B; }
+          if (fabsf(h1) > 65504.0f) { h1 = copysignf(65504.0f, h1); clamped = clamped || row < B; }
+        }
+        if (row < B) {
+          // position of column `col` in a row of TERMS terms (two terms: groups of eight hi values, then their lo values)
+          const size_t cpos = TERMS == 1 ? (size_t)col : (size_t)(col >> 3) * 16 + (col & 7);
+          const T a0 = (T)h0, a1 = (T)h1;
+          T* dst = hq + (size_t)row * ldo + cpos;
+          union { T t[2]; unsigned u; } pk;
+          pk.t[0] = a0; pk.t[1] = a1;
+          *reinterpret_cast<unsigned*>(dst) = pk.u;
+          if (TERMS == 2) {
+            pk.t[0] = (T)(h0 - (float)a0); pk.t[1] = (T)(h1 - (float)a1);
+            *reinterpret_cast<unsigned*>(dst + 8) = pk.u;
           }
         }
+      }
+      if (F16 && clamped && flags != nullptr) atomicOr(flags, GOOSE_FLAG_RANGE);
     }
   }
 }

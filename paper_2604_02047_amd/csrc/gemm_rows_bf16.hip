@@ -211,7 +211,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const typename Mma16<F16>
       for (int r = 0; r < 16; ++r) {
         const int row = row_base + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         const float g = acc[mt][0][r] * out_scale, u = acc[mt][1][r] * out_scale;
-        float hval = g / (1.0f + __expf(-g)) * u;
+        float hval = swiglu_f32(g, u);
         if (F16 && fabsf(hval) > 65504.0f) {  // beyond fp16: clamp, and say so (GOOSE_FLAG_RANGE)
           hval = copysignf(65504.0f, hval);
           if (flags != nullptr && row < B) atomicOr(flags, GOOSE_FLAG_RANGE);

@@ -792,7 +792,7 @@ int goose_gemm_swiglu_packed_ex(int dtype, const void* d_a, int lda, int terms, 
   if (!is16(dtype) || B < 1 || B > GOOSE_MAX_ROWS || (nw != 2 && nw != 4)) return GOOSE_ERR_ARG;
   if (terms != 1 && terms != 2) return GOOSE_ERR_ARG;
   const int Kpad = round_up(K, 128);
-  if (lda < Kpad * terms || (lda % 8) != 0 || ldh < N / 2 * terms) return GOOSE_ERR_ARG;
+  if (lda < Kpad * terms || (lda % 8) != 0 || ldh < N / 2 * terms || (ldh % 2) != 0) return GOOSE_ERR_ARG;
   return launch_gemm_16(dtype, EPI_SWIGLU, d_a, lda, terms, d_packed, N, Kpad, B, nw, 1, d_h, (size_t)ldh, 0, out_scale,
                         nullptr, as_stream(stream));
 }

@@ -151,6 +151,12 @@ enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_TOP2 = 2 };
 // stored in groups of eight inputs, 8 hi values then their 8 lo values; lda = elements per row = terms * K at least.
 // Element offset of input column c in such a row:
 static inline __host__ __device__ size_t term_pos(int terms, int c) { return terms == 1 ? (size_t)c : (size_t)(c >> 3) * 16 + (c & 7); }
+// silu(g) * u = g / (1 + exp(-g)) * u with the hardware exponential and reciprocal (about one ulp each,
+// far inside the 16-bit rounding of the result).  Both projection kernels use this one function, so that
+// a request gets the same bits from either.
+static __device__ __forceinline__ float swiglu_f32(float g, float u) {
+  return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
+}
 // out partials f32 [ksplit][Bpad][ldo] (EPI_PARTIAL) or 16-bit h [Bpad][ldo] in `terms` terms (EPI_SWIGLU, ksplit must be 1).
 // out_scale: an exact power of two applied to every sum before the epilogue uses it (1, or the inverse of
 // the scale of weights re-encoded by launch_pack_16).  flags (or null): GOOSE_FLAG_RANGE is raised when
