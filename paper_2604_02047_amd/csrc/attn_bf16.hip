@@ -104,7 +104,7 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   constexpr int VROW = TROWS * 2 + 16;     // bytes per V^T row in LDS (padded)
   constexpr int TAIL_BYTES = 3 * TROWS * KROW + D * VROW;  // tree keys, tree values, rotated queries (two terms)
   constexpr int OREGS = (D / 32) * 16;                     // accumulator floats per lane
-  constexpr int MERGE_BYTES = (NG / 2) * NQH * (OREGS + 4) * 64 * 4;
+  constexpr int MERGE_BYTES = NG > 1 ? NG * NQH * (OREGS + 4) * 64 * 4 : 0;  // every wavefront's state
   constexpr int LDS_BYTES = TAIL_BYTES > MERGE_BYTES ? TAIL_BYTES : MERGE_BYTES;
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
   unsigned char* Kt = lds;                  // tree keys   [i][c]  (rotated)
@@ -134,17 +134,60 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   const int Hq = n_heads * D, Hkv = n_kv_heads * D;
   const int kcol = Hq + kvh * D - h * D, vcol = kcol + Hkv;  // relative to this head's q columns
   const bool tail_writer = (h % group) == 0;                  // one head of the group stores the tree's K/V
-  int P = *sg.dP;
+  int P = *sg.dP;   // (used further down: the loads below do not wait for it)
+  const bool last = blockIdx.y == gridDim.y - 1;
+  // ---- q of all query tiles (every split), k and v of the tree (last split): sum the split-K
+  // slices, rotate q and k, bf16 into LDS.  One item = 4 columns j0.. and their rotation partners
+  // j0+d/2..: 16 neighbouring lanes read 256 contiguous bytes of a projection row.  The loads of
+  // the first two slices of all of a thread's items are issued together: the buffer was written
+  // by another kernel, so every dependent load is a trip to memory.
+  const int nbt = (B + 31) >> 5;
+  const int rows = nbt * 32;
+  constexpr int NIT = TROWS * (D / 8) / NTHR;
+  static_assert(TROWS * (D / 8) % NTHR == 0 && NIT >= 1, "items must divide over the workgroup");
+  // Items are handled UG at a time.  With at most two per thread (trees of up to 64 nodes) their
+  // loads are issued here, before anything waits for the cache length; larger trees take them two
+  // at a time in a loop further down (registers, and code that runs once is fetched at memory speed).
+  constexpr bool HOLD = NIT <= 2;
+  constexpr int UG = HOLD ? NIT : 2;
+  static_assert(NIT % UG == 0, "item groups");
+  const float* prow[UG];
+  f32x4 acc[UG][6], acc1[UG][6];  // q lo/hi, k lo/hi, v lo/hi of the first / second slice
+  f32x4 c01[UG], c23[UG];         // the rotation angles: cos, sin of columns j0, j0+1 / j0+2, j0+3
+  bool kv[UG];
+  const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  const bool two = ks > 1;
+  auto load_items = [&](int u0) {
+#pragma unroll
+    for (int u = 0; u < UG; ++u) {
+      const int it = tid + (u0 + u) * NTHR;
+      const int i = it / (D / 8), j0 = (it % (D / 8)) * 4;
+      prow[u] = part + (size_t)i * part_ld + h * D + j0;  // row i < Bpad exists in the buffer
+      kv[u] = last && i < B;
+      const float* p1 = prow[u] + part_stride;
+#pragma unroll
+      for (int w = 0; w < 3; ++w) {
+        const bool on = w == 0 || kv[u];
+        const int col = w == 0 ? 0 : (w == 1 ? kcol : vcol);
+        acc[u][2 * w] = on ? *reinterpret_cast<const f32x4*>(prow[u] + col) : zero4;
+        acc[u][2 * w + 1] = on ? *reinterpret_cast<const f32x4*>(prow[u] + col + D / 2) : zero4;
+        acc1[u][2 * w] = (on && two) ? *reinterpret_cast<const f32x4*>(p1 + col) : zero4;
+        acc1[u][2 * w + 1] = (on && two) ? *reinterpret_cast<const f32x4*>(p1 + col + D / 2) : zero4;
+      }
+      c01[u] = *reinterpret_cast<const f32x4*>(cs + (size_t)i * (D / 2) + j0);
+      c23[u] = *reinterpret_cast<const f32x4*>(cs + (size_t)i * (D / 2) + j0 + 2);
+    }
+  };
+  if (HOLD) load_items(0);
   // a cache length the launch was not sized for, or one that leaves no room for the tree: flagged
   // (GOOSE_FLAG_CAPACITY), and clamped so that nothing is indexed outside the cache
   if ((P < 0 || P > sg.P_max || P > cap - B) && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
     atomicOr(flags, GOOSE_FLAG_CAPACITY);
   if (P > cap - B) P = cap - B;
   if (P < 0) P = 0;
-  const bool last = split == nsplit - 1;
 
   // ---- prefix blocks of this split, then of this key group
-  const int nbp = (P + 31) >> 5, nbt = (B + 31) >> 5;
+  const int nbp = (P + 31) >> 5;
   int b_lo, b_hi;
   if (nsplit == 1) {
     b_lo = 0; b_hi = nbp;
@@ -205,47 +248,14 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   // the first block is on its way while q (and the tree's k, v) are prepared
   if (nblk > 0) { fetch_k(0); fetch_v(0); }
 
-  // ---- q of all query tiles (every split), k and v of the tree (last split): sum the split-K
-  // slices, rotate q and k, bf16 into LDS.  One item = 4 columns j0.. and their rotation partners
-  // j0+d/2..: 16 neighbouring lanes read 256 contiguous bytes of a projection row.  The loads of
-  // the first two slices of all of a thread's items are issued together: the buffer was written
-  // by another kernel, so every dependent load is a trip to memory.
-  const int rows = nbt * 32;
-  constexpr int NIT = TROWS * (D / 8) / NTHR;
-  static_assert(TROWS * (D / 8) % NTHR == 0 && NIT >= 1, "items must divide over the workgroup");
-  {
-    const float* prow[NIT];
-    f32x4 acc[NIT][6];  // q lo/hi, k lo/hi, v lo/hi
-    bool kv[NIT];
+  auto finish_items = [&](int u0) {
 #pragma unroll
-    for (int u = 0; u < NIT; ++u) {
-      const int it = tid + u * NTHR;
-      const int i = it / (D / 8), j0 = (it % (D / 8)) * 4;
-      prow[u] = part + (size_t)i * part_ld + h * D + j0;  // row i < Bpad exists in the buffer
-      kv[u] = last && i < B;
-    }
-    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
-    const bool two = ks > 1;
+    for (int u = 0; u < UG; ++u)
 #pragma unroll
-    for (int u = 0; u < NIT; ++u) {
-      const float* p1 = prow[u] + part_stride;
-#pragma unroll
-      for (int w = 0; w < 3; ++w) {
-        const bool on = w == 0 || kv[u];
-        const int col = w == 0 ? 0 : (w == 1 ? kcol : vcol);
-        f32x4 a = on ? *reinterpret_cast<const f32x4*>(prow[u] + col) : zero4;
-        f32x4 b = on ? *reinterpret_cast<const f32x4*>(prow[u] + col + D / 2) : zero4;
-        if (on && two) {
-          a += *reinterpret_cast<const f32x4*>(p1 + col);
-          b += *reinterpret_cast<const f32x4*>(p1 + col + D / 2);
-        }
-        acc[u][2 * w] = a;
-        acc[u][2 * w + 1] = b;
-      }
-    }
+      for (int w = 0; w < 6; ++w) acc[u][w] += acc1[u][w];
     for (int sl = 2; sl < ks; ++sl) {
 #pragma unroll
-      for (int u = 0; u < NIT; ++u) {
+      for (int u = 0; u < UG; ++u) {
         const float* p = prow[u] + sl * part_stride;
 #pragma unroll
         for (int w = 0; w < 3; ++w)
@@ -260,8 +270,8 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
       // per-head RMSNorm of q and k over the head's D columns: the D/8 items of a row sit in
       // neighbouring lanes, so the sum of squares is a short butterfly
 #pragma unroll
-      for (int u = 0; u < NIT; ++u) {
-        const int j0 = ((tid + u * NTHR) % (D / 8)) * 4;
+      for (int u = 0; u < UG; ++u) {
+        const int j0 = ((tid + (u0 + u) * NTHR) % (D / 8)) * 4;
 #pragma unroll
         for (int w = 0; w < 2; ++w) {
           float ss = 0.f;
@@ -280,12 +290,10 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
       }
     }
 #pragma unroll
-    for (int u = 0; u < NIT; ++u) {
-      const int it = tid + u * NTHR;
+    for (int u = 0; u < UG; ++u) {
+      const int it = tid + (u0 + u) * NTHR;
       const int i = it / (D / 8), j0 = (it % (D / 8)) * 4;
-      const f32x4 c01 = *reinterpret_cast<const f32x4*>(cs + (size_t)i * (D / 2) + j0);      // cos,sin of j0, j0+1
-      const f32x4 c23 = *reinterpret_cast<const f32x4*>(cs + (size_t)i * (D / 2) + j0 + 2);  // ... j0+2, j0+3
-      const float co[4] = {c01[0], c01[2], c23[0], c23[2]}, si[4] = {c01[1], c01[3], c23[1], c23[3]};
+      const float co[4] = {c01[u][0], c01[u][2], c23[u][0], c23[u][2]}, si[4] = {c01[u][1], c01[u][3], c23[u][1], c23[u][3]};
       // the query keeps two terms (the scores of a row share the query's rounding error, which
       // therefore does not average out over the keys as the keys' own rounding does)
       op4 rl, rh, rl2, rh2;
@@ -325,6 +333,15 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
           *reinterpret_cast<T*>(Vt + (j0 + D / 2 + e) * VROW + i * 2) = vh4[e];
         }
       }
+    }
+  };
+  if (HOLD) {
+    finish_items(0);
+  } else {
+#pragma unroll 1
+    for (int u0 = 0; u0 < NIT; u0 += UG) {
+      load_items(u0);
+      finish_items(u0);
     }
   }
   __syncthreads();
@@ -460,83 +477,89 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
     if (idx + 1 < total) fetch_v(idx + 1);
   }
 
-  // ---- merge the key groups of a query tile through LDS (pairwise, fixed order)
+  // ---- merge the key groups of a query tile through LDS, in one round: every wavefront leaves its
+  // state there ((m, l), then the accumulator four registers at a time: piece q of lane l at float
+  // 256 q + 4 l), and then owns QPW of the accumulator's register quads: it combines those quads of
+  // all NG groups, in group order, and writes them out.  No wavefront waits for another's sums, and
+  // the output stage is spread over all of them.
+  constexpr int QUADS = (D / 32) * 4, QPW = QUADS / NG;
+  static_assert(QUADS % NG == 0, "register quads must divide over the key groups");
+  f32x4 res[QPW];
+  float l_sum = l_run;
   if (NG > 1) {
     __syncthreads();  // every wavefront is done with the tree and query buffers
     float* mbuf = reinterpret_cast<float*>(lds);
-    // a wavefront's state as 16-byte pieces, piece q of lane l at float 256*q + 4*l: (m, l, -, -), then
-    // the accumulator four registers at a time
-    constexpr int WFLOATS = (OREGS + 4) * 64;
+    constexpr int WFLOATS = (QUADS + 1) * 256;
+    {
+      float* dst = mbuf + (size_t)(qh * NG + g) * WFLOATS + lane * 4;
+      *reinterpret_cast<f32x4*>(dst) = f32x4{m_run, l_run, 0.f, 0.f};
 #pragma unroll
-    for (int half = NG / 2; half >= 1; half >>= 1) {
-      if (g >= half && g < 2 * half) {
-        float* dst = mbuf + (size_t)(qh * (NG / 2) + (g - half)) * WFLOATS + lane * 4;
-        *reinterpret_cast<f32x4*>(dst) = f32x4{m_run, l_run, 0.f, 0.f};
+      for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-          for (int a = 0; a < 4; ++a)
-            *reinterpret_cast<f32x4*>(dst + 256 * (1 + dt * 4 + a)) =
-                f32x4{oacc[dt][a * 4], oacc[dt][a * 4 + 1], oacc[dt][a * 4 + 2], oacc[dt][a * 4 + 3]};
-      }
-      __syncthreads();
-      if (g < half) {
-        const float* src = mbuf + (size_t)(qh * (NG / 2) + g) * WFLOATS + lane * 4;
-        const f32x4 ml = *reinterpret_cast<const f32x4*>(src);
-        const float mo = ml[0], lo = ml[1];
-        const float m_new = fmaxf(m_run, mo);
-        const float a = __builtin_amdgcn_exp2f(m_run - m_new), b = __builtin_amdgcn_exp2f(mo - m_new);
-        m_run = m_new;
-        l_run = l_run * a + lo * b;
-#pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-          for (int q4 = 0; q4 < 4; ++q4) {
-            const f32x4 o4 = *reinterpret_cast<const f32x4*>(src + 256 * (1 + dt * 4 + q4));
-#pragma unroll
-            for (int e = 0; e < 4; ++e) oacc[dt][q4 * 4 + e] = oacc[dt][q4 * 4 + e] * a + o4[e] * b;
-          }
-      }
-      if (half > 1) __syncthreads();
+        for (int a = 0; a < 4; ++a)
+          *reinterpret_cast<f32x4*>(dst + 256 * (1 + dt * 4 + a)) =
+              f32x4{oacc[dt][a * 4], oacc[dt][a * 4 + 1], oacc[dt][a * 4 + 2], oacc[dt][a * 4 + 3]};
     }
+    __syncthreads();
+    const float* src = mbuf + (size_t)(qh * NG) * WFLOATS + lane * 4;
+    float mj[NG], lj[NG];
+    float m_all = NEG_BIG;
+#pragma unroll
+    for (int j = 0; j < NG; ++j) {
+      const f32x4 ml = *reinterpret_cast<const f32x4*>(src + (size_t)j * WFLOATS);
+      mj[j] = ml[0];
+      lj[j] = ml[1];
+      m_all = fmaxf(m_all, mj[j]);
+    }
+    l_sum = 0.f;
+#pragma unroll
+    for (int q = 0; q < QPW; ++q) res[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < NG; ++j) {
+      const float w = __builtin_amdgcn_exp2f(mj[j] - m_all);
+      l_sum += w * lj[j];
+#pragma unroll
+      for (int q = 0; q < QPW; ++q)
+        res[q] += w * *reinterpret_cast<const f32x4*>(src + (size_t)j * WFLOATS + 256 * (1 + g * QPW + q));
+    }
+    m_run = m_all;
+  } else {
+#pragma unroll
+    for (int q = 0; q < QPW; ++q)
+      res[q] = f32x4{oacc[q >> 2][(q & 3) * 4], oacc[q >> 2][(q & 3) * 4 + 1], oacc[q >> 2][(q & 3) * 4 + 2],
+                     oacc[q >> 2][(q & 3) * 4 + 3]};
   }
-  if (g != 0) return;
 
-  // ---- output: C layout of O^T, register r of lane (q, hh) is d = dt*32 + 8*(r/4) + 4*hh + r%4
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  // ---- output: C layout of O^T, register r of lane (q, hh) is d = dt*32 + 8*(r/4) + 4*hh + r%4;
+  // quad (dt, a) = registers 4a .. 4a+3 of block dt = columns dt*32 + a*8 + hh*4 ..
+  const float l_tot = l_sum + __shfl_xor(l_sum, 32, 64);
   if (qi >= B) return;
   if (nsplit == 1) {
     const float inv = 1.0f / l_tot;
     unsigned short* orow = o_out + (size_t)qi * ldo;
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
+    for (int q = 0; q < QPW; ++q) {
+      const int quad = g * QPW + q;
+      u16x4 v, v2;
 #pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        u16x4 v, v2;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float f = oacc[dt][a * 4 + e] * inv;
-          v[e] = out_bits16(f, o_f16);
-          v2[e] = out_bits16(f - out_back16(v[e], o_f16), o_f16);
-        }
-        unsigned short* dst = orow + term_pos(oterms, h * D + dt * 32 + a * 8 + hh * 4);  // four columns inside one group of eight
-        *reinterpret_cast<u16x4*>(dst) = v;
-        if (oterms == 2) *reinterpret_cast<u16x4*>(dst + 8) = v2;
+      for (int e = 0; e < 4; ++e) {
+        const float f = res[q][e] * inv;
+        v[e] = out_bits16(f, o_f16);
+        v2[e] = out_bits16(f - out_back16(v[e], o_f16), o_f16);
       }
+      unsigned short* dst = orow + term_pos(oterms, h * D + quad * 8 + hh * 4);  // four columns inside one group of eight
+      *reinterpret_cast<u16x4*>(dst) = v;
+      if (oterms == 2) *reinterpret_cast<u16x4*>(dst + 8) = v2;
+    }
   } else {
     const size_t base = ((size_t)h * nsplit + split) * Bpad + row0 + qi;
-    if (hh == 0) {
+    if (hh == 0 && g == 0) {
       att_ml[base * 2] = m_run;
       att_ml[base * 2 + 1] = l_tot;
     }
     float* orow = att_o + base * D;
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        f32x4 v = {oacc[dt][a * 4], oacc[dt][a * 4 + 1], oacc[dt][a * 4 + 2], oacc[dt][a * 4 + 3]};
-        *reinterpret_cast<f32x4*>(orow + dt * 32 + a * 8 + hh * 4) = v;
-      }
+    for (int q = 0; q < QPW; ++q) *reinterpret_cast<f32x4*>(orow + (g * QPW + q) * 8 + hh * 4) = res[q];
   }
 }
 

@@ -509,19 +509,30 @@ int launch_pack_16(int mode, const void* s0, const void* s1, const void* s2, int
   return goose_launch_status();
 }
 
-// Workgroup width (wavefronts = column tiles per workgroup) and split-K factor for a shape.
-// Measured on MI355X: the stream wants about 768 wavefronts in flight; every extra split costs an
-// fp32 tile written and re-read (and flushed at the kernel boundary), so take the smallest power of
-// two that reaches it, with every split at least 4 stages long; the 4-wide workgroup (more sharing
-// of the staged A block) whenever it leaves enough workgroups.
-void pick_gemm_config(int Npad, int Kpad, int max_ksplit, int* nw_out, int* ksplit_out) {
+// Workgroup width (wavefronts = column tiles per workgroup) and split-K factor for a shape, for a
+// context whose passes have up to max_rows rows (a property of the context, not of the call: the
+// split decides the order of the sums, and a request must get the same bits at any batch size).
+// Measured on MI355X: the stream wants 160 or more four-wavefront workgroups; every extra split
+// costs an fp32 tile written and re-read by the residual kernel, which is bound by how fast 64-128
+// workgroups can pull those slices.  So: the smallest power of two of splits that reaches the
+// workgroup count, every split at least 4 stages long.  With at most two row tiles (64 rows) half
+// the splits of two-wavefront workgroups stream as fast when that still gives 256 workgroups (the
+// 7B O and down projections: 4 splits instead of 8, and a microsecond less in each residual
+// kernel); with more rows the narrower workgroup's extra copies of the A block cost more than that.
+void pick_gemm_config(int Npad, int Kpad, int max_ksplit, int max_rows, int* nw_out, int* ksplit_out) {
   const int ntiles = Npad / 32, nstages = Kpad / KGRAN;
-  const int want = (768 + ntiles - 1) / ntiles;
+  const int groups4 = (ntiles + 3) / 4, groups2 = (ntiles + 1) / 2;
+  auto allowed = [&](int ks) {
+    return ks == 1 || (ks <= nstages / 4 && ks <= max_ksplit && ((nstages + ks - 1) / ks) * (ks - 1) < nstages);
+  };
   int ks = 1;
-  while (ks < want) ks *= 2;
-  while (ks > 1 && (ks > nstages / 4 || ks > max_ksplit)) ks /= 2;
-  while (ks > 1 && ((nstages + ks - 1) / ks) * (ks - 1) >= nstages) --ks;  // no empty split
-  *nw_out = (((ntiles + 3) / 4) * ks >= 160) ? 4 : 2;
+  while (groups4 * ks < 160 && allowed(ks * 2)) ks *= 2;
+  int nw = groups4 * ks >= 160 ? 4 : 2;
+  if (nw == 4 && ks >= 2 && max_rows <= 64 && groups2 * (ks / 2) >= 256) {
+    ks /= 2;
+    nw = 2;
+  }
+  *nw_out = nw;
   *ksplit_out = ks;
 }
 

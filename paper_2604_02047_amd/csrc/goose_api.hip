@@ -120,7 +120,7 @@ int check_tree_args(const goose_ctx* ctx, int B, int P) {
 struct GemmCfg { int nw, ks; };
 GemmCfg gemm_cfg(const goose_ctx* c, const char* env_name, int Npad, int Kpad) {
   GemmCfg g;
-  pick_gemm_config(Npad, Kpad, c->max_ksplit, &g.nw, &g.ks);
+  pick_gemm_config(Npad, Kpad, c->max_ksplit, c->Bpad, &g.nw, &g.ks);
 #ifdef GOOSE_TUNING
   const char* v = getenv(env_name);
   if (v && *v) {

@@ -180,7 +180,7 @@ int launch_split_operand(int dtype, const float* src, int rows, int cols, int ld
                          hipStream_t st);
 int launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
 int launch_argmax_top2(const void* top2, int n_groups, int B, int32_t* argmax, float* margin, hipStream_t st);
-void pick_gemm_config(int Npad, int Kpad, int max_ksplit, int* nw_out, int* ksplit_out);
+void pick_gemm_config(int Npad, int Kpad, int max_ksplit, int max_rows, int* nw_out, int* ksplit_out);
 // (cos, sin) of every node's rotary angles: cs is float2 [B][head_dim/2].
 int launch_rope_table(const int32_t* pos, const double* inv_freq, int B, int head_dim, void* cs, hipStream_t st);
 // One request's share of an attention launch: its rows [row0, row0 + B) of the stacked projections,
