@@ -564,29 +564,57 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
 }
 
 // o[q][h*D + c] = sum_s 2^(m_s - m) O_s[c] / sum_s 2^(m_s - m) l_s, splits taken in index order.
+// A workgroup of 256 threads merges 1024 / D rows of one head, four columns per thread; the loads of
+// up to eight splits are issued together (one load per loop round would make every split a trip to
+// memory of its own).
 template <bool F16, int TS>
-__global__ void k_attn_merge(const float* __restrict__ att_o, const float* __restrict__ att_ml, int nsplit, int Bpad,
-                             int D, unsigned short* __restrict__ o, int ldo, int oterms, int o_f16,
-                             const SegTable<TS> segs) {
-  typedef typename Mma16<F16>::T T;
+__global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ att_o, const float* __restrict__ att_ml,
+                                                    int nsplit, int Bpad, int D, unsigned short* __restrict__ o, int ldo,
+                                                    int oterms, int o_f16, const SegTable<TS> segs) {
   const SegDev& sg = segs.s[TS == 1 ? 0 : blockIdx.z];
-  if ((int)blockIdx.y >= sg.B) return;
+  const int tpr = D >> 2;  // threads per row
+  const int r = blockIdx.y * (256 / tpr) + threadIdx.x / tpr, c = (threadIdx.x % tpr) * 4;
+  if (r >= sg.B) return;
   // head = the fast grid index: the workgroup runs on the XCD whose L2 holds that head's partials
-  const int qi = sg.row0 + blockIdx.y, h = blockIdx.x, c = threadIdx.x;
+  const int qi = sg.row0 + r, h = blockIdx.x;
+  const size_t base0 = (size_t)h * nsplit * Bpad + qi, step = Bpad;  // split s at base0 + s * step
+  constexpr int CH = 8;
   float mmax = NEG_BIG;
-  for (int s = 0; s < nsplit; ++s) mmax = fmaxf(mmax, att_ml[(((size_t)h * nsplit + s) * Bpad + qi) * 2]);
-  float num = 0.f, den = 0.f;
-  for (int s = 0; s < nsplit; ++s) {
-    const size_t base = ((size_t)h * nsplit + s) * Bpad + qi;
-    const float w = exp2f(att_ml[base * 2] - mmax);
-    den += w * att_ml[base * 2 + 1];
-    num += w * att_o[base * D + c];
+  for (int s0 = 0; s0 < nsplit; s0 += CH) {
+    float m[CH];
+#pragma unroll
+    for (int k = 0; k < CH; ++k) m[k] = att_ml[(base0 + (size_t)min(s0 + k, nsplit - 1) * step) * 2];
+#pragma unroll
+    for (int k = 0; k < CH; ++k) mmax = fmaxf(mmax, m[k]);
   }
-  const float f = num / den;
-  const unsigned short hi = out_bits16(f, o_f16);
-  unsigned short* dst = o + (size_t)qi * ldo + term_pos(oterms, h * D + c);
-  dst[0] = hi;
-  if (oterms == 2) dst[8] = out_bits16(f - out_back16(hi, o_f16), o_f16);
+  f32x4 num = {0.f, 0.f, 0.f, 0.f};
+  float den = 0.f;
+  for (int s0 = 0; s0 < nsplit; s0 += CH) {
+    float2 ml[CH];
+    f32x4 ov[CH];
+#pragma unroll
+    for (int k = 0; k < CH; ++k) {
+      const size_t base = base0 + (size_t)min(s0 + k, nsplit - 1) * step;
+      ml[k] = *reinterpret_cast<const float2*>(att_ml + base * 2);
+      ov[k] = *reinterpret_cast<const f32x4*>(att_o + base * D + c);
+    }
+#pragma unroll
+    for (int k = 0; k < CH; ++k) {
+      const float w = (s0 + k < nsplit) ? exp2f(ml[k].x - mmax) : 0.f;
+      den += w * ml[k].y;
+      num += w * ov[k];
+    }
+  }
+  u16x4 v, v2;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float f = num[e] / den;
+    v[e] = out_bits16(f, o_f16);
+    v2[e] = out_bits16(f - out_back16(v[e], o_f16), o_f16);
+  }
+  unsigned short* dst = o + (size_t)qi * ldo + term_pos(oterms, h * D + c);  // four columns inside one group of eight
+  *reinterpret_cast<u16x4*>(dst) = v;
+  if (oterms == 2) *reinterpret_cast<u16x4*>(dst + 8) = v2;
 }
 
 // (cos, sin) of pos[m] * base^(-2j/d) for every node m and pair j: the angle is reduced in double,
@@ -643,10 +671,10 @@ int launch_merge(dim3 grid, int head_dim, hipStream_t st, const AttnArgs& a, int
   typedef typename Mma16<F16>::T T;
   if (grid.z == 1) {
     const SegTable<1> t1{{t.s[0]}};
-    hipLaunchKernelGGL((k_attn_merge<F16, 1>), grid, dim3(head_dim), 0, st, a.att_o, a.att_ml, splits, a.Bpad, head_dim,
+    hipLaunchKernelGGL((k_attn_merge<F16, 1>), grid, dim3(256), 0, st, a.att_o, a.att_ml, splits, a.Bpad, head_dim,
                        (unsigned short*)a.o, a.ldo, a.oterms, a.o_f16, t1);
   } else {
-    hipLaunchKernelGGL((k_attn_merge<F16, ATTN_MAX_SEGS>), grid, dim3(head_dim), 0, st, a.att_o, a.att_ml, splits, a.Bpad,
+    hipLaunchKernelGGL((k_attn_merge<F16, ATTN_MAX_SEGS>), grid, dim3(256), 0, st, a.att_o, a.att_ml, splits, a.Bpad,
                        head_dim, (unsigned short*)a.o, a.ldo, a.oterms, a.o_f16, t);
   }
   return goose_launch_status();
@@ -712,7 +740,8 @@ int launch_attn_16(int dtype, const float* part, int ks, size_t part_stride, siz
     int rc = head_dim == 128 ? launch_d<128>(cls, key_groups, grid, st, a, t) : launch_d<64>(cls, key_groups, grid, st, a, t);
     if (rc != GOOSE_OK) return rc;
     if (splits == 1) continue;
-    const dim3 mgrid(n_heads, b_max, n);
+    const int rows_per_wg = 1024 / head_dim;
+    const dim3 mgrid(n_heads, (b_max + rows_per_wg - 1) / rows_per_wg, n);
     rc = a.f16 ? launch_merge<true>(mgrid, head_dim, st, a, splits, t)
                : launch_merge<false>(mgrid, head_dim, st, a, splits, t);
     if (rc != GOOSE_OK) return rc;

@@ -138,8 +138,19 @@ __global__ __launch_bounds__(NTHR) void k_resid_norm(float* __restrict__ x, int 
     const int c4 = threadIdx.x + i * NTHR;
     if (c4 < nvec) {
       float4 a = *reinterpret_cast<const float4*>(xr + c4 * 4);
-      for (int s = 0; s < S; ++s) {
-        const float4 p = *reinterpret_cast<const float4*>(part + s * part_stride + (size_t)m * part_ld + c4 * 4);
+      // the slices are added in index order, four loads in flight at a time (one load per loop
+      // round would make every slice its own trip to memory)
+      const float* pp = part + (size_t)m * part_ld + c4 * 4;
+      int s = 0;
+      for (; s + 4 <= S; s += 4) {
+        float4 p[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) p[k] = *reinterpret_cast<const float4*>(pp + (size_t)(s + k) * part_stride);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { a.x += p[k].x; a.y += p[k].y; a.z += p[k].z; a.w += p[k].w; }
+      }
+      for (; s < S; ++s) {
+        const float4 p = *reinterpret_cast<const float4*>(pp + (size_t)s * part_stride);
         a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
       }
       if (S > 0) *reinterpret_cast<float4*>(xr + c4 * 4) = a;
