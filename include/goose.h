@@ -351,9 +351,9 @@ size_t goose_packed_matrix_bytes(int N, int K);
 int goose_pack_matrix(const void* d_w, int N, int K, void* d_packed, void* stream);
 int goose_gemm_packed(int dtype, const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, int ksplit,
                       float* d_partials, void* stream);
-/* Same product with the fused SwiGLU epilogue: the N rows of W (N a multiple of 64) alternate in blocks
- * of 32 between gate rows and up rows; d_h 16-bit [B][ldh] (ldh even, d_h 4-byte aligned) receives
- * silu(gate) * up, N/2 columns. */
+/* Same product with the fused SwiGLU epilogue: the N rows of W (N a multiple of 32) alternate in blocks
+ * of 16 between gate rows and up rows (rows 32t .. 32t+15 = gate rows 16t .., rows 32t+16 .. 32t+31 = up
+ * rows 16t ..); d_h 16-bit [B][ldh] (ldh even, d_h 4-byte aligned) receives silu(gate) * up, N/2 columns. */
 int goose_gemm_swiglu_packed(int dtype, const void* d_a, int lda, const void* d_packed, int N, int K, int B, int nw, void* d_h,
                              int ldh, void* stream);
 /* The same two products as the decoder layers run them.

@@ -31,7 +31,8 @@ constexpr int KGRAN = 128;  // granularity of K padding and of split-K ranges (i
 // Re-tile raw row-major matrices of 16-bit elements (moved as bit patterns: bf16 or fp16).  Packed row n comes from
 //   PACK_PLAIN   : s0 row n
 //   PACK_QKV     : q|k|v stacked: rows_each rows of s0, then rows_kv rows of s1, then rows_kv rows of s2
-//   PACK_GATE_UP : blocks of 32 rows alternate gate (s0) / up (s1): block b -> (b&1 ? up : gate) rows (b>>1)*32..
+//   PACK_GATE_UP : blocks of 16 rows alternate gate (s0) / up (s1): block b -> (b&1 ? up : gate) rows (b>>1)*16..,
+//                  so that every 32-row tile holds the gate rows AND the up rows of its 16 output columns
 // Rows and columns outside the source are zero.
 // cvt_exp > 0: the source is bf16 and every weight w is RE-ENCODED as the fp16 value w * 2^cvt_exp
 // (the projections then run the fp16 matrix instruction, whose activation operand keeps 11
@@ -59,8 +60,8 @@ __global__ __launch_bounds__(256) void k_pack_bf16(int mode, const bf16_t* __res
     else if (n < rows_each + rows_kv) { src = s1; row = n - rows_each; limit = rows_kv; }
     else if (n < rows_each + 2 * rows_kv) { src = s2; row = n - rows_each - rows_kv; limit = rows_kv; }
   } else {
-    const int blk = n >> 5;
-    row = (blk >> 1) * 32 + (n & 31);
+    const int blk = n >> 4;
+    row = (blk >> 1) * 16 + (n & 15);
     src = (blk & 1) ? s1 : s0;
   }
   union { uint4 u; bf16_t e[8]; _Float16 h[8]; } v;
@@ -110,8 +111,12 @@ __global__ __launch_bounds__(256) void k_pack_bf16(int mode, const bf16_t* __res
 //     including the A copy issued this stage (the weight loads issued after it stay in flight).
 // out_scale multiplies every sum before the epilogue uses it (an exact power of two: weights that
 // were re-encoded as scaled fp16, see launch_pack_16).
-// EPI_SWIGLU: even tiles are gate tiles, odd ones the matching up tiles; the up tile
-// is handed over through LDS and the even wavefront writes h = silu(gate) * up (in TERMS terms).
+// EPI_SWIGLU: every tile holds the gate rows (columns 0-15 of the tile) and the up rows (columns
+// 16-31) of 16 outputs, so a wavefront forms h = silu(gate) * up (in TERMS terms) from its own
+// accumulators.  Tiles are dealt to the wavefronts with a stride of the grid width (wavefront w of
+// workgroup g takes tile g + w * gridDim.x), and the grid is as wide as the chip when the tiles
+// allow: 688 tiles then load 256 compute units with at most three weight streams each instead of
+// 172 with four.
 // EPI_TOP2: besides the optional plain output, every workgroup reduces its columns to one
 // (largest, second largest, index of largest) triple per row, for the greedy argmax.
 // CHUNKED: more than MT*32 rows, computed as several row chunks that read the same weights (1-D
@@ -141,7 +146,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
   constexpr int COPIES = MT * 32 / ROWS_PER_COPY;
   constexpr int CPW = COPIES / NWAVES;                 // copy instructions per wavefront per stage
   static_assert(COPIES % NWAVES == 0, "the A copy must divide evenly over the wavefronts");
-  // SwiGLU: a gate tile and its up tile meet in LDS as fp32 (two wavefronts' accumulators each)
+  // SwiGLU: every wavefront passes its accumulators through LDS as fp32
   constexpr int SWAP_BYTES = (EPI == EPI_SWIGLU) ? NW * MT * 16 * 64 * 4 : 0;
   constexpr int CT_ROW = 33;  // floats per row of a transposed-read C tile (odd: conflict-free row scans)
   constexpr int TOP2_BYTES = (EPI == EPI_TOP2) ? NW * MT * 32 * (CT_ROW * 4 + 16) : 0;
@@ -188,11 +193,12 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
     row_base = chunk * MT * 32;
     ngroups = gx;
   }
-  const int tile = bx * NW + wt;
+  const int tile = EPI == EPI_SWIGLU ? bx + ngroups * wt : bx * NW + wt;
   const bool active = tile < ntiles;
-  // a wavefront past the last tile redoes the last tile (no divergent control flow in the
-  // pipeline, which lets the compiler count outstanding loads exactly) and skips the store
-  const int tile_ld = active ? tile : ntiles - 1;
+  // a wavefront without a tile runs the same pipeline (no divergent control flow: the compiler can
+  // then count outstanding loads exactly) on an empty weight range, i.e. on zeros that cost no
+  // memory traffic, and skips the store
+  const int tile_ld = active ? tile : 0;
   const int nstages_total = ksteps_total / STEPS;
   const int s_begin = by * stages_per_split;
   const int s_end = min(s_begin + stages_per_split, nstages_total);
@@ -242,7 +248,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
 #if defined(__HIP_DEVICE_COMPILE__)
   const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<u32x4*>(Wp + ((size_t)tile_ld * ksteps_total + (size_t)s_begin * STEPS) * 64), 0,
-      (nst > 0 ? nst : 0) * STEPS * 1024, GOOSE_BUFFER_WORD3);
+      (active && nst > 0 ? nst : 0) * STEPS * 1024, GOOSE_BUFFER_WORD3);
 #endif
   const int w_lane = lane * 16;
   auto load_w = [&](int i, auto slot_c) {  // (beyond the range: zeros, no memory traffic)
@@ -403,29 +409,27 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
       }
     }
   } else {  // EPI_SWIGLU
-    // Every wavefront leaves its accumulators in LDS (register r of lane l at [r][l]); then the two
-    // wavefronts of a gate/up pair share the pair's elements, two neighbouring columns per lane, in
-    // a short loop (compact code; the 16-bit results leave as 4-byte stores).
+    // The wavefront leaves its accumulators in LDS (register r of lane l at [r][l]) and walks its
+    // tile's 16 output columns two at a time in a short loop (compact code; the 16-bit results leave
+    // as 4-byte stores): the gate values of columns 2p, 2p+1 sit at lanes 2p, 2p+1 of a half, the up
+    // values 16 lanes further.  Nothing is shared between wavefronts: no barrier.
     constexpr int TILE_F = MT * 16 * 64;  // floats of one wavefront's accumulators
     float* mine = reinterpret_cast<float*>(lds) + (size_t)wt * TILE_F;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mine[(mt * 16 + r) * 64 + lane] = acc[mt][r] * out_scale;
-    __syncthreads();
-    const int gate_tile = tile & ~1;  // (a pair never straddles the last tile: the tile count is even)
-    if (gate_tile + 1 < ntiles) {
-      const float* gt = reinterpret_cast<const float*>(lds) + (size_t)(wt & ~1) * TILE_F;
-      const float* ut = gt + TILE_F;
+    __builtin_amdgcn_wave_barrier();  // (LDS operations of one wavefront complete in order)
+    if (writer) {
       T* hq = reinterpret_cast<T*>(out);
-      const int half = (wt & 1) * 64 + lane;  // 0..127 within the pair
       bool clamped = false;
-      for (int e = half; e < MT * 16 * 32; e += 128) {
-        const int l2 = (e & 31) * 2, rr = (e >> 5) & 15, mt = e >> 9;  // lane pair, register, row tile
-        const int row = row_base + mt * 32 + 8 * (rr >> 2) + 4 * (l2 >> 5) + (rr & 3);
-        const int col = (gate_tile >> 1) * 32 + (l2 & 31);
-        const float2 g = *reinterpret_cast<const float2*>(&gt[(mt * 16 + rr) * 64 + l2]);
-        const float2 u = *reinterpret_cast<const float2*>(&ut[(mt * 16 + rr) * 64 + l2]);
+      for (int e = lane; e < MT * 16 * 16; e += 64) {
+        const int pr = e & 7, half = (e >> 3) & 1, rr = (e >> 4) & 15, mt = e >> 8;  // column pair, lane half, register, row tile
+        const int row = row_base + mt * 32 + 8 * (rr >> 2) + 4 * half + (rr & 3);
+        const int col = tile * 16 + 2 * pr;
+        const float* src = &mine[(mt * 16 + rr) * 64 + half * 32 + 2 * pr];
+        const float2 g = *reinterpret_cast<const float2*>(src);
+        const float2 u = *reinterpret_cast<const float2*>(src + 16);
         float h0 = swiglu_f32(g.x, u.x), h1 = swiglu_f32(g.y, u.y);
         if (F16) {  // beyond fp16: clamp, and say so (GOOSE_FLAG_RANGE)
           if (fabsf(h0) > 65504.0f) { h0 = copysignf(65504.0f, h0); clamped = clamped || row < B; }
@@ -475,7 +479,10 @@ int launch_terms(const GemmCall& g, dim3 grid, int gx, int gps, int nchunk) {
 template <int MT, int NW, int EPI>
 int launch_one(const GemmCall& g) {
   const int ntiles = g.Npad / 32;
-  const int gx = (ntiles + NW - 1) / NW;
+  int gx = (ntiles + NW - 1) / NW;
+  // SwiGLU tiles stand alone and are dealt with a stride of the grid width: a grid as wide as the
+  // chip (or as the tiles allow) spreads the weight streams over more compute units
+  if (EPI == EPI_SWIGLU && gx < 256) gx = ntiles < 256 ? ntiles : 256;
   const int nchunk = (g.B + MT * 32 - 1) / (MT * 32);  // more than 128 rows: chunks of 4 row tiles
   const dim3 grid = nchunk == 1 ? dim3(gx, g.ksplit) : dim3((gx * g.ksplit + 7) / 8 * 8 * nchunk);
   const int granules = g.Kpad / KGRAN;                      // split-K ranges are multiples of 128 inputs

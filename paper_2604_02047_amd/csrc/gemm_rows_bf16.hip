@@ -199,29 +199,36 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_rows(const typename Mma16<F16>
           if (row < B) o[(size_t)row * ldo + col] = acc[mt][nt][r] * out_scale;
         }
     }
-  } else {  // EPI_SWIGLU: column tile 2c holds gate rows, 2c+1 the matching up rows
-    static_assert(NT == 2, "gate and up tile of a column block sit in one wavefront");
-    if (tile0 + 1 >= ntiles) return;
+  } else {  // EPI_SWIGLU: every tile holds the gate rows (columns 0-15) and the up rows (16-31) of 16 outputs
     T* hq = reinterpret_cast<T*>(out);
-    const int col = (tile0 >> 1) * 32 + (lane & 31);
-    const size_t cpos = term_pos(TERMS, col);
+    const bool lower = (lane & 16) == 0;  // this lane's column is a gate column
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int nt = 0; nt < NT; ++nt) {
+      if (tile0 + nt >= ntiles) continue;
+      const int col = (tile0 + nt) * 16 + (lane & 15);
+      const size_t cpos = term_pos(TERMS, col);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = row_base + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const float g = acc[mt][0][r] * out_scale, u = acc[mt][1][r] * out_scale;
-        float hval = swiglu_f32(g, u);
-        if (F16 && fabsf(hval) > 65504.0f) {  // beyond fp16: clamp, and say so (GOOSE_FLAG_RANGE)
-          hval = copysignf(65504.0f, hval);
-          if (flags != nullptr && row < B) atomicOr(flags, GOOSE_FLAG_RANGE);
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_base + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          // the partner lane (16 further) holds the other factor; the gate lane writes the even
+          // registers' rows, the up lane the odd ones
+          const float mine = acc[mt][nt][r] * out_scale, other = __shfl_xor(mine, 16, 64);
+          const float g = lower ? mine : other, u = lower ? other : mine;
+          float hval = swiglu_f32(g, u);
+          const bool store = ((r & 1) == 0) == lower && row < B;
+          if (F16 && fabsf(hval) > 65504.0f) {  // beyond fp16: clamp, and say so (GOOSE_FLAG_RANGE)
+            hval = copysignf(65504.0f, hval);
+            if (flags != nullptr && store) atomicOr(flags, GOOSE_FLAG_RANGE);
+          }
+          if (store) {
+            const T hi = (T)hval;
+            hq[(size_t)row * ldo + cpos] = hi;
+            if (TERMS == 2) hq[(size_t)row * ldo + cpos + 8] = (T)(hval - (float)hi);
+          }
         }
-        if (row < B) {
-          const T hi = (T)hval;
-          hq[(size_t)row * ldo + cpos] = hi;
-          if (TERMS == 2) hq[(size_t)row * ldo + cpos + 8] = (T)(hval - (float)hi);
-        }
-      }
+    }
   }
 }
 

@@ -788,7 +788,7 @@ int goose_split_operand(int dtype, const float* d_src, int rows, int cols, int l
 
 int goose_gemm_swiglu_packed_ex(int dtype, const void* d_a, int lda, int terms, const void* d_packed, int N, int K,
                                 int B, int nw, float out_scale, void* d_h, int ldh, void* stream) {
-  if (!d_a || !d_packed || !d_h || N < 64 || (N % 64) != 0 || K < 1) return GOOSE_ERR_ARG;
+  if (!d_a || !d_packed || !d_h || N < 32 || (N % 32) != 0 || K < 1) return GOOSE_ERR_ARG;
   if (!is16(dtype) || B < 1 || B > GOOSE_MAX_ROWS || (nw != 2 && nw != 4)) return GOOSE_ERR_ARG;
   if (terms != 1 && terms != 2) return GOOSE_ERR_ARG;
   const int Kpad = round_up(K, 128);

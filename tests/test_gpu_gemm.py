@@ -114,8 +114,8 @@ def test_gemm_swiglu_epilogue(B, F, K, nw, dt, terms):
     a, a_exact = _operand(torch.randn((B, K), generator=gen), _a_rows(B), Kp, dt, terms, dev)
     wg = (torch.randn((F, K), generator=gen) * 0.05).to(dt)
     wu = (torch.randn((F, K), generator=gen) * 0.05).to(dt)
-    assert F % 32 == 0
-    inter = torch.stack([wg.view(F // 32, 32, K), wu.view(F // 32, 32, K)], dim=1).reshape(2 * F, K).contiguous()
+    assert F % 16 == 0
+    inter = torch.stack([wg.view(F // 16, 16, K), wu.view(F // 16, 16, K)], dim=1).reshape(2 * F, K).contiguous()
     gd, ud = torch.from_numpy(a_exact) @ wg.double().T, torch.from_numpy(a_exact) @ wu.double().T
     ref = (gd / (1 + torch.exp(-gd)) * ud).numpy()
     packed = torch.zeros(g.goose_packed_matrix_bytes(2 * F, K), dtype=torch.uint8, device=dev)
