@@ -113,9 +113,9 @@ __global__ __launch_bounds__(256) void k_pack_bf16(int mode, const bf16_t* __res
 // were re-encoded as scaled fp16, see launch_pack_16).
 // EPI_SWIGLU: every tile holds the gate rows (columns 0-15 of the tile) and the up rows (columns
 // 16-31) of 16 outputs, so a wavefront forms h = silu(gate) * up (in TERMS terms) from its own
-// accumulators.  Tiles are dealt to the wavefronts with a stride of the grid width (wavefront w of
-// workgroup g takes tile g + w * gridDim.x), and the grid is as wide as the chip when the tiles
-// allow: 688 tiles then load 256 compute units with at most three weight streams each instead of
+// accumulators.  Tiles (of EPI_SWIGLU and EPI_PARTIAL) are dealt to the wavefronts with a stride of
+// the grid width (wavefront w of workgroup g takes tile g + w * gridDim.x), and the grid is as wide
+// as the chip when the tiles allow: 688 tiles then load 256 compute units with at most three weight streams each instead of
 // 172 with four.
 // EPI_TOP2: besides the optional plain output, every workgroup reduces its columns to one
 // (largest, second largest, index of largest) triple per row, for the greedy argmax.
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
     row_base = chunk * MT * 32;
     ngroups = gx;
   }
-  const int tile = EPI == EPI_SWIGLU ? bx + ngroups * wt : bx * NW + wt;
+  const int tile = EPI == EPI_TOP2 ? bx * NW + wt : bx + ngroups * wt;
   const bool active = tile < ntiles;
   // a wavefront without a tile runs the same pipeline (no divergent control flow: the compiler can
   // then count outstanding loads exactly) on an empty weight range, i.e. on zeros that cost no
@@ -483,6 +483,12 @@ int launch_one(const GemmCall& g) {
   // SwiGLU tiles stand alone and are dealt with a stride of the grid width: a grid as wide as the
   // chip (or as the tiles allow) spreads the weight streams over more compute units
   if (EPI == EPI_SWIGLU && gx < 256) gx = ntiles < 256 ? ntiles : 256;
+  // the same for the split-K products: tiles of one K range are dealt with a stride of the grid width,
+  // and the grid is widened until all ranges together fill the chip
+  if (EPI == EPI_PARTIAL && gx * g.ksplit < 256) {
+    const int want = (256 + g.ksplit - 1) / g.ksplit;
+    gx = want < ntiles ? (want > gx ? want : gx) : ntiles;
+  }
   const int nchunk = (g.B + MT * 32 - 1) / (MT * 32);  // more than 128 rows: chunks of 4 row tiles
   const dim3 grid = nchunk == 1 ? dim3(gx, g.ksplit) : dim3((gx * g.ksplit + 7) / 8 * 8 * nchunk);
   const int granules = g.Kpad / KGRAN;                      // split-K ranges are multiples of 128 inputs
