@@ -321,6 +321,17 @@ int goose_build_spine_tree(int32_t anchor, const int32_t* h_draft, int m, const 
 enum { GOOSE_MODE_AR = 0, GOOSE_MODE_TREE = 1, GOOSE_MODE_BYPASS = 2 };
 int goose_cycle_mode(int m, int consensus, int bypass_len, int anchor_has_successors);
 double goose_spine_ratio_tier(double p_hat);
+/* One call for the host side of a cycle (Alg. "Decoding Loop"): the context match on h_seq, the test
+ * whether the adjacency table holds a successor of `anchor` with a score >= min_score, the routing
+ * (goose_cycle_mode), and the nodes of the pass: the chain anchor + draft for a bypass cycle, the
+ * spine tree (goose_build_spine_tree with the spine ratio of goose_spine_ratio_tier(p_hat)) for a
+ * tree cycle, the anchor alone otherwise.  h_succ_ids / h_succ_scores: host [vocab][K]; h_tokens,
+ * h_parent int32 [B], h_is_spine uint8 [B]; *h_n = nodes written, *h_mode = GOOSE_MODE_*.
+ * B >= 1 + max_spine (a bypass chain must fit). */
+int goose_plan_cycle(const int32_t* h_seq, int n_seq, const int32_t* h_lens, int n_lens, int max_spine, int32_t anchor,
+                     const int32_t* h_succ_ids, const float* h_succ_scores, int vocab, int K, int B, double p_hat,
+                     double rho, int D, double min_score, int bypass_len, int32_t* h_tokens, int32_t* h_parent,
+                     uint8_t* h_is_spine, int32_t* h_n, int32_t* h_mode);
 double goose_ema_update(double p_hat, int accepted_spine, int offered_spine, double alpha);
 
 /* Device-side diagnostics of the calls queued on this context since the last read (the word is then

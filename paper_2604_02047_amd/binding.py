@@ -23,7 +23,7 @@ EXPORTS = [
     "goose_context_match", "goose_spine_budget", "goose_build_spine_tree", "goose_spine_ratio_tier", "goose_ema_update",
     "goose_cycle_mode", "goose_verify_step_batched",
     "goose_split_operand", "goose_gemm_packed_ex", "goose_gemm_swiglu_packed_ex",
-    "goose_lm_head_argmax_static",
+    "goose_lm_head_argmax_static", "goose_plan_cycle",
 ]
 
 GOOSE_DTYPE_BF16, GOOSE_DTYPE_F32, GOOSE_DTYPE_F16 = 0, 1, 2
@@ -160,6 +160,9 @@ def load_library():
     lib.goose_build_spine_tree.argtypes = [C.c_int32, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                            C.c_int, C.c_double, C.c_double, C.c_int, C.c_double] + [C.c_void_p] * 4
     lib.goose_spine_ratio_tier.argtypes = [C.c_double]
+    lib.goose_plan_cycle.argtypes = ([C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int32, C.c_void_p, C.c_void_p,
+                                      C.c_int, C.c_int, C.c_int, C.c_double, C.c_double, C.c_int, C.c_double, C.c_int]
+                                     + [C.c_void_p] * 5)
     lib.goose_spine_ratio_tier.restype = C.c_double
     lib.goose_ema_update.argtypes = [C.c_double, C.c_int, C.c_int, C.c_double]
     lib.goose_ema_update.restype = C.c_double
@@ -244,6 +247,23 @@ GOOSE_ERR_CAPACITY, GOOSE_ERR_NOT_TOPOLOGICAL = -3, -4
 def goose_cycle_mode(m, consensus, bypass_len, anchor_has_successors) -> int:
     return int(load_library().goose_cycle_mode(int(m), int(bool(consensus)), int(bypass_len),
                                                int(bool(anchor_has_successors))))
+
+
+def goose_plan_cycle(seq, lens, max_spine, anchor, succ_ids, succ_scores, B, p_hat, rho=0.5, D=6, min_score=0.01,
+                     bypass_len=8):
+    """Host side of a cycle in one call: returns (tokens, parent, is_spine, mode)."""
+    seq, lens = _np_i32(seq), _np_i32(lens)
+    assert succ_ids.dtype == np.int32 and succ_scores.dtype == np.float32
+    assert succ_ids.flags.c_contiguous and succ_scores.flags.c_contiguous and succ_ids.shape == succ_scores.shape
+    V, K = succ_ids.shape
+    tok, par, spn = np.zeros(B, np.int32), np.zeros(B, np.int32), np.zeros(B, np.uint8)
+    n, mode = C.c_int32(0), C.c_int32(0)
+    _check(load_library().goose_plan_cycle(seq.ctypes.data, len(seq), lens.ctypes.data, len(lens), int(max_spine),
+                                           int(anchor), succ_ids.ctypes.data, succ_scores.ctypes.data, V, K, int(B),
+                                           float(p_hat), float(rho), int(D), float(min_score), int(bypass_len),
+                                           tok.ctypes.data, par.ctypes.data, spn.ctypes.data, C.addressof(n),
+                                           C.addressof(mode)), "goose_plan_cycle")
+    return tok[:n.value].copy(), par[:n.value].copy(), spn[:n.value].copy(), int(mode.value)
 
 
 def goose_spine_ratio_tier(p_hat):

@@ -1,4 +1,4 @@
-// Host side of a decoding cycle: context n-gram match, budget split, spine-tree construction,
+// Host side of a decoding cycle: validation of a parent array, context n-gram match, budget split, spine-tree construction,
 // spine-ratio tiers and their moving average (Sec. 4.1, Sec. 4.3, Alg. BuildSpineTree, Alg.
 // "Decoding Loop" and the note on ContextMatch below it; hyperparameter table of App. C).
 // Plain C++ on host memory: per cycle this is a few microseconds on ~100 tokens, next to a
@@ -11,6 +11,14 @@
 #include "goose.h"
 
 extern "C" {
+
+int goose_check_parent(const int32_t* h_parent, int B) {
+  if (!h_parent || B < 1 || B > GOOSE_MAX_B) return GOOSE_ERR_ARG;
+  if (h_parent[0] != -1) return GOOSE_ERR_NOT_TOPOLOGICAL;
+  for (int i = 1; i < B; ++i)
+    if (h_parent[i] < 0 || h_parent[i] >= i) return GOOSE_ERR_NOT_TOPOLOGICAL;
+  return GOOSE_OK;
+}
 
 int goose_context_match(const int32_t* h_seq, int n_seq, const int32_t* h_lens, int n_lens, int max_len,
                         int32_t* h_draft, int32_t* h_m, int32_t* h_consensus) {
@@ -125,6 +133,48 @@ int goose_cycle_mode(int m, int consensus, int bypass_len, int anchor_has_succes
   if (m > 0 && (m >= bypass_len || consensus)) return GOOSE_MODE_BYPASS;
   if (m > 0 || anchor_has_successors) return GOOSE_MODE_TREE;
   return GOOSE_MODE_AR;
+}
+
+int goose_plan_cycle(const int32_t* h_seq, int n_seq, const int32_t* h_lens, int n_lens, int max_spine, int32_t anchor,
+                     const int32_t* h_succ_ids, const float* h_succ_scores, int vocab, int K, int B, double p_hat,
+                     double rho, int D, double min_score, int bypass_len, int32_t* h_tokens, int32_t* h_parent,
+                     uint8_t* h_is_spine, int32_t* h_n, int32_t* h_mode) {
+  if (!h_seq || !h_lens || !h_succ_ids || !h_succ_scores || !h_tokens || !h_parent || !h_is_spine || !h_n || !h_mode)
+    return GOOSE_ERR_ARG;
+  if (n_seq < 1 || max_spine < 1 || B < 1 + max_spine || B > GOOSE_MAX_B || vocab < 1 || K < 1) return GOOSE_ERR_ARG;
+  if (anchor < 0 || anchor >= vocab) return GOOSE_ERR_ARG;
+  std::vector<int32_t> draft((size_t)max_spine);
+  int32_t m = 0, consensus = 0;
+  int rc = goose_context_match(h_seq, n_seq, h_lens, n_lens, max_spine, draft.data(), &m, &consensus);
+  if (rc != GOOSE_OK) return rc;
+  // does the adjacency table hold a usable successor of the anchor?
+  int has_succ = 0;
+  for (int k = 0; k < K; ++k) {
+    const size_t e = (size_t)anchor * K + k;
+    if (h_succ_ids[e] >= 0 && h_succ_scores[e] >= (float)min_score) has_succ = 1;
+  }
+  const int mode = goose_cycle_mode(m, consensus, bypass_len, has_succ);
+  *h_mode = mode;
+  if (mode == GOOSE_MODE_BYPASS) {  // the anchor and the whole draft as one chain, every node on the spine
+    h_tokens[0] = anchor;
+    h_parent[0] = -1;
+    h_is_spine[0] = 1;
+    for (int i = 0; i < m; ++i) {
+      h_tokens[1 + i] = draft[i];
+      h_parent[1 + i] = i;
+      h_is_spine[1 + i] = 1;
+    }
+    *h_n = 1 + m;
+    return GOOSE_OK;
+  }
+  if (mode == GOOSE_MODE_TREE)
+    return goose_build_spine_tree(anchor, draft.data(), m, h_succ_ids, h_succ_scores, vocab, K, B,
+                                  goose_spine_ratio_tier(p_hat), rho, D, min_score, h_tokens, h_parent, h_is_spine, h_n);
+  h_tokens[0] = anchor;  // one autoregressive step
+  h_parent[0] = -1;
+  h_is_spine[0] = 1;
+  *h_n = 1;
+  return GOOSE_OK;
 }
 
 double goose_spine_ratio_tier(double p_hat) { return p_hat < 0.2 ? 0.15 : (p_hat < 0.4 ? 0.30 : 0.50); }

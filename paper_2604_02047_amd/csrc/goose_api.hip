@@ -165,14 +165,6 @@ const char* goose_strerror(int status) {
   return "unknown status";
 }
 
-int goose_check_parent(const int32_t* h_parent, int B) {
-  if (!h_parent || B < 1 || B > GOOSE_MAX_B) return GOOSE_ERR_ARG;
-  if (h_parent[0] != -1) return GOOSE_ERR_NOT_TOPOLOGICAL;
-  for (int i = 1; i < B; ++i)
-    if (h_parent[i] < 0 || h_parent[i] >= i) return GOOSE_ERR_NOT_TOPOLOGICAL;
-  return GOOSE_OK;
-}
-
 int goose_create(const goose_model_desc* desc, int max_B, int cap, goose_ctx** out) {
   return goose_create_batched(desc, max_B, round_up(max_B, 32), cap, out);
 }

@@ -72,23 +72,10 @@ class _Request:
         return self.anchor
 
     def plan(self, o):
-        """The tree of the next cycle (host side of Alg. "Decoding Loop"): tokens, parent, is_spine, mode."""
-        draft, consensus = gb.goose_context_match(self.seq, o.lens, o.max_spine)
-        has_succ = bool(((self.h_ids[self.anchor] >= 0) & (self.h_scores[self.anchor] >= o.min_score)).any())
-        mode = gb.goose_cycle_mode(len(draft), consensus, o.bypass_len, has_succ)
-        if mode == gb.MODE_BYPASS:
-            n = 1 + len(draft)
-            tokens = np.concatenate([[self.anchor], draft]).astype(np.int32)
-            parent = np.arange(-1, n - 1, dtype=np.int32)
-            is_spine = np.ones(n, np.uint8)
-        elif mode == gb.MODE_TREE:
-            r = gb.goose_spine_ratio_tier(self.p_hat)
-            tokens, parent, is_spine = gb.goose_build_spine_tree(self.anchor, draft, self.h_ids, self.h_scores, o.B,
-                                                                 r, o.rho, o.D, o.min_score)
-        else:
-            tokens, parent, is_spine = (np.array([self.anchor], np.int32), np.array([-1], np.int32),
-                                        np.ones(1, np.uint8))
-        return tokens, parent, is_spine, mode
+        """The nodes of the next cycle (host side of Alg. "Decoding Loop", one library call): tokens, parent,
+        is_spine, mode."""
+        return gb.goose_plan_cycle(self.seq, o.lens, o.max_spine, self.anchor, self.h_ids, self.h_scores, o.B,
+                                   self.p_hat, o.rho, o.D, o.min_score, o.bypass_len)
 
     def absorb(self, o, tokens, is_spine, mode, L, path, bonus, P):
         """Takes the walk's result of a cycle; returns the tokens the cycle emitted."""

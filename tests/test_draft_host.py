@@ -70,3 +70,41 @@ def test_spine_tree_matches_the_oracle():
         t, p, s = gb.goose_build_spine_tree(7, draft, ids, sc, B, r, rho, D, thr)
         assert t.tolist() == t_ref and p.tolist() == p_ref and s.tolist() == s_ref, trial
         assert gb.goose_check_parent(p) == 0
+
+
+def _plan_ref(seq, lens, max_spine, anchor, ids, sc, B, p_hat, rho, D, thr, bypass_len):
+    """The routing of Alg. "Decoding Loop" spelled out with the oracle's pieces."""
+    draft, consensus = dr.context_match(seq, lens, max_spine)
+    if draft and (len(draft) >= bypass_len or consensus):
+        return [anchor] + draft, list(range(-1, len(draft))), [1] * (1 + len(draft)), gb.MODE_BYPASS
+    if draft or dr.successors(ids, sc, anchor, thr):
+        t, p, s = dr.build_spine_tree(anchor, draft, ids, sc, B, dr.spine_ratio_tier(p_hat), rho, D, thr)
+        return t, p, s, gb.MODE_TREE
+    return [anchor], [-1], [1], gb.MODE_AR
+
+
+def test_cycle_plan_matches_the_oracle():
+    rng = np.random.default_rng(11)
+    seen = set()
+    for trial in range(400):
+        V, K = int(rng.choice([12, 40, 300])), int(rng.choice([1, 4, 10]))
+        ids = rng.integers(-1, V, size=(V, K)).astype(np.int32)
+        if trial % 2 == 0:
+            ids[rng.random(size=V) < 0.6] = -1                  # many tokens without successors
+        sc = (rng.random(size=(V, K)) * (rng.random(size=(V, K)) < 0.7)).astype(np.float32)
+        n = int(rng.integers(1, 80))
+        seq = rng.integers(0, min(V, int(rng.choice([3, 6, V]))), size=n).tolist()   # small alphabets repeat n-grams
+        anchor = int(seq[-1])
+        lens = (3, 4, 5) if trial % 3 else (2, 3)
+        max_spine = int(rng.choice([4, 20]))
+        B = int(rng.integers(1 + max_spine, 129))
+        p_hat = float(rng.random())
+        thr = float(rng.choice([0.01, 0.0, 0.3]))
+        bypass_len = int(rng.choice([3, 8]))
+        t_ref, p_ref, s_ref, mode_ref = _plan_ref(seq, lens, max_spine, anchor, ids, sc, B, p_hat, 0.5, 6, thr, bypass_len)
+        t, p, s, mode = gb.goose_plan_cycle(seq, lens, max_spine, anchor, ids, sc, B, p_hat, 0.5, 6, thr, bypass_len)
+        assert mode == mode_ref, trial
+        assert t.tolist() == list(t_ref) and p.tolist() == list(p_ref) and s.tolist() == list(s_ref), trial
+        assert gb.goose_check_parent(p) == 0
+        seen.add(mode)
+    assert seen == {gb.MODE_AR, gb.MODE_TREE, gb.MODE_BYPASS}
