@@ -273,31 +273,31 @@ def harvest_topk(logits, tokens, K, table_ids=None, table_scores=None, vocab=Non
 
 
 def greedy_walk(parent, tokens, is_spine, x_hat):
-    """Alg. UnifiedGreedyWalk: follow matching children from the root, spine child before branch children.
-    Returns (accepted node list without the root, bonus token)."""
+    """The accepted path of a verification pass (Sec. 4.2; what Alg. UnifiedGreedyWalk computes), from its
+    definition rather than as a walk:
+
+      * an edge (p -> c) MATCHES when the draft token at c equals the model's greedy prediction at p;
+      * among the matching children of a node exactly one is ELECTED: spine-tagged children rank before
+        branch children, lower node index first within a tag;
+      * a node is ACCEPTED when it is elected and its parent is accepted (the root is accepted by
+        definition), so the accepted nodes form one chain from the root;
+      * the bonus token is the prediction at the chain's last node.
+
+    Nodes are numbered in topological order (parent[i] < i), so one pass in index order settles every
+    node after its parent.  Returns (accepted nodes without the root, in root-to-leaf order; bonus token)."""
     B = len(parent)
-    children = [[] for _ in range(B)]
+    tag = np.ones(B, np.uint8) if is_spine is None else np.asarray(is_spine)
+    matches = [i > 0 and int(tokens[i]) == int(x_hat[int(parent[i])]) for i in range(B)]
+    rank = [(0 if tag[i] else 1, i) for i in range(B)]                       # spine first, then index
+    elected = [matches[i] and all(not matches[j] or rank[i] < rank[j]
+                                  for j in range(1, B) if j != i and int(parent[j]) == int(parent[i]))
+               for i in range(B)]
+    accepted = [True] + [False] * (B - 1)
     for i in range(1, B):
-        children[int(parent[i])].append(i)
-    tag = np.ones(B, np.uint8) if is_spine is None else is_spine
-    v = 0
-    accepted = []
-    while children[v]:
-        nxt = None
-        for c in children[v]:                      # priority 1: spine (context-match) child
-            if tag[c] and int(tokens[c]) == int(x_hat[v]):
-                nxt = c
-                break
-        if nxt is None:
-            for c in children[v]:                  # priority 2: branch (transition) children
-                if not tag[c] and int(tokens[c]) == int(x_hat[v]):
-                    nxt = c
-                    break
-        if nxt is None:
-            break
-        accepted.append(nxt)
-        v = nxt
-    return accepted, int(x_hat[v])
+        accepted[i] = elected[i] and accepted[int(parent[i])]
+    chain = [i for i in range(1, B) if accepted[i]]                          # index order = depth order on a chain
+    last = chain[-1] if chain else 0
+    return chain, int(x_hat[last])
 
 
 def accepted_nodes_bruteforce(parent, tokens, x_hat):
