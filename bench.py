@@ -41,20 +41,38 @@ COPY_PROBE_BYTES = 256 << 20
 
 
 def recorded_traffic(workload):
-    """HBM bytes per launch of the gate/up kernel from the committed profiler summary of this workload
-    (FETCH_SIZE + WRITE_SIZE, scaled by the copy probe), or None when there is none.  Counters cannot
-    be read from inside this process; the summary names the command that produced it."""
-    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    """What the committed profiler summary of this workload says (rocprofv3 FETCH_SIZE + WRITE_SIZE runs,
+    scaled by the copy probe): HBM bytes per launch of the gate/up kernel, HBM bytes of a whole step,
+    when it was recorded and for which sources.  Counters cannot be read from inside this process; the
+    summary names the commands that produced it.  The figures are reported only when the summary was
+    recorded for the sources of this very build (hash over csrc/ and goose.h), else as null."""
+    from paper_2604_02047_amd.profiling import source_hash
+    rel = f"profiles/traffic_{workload}.txt"
+    out = {"gate_up_bytes": None, "step_bytes": None, "source": None}
     try:
-        with open(path) as f:
-            for line in f:
-                m = line.split()
-                # the SwiGLU epilogue is template argument 3 == 1 of k_gemm_bf16<MT, NW, EPI, KC>
-                if line.startswith("k_gemm_bf16<") and line.split(">")[0].split(",")[2].strip() == "1":
-                    return int(round((float(m[-2]) + float(m[-1])) * 1e6))
-    except (OSError, ValueError, IndexError):
-        pass
-    return None
+        with open(os.path.join(ROOT, rel)) as f:
+            lines = f.read().splitlines()
+    except OSError:
+        return out
+    date = sha = None
+    for line in lines:
+        m = line.split()
+        try:
+            if line.startswith("recorded "):
+                date, sha = m[1], m[-1]
+            elif line.startswith("last step of the run:"):
+                out["step_bytes"] = int(round((float(m[m.index("fetch") + 1]) + float(m[m.index("write") + 1])) * 1e6))
+            # the SwiGLU epilogue is template argument 4 == 1 of k_gemm_bf16<MT, NW, TERMS, EPI, ..>
+            elif line.startswith("k_gemm_bf16<") and line.split(">")[0].split(",")[3].strip() == "1" \
+                    and out["gate_up_bytes"] is None:
+                out["gate_up_bytes"] = int(round((float(m[-2]) + float(m[-1])) * 1e6))
+        except (ValueError, IndexError):
+            pass
+    same = sha is not None and sha == source_hash()
+    out["source"] = f"{rel}, recorded {date} for sources {sha}" + ("" if same else " (NOT this build: figures withheld)")
+    if not same:
+        out["gate_up_bytes"] = out["step_bytes"] = None
+    return out
 
 
 def cap_for(P0, B, total_steps):
@@ -287,6 +305,7 @@ def main():
 
     # ---- per-kernel timing with HIP events on the launch stream, over the same steps
     roofline, kernels = None, None
+    rec = recorded_traffic(args.workload)
     if not args.no_kernel_timing:
         gm.set_P(P0)
         for t in range(W):
@@ -294,10 +313,13 @@ def main():
             one_step()
         torch.cuda.synchronize()
         gm.ctx.goose_profile_enable(True)
+        prof = {}
         for t in range(W, total):
             stage(t)
             one_step()
-        prof = gm.ctx.goose_profile_read()
+            if (t - W) % 32 == 31 or t == total - 1:   # (the library times a bounded number of launches per read)
+                for k, (ms, n) in gm.ctx.goose_profile_read().items():
+                    prof[k] = (prof.get(k, (0.0, 0))[0] + ms, prof.get(k, (0.0, 0))[1] + n)
         gm.ctx.goose_profile_enable(False)
         kernels = {k: {"avg_us": ms / max(n, 1) * 1e3, "launches": n} for k, (ms, n) in prof.items() if n}
         # what a pair of events reads with nothing between them (part of every figure above)
@@ -313,7 +335,8 @@ def main():
         ach = gu_bytes / (gu["avg_us"] * 1e-6) / 1e9
         roofline = {"kernel": "k_gemm_bf16<MT,NW,EPI_SWIGLU> (gate/up projection + SwiGLU)", "bound": "hbm",
                     "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": recorded_traffic(args.workload),
+                    "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": rec["gate_up_bytes"],
+                    "traffic_source": rec["source"],
                     "bytes_per_launch": gu_bytes, "avg_us": round(gu["avg_us"], 2),
                     "timing": "HIP events around each launch on the launch stream, averaged over the timed steps",
                     "empty_event_pair_us": round(floor_us, 2)}
@@ -321,7 +344,8 @@ def main():
     # ---- CPU baseline: the oracle on a bounded sample (two layers + LM head of the same step)
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(shape, gm, args.seed, B, P0, tree_kind, log)
+        n_cpu = max(2, min(8, int(round(8 * 6.7e9 / (shape.n_layers * shape.layer_param_count())))))
+        cpu = cpu_baseline(shape, gm, args.seed, [(trees[t], toks[t], P_hist[t]) for t in range(W, min(total, W + n_cpu))], log)
 
     out = {
         "metric": "tree-verify steps/s + achieved HBM GB/s, 7B-shape, B=64 spine tree, KV 1024"
@@ -337,6 +361,8 @@ def main():
         "tokens_emitted_per_s": round(float(np.sum(np.asarray(acc_hist[W:]) + 1)) / elapsed, 1),
         "achieved_GBps": round(achieved, 1), "hbm_frac": round(achieved / HBM_PEAK_GBPS, 4),
         "algorithmic_GB_per_step": round(bytes_timed / K / 1e9, 3),
+        # HBM bytes of one step by the hardware counters (profiles/traffic_<workload>.txt, same build only)
+        "counter_GB_per_step": None if rec["step_bytes"] is None else round(rec["step_bytes"] / 1e9, 3),
         # evidence that the matrix cores keep up with the stream (not the bound): 2 flops per weight per node
         # for the projections and the LM head, 4 * B * (P + B) * hidden per layer for the attention
         "achieved_TFLOPs": round(sum(2.0 * B * (shape.n_layers * shape.layer_param_count() + shape.vocab * shape.hidden)
@@ -456,11 +482,12 @@ def bench_batched(args, shape, P0, K, W, log):
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(shape, gm, seed, B, P0, tree_kind, log, n_steps=14):
-    """Times the NumPy fp64 oracle on a bounded sample of this workload: `n_steps` verification steps
-    (different trees and draft tokens, the device's own prefix KV as input, the same weights) through
-    half of the decoder layers, plus LM head, argmax and walk; the layer time is scaled to the full
-    layer count.  About 10 s of oracle arithmetic at the 7B shape."""
+def cpu_baseline(shape, gm, seed, steps_in, log):
+    """Times the NumPy fp64 oracle on the first timed steps of this very run: the same trees and draft
+    tokens, each step's own committed KV prefix (read back from the device: the prefix is an input of the
+    step on both sides), the same weights, through ALL decoder layers, the LM head, the argmax and the
+    walk.  One layer's weights are converted to fp64 at a time, outside the timed region (the GPU side
+    is timed with its weights resident too); only the oracle's arithmetic is timed."""
     import torch
     import goose_inputs as gi
     from oracle import goose_oracle as orc
@@ -473,43 +500,43 @@ def cpu_baseline(shape, gm, seed, B, P0, tree_kind, log, n_steps=14):
     def f64(t):
         return t.detach().to("cpu").to(torch.float64).numpy()
 
-    n_s = min(16, shape.n_layers)
-    log(f"cpu baseline: {n_steps} steps through a {n_s}-layer oracle sample")
-    om = orc.OracleModel(shape.n_heads, shape.head_dim, shape.rope_base, shape.rms_eps, [None] * n_s,
+    n_steps, L = len(steps_in), shape.n_layers
+    log(f"cpu baseline: {n_steps} whole steps through the {L}-layer oracle")
+    om = orc.OracleModel(shape.n_heads, shape.head_dim, shape.rope_base, shape.rms_eps, [None] * L,
                          f64(gm.embed), f64(gi.lm_head(shape, seed, gm.device)),
                          f64(gi.final_norm(shape, seed, gm.device)), n_kv_heads=shape.kv_heads, qk_norm=shape.qk_norm)
-    kr, vr = gm.k_rows(0, P0), gm.v_rows(0, P0)
+    P_top = max(P for _, _, P in steps_in)
+    kr, vr = gm.k_rows(0, P_top), gm.v_rows(0, P_top)   # slots below a step's P still hold that step's prefix
     steps = []
-    for t in range(n_steps):
-        tree = make_tree(tree_kind, t)
-        toks = gi.draft_tokens_uniform(seed + t, tree.parent, shape.vocab, 1 + t)
+    t_total = 0.0
+    for tree, toks, P in steps_in:
+        ta = time.perf_counter()
         anc, depth = orc.ancestor_mask(tree.parent)
-        steps.append({"tree": tree, "toks": toks, "pos": P0 + depth,
-                      "allow": np.concatenate([np.ones((B, P0), dtype=bool), anc], axis=1),
-                      "x": om.embed[toks.astype(np.int64)]})
-    t_layers = 0.0
-    for l in range(n_s):  # one layer's fp64 weights at a time; only the oracle's arithmetic is timed
+        steps.append({"tree": tree, "toks": toks, "P": P, "pos": P + depth,
+                      "allow": np.concatenate([np.ones((tree.B, P), dtype=bool), anc], axis=1),
+                      "x": om.embed[np.asarray(toks).astype(np.int64)]})
+        t_total += time.perf_counter() - ta
+    for l in range(L):
         w = {k: f64(v) for k, v in gi.layer_weights(shape, seed, l, gm.device).items()}
         Kc, Vc = f64(kr[l]), f64(vr[l])
         ta = time.perf_counter()
         for st in steps:
-            st["x"], _, _ = orc.decoder_layer(om, w, st["x"], Kc, Vc, st["pos"], st["allow"])
-        t_layers += time.perf_counter() - ta
+            st["x"], _, _ = orc.decoder_layer(om, w, st["x"], Kc[:, :st["P"]], Vc[:, :st["P"]], st["pos"], st["allow"])
+        t_total += time.perf_counter() - ta
         del w, Kc, Vc
-    tb = time.perf_counter()
+    ta = time.perf_counter()
     for st in steps:
         logits = orc.final_logits(om, st["x"])
         x_hat = orc.argmax_lowest(logits)
         orc.greedy_walk(st["tree"].parent, st["toks"], st["tree"].is_spine, x_hat)
-    tc = time.perf_counter()
-    t_step = (t_layers / n_s * shape.n_layers + (tc - tb)) / n_steps
-    log(f"cpu baseline: {n_steps} x {n_s} layers {t_layers:.2f}s, heads {tc - tb:.2f}s -> {t_step:.2f}s/step "
-        f"on {threads} threads")
+    t_total += time.perf_counter() - ta
+    t_step = t_total / n_steps
+    log(f"cpu baseline: {n_steps} steps x {L} layers + heads {t_total:.2f}s -> {t_step:.2f}s/step on {threads} threads")
     return {"value": round(1.0 / t_step, 5), "unit": "steps/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{n_steps} steps (B={B}, P={P0}, different trees and tokens) through {n_s} of "
-                      f"{shape.n_layers} decoder layers + LM head + walk; layer time scaled linearly to "
-                      f"{shape.n_layers} layers",
-            "seconds_measured": round(t_layers + tc - tb, 2)}
+            "sample": f"the first {n_steps} timed steps of this run (same trees, draft tokens and KV prefixes), "
+                      f"all {L} decoder layers + LM head + argmax + walk",
+            "extrapolated": False, "blas_threads": int(threads), "nproc": int(os.cpu_count() or 1),
+            "seconds_measured": round(t_total, 2)}
 
 
 if __name__ == "__main__":

@@ -387,7 +387,9 @@ int goose_gemm_swiglu_packed_ex(int dtype, const void* d_a, int lda, int terms, 
  * hipEvents recorded on the caller's stream (this adds gaps between kernels: use it to time
  * kernels, not whole steps; do not enable it under stream capture).  goose_profile_read
  * synchronises the stream, adds the elapsed milliseconds per kernel kind into
- * h_ms_sum[goose_profile_kinds()] / h_count[...] (HOST arrays) and resets the records. */
+ * h_ms_sum[goose_profile_kinds()] / h_count[...] (HOST arrays) and resets the records.
+ * goose_profile_enable creates the events (a pool for 16384 launches between two reads; launches
+ * beyond that go untimed), so the timed entry points still create and allocate nothing. */
 int goose_profile_enable(goose_ctx* ctx, int enable);
 int goose_profile_kinds(void);
 const char* goose_profile_kind_name(int kind);

@@ -42,6 +42,7 @@ const char* const kProfNames[PK_COUNT] = {"rmsnorm_residual", "gemm_qkv", "rope_
                                           "gemm_gate_up_swiglu", "gemm_down", "gemm_lm_head", "argmax",
                                           "harvest_topk", "mask_embed_accept_compact"};
 }  // namespace
+enum { GOOSE_PROFILE_POOL = 16384 };  // launches that can be timed between two goose_profile_read calls
 struct goose_prof {
   bool on = false;
   std::vector<hipEvent_t> ev;   // pairs: ev[2i] start, ev[2i+1] end
@@ -54,13 +55,7 @@ struct ProfScope {
   hipStream_t st;
   ProfScope(goose_ctx* c, int kind, hipStream_t s) : p(c->prof && c->prof->on ? c->prof : nullptr), st(s) {
     if (!p) return;
-    if (p->used * 2 >= p->ev.size()) {
-      hipEvent_t a, b;
-      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { p = nullptr; return; }
-      p->ev.push_back(a);
-      p->ev.push_back(b);
-      p->kind.push_back(kind);
-    }
+    if (p->used * 2 >= p->ev.size()) { p = nullptr; return; }  // the pool is used up: not timed (nothing is created here)
     p->kind[p->used] = kind;
     (void)hipEventRecord(p->ev[2 * p->used], st);
   }
@@ -822,6 +817,16 @@ int goose_profile_enable(goose_ctx* c, int enable) {
   if (!c) return GOOSE_ERR_ARG;
   if (!c->prof) c->prof = new (std::nothrow) goose_prof();
   if (!c->prof) return GOOSE_ERR_ARG;
+  // all events are created here, so that the timed entry points themselves create nothing
+  if (enable && c->prof->ev.empty()) {
+    c->prof->ev.reserve(2 * GOOSE_PROFILE_POOL);
+    c->prof->kind.assign(GOOSE_PROFILE_POOL, 0);
+    for (int i = 0; i < 2 * GOOSE_PROFILE_POOL; ++i) {
+      hipEvent_t e;
+      GOOSE_HIP_TRY(hipEventCreate(&e));
+      c->prof->ev.push_back(e);
+    }
+  }
   c->prof->on = enable != 0;
   return GOOSE_OK;
 }

@@ -58,6 +58,40 @@ def counter_per_kernel(db, counter):
     return {k: (len(v), sum(x for x, _ in v) / len(v), sum(d for _, d in v) / len(v) / 1e3) for k, v in acc.items()}
 
 
+def last_step_total(db, counter):
+    """(sum of the counter, dispatches) over the last verification step of the run: from the last
+    k_build_mask dispatch up to (not including) the copy probe that follows the steps."""
+    c = sqlite3.connect(db)
+    q = ("select p.dispatch_id, k.name, sum(p.counter_value) from pmc_events p join kernels k "
+         "on p.dispatch_id = k.dispatch_id where p.counter_name = ? group by p.dispatch_id order by k.start")
+    rows = [(d, short_name(n), v) for d, n, v in c.execute(q, (counter,))]
+    first = max((i for i, r in enumerate(rows) if r[1].startswith("k_build_mask")), default=None)
+    if first is None:
+        return None
+    step = []
+    for r in rows[first:]:
+        if r[1].startswith("k_copy_probe"):
+            break
+        if r[1].startswith("k_"):
+            step.append(r)
+    return sum(r[2] for r in step), len(step)
+
+
+def source_hash():
+    """First 12 hex digits of the SHA-256 over the library's sources (csrc/ and include/goose.h, sorted by
+    name): says which build a counter summary belongs to."""
+    import hashlib
+    import os
+    pkg = os.path.dirname(os.path.abspath(__file__))
+    files = sorted(os.path.join(pkg, "csrc", f) for f in os.listdir(os.path.join(pkg, "csrc")))
+    files.append(os.path.join(os.path.dirname(pkg), "include", "goose.h"))
+    h = hashlib.sha256()
+    for f in files:
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:12]
+
+
 def print_traffic(fetch_db, write_db, probe_bytes):
     fetch = counter_per_kernel(fetch_db, "FETCH_SIZE")
     write = counter_per_kernel(write_db, "WRITE_SIZE")
@@ -70,6 +104,11 @@ def print_traffic(fetch_db, write_db, probe_bytes):
     w_unit = probe_bytes / pw[0][1]
     print(f"copy probe of {probe_bytes} bytes: FETCH_SIZE reads {pf[0][1]:.1f} -> {f_unit:.2f} bytes per count "
           f"(1024 if it counted KiB exactly); WRITE_SIZE reads {pw[0][1]:.1f} -> {w_unit:.2f} bytes per count")
+    import datetime
+    print(f"recorded {datetime.date.today().isoformat()} for the library sources with hash {source_hash()}")
+    lf, lw = last_step_total(fetch_db, "FETCH_SIZE"), last_step_total(write_db, "WRITE_SIZE")
+    if lf and lw:
+        print(f"last step of the run: {lf[1]} launches, fetch {lf[0] * f_unit / 1e6:.2f} MB, write {lw[0] * w_unit / 1e6:.2f} MB")
     print(f"{'kernel':52s} {'wgs_x':>6s} {'gy':>3s} {'n':>5s} {'avg_us':>8s} {'fetch_MB':>10s} {'write_MB':>10s}")
     for key in sorted(fetch, key=lambda k: -fetch[k][0] * fetch[k][2]):
         if not key[0].startswith("k_"):
