@@ -406,6 +406,7 @@ def bench_batched(args, shape, P0, K, W, log):
             out = gm.verify_step_calls(prefix[done:done + m], ch.parent, ch.is_spine, commit=False)
             done += m
             gm.set_P(done)
+        log(f"request {r} prefilled")
         tree = gi.tree_random(Br, seed=r, spine_len=min(8, Br - 1))
         tokens = gi.draft_tokens_uniform(args.seed + r, tree.parent, shape.vocab, int(out["argmax"][m - 1].item()))
         t, p, s = gm.stage_tree(tokens, tree.parent, tree.is_spine)
@@ -440,18 +441,23 @@ def bench_batched(args, shape, P0, K, W, log):
             fn()
         torch.cuda.current_stream().wait_stream(s)
         torch.cuda.synchronize()
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=s):
-            fn()
-        torch.cuda.synchronize()
+        if args.graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=s):
+                fn()
+            torch.cuda.synchronize()
+            step = g.replay
+        else:   # plain launches (what the profiler's counter passes use)
+            step = fn
         for q in reqs:
             q["P"].fill_(P0)
         for _ in range(W):
-            g.replay()
+            step()
         torch.cuda.synchronize()
+        log(f"{fn.__name__}: timing {K} steps")
         t1 = time.perf_counter()
         for _ in range(K):
-            g.replay()
+            step()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t1
         P_end = [int(q["P"].item()) for q in reqs]
@@ -471,7 +477,8 @@ def bench_batched(args, shape, P0, K, W, log):
            "ms_per_step": round(dt_b / K * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": shape.dtype, "data": "synthetic",
            "config": {"workload": args.workload, "shape": shape.name, "requests": n, "B_per_request": Br,
-                      "rows_per_pass": rows, "P0": P0, "P_end": P_b, "drafts": "random", "launch": "hipGraph per step"},
+                      "rows_per_pass": rows, "P0": P0, "P_end": P_b, "drafts": "random",
+                      "launch": "hipGraph per step" if args.graph else "plain"},
            "one_by_one_ms_per_step": round(dt_s / K * 1e3, 4), "speedup_over_one_by_one": round(dt_s / dt_b, 3),
            "draft_tokens_verified_per_s": round(n * Br * K / dt_b, 1),
            "achieved_GBps": round((w_bytes + kv_bytes) / (dt_b / K) / 1e9, 1),

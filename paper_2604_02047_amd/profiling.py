@@ -4,6 +4,7 @@ for the library's copy probe (a kernel that moves a known number of bytes) in th
 
     python -m paper_2604_02047_amd.profiling kernels <run_results.db>
     python -m paper_2604_02047_amd.profiling traffic <fetch_run.db> <write_run.db> <copy_probe_bytes>
+    python -m paper_2604_02047_amd.profiling counters <pmc_run.db> [<pmc_run.db> ...]
 
 Reads only; prints to stdout.  Nothing here runs on the GPU.
 """
@@ -119,11 +120,40 @@ def print_traffic(fetch_db, write_db, probe_bytes):
               f"{wv * w_unit / 1e6:10.2f}")
 
 
+def print_counters(dbs):
+    """Per kernel and launch shape: the mean over its launches of every counter the runs collected (a raw
+    counter summed over its hardware instances, a derived metric as rocprofv3 evaluated it)."""
+    acc = collections.defaultdict(lambda: collections.defaultdict(list))
+    durs = collections.defaultdict(list)
+    names = []
+    for db in dbs:
+        c = sqlite3.connect(db)
+        q = ("select k.name, k.grid_x, k.grid_y, k.workgroup_x, p.counter_name, p.dispatch_id, sum(p.counter_value), "
+             "k.end - k.start from pmc_events p join kernels k on p.dispatch_id = k.dispatch_id "
+             "group by p.dispatch_id, p.counter_name")
+        for name, gx, gy, wx, cn, _, val, dur in c.execute(q):
+            key = (short_name(name), gx // wx if wx else gx, gy)
+            acc[key][cn].append(val)
+            durs[key].append(dur)
+            if cn not in names:
+                names.append(cn)
+    print(f"{'kernel':44s} {'wgs_x':>6s} {'gy':>3s} {'n':>5s} {'avg_us':>8s} " + " ".join(f"{n[-22:]:>22s}" for n in names))
+    for key in sorted(acc, key=lambda k: -sum(durs[k])):
+        if not key[0].startswith("k_"):
+            continue
+        v = acc[key]
+        n = max(len(x) for x in v.values())
+        print(f"{key[0][:44]:44s} {key[1]:6d} {key[2]:3d} {n:5d} {sum(durs[key]) / len(durs[key]) / 1e3:8.1f} " +
+              " ".join(f"{sum(v[cn]) / len(v[cn]):22.5g}" if cn in v else f"{'-':>22s}" for cn in names))
+
+
 def main(argv):
     if len(argv) >= 3 and argv[1] == "kernels":
         print_kernels(argv[2])
     elif len(argv) >= 5 and argv[1] == "traffic":
         print_traffic(argv[2], argv[3], int(argv[4]))
+    elif len(argv) >= 3 and argv[1] == "counters":
+        print_counters(argv[2:])
     else:
         raise SystemExit(__doc__)
 
