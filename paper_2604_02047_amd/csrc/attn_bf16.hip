@@ -203,7 +203,7 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
       b_hi = (int)(((long)rest * (split + 1)) / (nsplit - 1));
     }
   }
-  // a wavefront whose query tile lies wholly beyond the tree (a 3-tile tree in the 4-tile kernel)
+  // a wavefront whose query tile lies wholly beyond the tree
   // walks no blocks; it still takes part in the prologue and in the barriers
   const bool idle = qh * 32 >= B;
   const int nb_split = idle ? 0 : b_hi - b_lo;
@@ -662,6 +662,7 @@ int launch_d(int QT, int ng, dim3 grid, hipStream_t st, const AttnArgs& a, const
   // one wavefront per (query tile, key group); at most 8 wavefronts per workgroup
   if (QT == 1) return ng == 4 ? launch_cfg<D, 4, 1>(grid, st, a, t) : launch_cfg<D, 2, 1>(grid, st, a, t);
   if (QT == 2) return ng == 4 ? launch_cfg<D, 4, 2>(grid, st, a, t) : launch_cfg<D, 2, 2>(grid, st, a, t);
+  if (QT == 3) return launch_cfg<D, 2, 3>(grid, st, a, t);
   return launch_cfg<D, 2, 4>(grid, st, a, t);
 }
 
@@ -714,16 +715,15 @@ int launch_attn_16(int dtype, const float* part, int ks, size_t part_stride, siz
   if ((oterms != 1 && oterms != 2) || (o_dtype != GOOSE_DTYPE_BF16 && o_dtype != GOOSE_DTYPE_F16)) return GOOSE_ERR_ARG;
   const AttnArgs a{part, ks, part_stride, part_ld, n_heads, n_kv_heads, (const float2*)cs, cap, gq, gk, eps,
                    att_o, att_ml, Bpad, o, ldo, oterms, o_dtype == GOOSE_DTYPE_F16 ? 1 : 0, dtype == GOOSE_DTYPE_F16, flags};
-  // a 3-tile tree runs the 4-tile kernel, which reads projection rows up to row0 + 128
-  auto tiles_of = [](int B) { const int qt = (B + 31) / 32; return qt >= 3 ? 4 : qt; };
+  auto tiles_of = [](int B) { return (B + 31) / 32; };
   for (int r = 0; r < nseg; ++r) {
     const AttnSeg& g = segs[r];
     if (g.B < 1 || g.B > GOOSE_MAX_B || g.row0 < 0 || (g.row0 & 31) || g.row0 + tiles_of(g.B) * 32 > Bpad ||
         g.P_max < 0 || g.P_max + g.B > cap || !g.kc || !g.vc || !g.dP || !g.mask)
       return GOOSE_ERR_ARG;
   }
-  // one launch per class of tree size (1, 2, or 3-4 query tiles): the class fixes the workgroup shape
-  for (int cls : {1, 2, 4}) {
+  // one launch per class of tree size (1 to 4 query tiles): the class fixes the workgroup shape
+  for (int cls : {1, 2, 3, 4}) {
     SegTable<ATTN_MAX_SEGS> t{};
     int n = 0, keys_max = 0, b_max = 0;
     for (int r = 0; r < nseg; ++r) {

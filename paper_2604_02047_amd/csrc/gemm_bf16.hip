@@ -144,8 +144,9 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
   constexpr int STAGE_BYTES = MT * 32 * ROW_BYTES;
   constexpr int ROWS_PER_COPY = 64 / SU;               // rows one wavefront-wide copy instruction fills
   constexpr int COPIES = MT * 32 / ROWS_PER_COPY;
-  constexpr int CPW = COPIES / NWAVES;                 // copy instructions per wavefront per stage
-  static_assert(COPIES % NWAVES == 0, "the A copy must divide evenly over the wavefronts");
+  // copy instructions per wavefront per stage: the same number for every wavefront (the wait counts
+  // below are immediates); where the copies do not divide evenly the last ones are issued twice
+  constexpr int CPW = (COPIES + NWAVES - 1) / NWAVES;
   // SwiGLU: every wavefront passes its accumulators through LDS as fp32
   constexpr int SWAP_BYTES = (EPI == EPI_SWIGLU) ? NW * MT * 16 * 64 * 4 : 0;
   constexpr int CT_ROW = 33;  // floats per row of a transposed-read C tile (odd: conflict-free row scans)
@@ -225,7 +226,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
   const int row_units = lda >> 3;  // 16-byte units per operand row
 #pragma unroll
   for (int q = 0; q < CPW; ++q) {
-    const int c = wave * CPW + q;
+    const int c = min(wave * CPW + q, COPIES - 1);
     const int row = c * ROWS_PER_COPY + lane / SU, pos = lane % SU;
     const int unit = (pos & ~15) | ((pos ^ row) & 15);
     a_src[q] = reinterpret_cast<const u32x4*>(A) + (size_t)(row_base + row) * row_units +
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
     const int ic = min(i, nst - 1);
 #pragma unroll
     for (int q = 0; q < CPW; ++q) {
-      const int c = wave * CPW + q;  // (wavefront-uniform)
+      const int c = min(wave * CPW + q, COPIES - 1);  // (wavefront-uniform)
       unsigned char* dst = lds_buf(buf_c) + c * 1024;
 #if defined(__HIP_DEVICE_COMPILE__)  // (the host pass knows no such builtin and would silently drop the kernel's stub)
       __builtin_amdgcn_global_load_lds(a_src[q] + (size_t)ic * SU, GOOSE_LDS_PTR(dst), 16, 0, 0);
@@ -457,6 +458,7 @@ __global__ __launch_bounds__(64 * NW) void k_gemm_bf16(const typename Mma16<F16>
 struct GemmCall {
   const void* A; int lda; const void* Wp; int Npad, Kpad, B, ksplit; void* out; size_t ldo, split_stride;
   hipStream_t st; void* top2; int n_valid; bool f16; int terms; float out_scale; int32_t* flags;
+  int gx = 0;  // grid width in workgroups per K range (0: chosen by launch_one)
 };
 
 template <int MT, int NW, int TERMS, int EPI, bool CHUNKED, bool F16>
@@ -482,10 +484,11 @@ int launch_one(const GemmCall& g) {
   int gx = (ntiles + NW - 1) / NW;
   // SwiGLU tiles stand alone and are dealt with a stride of the grid width: a grid as wide as the
   // chip (or as the tiles allow) spreads the weight streams over more compute units
-  if (EPI == EPI_SWIGLU && gx < 256) gx = ntiles < 256 ? ntiles : 256;
+  if (g.gx > 0) gx = g.gx;
+  else if (EPI == EPI_SWIGLU && gx < 256) gx = ntiles < 256 ? ntiles : 256;
   // the same for the split-K products: tiles of one K range are dealt with a stride of the grid width,
   // and the grid is widened until all ranges together fill the chip
-  if (EPI == EPI_PARTIAL && gx * g.ksplit < 256) {
+  if (g.gx == 0 && EPI == EPI_PARTIAL && gx * g.ksplit < 256) {
     const int want = (256 + g.ksplit - 1) / g.ksplit;
     gx = want < ntiles ? (want > gx ? want : gx) : ntiles;
   }
@@ -497,6 +500,24 @@ int launch_one(const GemmCall& g) {
     if (nchunk > 1) return launch_terms<MT, NW, EPI, true>(g, grid, gx, gps, nchunk);
   }
   return launch_terms<MT, NW, EPI, false>(g, grid, gx, gps, nchunk);
+}
+
+// five-wavefront workgroups (single row chunk only): see launch_gemm_16
+template <int MT, int EPI>
+int launch_five(const GemmCall& g) {
+  const int granules = g.Kpad / KGRAN;
+  const int gps = (granules + g.ksplit - 1) / g.ksplit;
+  return launch_terms<MT, 5, EPI, false>(g, dim3(g.gx, g.ksplit), g.gx, gps, 1);
+}
+template <int EPI>
+int launch_mt5(int MT, const GemmCall& g) {
+  switch (MT) {
+    case 1: return launch_five<1, EPI>(g);
+    case 2: return launch_five<2, EPI>(g);
+    case 3: return launch_five<3, EPI>(g);
+    case 4: return launch_five<4, EPI>(g);
+  }
+  return GOOSE_ERR_ARG;
 }
 
 template <int NW, int EPI>
@@ -579,10 +600,19 @@ int launch_gemm_16(int dtype, int epi, const void* A, int lda, int terms, const 
     return launch_gemm_rows_16(dtype, epi, A, lda, terms, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, out_scale,
                                flags, st);
   const int MT = (B + 31) / 32;
+  // More four-tile workgroups than compute units would run as one round plus a few stragglers (or
+  // with some units loaded twice, which then take twice as long: a unit pulls only so many bytes
+  // per microsecond).  Where five tiles per workgroup fit all tiles into one round of at most 256
+  // workgroups, take those: 33B gate/up, 1120 tiles = 256 workgroups of five wavefronts.
+  const int ntiles = Npad / 32;
+  const int gx5 = 256 / ksplit;
+  const bool five = nw == 4 && ((ntiles + 3) / 4) * ksplit > 256 && gx5 * 5 >= ntiles;
   if (epi == EPI_SWIGLU) {
-    const GemmCall g{A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st, nullptr, 0, f16, terms, out_scale, flags};
+    GemmCall g{A, lda, Wp, Npad, Kpad, B, 1, out, ldo, 0, st, nullptr, 0, f16, terms, out_scale, flags};
+    if (five) { g.gx = gx5; return launch_mt5<EPI_SWIGLU>(MT, g); }
     return nw == 4 ? launch_mt<4, EPI_SWIGLU>(MT, g) : launch_mt<2, EPI_SWIGLU>(MT, g);
   }
-  const GemmCall g{A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st, nullptr, 0, f16, terms, out_scale, flags};
+  GemmCall g{A, lda, Wp, Npad, Kpad, B, ksplit, out, ldo, out_split_stride, st, nullptr, 0, f16, terms, out_scale, flags};
+  if (five) { g.gx = gx5; return launch_mt5<EPI_PARTIAL>(MT, g); }
   return nw == 4 ? launch_mt<4, EPI_PARTIAL>(MT, g) : launch_mt<2, EPI_PARTIAL>(MT, g);
 }

@@ -103,6 +103,7 @@ def test_gemm_ragged_shapes():
 
 
 @pytest.mark.parametrize("B,F,K,nw", [(16, 96, 256, 2), (16, 2752, 1024, 2), (64, 2752, 1024, 4), (80, 352, 640, 2),
+                                       (80, 17920, 256, 4),
                                        (128, 704, 256, 4), (33, 64, 4096, 2), (300, 704, 256, 4), (512, 352, 640, 2),
                                        (160, 2752, 1024, 4)])
 @pytest.mark.parametrize("dt", [torch.bfloat16, torch.float16])
@@ -135,6 +136,13 @@ def test_gemm_swiglu_epilogue(B, F, K, nw, dt, terms):
         out = (pair[:, :, 0] + pair[:, :, 1]).reshape(B, F).numpy()
         tol = 2e-5
     assert np.abs(out - ref).max() <= tol * np.abs(ref).max()
+
+
+def test_gemm_more_tiles_than_one_round_of_four_tile_workgroups():
+    """Beyond 1024 column tiles the launcher switches to five-wavefront workgroups (one round of 256)."""
+    _run(80, 33024, 256, 4, 1)            # 1032 tiles
+    _run(64, 20000, 512, 4, 2, seed=3)    # 625 tiles x 2 K ranges
+    _run(33, 40960, 128, 4, 1, seed=4)    # 1280 tiles: the last five-wide grid that fits
 
 
 def test_gemm_repeated_large_launches_are_stable():
