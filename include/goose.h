@@ -138,7 +138,9 @@ int goose_check_parent(const int32_t* h_parent, int B);
  * The kernels stream weights from a packed copy: for the 16-bit types each matrix is re-tiled so
  * that one wavefront load instruction reads 1 KiB of consecutive bytes that is exactly
  * one MFMA operand (32 output rows x 16 inputs); q,k,v rows are concatenated and
- * gate/up rows interleaved in blocks of 32.  For fp32 the blob holds plain row-major
+ * gate/up rows interleaved in blocks of 16 (a 32-row tile = the gate rows and the up rows of 16
+ * outputs); with bf16 storage and GOOSE_ACT_F16 the packed elements are the fp16 values 256 * w (exact
+ * for 2^-32 <= |w| < 256, else GOOSE_FLAG_WEIGHT_RANGE).  For fp32 the blob holds plain row-major
  * matrices.  The caller allocates goose_packed_layer_bytes() per layer; all layers of a
  * model live in one allocation, layer l at byte offset l * goose_packed_layer_bytes(). */
 size_t goose_packed_layer_bytes(const goose_ctx* ctx);
