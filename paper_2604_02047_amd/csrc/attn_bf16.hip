@@ -123,17 +123,17 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
     // grouped queries: the heads of one KV head stream the same cache blocks, so they share an XCD
     // (KV head j on XCD j % 8) and all but the first find the blocks in its L2; 8 | n_kv_heads
     // makes this a permutation of the heads
-    const int grp = n_heads / n_kv_heads, xcd = h & 7, s = h >> 3;
-    const int t = s / grp;
+    const int grp = (int)((unsigned)n_heads / (unsigned)n_kv_heads), xcd = h & 7, s = h >> 3;
+    const int t = (int)((unsigned)s / (unsigned)grp);
     h = (xcd + 8 * t) * grp + (s - t * grp);
   }
   const int l31 = lane & 31, hh = lane >> 5;
   // grouped queries: `group` query heads share KV head kvh; their projections sit at columns
   // [0,Hq) q, [Hq, Hq+Hkv) k, [Hq+Hkv, Hq+2Hkv) v of the fused projection
-  const int group = n_heads / n_kv_heads, kvh = h / group;
+  const int group = (int)((unsigned)n_heads / (unsigned)n_kv_heads), kvh = (int)((unsigned)h / (unsigned)group);
   const int Hq = n_heads * D, Hkv = n_kv_heads * D;
   const int kcol = Hq + kvh * D - h * D, vcol = kcol + Hkv;  // relative to this head's q columns
-  const bool tail_writer = (h % group) == 0;                  // one head of the group stores the tree's K/V
+  const bool tail_writer = h == kvh * group;                 // one head of the group stores the tree's K/V
   int P = *sg.dP;   // (used further down: the loads below do not wait for it)
   const bool last = blockIdx.y == gridDim.y - 1;
   // ---- q of all query tiles (every split), k and v of the tree (last split): sum the split-K
@@ -192,15 +192,18 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   if (nsplit == 1) {
     b_lo = 0; b_hi = nbp;
   } else {
+    // (unsigned 32-bit divisions: block counts times split counts stay far below 2^32, and a 64-bit
+    // division is a hundred instructions of code that every wavefront would fetch and run once)
     const int tc = nbt * TAIL_COST;
-    const int per = (nbp + tc + nsplit - 1) / nsplit;
+    const int per = (int)((unsigned)(nbp + tc + nsplit - 1) / (unsigned)nsplit);
     int pl = per - tc;
     pl = pl < 0 ? 0 : (pl > nbp ? nbp : pl);
     const int rest = nbp - pl;  // dealt evenly to splits 0 .. nsplit-2
     if (last) { b_lo = rest; b_hi = nbp; }
     else {
-      b_lo = (int)(((long)rest * split) / (nsplit - 1));
-      b_hi = (int)(((long)rest * (split + 1)) / (nsplit - 1));
+      const unsigned den = (unsigned)(nsplit - 1);
+      b_lo = (int)((unsigned)(rest * split) / den);
+      b_hi = (int)((unsigned)(rest * (split + 1)) / den);
     }
   }
   // a wavefront whose query tile lies wholly beyond the tree
