@@ -486,6 +486,15 @@ def bench_batched(args, shape, P0, K, W, log):
            # projections + LM head only (2 flops per weight per row); dense bf16 MFMA peak 2500 TFLOP/s
            "projection_TFLOPs": round(2.0 * n * Br * (w_bytes / es) / (dt_b / K) / 1e12, 1)}
     out["mfma_frac"] = round(out["projection_TFLOPs"] / 2500.0, 4)
+    # beyond 128 stacked rows the projections meet the matrix cores: priced against the dense MFMA peak of
+    # the operand type, as a whole-step rate (matrix flops of all projections / step time; the kernels' own
+    # durations and matrix-core counters are in profiles/*_batched_*.txt).  No oracle timing in this mode.
+    out["roofline"] = {"kernel": "projections of the step (k_gemm_rows beyond 128 rows, k_gemm_bf16 up to 128)",
+                       "bound": "mfma" if rows > 128 else "hbm",
+                       "achieved": out["projection_TFLOPs"] if rows > 128 else out.get("achieved_GBps"),
+                       "peak": 2500.0 if rows > 128 else HBM_PEAK_GBPS, "unit": "TFLOP/s" if rows > 128 else "GB/s",
+                       "frac": out["mfma_frac"] if rows > 128 else out.get("hbm_frac"), "traffic": None}
+    out["cpu_baseline"] = None
     print(json.dumps(out), flush=True)
 
 
