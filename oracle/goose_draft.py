@@ -10,7 +10,7 @@ Only tier 1 of the adjacency table (one-token context, dense [vocab][K] ids and 
 modelled; the two-token hash tier and the score-proportional re-weighting of branch widths
 (App. C) are not.
 
-Readings where the paper leaves room (each also listed in the design doc):
+Readings where the paper leaves room:
   * context match: for every n in the query lengths, the MOST RECENT earlier occurrence of the
     sequence's last n tokens; the draft chain is the continuation after the match of the largest
     n that matched, at most `max_len` tokens, never running past the end of the sequence;
