@@ -566,6 +566,525 @@ __global__ __launch_bounds__(64 * NG * NQH) void k_attn_fused(
   }
 }
 
+// ---- Trees of more than 64 nodes (three or four 32-query tiles), head size 128 ------------------
+// In k_attn_fused every wavefront loads the key blocks it walks itself, so a block is pulled into
+// the compute unit once per query tile; with three or four tiles that traffic (not HBM) bounds the
+// kernel.  Here the workgroup (2 key groups x NQH query tiles, one wavefront each) brings every
+// block in ONCE, global -> LDS without passing registers (global_load_lds, 1 KiB per instruction,
+// which is exactly one operand piece of the operand-ordered caches), into a ring of RING slots of
+// one block (8 KiB of K + 8 KiB of V) each; the wavefronts read their operands from the ring.  The
+// prefix blocks of the split are taken two per step, block 2j by key group 0 and block 2j+1 by key
+// group 1; block k lives in slot k % RING.  Step j: wait until blocks 2j and 2j+1 have landed,
+// barrier (which also tells that the blocks of step j-1 have been consumed), issue the copies of
+// blocks 2j+3 and 2j+4 into the two slots just freed, compute.  Three blocks (48 KiB) are in flight
+// per compute unit, at no cost in registers.  Every wavefront issues the same number of copies per
+// block (LPB), so that one immediate wait count fits all of them; blocks beyond the split's range
+// re-read its last block (from the L2) and are never consumed.  The tree's own blocks (last split)
+// follow from LDS as in k_attn_fused, without barriers.  The ring also serves as the staging
+// buffer of the rotated queries (both terms end up in registers) and as the merge buffer at the
+// end.  Arithmetic, masking, summation order within a wavefront and the outputs are those of
+// k_attn_fused with two key groups, except that a group walks every other block instead of a
+// contiguous half.
+#define GOOSE_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }  // s_waitcnt vmcnt(n) only
+
+template <int NQH, bool F16, int TS>
+__global__ __launch_bounds__(128 * NQH) void k_attn_wide(
+    const SegTable<TS> segs, int n_heads, int n_kv_heads, int cap, const float* part, int ks, size_t part_stride,
+    size_t part_ld, const float2* cs, const typename Mma16<F16>::T* __restrict__ gq,
+    const typename Mma16<F16>::T* __restrict__ gk, float eps, float* __restrict__ att_o, float* __restrict__ att_ml,
+    int Bpad, unsigned short* o_out, int ldo, int oterms, int o_f16, int32_t* __restrict__ flags) {
+  typedef typename Mma16<F16>::T T;
+  typedef typename Mma16<F16>::v8 op8;
+  typedef typename Mma16<F16>::v4 op4;
+  constexpr int D = 128, NG = 2;
+  const SegDev& sg = segs.s[TS == 1 ? 0 : blockIdx.z];
+  const int B = sg.B, row0 = sg.row0;
+  T* const kc = static_cast<T*>(sg.kc);
+  T* const vc = static_cast<T*>(sg.vc);
+  const uint64_t* const mask = sg.mask;
+  part += (size_t)row0 * part_ld;
+  cs += (size_t)row0 * (D / 2);
+  o_out += (size_t)row0 * ldo;
+  constexpr int NTHR = 64 * NG * NQH, NWAVES = NG * NQH;
+  constexpr int NS = D / 16;               // operand pieces (1 KiB) per block, for K and for V
+  constexpr int TROWS = NQH * 32;          // tree rows the LDS buffers hold
+  constexpr int KROW = D * 2 + 16;         // bytes per K / Q row in LDS (padded)
+  constexpr int VROW = TROWS * 2 + 16;     // bytes per V^T row in LDS (padded)
+  constexpr int KV_BYTES = TROWS * KROW + D * VROW;  // the tree's keys and values
+  constexpr int SLOT = 2 * NS * 1024;      // one block: its K pieces, then its V pieces
+  constexpr int RING = 5;
+  constexpr int RING_BYTES = RING * SLOT;
+  constexpr int OREGS = (D / 32) * 16;
+  constexpr int QUADS = (D / 32) * 4, QPW = QUADS / NG;
+  constexpr int WFLOATS = (QPW + 1) * 256;  // what a wavefront leaves for its partner at the merge
+  static_assert(2 * TROWS * KROW <= RING_BYTES, "the query staging buffer lies in the ring");
+  static_assert(NWAVES * WFLOATS * 4 <= RING_BYTES, "the merge buffer lies in the ring");
+  static_assert(KV_BYTES + RING_BYTES <= 160 * 1024, "LDS of one compute unit");
+  // (two arrays: the compiler then knows that the copies into the ring do not touch the tree's buffers)
+  __shared__ __attribute__((aligned(16))) unsigned char kv_lds[KV_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char ring[RING_BYTES];
+  unsigned char* Kt = kv_lds;                 // tree keys   [i][c]  (rotated)
+  unsigned char* Vt = kv_lds + TROWS * KROW;  // tree values [c][i]  (transposed)
+  unsigned char* Qs = ring;                   // rotated queries [i][c]: the 16-bit value ...
+  unsigned char* Ql = ring + TROWS * KROW;    // ... and the 16-bit remainder
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = wave % NG, qh = wave / NG;  // key group, query tile
+  const int split = blockIdx.y, nsplit = gridDim.y;
+  int h = blockIdx.x;  // head = the fast grid index, as in k_attn_fused (same XCD as the projection's columns)
+  if (n_kv_heads != n_heads && (n_kv_heads & 7) == 0) {
+    const int grp = (int)((unsigned)n_heads / (unsigned)n_kv_heads), xcd = h & 7, s = h >> 3;
+    const int t = (int)((unsigned)s / (unsigned)grp);
+    h = (xcd + 8 * t) * grp + (s - t * grp);
+  }
+  const int l31 = lane & 31, hh = lane >> 5;
+  const int group = (int)((unsigned)n_heads / (unsigned)n_kv_heads), kvh = (int)((unsigned)h / (unsigned)group);
+  const int Hq = n_heads * D, Hkv = n_kv_heads * D;
+  const int kcol = Hq + kvh * D - h * D, vcol = kcol + Hkv;
+  const bool tail_writer = h == kvh * group;
+  int P = *sg.dP;
+  const bool last = blockIdx.y == gridDim.y - 1;
+  const int nbt = (B + 31) >> 5;
+  const int rows = nbt * 32;
+  constexpr int NIT = TROWS * (D / 8) / NTHR, UG = 2;
+  static_assert(TROWS * (D / 8) % NTHR == 0 && NIT % UG == 0, "items must divide over the workgroup");
+  const float* prow[UG];
+  f32x4 acc[UG][6], acc1[UG][6];
+  f32x4 c01[UG], c23[UG];
+  bool kv[UG];
+  const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  const bool two = ks > 1;
+  auto load_items = [&](int u0) {
+#pragma unroll
+    for (int u = 0; u < UG; ++u) {
+      const int it = tid + (u0 + u) * NTHR;
+      const int i = it / (D / 8), j0 = (it % (D / 8)) * 4;
+      prow[u] = part + (size_t)i * part_ld + h * D + j0;  // row i < Bpad exists in the buffer
+      kv[u] = last && i < B;
+      const float* p1 = prow[u] + part_stride;
+#pragma unroll
+      for (int w = 0; w < 3; ++w) {
+        const bool on = w == 0 || kv[u];
+        const int col = w == 0 ? 0 : (w == 1 ? kcol : vcol);
+        acc[u][2 * w] = on ? *reinterpret_cast<const f32x4*>(prow[u] + col) : zero4;
+        acc[u][2 * w + 1] = on ? *reinterpret_cast<const f32x4*>(prow[u] + col + D / 2) : zero4;
+        acc1[u][2 * w] = (on && two) ? *reinterpret_cast<const f32x4*>(p1 + col) : zero4;
+        acc1[u][2 * w + 1] = (on && two) ? *reinterpret_cast<const f32x4*>(p1 + col + D / 2) : zero4;
+      }
+      c01[u] = *reinterpret_cast<const f32x4*>(cs + (size_t)i * (D / 2) + j0);
+      c23[u] = *reinterpret_cast<const f32x4*>(cs + (size_t)i * (D / 2) + j0 + 2);
+    }
+  };
+  if ((P < 0 || P > sg.P_max || P > cap - B) && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+    atomicOr(flags, GOOSE_FLAG_CAPACITY);
+  if (P > cap - B) P = cap - B;
+  if (P < 0) P = 0;
+
+  // ---- prefix blocks of this split (the same division as k_attn_fused)
+  const int nbp = (P + 31) >> 5;
+  int b_lo, b_hi;
+  if (nsplit == 1) {
+    b_lo = 0; b_hi = nbp;
+  } else {
+    const int tc = nbt * TAIL_COST;
+    const int per = (int)((unsigned)(nbp + tc + nsplit - 1) / (unsigned)nsplit);
+    int pl = per - tc;
+    pl = pl < 0 ? 0 : (pl > nbp ? nbp : pl);
+    const int rest = nbp - pl;
+    if (last) { b_lo = rest; b_hi = nbp; }
+    else {
+      const unsigned den = (unsigned)(nsplit - 1);
+      b_lo = (int)((unsigned)(rest * split) / den);
+      b_hi = (int)((unsigned)(rest * (split + 1)) / den);
+    }
+  }
+  const bool idle = qh * 32 >= B;          // a query tile wholly beyond the tree: copies and barriers only
+  const int nb_split = b_hi - b_lo;        // (the same for every wavefront of the workgroup)
+  const int nsteps = (nb_split + 1) >> 1;
+  const int ntail = (last && !idle) ? (nbt - g + NG - 1) / NG : 0;
+  const int total = nsteps + (ntail > 0 ? ntail : 0);
+
+  const T* kh = kc + (size_t)kvh * cap * D;
+  const T* vh = vc + (size_t)kvh * cap * D;
+
+  auto finish_items = [&](int u0) {
+#pragma unroll
+    for (int u = 0; u < UG; ++u)
+#pragma unroll
+      for (int w = 0; w < 6; ++w) acc[u][w] += acc1[u][w];
+    for (int sl = 2; sl < ks; ++sl) {
+#pragma unroll
+      for (int u = 0; u < UG; ++u) {
+        const float* p = prow[u] + sl * part_stride;
+#pragma unroll
+        for (int w = 0; w < 3; ++w)
+          if (w == 0 || kv[u]) {
+            const int col = w == 0 ? 0 : (w == 1 ? kcol : vcol);
+            acc[u][2 * w] += *reinterpret_cast<const f32x4*>(p + col);
+            acc[u][2 * w + 1] += *reinterpret_cast<const f32x4*>(p + col + D / 2);
+          }
+      }
+    }
+    if (gq != nullptr) {
+#pragma unroll
+      for (int u = 0; u < UG; ++u) {
+        const int j0 = ((tid + (u0 + u) * NTHR) % (D / 8)) * 4;
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+          float ss = 0.f;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) ss += acc[u][2 * w][e] * acc[u][2 * w][e] + acc[u][2 * w + 1][e] * acc[u][2 * w + 1][e];
+#pragma unroll
+          for (int off = 1; off < D / 8; off <<= 1) ss += __shfl_xor(ss, off, 64);
+          const float rstd = 1.0f / sqrtf(ss / (float)D + eps);
+          const T* gn = w == 0 ? gq : gk;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc[u][2 * w][e] *= rstd * (float)gn[j0 + e];
+            acc[u][2 * w + 1][e] *= rstd * (float)gn[j0 + D / 2 + e];
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UG; ++u) {
+      const int it = tid + (u0 + u) * NTHR;
+      const int i = it / (D / 8), j0 = (it % (D / 8)) * 4;
+      const float co[4] = {c01[u][0], c01[u][2], c23[u][0], c23[u][2]}, si[4] = {c01[u][1], c01[u][3], c23[u][1], c23[u][3]};
+      op4 rl, rh, rl2, rh2;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float qlo = acc[u][0][e] * co[e] - acc[u][1][e] * si[e];
+        const float qhi = acc[u][1][e] * co[e] + acc[u][0][e] * si[e];
+        rl[e] = (T)qlo;
+        rh[e] = (T)qhi;
+        rl2[e] = (T)(qlo - (float)rl[e]);
+        rh2[e] = (T)(qhi - (float)rh[e]);
+      }
+      *reinterpret_cast<op4*>(Qs + i * KROW + j0 * 2) = rl;
+      *reinterpret_cast<op4*>(Qs + i * KROW + (j0 + D / 2) * 2) = rh;
+      *reinterpret_cast<op4*>(Ql + i * KROW + j0 * 2) = rl2;
+      *reinterpret_cast<op4*>(Ql + i * KROW + (j0 + D / 2) * 2) = rh2;
+      if (last && i < rows) {  // rows of the tree's blocks beyond B are zero (kv false)
+        op4 kl, kh4, vl, vh4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          kl[e] = (T)(acc[u][2][e] * co[e] - acc[u][3][e] * si[e]);
+          kh4[e] = (T)(acc[u][3][e] * co[e] + acc[u][2][e] * si[e]);
+          vl[e] = (T)acc[u][4][e];
+          vh4[e] = (T)acc[u][5][e];
+        }
+        if (kv[u] && tail_writer) {
+          T* kw = const_cast<T*>(kh);
+          *reinterpret_cast<op4*>(kw + k_chunk_off<D>(P + i, j0 >> 4, (j0 >> 3) & 1) + (j0 & 7)) = kl;
+          *reinterpret_cast<op4*>(kw + k_chunk_off<D>(P + i, (j0 + D / 2) >> 4, (j0 >> 3) & 1) + (j0 & 7)) = kh4;
+        }
+        *reinterpret_cast<op4*>(Kt + i * KROW + j0 * 2) = kl;
+        *reinterpret_cast<op4*>(Kt + i * KROW + (j0 + D / 2) * 2) = kh4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          *reinterpret_cast<T*>(Vt + (j0 + e) * VROW + i * 2) = vl[e];
+          *reinterpret_cast<T*>(Vt + (j0 + D / 2 + e) * VROW + i * 2) = vh4[e];
+        }
+      }
+    }
+  };
+#pragma unroll 1
+  for (int u0 = 0; u0 < NIT; u0 += UG) {
+    load_items(u0);
+    finish_items(u0);
+  }
+  __syncthreads();
+
+  // ---- this wavefront's q operand, both terms, and ancestor row
+  const int qi = qh * 32 + l31;
+  op8 qf[NS], qf2[NS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) {
+    qf[s] = *reinterpret_cast<const op8*>(Qs + qi * KROW + (16 * s + 8 * hh) * 2);
+    qf2[s] = *reinterpret_cast<const op8*>(Ql + qi * KROW + (16 * s + 8 * hh) * 2);
+  }
+  uint64_t mw0 = 0, mw1 = 0;
+  if (qi < B) {
+    const int W = (B + 63) >> 6;
+    mw0 = mask[(size_t)qi * W];
+    if (W > 1) mw1 = mask[(size_t)qi * W + 1];
+  }
+  // ---- the tree's values into the cache (as in k_attn_fused)
+  if (last && tail_writer) {
+    T* vw = const_cast<T*>(vh);
+    const int g_lo = P >> 3, ngrp = ((P + B - 1) >> 3) - g_lo + 1;
+    for (int it = tid; it < ngrp * D; it += NTHR) {
+      const int c = it % D, G = g_lo + it / D;
+      const int i0 = (G << 3) - P;
+      const unsigned char* src = Vt + c * VROW;
+      T* dst = vw + v_elem_off<D>(G << 3, c);
+      if (i0 >= 0 && i0 + 8 <= B) {
+        op8 v;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = *reinterpret_cast<const T*>(src + (i0 + e) * 2);
+        *reinterpret_cast<op8*>(dst) = v;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (i0 + e >= 0 && i0 + e < B) dst[e] = *reinterpret_cast<const T*>(src + (i0 + e) * 2);
+      }
+    }
+  }
+  // Everything this wavefront has loaded or stored so far is done (the wait counts below count the
+  // ring's copies only), and every wavefront holds its queries: the staging buffer becomes the ring.
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+  __syncthreads();
+
+  // ---- the ring.  Copy instruction q of a wavefront moves piece min(wave*LPB + q, 2 NS - 1) of a block.
+  constexpr int LPB = (2 * NS + NWAVES - 1) / NWAVES;
+  const unsigned char* csrc[LPB];
+  int cdst[LPB];
+#pragma unroll
+  for (int q = 0; q < LPB; ++q) {
+    const int p = min(wave * LPB + q, 2 * NS - 1);
+    csrc[q] = reinterpret_cast<const unsigned char*>(p < NS ? kh : vh) + (size_t)b_lo * (32 * D * 2) + (p & (NS - 1)) * 1024 +
+              lane * 16;
+    cdst[q] = p * 1024;
+  }
+  auto issue = [&](int k) {  // block k of the split into slot k % RING (beyond the range: the last block again)
+    const int kc_ = min(k, nb_split - 1);
+    const int slot = (int)((unsigned)k % (unsigned)RING);
+#pragma unroll
+    for (int q = 0; q < LPB; ++q) {
+      unsigned char* dst = ring + slot * SLOT + cdst[q];
+#if defined(__HIP_DEVICE_COMPILE__)  // (the host pass knows no such builtin and would silently drop the kernel's stub)
+      __builtin_amdgcn_global_load_lds(reinterpret_cast<const u32x4*>(csrc[q] + (size_t)kc_ * (32 * D * 2)),
+                                       GOOSE_LDS_PTR(dst), 16, 0, 0);
+#else
+      (void)dst;
+#endif
+    }
+  };
+  auto barrier = [&]() {  // (raw: __syncthreads would also drain every copy in flight)
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+  // eight operand pieces of a ring slot: the reads and the wait for them in one statement (the
+  // compiler is not told about these reads, so it does not make them wait for the copies in flight,
+  // and it never sees registers whose data is still on its way)
+  const unsigned ring_addr = (unsigned)(uintptr_t)GOOSE_LDS_PTR(ring) + lane * 16;
+  u32x4 kreg[NS];
+  auto read_ring = [&](unsigned addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile(
+        "ds_read_b128 %0, %8\n\t"
+        "ds_read_b128 %1, %8 offset:1024\n\t"
+        "ds_read_b128 %2, %8 offset:2048\n\t"
+        "ds_read_b128 %3, %8 offset:3072\n\t"
+        "ds_read_b128 %4, %8 offset:4096\n\t"
+        "ds_read_b128 %5, %8 offset:5120\n\t"
+        "ds_read_b128 %6, %8 offset:6144\n\t"
+        "ds_read_b128 %7, %8 offset:7168\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(kreg[0]), "=&v"(kreg[1]), "=&v"(kreg[2]), "=&v"(kreg[3]), "=&v"(kreg[4]), "=&v"(kreg[5]),
+          "=&v"(kreg[6]), "=&v"(kreg[7])
+        : "v"(addr)
+        : "memory");
+#else
+    (void)addr;
+#endif
+  };
+  static_assert(NS == 8, "read_ring moves eight pieces");
+  if (nsteps > 0) {
+    issue(0);
+    issue(1);
+    issue(2);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  f32x16 oacc[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+  float m_run = NEG_BIG, l_run = 0.f;
+  const float scale = 1.4426950408889634f / sqrtf((float)D);  // log2(e) / sqrt(d): softmax in base 2
+
+  for (int idx = 0; idx < total; ++idx) {
+    const bool staged = idx < nsteps;
+    const int kblk = 2 * idx + g;  // this wavefront's block of the split in a staged step
+    unsigned slot_addr = 0;
+    if (staged) {
+      // blocks 2 idx and 2 idx + 1 have landed once at most the copies of block 2 idx + 2 are pending
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(LPB));
+      barrier();
+      issue(2 * idx + 3);
+      issue(2 * idx + 4);
+      __builtin_amdgcn_sched_barrier(0);
+      if (idle || kblk >= nb_split) continue;
+      slot_addr = ring_addr + ((unsigned)kblk % (unsigned)RING) * SLOT;
+    }
+    // visibility of this lane's 16 keys
+    bool masked = false, ragged = false;
+    unsigned vis = 0xFFFFu;
+    if (!staged) {  // tree block: the ancestor bits of nodes j0 .. j0+15
+      masked = true;
+      const int j0 = (g + NG * (idx - nsteps)) * 32 + hh * 16;
+      vis = (unsigned)(j0 < 64 ? mw0 >> j0 : mw1 >> (j0 - 64)) & 0xFFFFu;
+      const int t = g + NG * (idx - nsteps);
+      const unsigned char* kp = Kt + (t * 32 + ((l31 >> 2) & 1) * 16 + (l31 & 3) + 4 * (l31 >> 3)) * KROW + hh * 16;
+#pragma unroll
+      for (int s = 0; s < NS; ++s) kreg[s] = *reinterpret_cast<const u32x4*>(kp + s * 32);
+    } else {
+      const int nvalid = P - (b_lo + kblk) * 32;  // >= 32 except in the ragged last prefix block
+      if (nvalid < 32) {
+        masked = ragged = true;
+        const int mine = nvalid - hh * 16;
+        vis = mine >= 16 ? 0xFFFFu : (mine <= 0 ? 0u : ((1u << mine) - 1u));
+      }
+      read_ring(slot_addr);
+    }
+    f32x16 sacc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      sacc = Mma16<F16>::mfma(__builtin_bit_cast(op8, kreg[s]), qf[s], sacc);
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      sacc = Mma16<F16>::mfma(__builtin_bit_cast(op8, kreg[s]), qf2[s], sacc);
+    if (masked) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[r] = ((vis >> r) & 1u) ? sacc[r] : NEG_BIG;  // also drops NaNs of stale keys
+    }
+    float tmax = NEG_BIG;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      sacc[r] = fmaxf(sacc[r] * scale, NEG_BIG);
+      tmax = fmaxf(tmax, sacc[r]);
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float m_new = fmaxf(m_run, tmax);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    const bool grew = m_new > m_run;
+    m_run = m_new;
+    float p[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) p[r] = __builtin_amdgcn_exp2f(sacc[r] - m_new);
+    if (masked) {  // a fully masked row has m_new == NEG_BIG: exp2(0) must not count
+#pragma unroll
+      for (int r = 0; r < 16; ++r) p[r] = ((vis >> r) & 1u) ? p[r] : 0.f;
+    }
+    float psum = 0.f;
+    op8 pf[2];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      psum += p[r];
+      pf[r >> 3][r & 7] = (T)p[r];
+    }
+    l_run = l_run * alpha + psum;
+    if (__builtin_amdgcn_ballot_w64(grew) != 0) {
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+    }
+    // the values take the registers the keys had
+    if (!staged) {
+      const int t = g + NG * (idx - nsteps);
+      const unsigned char* vp = Vt + l31 * VROW + (t * 32 + hh * 16) * 2;
+#pragma unroll
+      for (int s = 0; s < NS; ++s) kreg[s] = *reinterpret_cast<const u32x4*>(vp + (s >> 1) * 32 * VROW + (s & 1) * 16);
+    } else {
+      read_ring(slot_addr + NS * 1024);
+    }
+    if (ragged) {  // stale values -> 0
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const unsigned bits = (vis >> ((s & 1) * 8)) & 0xFFu;
+        u16x8 e = __builtin_bit_cast(u16x8, kreg[s]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+          if (!((bits >> k) & 1u)) e[k] = 0;
+        kreg[s] = __builtin_bit_cast(u32x4, e);
+      }
+    }
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        oacc[dt] = Mma16<F16>::mfma(__builtin_bit_cast(op8, kreg[dt * 2 + j]), pf[j], oacc[dt]);
+  }
+
+  // ---- merge the two key groups of a query tile through the ring's memory: every wavefront leaves
+  // (m, l) and the accumulator quads its partner owns, then combines its own QPW quads with the
+  // partner's copy of them, group 0 first, and writes them out.
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // (copies of blocks beyond the range may still be landing)
+  __syncthreads();
+  f32x4 res[QPW];
+  float l_sum;
+  {
+    float* mbuf = reinterpret_cast<float*>(ring);
+    float* dst = mbuf + (size_t)wave * WFLOATS + lane * 4;
+    *reinterpret_cast<f32x4*>(dst) = f32x4{m_run, l_run, 0.f, 0.f};
+#pragma unroll
+    for (int q = 0; q < QPW; ++q) {
+      // quad q of the partner's share: group 0 gives away quads QPW .. 2 QPW - 1, group 1 quads 0 .. QPW - 1
+      const int q0 = q, q1 = QPW + q;
+      const f32x4 a = {oacc[q0 >> 2][(q0 & 3) * 4], oacc[q0 >> 2][(q0 & 3) * 4 + 1], oacc[q0 >> 2][(q0 & 3) * 4 + 2],
+                       oacc[q0 >> 2][(q0 & 3) * 4 + 3]};
+      const f32x4 b = {oacc[q1 >> 2][(q1 & 3) * 4], oacc[q1 >> 2][(q1 & 3) * 4 + 1], oacc[q1 >> 2][(q1 & 3) * 4 + 2],
+                       oacc[q1 >> 2][(q1 & 3) * 4 + 3]};
+      *reinterpret_cast<f32x4*>(dst + 256 * (1 + q)) = g == 0 ? b : a;
+      res[q] = g == 0 ? a : b;  // (its own share, for now)
+    }
+    __syncthreads();
+    const float* src = mbuf + (size_t)(wave ^ 1) * WFLOATS + lane * 4;  // (NG == 2: the partner is wave ^ 1)
+    const f32x4 ml = *reinterpret_cast<const f32x4*>(src);
+    const float m0 = g == 0 ? m_run : ml[0], m1 = g == 0 ? ml[0] : m_run;
+    const float l0 = g == 0 ? l_run : ml[1], l1 = g == 0 ? ml[1] : l_run;
+    const float m_all = fmaxf(m0, m1);
+    const float w0 = __builtin_amdgcn_exp2f(m0 - m_all), w1 = __builtin_amdgcn_exp2f(m1 - m_all);
+    l_sum = w0 * l0 + w1 * l1;
+#pragma unroll
+    for (int q = 0; q < QPW; ++q) {
+      const f32x4 other = *reinterpret_cast<const f32x4*>(src + 256 * (1 + q));
+      res[q] = g == 0 ? w0 * res[q] + w1 * other : w0 * other + w1 * res[q];
+    }
+    m_run = m_all;
+  }
+
+  // ---- output (as in k_attn_fused)
+  const float l_tot = l_sum + __shfl_xor(l_sum, 32, 64);
+  if (qi >= B) return;
+  if (nsplit == 1) {
+    const float inv = 1.0f / l_tot;
+    unsigned short* orow = o_out + (size_t)qi * ldo;
+#pragma unroll
+    for (int q = 0; q < QPW; ++q) {
+      const int quad = g * QPW + q;
+      u16x4 v, v2;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float f = res[q][e] * inv;
+        v[e] = out_bits16(f, o_f16);
+        v2[e] = out_bits16(f - out_back16(v[e], o_f16), o_f16);
+      }
+      unsigned short* dst = orow + term_pos(oterms, h * D + quad * 8 + hh * 4);
+      *reinterpret_cast<u16x4*>(dst) = v;
+      if (oterms == 2) *reinterpret_cast<u16x4*>(dst + 8) = v2;
+    }
+  } else {
+    const size_t base = ((size_t)h * nsplit + split) * Bpad + row0 + qi;
+    if (hh == 0 && g == 0) {
+      att_ml[base * 2] = m_run;
+      att_ml[base * 2 + 1] = l_tot;
+    }
+    float* orow = att_o + base * D;
+#pragma unroll
+    for (int q = 0; q < QPW; ++q) *reinterpret_cast<f32x4*>(orow + (g * QPW + q) * 8 + hh * 4) = res[q];
+  }
+}
+
 // o[q][h*D + c] = sum_s 2^(m_s - m) O_s[c] / sum_s 2^(m_s - m) l_s, splits taken in index order.
 // A workgroup of 256 threads merges 1024 / D rows of one head, four columns per thread; the loads of
 // up to eight splits are issued together (one load per loop round would make every split a trip to
@@ -660,11 +1179,36 @@ int launch_cfg(dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable<ATTN
   return a.f16 ? launch_t<D, NG, NQH, true>(grid, st, a, t) : launch_t<D, NG, NQH, false>(grid, st, a, t);
 }
 
+template <int NQH, bool F16>
+int launch_wide_t(dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable<ATTN_MAX_SEGS>& t) {
+  typedef typename Mma16<F16>::T T;
+  if (grid.z == 1) {
+    const SegTable<1> t1{{t.s[0]}};
+    hipLaunchKernelGGL((k_attn_wide<NQH, F16, 1>), grid, dim3(128 * NQH), 0, st, t1, a.n_heads, a.n_kv, a.cap, a.part,
+                       a.ks, a.part_stride, a.part_ld, a.cs, (const T*)a.gq, (const T*)a.gk, a.eps, a.att_o, a.att_ml,
+                       a.Bpad, (unsigned short*)a.o, a.ldo, a.oterms, a.o_f16, a.flags);
+  } else {
+    hipLaunchKernelGGL((k_attn_wide<NQH, F16, ATTN_MAX_SEGS>), grid, dim3(128 * NQH), 0, st, t, a.n_heads, a.n_kv,
+                       a.cap, a.part, a.ks, a.part_stride, a.part_ld, a.cs, (const T*)a.gq, (const T*)a.gk, a.eps,
+                       a.att_o, a.att_ml, a.Bpad, (unsigned short*)a.o, a.ldo, a.oterms, a.o_f16, a.flags);
+  }
+  return goose_launch_status();
+}
+template <int NQH>
+int launch_wide(dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable<ATTN_MAX_SEGS>& t) {
+  return a.f16 ? launch_wide_t<NQH, true>(grid, st, a, t) : launch_wide_t<NQH, false>(grid, st, a, t);
+}
+
 template <int D>
 int launch_d(int QT, int ng, dim3 grid, hipStream_t st, const AttnArgs& a, const SegTable<ATTN_MAX_SEGS>& t) {
   // one wavefront per (query tile, key group); at most 8 wavefronts per workgroup
   if (QT == 1) return ng == 4 ? launch_cfg<D, 4, 1>(grid, st, a, t) : launch_cfg<D, 2, 1>(grid, st, a, t);
   if (QT == 2) return ng == 4 ? launch_cfg<D, 4, 2>(grid, st, a, t) : launch_cfg<D, 2, 2>(grid, st, a, t);
+  // three and four tiles: the kernel that stages the key blocks through LDS (head size 128)
+  if constexpr (D == 128) {
+    if (QT == 3) return launch_wide<3>(grid, st, a, t);
+    return launch_wide<4>(grid, st, a, t);
+  }
   if (QT == 3) return launch_cfg<D, 2, 3>(grid, st, a, t);
   return launch_cfg<D, 2, 4>(grid, st, a, t);
 }
