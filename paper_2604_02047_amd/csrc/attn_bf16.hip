@@ -7,7 +7,9 @@
 // (see goose.h): a 32-key block of one head is D/16 x 1 KiB of K and D/16 x 1 KiB of V, each
 // 1 KiB piece being the 64 lanes x 16 bytes of one operand load.  A wavefront therefore streams
 // its key blocks global -> registers -> MFMA with perfectly coalesced loads: no LDS staging, no
-// barriers.
+// barriers (k_attn_fused).  Trees of more than 64 nodes at head size 128 take k_attn_wide instead,
+// which brings every block into LDS once per workgroup: with three or four query tiles the
+// per-wavefront loads of the same block are what limits the kernel.
 //
 // Per 32-key block and 32-query tile:
 //     S^T[key][query]  = K . Q^T          (v_mfma_f32_32x32x16_{bf16,f16}, rows = keys)
