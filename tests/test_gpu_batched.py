@@ -109,7 +109,8 @@ def _rows_of(sizes):
                                               ("tiny_bf16", [16, 9, 1, 32]), ("tiny_gqa_bf16", [128]),
                                               ("small_bf16", [32] * 8), ("tiny_bf16", [16, 9, 1, 32, 64, 100, 3]),
                                               ("small_gqa_qknorm_bf16", [32] * 16),
-                                              ("small_gqa_qknorm_f16", [64, 20, 32, 100, 7])])
+                                              ("small_gqa_qknorm_f16", [64, 20, 32, 100, 7]),
+                                              ("small_bf16", [100, 128, 70, 96])])
 def test_batched_step_equals_the_requests_alone(shape_name, sizes):
     """Short prefixes: one key split alone and batched, hence identical arithmetic per request
     (also beyond 128 stacked rows, where the projections run in chunks of 128 rows)."""
@@ -138,7 +139,8 @@ def test_batched_step_equals_the_requests_alone(shape_name, sizes):
 @pytest.mark.parametrize("shape_name,sizes,P0s", [("small_bf16", [32, 32, 32, 32], [700, 513, 640, 96]),
                                                   ("small_gqa_qknorm_bf16", [40, 17, 9], [600, 777, 31]),
                                                   ("tiny_gqa_bf16", [90], [500]),
-                                                  ("small_gqa_qknorm_bf16", [64, 17, 40, 128, 5], [600, 777, 31, 300, 512])])
+                                                  ("small_gqa_qknorm_bf16", [64, 17, 40, 128, 5], [600, 777, 31, 300, 512]),
+                                                  ("small_gqa_qknorm_bf16", [100, 128, 70, 96], [300, 513, 96, 640])])
 def test_batched_step_with_long_prefixes_matches_the_oracle(shape_name, sizes, P0s):
     """Prefixes long enough for several key splits, mixed tree-size classes: every request against the oracle."""
     shape = gi.SHAPES[shape_name]

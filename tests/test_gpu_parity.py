@@ -193,6 +193,32 @@ def test_bf16_independent_prefill_stays_within_tolerance(shape_name):
     _run_cycles(shape_name, 2, 96, trees, seed=5, oracle_prefill=True, chunk=32)
 
 
+@pytest.mark.parametrize("shape_name", ["small_bf16", "small_gqa_qknorm_f16"])
+def test_wide_trees_over_prefix_lengths(shape_name):
+    """Trees of 65 to 128 nodes at head size 128 (the kernel that stages the key blocks through an LDS ring)
+    over prefix lengths that give every case of the ring: no prefix block at all, one, odd and even counts, a
+    ragged last block in either key group's slot, one to three key splits.  The prefix is shortened from
+    step to step, so the slots beyond it hold stale rows of the earlier, longer one."""
+    shape = gi.SHAPES[shape_name]
+    tol = tol_for(shape)
+    tm = torch_model(shape, seed=11, gain_jitter=0.1)
+    om = oracle_model(shape, tm)
+    P_top = 417
+    gm = gpu_model(shape, tm, max_B=128, cap=(P_top + 128 + 63) // 64 * 64)
+    prefix = gi.prefix_tokens(11, P_top, shape.vocab)
+    _gpu_prefill(gm, prefix, 64)
+    trees = [gi.tree_random(65, 3, spine_len=9), gi.tree_spine_13b(), gi.tree_random(97, 4, spine_len=12),
+             gi.tree_spine_stress(), gi.tree_balanced()]
+    for n, P in enumerate([417, 385, 352, 321, 300, 289, 257, 224, 193, 161, 130, 97, 64, 33, 31, 1, 0]):
+        gm.set_P(P)
+        cache = device_cache_as_oracle(gm, P) if P else orc.empty_cache(om)
+        tree = trees[n % len(trees)]
+        tokens = gi.draft_tokens_uniform(300 + n, tree.parent, shape.vocab, int(prefix[P - 1]) if P else 17)
+        print(f"P={P} B={tree.B}", flush=True)
+        _compare_step(shape, gm, om, cache, tokens, tree, tol)
+    gm.ctx.close()
+
+
 def test_16bit_tree_that_fills_the_cache_to_its_last_slot():
     """P + B == cap exactly (the largest tree in the last free slots), and one slot more is refused."""
     from paper_2604_02047_amd.binding import GooseError
